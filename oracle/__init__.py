@@ -1,0 +1,128 @@
+"""fp64 CPU oracle for paged decode attention: ctypes front end of oracle_attn.c.
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  It imports nothing from the HIP package; inputs
+come in as host numpy arrays (fp32, or uint16 bf16 bit patterns).
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+_DT = {"f32": 0, "bf16": 1}
+
+
+class _Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "ps", "MB", "q_dtype", "kv_dtype")]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        L.oracle_paged_decode_attn.restype = C.c_int
+        L.oracle_paged_decode_attn.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 5 + [C.c_float, C.c_void_p,
+                                                                                       C.c_void_p, C.c_int32, C.c_int32]
+        L.oracle_partial.restype = None
+        L.oracle_partial.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 4 + [C.c_float] + [C.c_int32] * 4 + [C.c_void_p] * 3
+        L.oracle_merge.restype = None
+        L.oracle_merge.argtypes = [C.c_int32, C.c_int32] + [C.c_void_p] * 4
+        L.oracle_kv_append.restype = None
+        L.oracle_kv_append.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 6
+        L.oracle_gather.restype = None
+        L.oracle_gather.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 3 + [C.c_int32, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(a: np.ndarray, dtype: str, what: str) -> np.ndarray:
+    want = np.float32 if dtype == "f32" else np.uint16
+    if a.dtype != want or not a.flags.c_contiguous:
+        raise TypeError(f"{what}: need C-contiguous {want.__name__} array for dtype {dtype}, got {a.dtype}")
+    return a
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _shape(q, k_cache, block_table, dtype, q_dtype=None) -> _Shape:
+    B, Hq, D = q.shape
+    P, Hkv, ps, D2 = k_cache.shape
+    assert D == D2 and Hq % Hkv == 0
+    assert block_table.dtype == np.int32 and block_table.flags.c_contiguous and block_table.shape[0] == B
+    return _Shape(B, Hq, Hkv, D, ps, block_table.shape[1], _DT[q_dtype or dtype], _DT[dtype])
+
+
+def paged_decode_attn(q, k_cache, v_cache, block_table, context_lens, scale, dtype: str,
+                      pairs: Optional[Sequence[Tuple[int, int]]] = None, num_threads: int = 0,
+                      return_threads: bool = False):
+    """softmax(scale q K^T) V per (request, query head) in fp64.
+
+    Returns [B, Hq, D] float64, or [len(pairs), D] when `pairs` lists (b, h) to compute.
+    """
+    _check(q, dtype, "q"); _check(k_cache, dtype, "k_cache"); _check(v_cache, dtype, "v_cache")
+    s = _shape(q, k_cache, block_table, dtype)
+    lens = np.ascontiguousarray(context_lens, dtype=np.int32)
+    if pairs is None:
+        out = np.zeros((s.B, s.Hq, s.D), dtype=np.float64)
+        pr, n = None, 0
+    else:
+        pr = np.ascontiguousarray(np.asarray(pairs, dtype=np.int32).reshape(-1, 2))
+        n = pr.shape[0]
+        out = np.zeros((n, s.D), dtype=np.float64)
+    used = lib().oracle_paged_decode_attn(C.byref(s), _p(q), _p(k_cache), _p(v_cache), _p(block_table), _p(lens),
+                                          C.c_float(float(scale)), _p(out), _p(pr), n, int(num_threads))
+    return (out, used) if return_threads else out
+
+
+def partial(q, k_cache, v_cache, block_table, scale, dtype: str, b: int, h: int, t0: int, t1: int):
+    """Unnormalised (o[D], m, l) of (b, h) over tokens [t0, t1)."""
+    s = _shape(q, k_cache, block_table, dtype)
+    o = np.zeros(s.D, dtype=np.float64)
+    m = np.zeros(1, dtype=np.float64)
+    l = np.zeros(1, dtype=np.float64)
+    lib().oracle_partial(C.byref(s), _p(q), _p(k_cache), _p(v_cache), _p(block_table), C.c_float(float(scale)),
+                         b, h, t0, t1, _p(o), _p(m), _p(l))
+    return o, float(m[0]), float(l[0])
+
+
+def merge(o: np.ndarray, m: np.ndarray, l: np.ndarray) -> np.ndarray:
+    """Log-sum-exp merge of partitions: o [n, D], m [n], l [n] -> [D]."""
+    o = np.ascontiguousarray(o, dtype=np.float64)
+    m = np.ascontiguousarray(m, dtype=np.float64)
+    l = np.ascontiguousarray(l, dtype=np.float64)
+    out = np.zeros(o.shape[1], dtype=np.float64)
+    lib().oracle_merge(o.shape[0], o.shape[1], _p(o), _p(m), _p(l), _p(out))
+    return out
+
+
+def kv_append(k_new, v_new, k_cache, v_cache, block_table, positions, dtype: str) -> None:
+    """In-place bit copy of the new rows into their page slots (positions < 0 are skipped)."""
+    for a, w in ((k_new, "k_new"), (v_new, "v_new"), (k_cache, "k_cache"), (v_cache, "v_cache")):
+        _check(a, dtype, w)
+    B, Hkv, D = k_new.shape
+    P, Hkv2, ps, D2 = k_cache.shape
+    assert (Hkv, D) == (Hkv2, D2)
+    s = _Shape(B, Hkv, Hkv, D, ps, block_table.shape[1], _DT[dtype], _DT[dtype])
+    pos = np.ascontiguousarray(positions, dtype=np.int32)
+    lib().oracle_kv_append(C.byref(s), _p(k_new), _p(v_new), _p(k_cache), _p(v_cache), _p(block_table), _p(pos))
+
+
+def gather(cache, block_table, context_lens, b: int, dtype: str) -> np.ndarray:
+    """Request b's rows in token order, [L_b, Hkv, D], same dtype as the cache (bit copy)."""
+    _check(cache, dtype, "cache")
+    P, Hkv, ps, D = cache.shape
+    s = _Shape(block_table.shape[0], Hkv, Hkv, D, ps, block_table.shape[1], _DT[dtype], _DT[dtype])
+    lens = np.ascontiguousarray(context_lens, dtype=np.int32)
+    out = np.zeros((int(lens[b]), Hkv, D), dtype=cache.dtype)
+    lib().oracle_gather(C.byref(s), _p(cache), _p(block_table), _p(lens), b, _p(out))
+    return out

@@ -1,0 +1,333 @@
+"""Pins for the fp64 CPU oracle (CPU only).
+
+Each test checks the oracle against something fixed by the mathematics of
+softmax attention or by the paged layout, never against the oracle itself:
+dense brute force written separately in numpy, closed forms, invariants,
+hand-worked values.  A dropped term, a wrong sign, a wrong GQA map or a wrong
+page/slot formula in the oracle fails at least one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2602_02204_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "closed_form_cases.txt")
+
+
+# --------------------------------------------------------------------------- helpers
+def to_f64(a, dtype):
+    return a.astype(np.float64) if dtype == W.F32 else W.bf16_bits_to_f32(a).astype(np.float64)
+
+
+def dense_bruteforce(wl):
+    """Unpaged reference: gather with plain numpy indexing, repeat KV heads G times, softmax(QK^T)V in fp64."""
+    out = np.zeros((wl.B, wl.Hq, wl.D))
+    kc, vc = to_f64(wl.k_cache, wl.dtype), to_f64(wl.v_cache, wl.dtype)
+    q = to_f64(wl.q, wl.dtype)
+    for b in range(wl.B):
+        L = int(wl.context_lens[b])
+        if L == 0:
+            continue
+        t = np.arange(L)
+        pages = wl.block_table[b, t // wl.ps]
+        K = kc[pages, :, t % wl.ps, :]                    # [L, Hkv, D]
+        V = vc[pages, :, t % wl.ps, :]
+        K = np.repeat(K, wl.G, axis=1)                    # [L, Hq, D]: head h uses KV head h // G
+        V = np.repeat(V, wl.G, axis=1)
+        s = np.einsum("hd,lhd->hl", q[b], K) * np.float64(wl.scale)
+        s = s - s.max(axis=1, keepdims=True)
+        p = np.exp(s)
+        p /= p.sum(axis=1, keepdims=True)
+        out[b] = np.einsum("hl,lhd->hd", p, V)
+    return out
+
+
+def run(wl, **kw):
+    return oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens,
+                                    wl.scale, wl.dtype, **kw)
+
+
+def small(seed, dtype=W.F32, lens=(1, 5, 16, 17, 33, 40), Hq=6, Hkv=2, D=8, ps=4, **kw):
+    return W.build("small", seed, lens, Hq=Hq, Hkv=Hkv, D=D, ps=ps, dtype=dtype, pool_factor=1.5, **kw)
+
+
+# --------------------------------------------------------------------------- brute force
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+@pytest.mark.parametrize("hq,hkv", [(6, 2), (4, 4), (7, 1), (8, 2)])
+def test_matches_dense_bruteforce(dtype, hq, hkv):
+    wl = small(3, dtype=dtype, Hq=hq, Hkv=hkv)
+    got, ref = run(wl), dense_bruteforce(wl)
+    assert np.max(np.abs(got - ref)) < 1e-13
+
+
+def test_tiny_config_matches_bruteforce():
+    wl = W.make("tiny")
+    assert (wl.B, wl.Hq, wl.Hkv, wl.D, wl.ps, wl.P) == (4, 4, 2, 64, 16, 64)
+    assert list(wl.context_lens) == [17, 64, 129, 200] and float(wl.scale) == 0.125
+    assert np.max(np.abs(run(wl) - dense_bruteforce(wl))) < 1e-13
+
+
+def test_gqa_map_is_contiguous_groups():
+    # Make KV head 0 and KV head 1 carry constant, different V: every query head must return its own group's constant.
+    wl = small(5, Hq=6, Hkv=2)
+    live = ~np.isnan(wl.v_cache)
+    wl.v_cache[:, 0][live[:, 0]] = 10.0
+    wl.v_cache[:, 1][live[:, 1]] = 20.0
+    out = run(wl)
+    assert np.allclose(out[:, 0:3], 10.0, atol=1e-12) and np.allclose(out[:, 3:6], 20.0, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- special cases and closed forms
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_length_one_returns_v_row_exactly(dtype):
+    wl = small(7, dtype=dtype, lens=(1, 1, 1))
+    out = run(wl)
+    v = to_f64(wl.v_cache, wl.dtype)
+    for b in range(wl.B):
+        page = wl.block_table[b, 0]
+        for h in range(wl.Hq):
+            assert np.array_equal(out[b, h], v[page, h // wl.G, 0])
+
+
+def test_identical_keys_give_mean_of_v():
+    wl = small(11, lens=(9, 23))
+    live = ~np.isnan(wl.k_cache)
+    wl.k_cache[live] = 0.37
+    out = run(wl)
+    v = to_f64(wl.v_cache, wl.dtype)
+    for b in range(wl.B):
+        L = int(wl.context_lens[b]); t = np.arange(L)
+        V = v[wl.block_table[b, t // wl.ps], :, t % wl.ps, :]
+        for h in range(wl.Hq):
+            assert np.allclose(out[b, h], V[:, h // wl.G].mean(axis=0), atol=1e-14)
+
+
+def test_zero_query_gives_mean_of_v():
+    wl = small(12, lens=(13,))
+    wl.q[...] = 0.0
+    out = run(wl)
+    v = to_f64(wl.v_cache, wl.dtype)
+    t = np.arange(13)
+    V = v[wl.block_table[0, t // wl.ps], :, t % wl.ps, :]
+    for h in range(wl.Hq):
+        assert np.allclose(out[0, h], V[:, h // wl.G].mean(axis=0), atol=1e-14)
+
+
+def test_length_two_closed_form():
+    wl = small(13, lens=(2, 2, 2), Hq=2, Hkv=2)
+    out = run(wl)
+    q, k, v = (to_f64(a, wl.dtype) for a in (wl.q, wl.k_cache, wl.v_cache))
+    for b in range(wl.B):
+        pg = wl.block_table[b, 0]
+        for h in range(wl.Hq):
+            s0 = float(wl.scale) * math.fsum(q[b, h] * k[pg, h, 0])
+            s1 = float(wl.scale) * math.fsum(q[b, h] * k[pg, h, 1])
+            w0 = 1.0 / (1.0 + math.exp(s1 - s0))
+            assert np.allclose(out[b, h], w0 * v[pg, h, 0] + (1 - w0) * v[pg, h, 1], atol=1e-14)
+
+
+def _parse_vals(txt):
+    return [math.log(float(tok[2:])) if tok.startswith("ln") else float(tok) for tok in txt.split()]
+
+
+def test_golden_hand_worked_cases():
+    n = 0
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, scale, q, K, V, exp = [f.strip() for f in line.split("|")]
+        q = np.array(_parse_vals(q), dtype=np.float32)[None, None, :]
+        K = np.array([_parse_vals(r) for r in K.split(";")], dtype=np.float32)
+        V = np.array([_parse_vals(r) for r in V.split(";")], dtype=np.float32)
+        L, D = K.shape
+        ps = 2
+        npg = (L + ps - 1) // ps
+        kc = np.full((npg + 1, 1, ps, D), np.nan, dtype=np.float32)
+        vc = kc.copy()
+        table = np.arange(npg, 0, -1, dtype=np.int32)[None, :]           # pages npg..1, page 0 unused
+        for t in range(L):
+            kc[table[0, t // ps], 0, t % ps] = K[t]
+            vc[table[0, t // ps], 0, t % ps] = V[t]
+        out = oracle.paged_decode_attn(q, kc, vc, table, np.array([L], np.int32), float(scale), W.F32)
+        assert np.allclose(out[0, 0], _parse_vals(exp), atol=2e-6), name
+        n += 1
+    assert n == 4
+
+
+# --------------------------------------------------------------------------- invariants
+def test_key_shift_invariance_large_shift():
+    # Adding u to every key adds the constant scale*q.u to every score of a head: softmax does not move.
+    wl = small(17, lens=(31,), Hq=2, Hkv=1, D=8)
+    base = run(wl)
+    q = wl.q[0].astype(np.float64)
+    u = 80.0 / float(wl.scale) * q[0] / np.dot(q[0], q[0])          # shifts head 0 by exactly ~80
+    live = ~np.isnan(wl.k_cache)
+    k2 = wl.k_cache.astype(np.float64)
+    k2[0:wl.P, 0, :, :] += u
+    wl2 = small(17, lens=(31,), Hq=2, Hkv=1, D=8)
+    wl2.k_cache = np.where(live, k2, np.nan).astype(np.float32)
+    shifted = run(wl2)
+    assert np.all(np.isfinite(shifted))
+    # fp32 rounding of the shifted keys perturbs scores by ~80 * 2^-24: compare at 1e-4
+    assert np.max(np.abs(shifted[0, 0] - base[0, 0])) < 1e-4
+
+
+def test_dominant_key_limit():
+    wl = small(19, lens=(25,), Hq=1, Hkv=1, D=8)
+    t_star = 9
+    pg, sl = wl.block_table[0, t_star // wl.ps], t_star % wl.ps
+    qv = wl.q[0, 0].astype(np.float64)
+    live = ~np.isnan(wl.k_cache)
+    wl.k_cache[live] = 0.0
+    wl.k_cache[pg, 0, sl] = (100.0 / float(wl.scale) * qv / np.dot(qv, qv)).astype(np.float32)
+    out = run(wl)
+    assert np.max(np.abs(out[0, 0] - wl.v_cache[pg, 0, sl].astype(np.float64))) < 1e-20
+
+
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_output_in_convex_hull_of_v(dtype):
+    wl = small(23, dtype=dtype)
+    out = run(wl)
+    v = to_f64(wl.v_cache, wl.dtype)
+    for b in range(wl.B):
+        L = int(wl.context_lens[b]); t = np.arange(L)
+        V = v[wl.block_table[b, t // wl.ps], :, t % wl.ps, :]
+        for h in range(wl.Hq):
+            lo, hi = V[:, h // wl.G].min(axis=0), V[:, h // wl.G].max(axis=0)
+            assert np.all(out[b, h] >= lo - 1e-12) and np.all(out[b, h] <= hi + 1e-12)
+
+
+def test_page_permutation_is_bit_invariant():
+    wl = small(29, dtype=W.BF16)
+    base = run(wl)
+    rng = np.random.default_rng(1)
+    perm = rng.permutation(wl.P)                      # new physical id of old page p is perm[p]
+    k2, v2 = np.empty_like(wl.k_cache), np.empty_like(wl.v_cache)
+    k2[perm] = wl.k_cache
+    v2[perm] = wl.v_cache
+    t2 = np.where(wl.block_table >= 0, perm[np.maximum(wl.block_table, 0)], -1).astype(np.int32)
+    out = oracle.paged_decode_attn(wl.q, k2, v2, t2, wl.context_lens, wl.scale, wl.dtype)
+    assert np.array_equal(out, base)
+
+
+def test_page_size_change_is_bit_invariant():
+    lens = (1, 15, 16, 17, 47, 64)
+    a = small(31, lens=lens, ps=16, D=16)
+    # same logical rows, re-paged at ps = 32 with a different physical assignment
+    rng = np.random.default_rng(2)
+    ps2 = 32
+    npg = [(L + ps2 - 1) // ps2 for L in lens]
+    P2 = sum(npg) + 3
+    ids = rng.permutation(P2)[: sum(npg)].astype(np.int32)
+    table = np.full((len(lens), max(npg)), -1, np.int32)
+    kc = np.full((P2, a.Hkv, ps2, a.D), np.nan, np.float32); vc = kc.copy()
+    pos = 0
+    for b, L in enumerate(lens):
+        table[b, : npg[b]] = ids[pos: pos + npg[b]]; pos += npg[b]
+        for t in range(L):
+            src = (a.block_table[b, t // a.ps], slice(None), t % a.ps)
+            dst = (table[b, t // ps2], slice(None), t % ps2)
+            kc[dst] = a.k_cache[src]; vc[dst] = a.v_cache[src]
+    out = oracle.paged_decode_attn(a.q, kc, vc, table, a.context_lens, a.scale, a.dtype)
+    assert np.array_equal(out, run(a))
+
+
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_poison_never_reaches_output(dtype):
+    wl = small(37, dtype=dtype)
+    # unowned slots and pages are NaN by construction; padded table entries are -1
+    raw = wl.k_cache if dtype == W.F32 else W.bf16_bits_to_f32(wl.k_cache)
+    assert np.isnan(raw).any() and (wl.block_table == -1).any()
+    assert np.all(np.isfinite(run(wl)))
+
+
+def test_empty_request_gives_zero_row():
+    wl = small(41, lens=(0, 7, 0))
+    out = run(wl)
+    assert np.all(out[0] == 0.0) and np.all(out[2] == 0.0) and np.all(np.isfinite(out[1]))
+
+
+def test_scale_is_the_callers_fp32_value():
+    # 1/sqrt(128) is not representable: the oracle must use the fp32 value handed in, widened.
+    wl = small(43, lens=(6,), Hq=1, Hkv=1, D=8)
+    s32 = np.float32(1.0 / math.sqrt(128.0))
+    out = oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, s32, wl.dtype)
+    wl.scale = s32
+    assert np.max(np.abs(out - dense_bruteforce(wl))) < 1e-15
+
+
+def test_pairs_subset_matches_full():
+    wl = small(47)
+    full = run(wl)
+    pairs = [(0, 0), (3, 5), (5, 2), (2, 4)]
+    sub = run(wl, pairs=pairs)
+    for i, (b, h) in enumerate(pairs):
+        assert np.array_equal(sub[i], full[b, h])
+
+
+# --------------------------------------------------------------------------- split + merge identity
+def test_split_and_merge_equals_unsplit():
+    wl = small(53, lens=(40, 33), dtype=W.BF16)
+    full = run(wl)
+    for b in range(wl.B):
+        L = int(wl.context_lens[b])
+        for h in (0, wl.Hq - 1):
+            for cuts in ([0, L], [0, 1, L], [0, 16, 17, L], [0, 7, 7, 30, L], [0, L, L]):
+                parts = [oracle.partial(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.scale, wl.dtype,
+                                        b, h, cuts[i], cuts[i + 1]) for i in range(len(cuts) - 1)]
+                o = np.stack([p[0] for p in parts]); m = np.array([p[1] for p in parts]); l = np.array([p[2] for p in parts])
+                assert np.max(np.abs(oracle.merge(o, m, l) - full[b, h])) < 1e-14
+
+
+def test_partial_is_the_unnormalised_sum():
+    # (o, m, l) of a range, recomputed with numpy from gathered rows
+    wl = small(59, lens=(20,), Hq=2, Hkv=1, D=8)
+    o, m, l = oracle.partial(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.scale, wl.dtype, 0, 1, 3, 15)
+    t = np.arange(3, 15)
+    K = wl.k_cache[wl.block_table[0, t // wl.ps], 0, t % wl.ps].astype(np.float64)
+    V = wl.v_cache[wl.block_table[0, t // wl.ps], 0, t % wl.ps].astype(np.float64)
+    s = K @ wl.q[0, 1].astype(np.float64) * float(wl.scale)
+    assert m == s.max() and abs(l - np.exp(s - s.max()).sum()) < 1e-14
+    assert np.max(np.abs(o - np.exp(s - s.max()) @ V)) < 1e-13
+
+
+def test_merge_ignores_empty_partitions():
+    o = np.array([[0.0, 0.0], [2.0, 4.0]]); m = np.array([-np.inf, 0.3]); l = np.array([0.0, 2.0])
+    assert np.allclose(oracle.merge(o, m, l), [1.0, 2.0])
+    assert np.all(oracle.merge(o[:1], m[:1], l[:1]) == 0.0)
+
+
+# --------------------------------------------------------------------------- append and gather
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_append_writes_exactly_one_row_per_head(dtype):
+    wl = small(61, dtype=dtype, lens=(1, 4, 5, 17, 0), append=True)
+    k0, v0 = wl.k_cache.copy(), wl.v_cache.copy()
+    oracle.kv_append(wl.k_new, wl.v_new, wl.k_cache, wl.v_cache, wl.block_table, wl.positions, wl.dtype)
+    changed = np.zeros(wl.k_cache.shape[:3], dtype=bool)
+    for b in range(wl.B):
+        pos = int(wl.positions[b])
+        if pos < 0:
+            continue
+        pg, sl = wl.block_table[b, pos // wl.ps], pos % wl.ps
+        assert np.array_equal(wl.k_cache[pg, :, sl], wl.k_new[b])
+        assert np.array_equal(wl.v_cache[pg, :, sl], wl.v_new[b])
+        changed[pg, :, sl] = True
+    same_bits = lambda a, b: np.array_equal(a.view(np.uint8), b.view(np.uint8))
+    assert same_bits(wl.k_cache[~changed], k0[~changed]) and same_bits(wl.v_cache[~changed], v0[~changed])
+    # after the append every live slot is finite
+    assert np.all(np.isfinite(run(wl)))
+    g = oracle.gather(wl.k_cache, wl.block_table, wl.context_lens, 3, wl.dtype)
+    assert np.array_equal(g[16], wl.k_new[3])
+
+
+def test_gather_is_token_ordered_bit_copy():
+    wl = small(67, dtype=W.BF16)
+    for b in range(wl.B):
+        g = oracle.gather(wl.v_cache, wl.block_table, wl.context_lens, b, wl.dtype)
+        L = int(wl.context_lens[b]); t = np.arange(L)
+        assert np.array_equal(g, wl.v_cache[wl.block_table[b, t // wl.ps], :, t % wl.ps, :])
