@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode hot path on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch: omni_kv_append (the new token's K/V rows into their
+pages) followed by omni_paged_decode_attn (device-side plan, split-context partition kernel, log-sum-exp merge).
+Inputs are resident in HBM before the timed region.  The KV pools are replicated and the steps rotate over the
+replicas so that the 256 MB memory-side cache cannot serve the reads of the next step.
+
+Prints ONE JSON line: metric/value (tokens/s = requests decoded per second, one token each), ms_per_step, the roofline
+of the dominant kernel (algorithmic KV bytes per launch / its average duration from HIP events recorded by the
+library around that kernel) and the fp64 CPU oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="thinker", choices=["thinker", "talker", "long", "mixed"])
+    ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--replicas", type=int, default=0, help="KV pool replicas to rotate over (0 = enough for >= 1 GiB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector-ALU, 2 MFMA")
+    ap.add_argument("--target-wgs", type=int, default=0)
+    ap.add_argument("--min-partition", type=int, default=0)
+    ap.add_argument("--force-partition", type=int, default=0)
+    ap.add_argument("--verbose", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); nothing here shards across devices.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2602_02204_amd import binding as omni
+    from paper_2602_02204_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    log = (lambda *a: print(*a, file=sys.stderr, flush=True)) if args.verbose else (lambda *a: None)
+
+    wl = W.make(args.workload, seed=args.seed, append=True)
+    kv_bytes = wl.kv_bytes
+    log(f"workload {wl.name}: B={wl.B} Hq={wl.Hq} Hkv={wl.Hkv} D={wl.D} ps={wl.ps} T={wl.total_tokens} "
+        f"KV bytes/call={kv_bytes / 1e6:.1f} MB pool pages={wl.P}")
+
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import to_dev
+
+    kvd = omni.OMNI_BF16 if wl.dtype == W.BF16 else omni.OMNI_F32
+    h = omni.Handle(batch=wl.B, num_q_heads=wl.Hq, num_kv_heads=wl.Hkv, head_dim=wl.D, page_size=wl.ps,
+                    num_pages=wl.P, max_blocks_per_seq=wl.MB, kv_dtype=kvd, out_dtype=omni.OMNI_F32)
+    if args.kernel:
+        h.omni_set_tuning(omni.OMNI_TUNE_KERNEL, args.kernel)
+    if args.target_wgs:
+        h.omni_set_tuning(omni.OMNI_TUNE_TARGET_WORKGROUPS, args.target_wgs)
+    if args.min_partition:
+        h.omni_set_tuning(omni.OMNI_TUNE_MIN_PARTITION, args.min_partition)
+    if args.force_partition:
+        h.omni_set_tuning(omni.OMNI_TUNE_FORCE_PARTITION, args.force_partition)
+    ws = h.alloc_workspace()
+
+    pool_bytes = 2 * wl.k_cache.nbytes
+    R = args.replicas or max(2, int(np.ceil((1 << 30) / max(kv_bytes, 1))))
+    R = min(R, max(1, int(150e9 // pool_bytes)))
+    q = to_dev(wl.q, wl.dtype)
+    k0, v0 = to_dev(wl.k_cache, wl.dtype), to_dev(wl.v_cache, wl.dtype)
+    kc = [k0] + [k0.clone() for _ in range(R - 1)]
+    vc = [v0] + [v0.clone() for _ in range(R - 1)]
+    bt = torch.from_numpy(wl.block_table).cuda()
+    lens = torch.from_numpy(wl.context_lens).cuda()
+    k_new, v_new = to_dev(wl.k_new, wl.dtype), to_dev(wl.v_new, wl.dtype)
+    pos = torch.from_numpy(wl.positions).cuda()
+    out = torch.empty((wl.B, wl.Hq, wl.D), dtype=torch.float32, device="cuda")
+    scale = float(wl.scale)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        r = i % R
+        h.omni_kv_append(k_new, v_new, kc[r], vc[r], bt, pos, stream)
+        h.omni_paged_decode_attn(q, kc[r], vc[r], bt, lens, scale, out, stream)
+
+    for r in range(R):                       # every replica holds the appended token before anything is timed
+        h.omni_kv_append(k_new, v_new, kc[r], vc[r], bt, pos, stream)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    plan = h.omni_debug_last_plan()
+    plan.update(h.omni_get_plan())
+
+    # ---- timed region: exactly K steps; the library records an event pair around the partition kernel of each step
+    K = args.steps
+    h.omni_debug_profile_begin(K)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms = h.omni_debug_profile_end()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    tokens_per_s = wl.B / (ms_per_step * 1e-3)
+    k_avg_ms = float(np.mean(kernel_ms))
+    k_med_ms = float(np.median(kernel_ms))
+    achieved = kv_bytes / (k_avg_ms * 1e-3) / 1e9
+
+    # ---- same K steps without the event pairs and on a single replica (cache-warm), for the record
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for i in range(K):
+        step(i)
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    ms_noevents = (t3 - t2) * 1e3 / K
+    t4 = time.perf_counter()
+    for i in range(K):
+        step(0)
+    torch.cuda.synchronize()
+    t5 = time.perf_counter()
+    ms_warm = (t5 - t4) * 1e3 / K
+
+    # ---- validity: sampled rows of the last step against the oracle (the appended token is in the pools now)
+    import oracle
+    oracle.kv_append(wl.k_new, wl.v_new, wl.k_cache, wl.v_cache, wl.block_table, wl.positions, wl.dtype)
+    rng = np.random.default_rng(0)
+    pairs = [(int(b), int(hh)) for b, hh in zip(rng.integers(0, wl.B, 4), rng.integers(0, wl.Hq, 4))]
+    ref = oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, wl.scale, wl.dtype,
+                                   pairs=pairs)
+    got = out.cpu().numpy().astype(np.float64)
+    max_err = float(max(np.max(np.abs(got[b, hh] - ref[i])) for i, (b, hh) in enumerate(pairs)))
+    tol = 2e-3 if wl.dtype == W.BF16 else 1e-5
+    if not (max_err <= tol):
+        print(f"bench.py: parity check failed, max|err|={max_err:.3e} > {tol}", file=sys.stderr)
+        sys.exit(1)
+
+    # ---- CPU baseline: the oracle as it stands, all host threads, whole batch, one warm-up slice then timed passes
+    cpu = None
+    if not args.no_cpu_baseline:
+        oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, wl.scale, wl.dtype,
+                                 pairs=[(0, 0)])
+        reps, spent, used = 0, 0.0, 1
+        while reps < 1 or (spent < 4.0 and reps < 5):
+            c0 = time.perf_counter()
+            _, used = oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens,
+                                               wl.scale, wl.dtype, return_threads=True)
+            spent += time.perf_counter() - c0
+            reps += 1
+        cpu_s = spent / reps
+        cpu = {"value": wl.B / cpu_s, "unit": "tokens/s", "cores": int(used), "kind": "oracle",
+               "sample": f"whole {wl.name} batch ({wl.B} requests, {wl.total_tokens} context tokens), "
+                         f"{reps} pass(es) of {cpu_s:.2f} s, fp64, OpenMP over (request, head)",
+               "kv_gbs": kv_bytes / cpu_s / 1e9}
+
+    result = {
+        "metric": "decode-attention tokens/s (one token per request per step; kv_append + paged decode attention)",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if wl.dtype == W.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={wl.B}, context U[512,4096], Hq={wl.Hq}, Hkv={wl.Hkv}, D={wl.D}, "
+                               f"page={wl.ps}, bf16 KV/Q, fp32 accumulate and output" if wl.name == "thinker" else
+                               f"{wl.name}: B={wl.B}, Hq={wl.Hq}, Hkv={wl.Hkv}, D={wl.D}, page={wl.ps}",
+                   "seed": wl.seed, "total_context_tokens": wl.total_tokens, "kv_bytes_per_step": kv_bytes,
+                   "pool_replicas": R, "plan": plan},
+        "kv_gbs_per_step": kv_bytes / (ms_per_step * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "decode_mfma_kernel" if plan["kernel"] == 2 else "decode_valu_kernel",
+                     "kernel_avg_us": k_avg_ms * 1e3, "kernel_median_us": k_med_ms * 1e3,
+                     "algorithmic_bytes_per_launch": kv_bytes},
+        "cpu_baseline": cpu,
+        "extra": {"ms_per_step_without_event_pairs": ms_noevents, "ms_per_step_single_replica_cache_warm": ms_warm,
+                  "parity_max_abs_err_sampled": max_err},
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,159 @@
+/*
+ * omni_attn.h - C ABI of the MI355X (gfx950) batched decode-attention library.
+ *
+ * The operation is the attention inside the "one batched forward step for each
+ * iteration" that the paper's model runner executes for an autoregressive stage
+ * (Section 3.1 "Overview"; Section 3.3 "AR stage support": each engine has its
+ * own scheduler, KV manager and model runner), over the paged KV cache the
+ * engine inherits (Section 5, "LLM serving systems": paged attention, KV cache
+ * management).  It is the same call for a Thinker-like text stage and a
+ * Talker-like speech-token stage (Section 2.1).  One call = one attention
+ * layer's decode step for the whole batch: every request contributes exactly
+ * one query token, which attends to all context_lens[b] tokens of its request.
+ *
+ * Conventions for every entry point
+ *   - Plain C, no exceptions, no errno.  Every function returns omni_status_t
+ *     (except omni_status_string / omni_destroy).
+ *   - All tensor arguments are DEVICE pointers unless the name says "host".
+ *     The caller owns every tensor and the workspace.  The library allocates no
+ *     device memory, frees none, and never synchronises the stream: calls are
+ *     asynchronous with respect to the host (the omni_debug_* calls excepted).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *   - Only host-checkable conditions are reported (null pointers, shapes,
+ *     dtypes, workspace size, launch errors).  Page ids or lengths stored in
+ *     device arrays that point outside the pool are undefined behaviour.
+ *   - A handle is not thread-safe; distinct handles are independent.
+ *
+ * Layouts (row-major, contiguous)
+ *   q, out              [batch, num_q_heads, head_dim]
+ *   k_new, v_new        [batch, num_kv_heads, head_dim]
+ *   k_cache, v_cache    [num_pages, num_kv_heads, page_size, head_dim]   (two separate pools)
+ *   block_table         [batch, max_blocks_per_seq] int32; entry j of row b is the physical page of
+ *                       tokens [j*page_size, (j+1)*page_size) of request b; entries at or beyond
+ *                       ceil(context_lens[b] / page_size) are never read
+ *   context_lens        [batch] int32; tokens the query attends to, INCLUDING a token appended in
+ *                       this step; 0 is legal and yields an all-zero output row
+ *   positions           [batch] int32; token index at which omni_kv_append writes; < 0 skips the request
+ * Query head h reads KV head h / (num_q_heads / num_kv_heads).  No mask, bias, window or soft-cap.
+ */
+#ifndef OMNI_ATTN_H
+#define OMNI_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    OMNI_OK = 0,
+    OMNI_ERR_NULL = 1,          /* a required pointer is NULL */
+    OMNI_ERR_SHAPE = 2,         /* a size is non-positive, or num_q_heads is not a multiple of num_kv_heads */
+    OMNI_ERR_DTYPE = 3,         /* unknown dtype code or unsupported q/kv/out combination */
+    OMNI_ERR_UNSUPPORTED = 4,   /* head_dim, page_size or group size outside what the kernels cover */
+    OMNI_ERR_WORKSPACE = 5,     /* workspace missing, misaligned or smaller than omni_workspace_bytes */
+    OMNI_ERR_HIP = 6            /* the HIP runtime reported an error at launch */
+} omni_status_t;
+
+typedef enum { OMNI_F32 = 0, OMNI_BF16 = 1 } omni_dtype_t;
+
+/* Problem description, fixed for the lifetime of a handle.  Set struct_size = sizeof(omni_attn_desc_t). */
+typedef struct {
+    uint32_t struct_size;
+    int32_t  batch;                 /* B  >= 1 */
+    int32_t  num_q_heads;           /* Hq, multiple of num_kv_heads; group size Hq/Hkv <= 16 */
+    int32_t  num_kv_heads;          /* Hkv */
+    int32_t  head_dim;              /* 64 or 128 */
+    int32_t  page_size;             /* 16 or 32 tokens */
+    int32_t  num_pages;             /* P, pages in each pool */
+    int32_t  max_blocks_per_seq;    /* row length of block_table */
+    int32_t  q_dtype;               /* omni_dtype_t; must equal kv_dtype */
+    int32_t  kv_dtype;              /* omni_dtype_t */
+    int32_t  out_dtype;             /* omni_dtype_t; OMNI_BF16 only with bf16 q/kv */
+    int32_t  max_context_hint;      /* upper bound on any context_lens[b] if the caller knows one; <= 0: max_blocks_per_seq*page_size */
+} omni_attn_desc_t;
+
+typedef struct omni_handle_s *omni_handle_t;
+
+/* Tuning keys for omni_set_tuning.  Defaults are chosen for 256 compute units. */
+typedef enum {
+    OMNI_TUNE_KERNEL = 0,           /* 0 = auto, 1 = vector-ALU kernel, 2 = matrix-core (MFMA) kernel (bf16, head_dim 128 only) */
+    OMNI_TUNE_TARGET_WORKGROUPS = 1,/* how many workgroups the split-context plan aims to fill (> 0) */
+    OMNI_TUNE_MIN_PARTITION = 2,    /* smallest partition length in tokens the plan may choose (multiple of 32) */
+    OMNI_TUNE_FORCE_PARTITION = 3   /* > 0: use exactly this partition length (multiple of 32); 0 = let the plan decide */
+} omni_tune_key_t;
+
+/* Validate `desc` and create a handle holding host-side plan state only (no device memory).
+ * Errors: NULL, SHAPE, DTYPE, UNSUPPORTED.  On error *out_handle is set to NULL. */
+omni_status_t omni_create(const omni_attn_desc_t *desc, omni_handle_t *out_handle);
+
+/* Release the host-side state.  NULL is ignored.  The workspace stays the caller's. */
+void omni_destroy(omni_handle_t h);
+
+/* Change a tuning value.  May change omni_workspace_bytes: query it again afterwards.  Errors: NULL, SHAPE (bad value). */
+omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value);
+
+/* Bytes of device workspace omni_paged_decode_attn needs for this handle (split-context partials and plan words). */
+omni_status_t omni_workspace_bytes(omni_handle_t h, size_t *bytes);
+
+/* Hand the library a caller-owned device buffer of at least omni_workspace_bytes, 256-byte aligned.
+ * The library keeps the pointer only; contents need no initialisation.  Errors: NULL, WORKSPACE. */
+omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes);
+
+/*
+ * out[b, h, :] = sum_t softmax_t(scale * q[b, h, :] . K_t) V_t over the context_lens[b] tokens of request b,
+ * K_t / V_t being row (t % page_size) of page block_table[b][t / page_size], KV head h / (Hq/Hkv).
+ * Accumulation is fp32.  The context is cut into partitions on the device (split-context / flash-decoding with an
+ * online softmax per partition) and the partitions are combined by a log-sum-exp merge; both are exact
+ * re-associations of the definition above.  Writes `out` and the workspace, nothing else.
+ * For a fixed handle and tuning the result is bit-identical from run to run and under any physical page permutation.
+ * Errors: NULL, WORKSPACE, HIP.
+ */
+omni_status_t omni_paged_decode_attn(omni_handle_t h,
+                                     const void *q, const void *k_cache, const void *v_cache,
+                                     const int32_t *block_table, const int32_t *context_lens,
+                                     float scale, void *out, void *stream);
+
+/*
+ * Autoregressive decoding adds one token per request per iteration (Section 2.2, the AR decoding loop): copy, bit for
+ * bit, k_new[b, g, :] and v_new[b, g, :] into row (positions[b] % page_size) of page
+ * block_table[b][positions[b] / page_size], KV head g, of k_cache / v_cache.  Requests with positions[b] < 0 are
+ * skipped.  Writes only the addressed rows.  Errors: NULL, HIP.
+ */
+omni_status_t omni_kv_append(omni_handle_t h,
+                             const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                             const int32_t *block_table, const int32_t *positions, void *stream);
+
+/* Host-known part of the launch plan: which kernel (OMNI_TUNE_KERNEL value actually used), the data-independent
+ * grid (workgroups) of the partition kernel and of the merge kernel, the largest number of (request, partition)
+ * pairs the workspace is sized for, and threads per workgroup.  The partition length itself is chosen on the
+ * device from context_lens; omni_debug_last_plan reads it back. */
+omni_status_t omni_get_plan(omni_handle_t h, int32_t *kernel, int32_t *partition_grid, int32_t *merge_grid,
+                            int32_t *max_request_parts, int32_t *threads_per_workgroup);
+
+const char *omni_status_string(omni_status_t s);
+
+/* ---- test / debugging aids: these synchronise the stream and copy to HOST memory ---- */
+
+/* After an omni_paged_decode_attn call on `stream`: host_out[0] = partition length (tokens) the device chose,
+ * host_out[1] = number of (request, partition) pairs, host_out[2] = total context tokens, host_out[3] = reserved. */
+omni_status_t omni_debug_last_plan(omni_handle_t h, int32_t host_out[4], void *stream);
+
+/* Dense copy of one request's rows of `cache` (k_cache or v_cache), in token order, into DEVICE buffer
+ * dense_out [context_lens[request], num_kv_heads, head_dim] (a bit copy).  Launches on `stream`, no sync. */
+omni_status_t omni_debug_gather(omni_handle_t h, const void *cache, const int32_t *block_table,
+                                const int32_t *context_lens, int32_t request, void *dense_out, void *stream);
+
+/* Profiling aid for the benchmark.  After omni_debug_profile_begin(h, capacity) every omni_paged_decode_attn call
+ * records a HIP event pair around its partition kernel (the kernel that reads the KV cache) on the caller's stream,
+ * up to `capacity` calls; later calls are not recorded.  omni_debug_profile_end synchronises the recorded events,
+ * writes the elapsed milliseconds of each recorded launch to host_ms[0 .. *count) (host_ms must hold `capacity`
+ * floats), destroys the events and switches recording off.  Errors: NULL, SHAPE (capacity <= 0), HIP. */
+omni_status_t omni_debug_profile_begin(omni_handle_t h, int32_t capacity);
+omni_status_t omni_debug_profile_end(omni_handle_t h, float *host_ms, int32_t *count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OMNI_ATTN_H */

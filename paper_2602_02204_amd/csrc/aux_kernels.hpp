@@ -1,0 +1,90 @@
+// Log-sum-exp merge of split-context partitions, KV append, and the debug gather.
+#pragma once
+#include "common.hpp"
+
+namespace omni {
+
+// One workgroup per (request, KV head).  Requests with a single partition were finalised by the partition kernel.
+// out = sum_j 2^(m_j - M) o_j / sum_j 2^(m_j - M) l_j with M = max_j m_j; partitions with l_j = 0 carry weight 0.
+template <int D>
+__global__ __launch_bounds__(kThreads) void merge_kernel(AttnParams p) {
+    const int b = blockIdx.x / p.Hkv, kvh = blockIdx.x - b * p.Hkv;
+    if (p.context_lens[b] <= 0) return;                 // the partition kernel wrote the zero row
+    const int2 info = p.ws.req_info[b];
+    const int start = info.x, n = info.y;
+    if (n <= 1) return;
+    const int G = p.G;
+    const int head0 = kvh * G;
+    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+        const int g = idx / D;
+        float M = -INFINITY;
+        for (int jx = 0; jx < n; ++jx) {
+            const float2 ml = p.ws.part_ml[(size_t)(start + jx) * p.Hq + head0 + g];
+            if (ml.y > 0.f) M = fmaxf(M, ml.x);
+        }
+        float num = 0.f, den = 0.f;
+        for (int jx = 0; jx < n; ++jx) {
+            const size_t pi = (size_t)(start + jx) * p.Hq + head0;
+            const float2 ml = p.ws.part_ml[pi + g];
+            if (ml.y > 0.f) {
+                const float w = fast_exp2(ml.x - M);
+                num += w * p.ws.part_o[pi * D + idx];
+                den += w * ml.y;
+            }
+        }
+        const float res = den > 0.f ? num / den : 0.f;
+        const size_t oi = ((size_t)b * p.Hq + head0) * D + idx;
+        if (p.out_bf16) reinterpret_cast<uint16_t *>(p.out)[oi] = float_to_bf16_rne(res);
+        else reinterpret_cast<float *>(p.out)[oi] = res;
+    }
+}
+
+struct AppendParams {
+    const void *k_new, *v_new;
+    void *k_cache, *v_cache;
+    const int32_t *block_table, *positions;
+    int B, Hkv, MB, log2_ps;
+    int row_vecs;                    // 16-byte vectors per row (D * elem_size / 16)
+};
+
+// One thread per 16 bytes of one (request, KV head) row; K and V rows are copied bit for bit.
+__global__ __launch_bounds__(kThreads) void kv_append_kernel(AppendParams p) {
+    const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+    const long long total = (long long)p.B * p.Hkv * p.row_vecs;
+    if (idx >= total) return;
+    const int c = (int)(idx % p.row_vecs);
+    const long long row = idx / p.row_vecs;
+    const int g = (int)(row % p.Hkv), b = (int)(row / p.Hkv);
+    const int pos = p.positions[b];
+    if (pos < 0) return;
+    const int page = p.block_table[(size_t)b * p.MB + (pos >> p.log2_ps)];
+    const int slot = pos & ((1 << p.log2_ps) - 1);
+    const size_t dst = ((((size_t)page * p.Hkv + g) << p.log2_ps) + slot) * p.row_vecs + c;
+    const size_t src = (size_t)row * p.row_vecs + c;
+    reinterpret_cast<uint4 *>(p.k_cache)[dst] = reinterpret_cast<const uint4 *>(p.k_new)[src];
+    reinterpret_cast<uint4 *>(p.v_cache)[dst] = reinterpret_cast<const uint4 *>(p.v_new)[src];
+}
+
+struct GatherParams {
+    const void *cache;
+    const int32_t *block_table, *context_lens;
+    void *dense_out;
+    int request, Hkv, MB, log2_ps, row_vecs;
+};
+
+// dense_out[t, g, :] = cache row of token t of the request, KV head g.
+__global__ __launch_bounds__(kThreads) void gather_kernel(GatherParams p) {
+    const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+    const int L = p.context_lens[p.request];
+    const long long total = (long long)L * p.Hkv * p.row_vecs;
+    if (idx >= total) return;
+    const int c = (int)(idx % p.row_vecs);
+    const long long row = idx / p.row_vecs;
+    const int g = (int)(row % p.Hkv), t = (int)(row / p.Hkv);
+    const int page = p.block_table[(size_t)p.request * p.MB + (t >> p.log2_ps)];
+    const int slot = t & ((1 << p.log2_ps) - 1);
+    const size_t src = ((((size_t)page * p.Hkv + g) << p.log2_ps) + slot) * p.row_vecs + c;
+    reinterpret_cast<uint4 *>(p.dense_out)[idx] = reinterpret_cast<const uint4 *>(p.cache)[src];
+}
+
+}  // namespace omni

@@ -1,0 +1,310 @@
+// C ABI of the decode-attention library: argument validation, host-side plan state, kernel dispatch.
+// See include/omni_attn.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "omni_attn.h"
+#include "aux_kernels.hpp"
+#include "decode_mfma.hpp"
+#include "decode_valu.hpp"
+
+using namespace omni;
+
+namespace {
+
+constexpr int kDefaultTargetWorkgroups = 1024;
+constexpr int kDefaultMinPartition = 256;
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
+
+}  // namespace
+
+struct omni_handle_s {
+    omni_attn_desc_t d;
+    int tune_kernel = 0;
+    int tune_target_wgs = kDefaultTargetWorkgroups;
+    int tune_min_partition = kDefaultMinPartition;
+    int tune_force_partition = 0;
+    // derived
+    int kernel = 1;              // 1 = vector ALU, 2 = MFMA
+    int G = 1;
+    int max_ctx = 0;
+    int r_target = 0;
+    int r_cap = 0;               // bound on (request, partition) pairs
+    size_t off_req = 0, off_ml = 0, off_o = 0, ws_bytes = 0;
+    void *ws = nullptr;
+    size_t ws_given = 0;
+    // profiling aid: event pairs around the partition kernel
+    std::vector<hipEvent_t> prof_events;
+    int prof_used = 0;
+
+    void derive() {
+        G = d.num_q_heads / d.num_kv_heads;
+        const long long cap_ctx = (long long)d.max_blocks_per_seq * d.page_size;
+        max_ctx = (d.max_context_hint > 0 && d.max_context_hint < cap_ctx) ? d.max_context_hint : (int)(cap_ctx > 0x3fffffe0 ? 0x3fffffe0 : cap_ctx);
+        const bool mfma_ok = d.kv_dtype == OMNI_BF16 && d.head_dim == 128;
+        kernel = (tune_kernel == 2 && mfma_ok) ? 2 : (tune_kernel == 1 ? 1 : (mfma_ok ? 2 : 1));
+        r_target = (tune_target_wgs + d.num_kv_heads - 1) / d.num_kv_heads;
+        long long cap;
+        if (tune_force_partition > 0) {
+            cap = (long long)d.batch * ((max_ctx + tune_force_partition - 1) / tune_force_partition);
+            if (cap < d.batch) cap = d.batch;
+        } else {
+            cap = r_target > d.batch ? r_target : d.batch;
+        }
+        if (cap > 0x7fffffff / (d.num_kv_heads > 0 ? d.num_kv_heads : 1)) cap = 0x7fffffff / d.num_kv_heads;
+        r_cap = (int)cap;
+        off_req = 256;
+        off_ml = align256(off_req + (size_t)d.batch * sizeof(int2));
+        off_o = align256(off_ml + (size_t)r_cap * d.num_q_heads * sizeof(float2));
+        ws_bytes = align256(off_o + (size_t)r_cap * d.num_q_heads * d.head_dim * sizeof(float));
+    }
+};
+
+extern "C" {
+
+const char *omni_status_string(omni_status_t s) {
+    switch (s) {
+        case OMNI_OK: return "ok";
+        case OMNI_ERR_NULL: return "null pointer";
+        case OMNI_ERR_SHAPE: return "bad shape";
+        case OMNI_ERR_DTYPE: return "bad dtype";
+        case OMNI_ERR_UNSUPPORTED: return "unsupported configuration";
+        case OMNI_ERR_WORKSPACE: return "workspace missing or too small";
+        case OMNI_ERR_HIP: return "HIP error";
+    }
+    return "unknown status";
+}
+
+omni_status_t omni_create(const omni_attn_desc_t *desc, omni_handle_t *out_handle) {
+    if (out_handle) *out_handle = nullptr;
+    if (!desc || !out_handle) return OMNI_ERR_NULL;
+    if (desc->struct_size != sizeof(omni_attn_desc_t)) return OMNI_ERR_SHAPE;
+    if (desc->batch <= 0 || desc->num_q_heads <= 0 || desc->num_kv_heads <= 0 || desc->num_pages <= 0 ||
+        desc->max_blocks_per_seq <= 0 || desc->head_dim <= 0 || desc->page_size <= 0)
+        return OMNI_ERR_SHAPE;
+    if (desc->num_q_heads % desc->num_kv_heads != 0) return OMNI_ERR_SHAPE;
+    auto known = [](int t) { return t == OMNI_F32 || t == OMNI_BF16; };
+    if (!known(desc->q_dtype) || !known(desc->kv_dtype) || !known(desc->out_dtype)) return OMNI_ERR_DTYPE;
+    if (desc->q_dtype != desc->kv_dtype) return OMNI_ERR_DTYPE;
+    if (desc->out_dtype == OMNI_BF16 && desc->kv_dtype != OMNI_BF16) return OMNI_ERR_DTYPE;
+    if (desc->head_dim != 64 && desc->head_dim != 128) return OMNI_ERR_UNSUPPORTED;
+    if (desc->page_size != 16 && desc->page_size != 32) return OMNI_ERR_UNSUPPORTED;
+    if (desc->num_q_heads / desc->num_kv_heads > kMaxGroup) return OMNI_ERR_UNSUPPORTED;
+    omni_handle_s *h = new (std::nothrow) omni_handle_s();
+    if (!h) return OMNI_ERR_HIP;
+    h->d = *desc;
+    h->derive();
+    *out_handle = h;
+    return OMNI_OK;
+}
+
+void omni_destroy(omni_handle_t h) {
+    if (!h) return;
+    for (hipEvent_t e : h->prof_events) (void)hipEventDestroy(e);
+    delete h;
+}
+
+omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value) {
+    if (!h) return OMNI_ERR_NULL;
+    switch (key) {
+        case OMNI_TUNE_KERNEL:
+            if (value < 0 || value > 2) return OMNI_ERR_SHAPE;
+            if (value == 2 && !(h->d.kv_dtype == OMNI_BF16 && h->d.head_dim == 128)) return OMNI_ERR_UNSUPPORTED;
+            h->tune_kernel = value; break;
+        case OMNI_TUNE_TARGET_WORKGROUPS:
+            if (value <= 0) return OMNI_ERR_SHAPE;
+            h->tune_target_wgs = value; break;
+        case OMNI_TUNE_MIN_PARTITION:
+            if (value < kTile || value % kTile) return OMNI_ERR_SHAPE;
+            h->tune_min_partition = value; break;
+        case OMNI_TUNE_FORCE_PARTITION:
+            if (value < 0 || value % kTile) return OMNI_ERR_SHAPE;
+            h->tune_force_partition = value; break;
+        default: return OMNI_ERR_SHAPE;
+    }
+    h->derive();
+    return OMNI_OK;
+}
+
+omni_status_t omni_workspace_bytes(omni_handle_t h, size_t *bytes) {
+    if (!h || !bytes) return OMNI_ERR_NULL;
+    *bytes = h->ws_bytes;
+    return OMNI_OK;
+}
+
+omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes) {
+    if (!h || !dev_ptr) return OMNI_ERR_NULL;
+    if (((uintptr_t)dev_ptr & 255) != 0 || bytes < h->ws_bytes) return OMNI_ERR_WORKSPACE;
+    h->ws = dev_ptr;
+    h->ws_given = bytes;
+    return OMNI_OK;
+}
+
+omni_status_t omni_get_plan(omni_handle_t h, int32_t *kernel, int32_t *partition_grid, int32_t *merge_grid,
+                            int32_t *max_request_parts, int32_t *threads_per_workgroup) {
+    if (!h) return OMNI_ERR_NULL;
+    if (kernel) *kernel = h->kernel;
+    if (partition_grid) *partition_grid = h->r_cap * h->d.num_kv_heads;
+    if (merge_grid) *merge_grid = h->d.batch * h->d.num_kv_heads;
+    if (max_request_parts) *max_request_parts = h->r_cap;
+    if (threads_per_workgroup) *threads_per_workgroup = kThreads;
+    return OMNI_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+template <typename T, int D>
+void launch_valu(const AttnParams &p, dim3 grid, hipStream_t s) {
+    if (p.G <= 1) decode_valu_kernel<T, D, 1><<<grid, kThreads, 0, s>>>(p);
+    else if (p.G <= 2) decode_valu_kernel<T, D, 2><<<grid, kThreads, 0, s>>>(p);
+    else if (p.G <= 4) decode_valu_kernel<T, D, 4><<<grid, kThreads, 0, s>>>(p);
+    else if (p.G <= 8) decode_valu_kernel<T, D, 8><<<grid, kThreads, 0, s>>>(p);
+    else decode_valu_kernel<T, D, 16><<<grid, kThreads, 0, s>>>(p);
+}
+
+}  // namespace
+
+extern "C" {
+
+omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
+                                     const int32_t *block_table, const int32_t *context_lens, float scale, void *out,
+                                     void *stream) {
+    if (!h || !q || !k_cache || !v_cache || !block_table || !context_lens || !out) return OMNI_ERR_NULL;
+    if (!h->ws || h->ws_given < h->ws_bytes) return OMNI_ERR_WORKSPACE;
+    const omni_attn_desc_t &d = h->d;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    AttnParams p;
+    p.q = q; p.k_cache = k_cache; p.v_cache = v_cache;
+    p.block_table = block_table; p.context_lens = context_lens; p.out = out;
+    char *ws = reinterpret_cast<char *>(h->ws);
+    p.ws.plan_words = reinterpret_cast<int32_t *>(ws);
+    p.ws.req_info = reinterpret_cast<int2 *>(ws + h->off_req);
+    p.ws.part_ml = reinterpret_cast<float2 *>(ws + h->off_ml);
+    p.ws.part_o = reinterpret_cast<float *>(ws + h->off_o);
+    p.plan.B = d.batch;
+    p.plan.r_target = h->r_target;
+    p.plan.pl_min = h->tune_min_partition;
+    p.plan.pl_force = h->tune_force_partition;
+    p.scale_log2 = scale * kLog2e;
+    p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
+    p.log2_ps = ilog2(d.page_size);
+    p.out_bf16 = d.out_dtype == OMNI_BF16;
+
+    const dim3 grid((unsigned)(h->r_cap * d.num_kv_heads));
+    (void)hipGetLastError();
+    const bool prof = (size_t)(2 * h->prof_used + 1) < h->prof_events.size();
+    if (prof && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
+    if (h->kernel == 2) {
+        if (d.page_size == 16) decode_mfma_kernel<16><<<grid, kThreads, 0, s>>>(p);
+        else decode_mfma_kernel<32><<<grid, kThreads, 0, s>>>(p);
+    } else if (d.kv_dtype == OMNI_BF16) {
+        if (d.head_dim == 128) launch_valu<uint16_t, 128>(p, grid, s);
+        else launch_valu<uint16_t, 64>(p, grid, s);
+    } else {
+        if (d.head_dim == 128) launch_valu<float, 128>(p, grid, s);
+        else launch_valu<float, 64>(p, grid, s);
+    }
+    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+    if (prof) {
+        if (hipEventRecord(h->prof_events[2 * h->prof_used + 1], s) != hipSuccess) return OMNI_ERR_HIP;
+        ++h->prof_used;
+    }
+
+    // Whether any request was split is known only on the device: the merge always runs; its workgroups return at
+    // once for requests with a single partition.
+    const dim3 mgrid((unsigned)(d.batch * d.num_kv_heads));
+    if (d.head_dim == 128) merge_kernel<128><<<mgrid, kThreads, 0, s>>>(p);
+    else merge_kernel<64><<<mgrid, kThreads, 0, s>>>(p);
+    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+    return OMNI_OK;
+}
+
+omni_status_t omni_kv_append(omni_handle_t h, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                             const int32_t *block_table, const int32_t *positions, void *stream) {
+    if (!h || !k_new || !v_new || !k_cache || !v_cache || !block_table || !positions) return OMNI_ERR_NULL;
+    const omni_attn_desc_t &d = h->d;
+    AppendParams p;
+    p.k_new = k_new; p.v_new = v_new; p.k_cache = k_cache; p.v_cache = v_cache;
+    p.block_table = block_table; p.positions = positions;
+    p.B = d.batch; p.Hkv = d.num_kv_heads; p.MB = d.max_blocks_per_seq; p.log2_ps = ilog2(d.page_size);
+    p.row_vecs = d.head_dim * (d.kv_dtype == OMNI_BF16 ? 2 : 4) / 16;
+    const long long total = (long long)p.B * p.Hkv * p.row_vecs;
+    const dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    (void)hipGetLastError();
+    kv_append_kernel<<<grid, kThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(p);
+    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+    return OMNI_OK;
+}
+
+omni_status_t omni_debug_last_plan(omni_handle_t h, int32_t host_out[4], void *stream) {
+    if (!h || !host_out) return OMNI_ERR_NULL;
+    if (!h->ws) return OMNI_ERR_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (hipStreamSynchronize(s) != hipSuccess) return OMNI_ERR_HIP;
+    int32_t words[4];
+    if (hipMemcpy(words, h->ws, sizeof(words), hipMemcpyDeviceToHost) != hipSuccess) return OMNI_ERR_HIP;
+    host_out[0] = words[0]; host_out[1] = words[1]; host_out[2] = words[2]; host_out[3] = 0;
+    return OMNI_OK;
+}
+
+omni_status_t omni_debug_profile_begin(omni_handle_t h, int32_t capacity) {
+    if (!h) return OMNI_ERR_NULL;
+    if (capacity <= 0) return OMNI_ERR_SHAPE;
+    for (hipEvent_t e : h->prof_events) (void)hipEventDestroy(e);
+    h->prof_events.clear();
+    h->prof_used = 0;
+    for (int i = 0; i < 2 * capacity; ++i) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return OMNI_ERR_HIP;
+        h->prof_events.push_back(e);
+    }
+    return OMNI_OK;
+}
+
+omni_status_t omni_debug_profile_end(omni_handle_t h, float *host_ms, int32_t *count) {
+    if (!h || !host_ms || !count) return OMNI_ERR_NULL;
+    omni_status_t st = OMNI_OK;
+    *count = 0;
+    for (int i = 0; i < h->prof_used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(h->prof_events[2 * i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, h->prof_events[2 * i], h->prof_events[2 * i + 1]) != hipSuccess) {
+            st = OMNI_ERR_HIP;
+            break;
+        }
+        host_ms[(*count)++] = ms;
+    }
+    for (hipEvent_t e : h->prof_events) (void)hipEventDestroy(e);
+    h->prof_events.clear();
+    h->prof_used = 0;
+    return st;
+}
+
+omni_status_t omni_debug_gather(omni_handle_t h, const void *cache, const int32_t *block_table,
+                                const int32_t *context_lens, int32_t request, void *dense_out, void *stream) {
+    if (!h || !cache || !block_table || !context_lens || !dense_out) return OMNI_ERR_NULL;
+    const omni_attn_desc_t &d = h->d;
+    if (request < 0 || request >= d.batch) return OMNI_ERR_SHAPE;
+    GatherParams p;
+    p.cache = cache; p.block_table = block_table; p.context_lens = context_lens; p.dense_out = dense_out;
+    p.request = request; p.Hkv = d.num_kv_heads; p.MB = d.max_blocks_per_seq; p.log2_ps = ilog2(d.page_size);
+    p.row_vecs = d.head_dim * (d.kv_dtype == OMNI_BF16 ? 2 : 4) / 16;
+    const long long total = (long long)h->max_ctx * p.Hkv * p.row_vecs;
+    const dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    (void)hipGetLastError();
+    gather_kernel<<<grid, kThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(p);
+    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+    return OMNI_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,88 @@
+"""C-ABI checks that need no GPU: the library loads, exports every declared symbol, and rejects bad arguments."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2602_02204_amd import binding as omni
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def good(**over):
+    kw = dict(batch=4, num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16, num_pages=64,
+              max_blocks_per_seq=8, kv_dtype=omni.OMNI_BF16)
+    kw.update(over)
+    return kw
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "omni_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(omni_[a-z_]+)\s*\(", text))
+    assert declared == set(omni.EXPORTS)
+    L = omni.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings():
+    assert omni.status_string(0) == "ok"
+    assert len({omni.status_string(i) for i in range(7)}) == 7
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(batch=0), 2), (dict(num_q_heads=7), 2), (dict(num_kv_heads=0), 2), (dict(num_pages=-1), 2),
+    (dict(kv_dtype=5), 3), (dict(q_dtype=omni.OMNI_F32), 3), (dict(kv_dtype=omni.OMNI_F32, out_dtype=omni.OMNI_BF16), 3),
+    (dict(head_dim=96), 4), (dict(page_size=8), 4), (dict(num_q_heads=34, num_kv_heads=2), 4),
+])
+def test_create_rejects(over, status):
+    with pytest.raises(omni.OmniError) as e:
+        omni.Handle(**good(**over))
+    assert e.value.status == status
+
+
+def test_create_null_and_struct_size():
+    L = omni.lib()
+    h = C.c_void_p()
+    assert L.omni_create(None, C.byref(h)) == 1
+    d = omni.omni_attn_desc_t(4, 4, 8, 2, 128, 16, 64, 8, 1, 1, 0, 0)      # wrong struct_size
+    assert L.omni_create(C.byref(d), C.byref(h)) == 2 and not h.value
+
+
+def test_workspace_and_null_argument_errors_without_touching_the_gpu():
+    h = omni.Handle(**good())
+    n = h.omni_workspace_bytes()
+    assert n > 0 and n % 256 == 0
+    L = omni.lib()
+    # no workspace yet
+    assert L.omni_paged_decode_attn(h._h, 256, 256, 256, 256, 256, C.c_float(1.0), 256, None) == 5
+    assert L.omni_set_workspace(h._h, None, n) == 1
+    assert L.omni_set_workspace(h._h, 4096 + 8, n) == 5          # misaligned
+    assert L.omni_set_workspace(h._h, 4096, n - 1) == 5          # too small
+    assert L.omni_paged_decode_attn(h._h, None, 256, 256, 256, 256, C.c_float(1.0), 256, None) == 1
+    assert L.omni_kv_append(h._h, None, 256, 256, 256, 256, 256, None) == 1
+    assert L.omni_kv_append(None, 256, 256, 256, 256, 256, 256, None) == 1
+    assert L.omni_debug_gather(h._h, 256, 256, 256, 99, 256, None) == 2
+
+
+def test_tuning_validation_and_plan():
+    h = omni.Handle(**good())
+    plan = h.omni_get_plan()
+    assert plan["kernel"] == omni.KERNEL_MFMA and plan["threads_per_workgroup"] == 256
+    assert plan["merge_grid"] == 4 * 2 and plan["partition_grid"] == plan["max_request_parts"] * 2
+    h.omni_set_tuning(omni.OMNI_TUNE_KERNEL, omni.KERNEL_VALU)
+    assert h.omni_get_plan()["kernel"] == omni.KERNEL_VALU
+    for key, val in [(omni.OMNI_TUNE_KERNEL, 3), (omni.OMNI_TUNE_TARGET_WORKGROUPS, 0),
+                     (omni.OMNI_TUNE_MIN_PARTITION, 48), (omni.OMNI_TUNE_FORCE_PARTITION, 40), (99, 1)]:
+        with pytest.raises(omni.OmniError):
+            h.omni_set_tuning(key, val)
+    big = omni.Handle(**good(max_blocks_per_seq=4096))
+    before = big.omni_workspace_bytes()
+    big.omni_set_tuning(omni.OMNI_TUNE_FORCE_PARTITION, 32)
+    assert big.omni_workspace_bytes() > before                  # more partitions -> more partial rows
+    f32 = omni.Handle(**good(kv_dtype=omni.OMNI_F32))
+    assert f32.omni_get_plan()["kernel"] == omni.KERNEL_VALU
+    with pytest.raises(omni.OmniError):
+        f32.omni_set_tuning(omni.OMNI_TUNE_KERNEL, omni.KERNEL_MFMA)
