@@ -51,7 +51,7 @@ typedef enum {
     OMNI_ERR_NULL = 1,          /* a required pointer is NULL */
     OMNI_ERR_SHAPE = 2,         /* a size is non-positive, or num_q_heads is not a multiple of num_kv_heads */
     OMNI_ERR_DTYPE = 3,         /* unknown dtype code or unsupported q/kv/out combination */
-    OMNI_ERR_UNSUPPORTED = 4,   /* head_dim, page_size or group size outside what the kernels cover */
+    OMNI_ERR_UNSUPPORTED = 4,   /* head_dim, page_size, group size or batch outside what the kernels cover */
     OMNI_ERR_WORKSPACE = 5,     /* workspace missing, misaligned or smaller than omni_workspace_bytes */
     OMNI_ERR_HIP = 6            /* the HIP runtime reported an error at launch */
 } omni_status_t;
@@ -61,7 +61,7 @@ typedef enum { OMNI_F32 = 0, OMNI_BF16 = 1 } omni_dtype_t;
 /* Problem description, fixed for the lifetime of a handle.  Set struct_size = sizeof(omni_attn_desc_t). */
 typedef struct {
     uint32_t struct_size;
-    int32_t  batch;                 /* B  >= 1 */
+    int32_t  batch;                 /* B, 1 .. 4096 */
     int32_t  num_q_heads;           /* Hq, multiple of num_kv_heads; group size Hq/Hkv <= 16 */
     int32_t  num_kv_heads;          /* Hkv */
     int32_t  head_dim;              /* 64 or 128 */
@@ -79,9 +79,9 @@ typedef struct omni_handle_s *omni_handle_t;
 /* Tuning keys for omni_set_tuning.  Defaults are chosen for 256 compute units. */
 typedef enum {
     OMNI_TUNE_KERNEL = 0,           /* 0 = auto, 1 = vector-ALU kernel, 2 = matrix-core (MFMA) kernel (bf16, head_dim 128 only) */
-    OMNI_TUNE_TARGET_WORKGROUPS = 1,/* how many workgroups the split-context plan aims to fill (> 0) */
-    OMNI_TUNE_MIN_PARTITION = 2,    /* smallest partition length in tokens the plan may choose (multiple of 32) */
-    OMNI_TUNE_FORCE_PARTITION = 3   /* > 0: use exactly this partition length (multiple of 32); 0 = let the plan decide */
+    OMNI_TUNE_TARGET_WORKGROUPS = 1,/* workgroups the attention kernel is launched with (> 0; rounded down to a multiple of Hkv) */
+    OMNI_TUNE_MIN_PARTITION = 2,    /* smallest range of context, in tokens, one workgroup may be given (multiple of 32) */
+    OMNI_TUNE_FORCE_PARTITION = 3   /* > 0: every workgroup range is exactly this many tokens (multiple of 32); 0 = plan decides */
 } omni_tune_key_t;
 
 /* Validate `desc` and create a handle holding host-side plan state only (no device memory).
@@ -91,22 +91,27 @@ omni_status_t omni_create(const omni_attn_desc_t *desc, omni_handle_t *out_handl
 /* Release the host-side state.  NULL is ignored.  The workspace stays the caller's. */
 void omni_destroy(omni_handle_t h);
 
-/* Change a tuning value.  May change omni_workspace_bytes: query it again afterwards.  Errors: NULL, SHAPE (bad value). */
+/* Change a tuning value.  This may change the workspace size and layout, so it forgets the registered workspace:
+ * query omni_workspace_bytes and call omni_set_workspace again afterwards.  Errors: NULL, SHAPE (bad value),
+ * UNSUPPORTED (kernel not available for this description). */
 omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value);
 
 /* Bytes of device workspace omni_paged_decode_attn needs for this handle (split-context partials and plan words). */
 omni_status_t omni_workspace_bytes(omni_handle_t h, size_t *bytes);
 
 /* Hand the library a caller-owned device buffer of at least omni_workspace_bytes, 256-byte aligned.
- * The library keeps the pointer only; contents need no initialisation.  Errors: NULL, WORKSPACE. */
+ * The library keeps the pointer and clears a few KB of counters in it with a synchronous hipMemset (the one place
+ * outside omni_debug_* where the library blocks); every attention call leaves those counters cleared again, so the
+ * buffer must not be shared by calls that run concurrently.  Errors: NULL, WORKSPACE, HIP. */
 omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes);
 
 /*
  * out[b, h, :] = sum_t softmax_t(scale * q[b, h, :] . K_t) V_t over the context_lens[b] tokens of request b,
  * K_t / V_t being row (t % page_size) of page block_table[b][t / page_size], KV head h / (Hq/Hkv).
- * Accumulation is fp32.  The context is cut into partitions on the device (split-context / flash-decoding with an
- * online softmax per partition) and the partitions are combined by a log-sum-exp merge; both are exact
- * re-associations of the definition above.  Writes `out` and the workspace, nothing else.
+ * Accumulation is fp32.  The batch's context, laid end to end in 32-token tiles, is cut on the device into equal
+ * ranges, one per workgroup (split-context / flash-decoding with an online softmax per piece); a request that is cut
+ * by a range boundary is put together again by a log-sum-exp merge.  Both are exact re-associations of the definition
+ * above.  One kernel launch.  Writes `out` and the workspace, nothing else.
  * For a fixed handle and tuning the result is bit-identical from run to run and under any physical page permutation.
  * Errors: NULL, WORKSPACE, HIP.
  */
@@ -126,9 +131,10 @@ omni_status_t omni_kv_append(omni_handle_t h,
                              const int32_t *block_table, const int32_t *positions, void *stream);
 
 /* Host-known part of the launch plan: which kernel (OMNI_TUNE_KERNEL value actually used), the data-independent
- * grid (workgroups) of the partition kernel and of the merge kernel, the largest number of (request, partition)
- * pairs the workspace is sized for, and threads per workgroup.  The partition length itself is chosen on the
- * device from context_lens; omni_debug_last_plan reads it back. */
+ * grid (workgroups) of the attention kernel, the grid of a separate merge kernel (0: the merge runs inside the
+ * attention kernel, in the workgroup that finishes a request's last piece), the number of partial-result slots the
+ * workspace is sized for, and threads per workgroup.  The range length itself is chosen on the device from
+ * context_lens; omni_debug_last_plan reads it back. */
 omni_status_t omni_get_plan(omni_handle_t h, int32_t *kernel, int32_t *partition_grid, int32_t *merge_grid,
                             int32_t *max_request_parts, int32_t *threads_per_workgroup);
 
@@ -136,8 +142,8 @@ const char *omni_status_string(omni_status_t s);
 
 /* ---- test / debugging aids: these synchronise the stream and copy to HOST memory ---- */
 
-/* After an omni_paged_decode_attn call on `stream`: host_out[0] = partition length (tokens) the device chose,
- * host_out[1] = number of (request, partition) pairs, host_out[2] = total context tokens, host_out[3] = reserved. */
+/* After an omni_paged_decode_attn call on `stream`: host_out[0] = range length (tokens) the device chose,
+ * host_out[1] = number of ranges, host_out[2] = total context tokens, host_out[3] = reserved. */
 omni_status_t omni_debug_last_plan(omni_handle_t h, int32_t host_out[4], void *stream);
 
 /* Dense copy of one request's rows of `cache` (k_cache or v_cache), in token order, into DEVICE buffer

@@ -11,7 +11,7 @@ import os
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libomni_attn.so")
+LIB_PATH = os.environ.get("OMNI_ATTN_LIB") or os.path.join(_HERE, "libomni_attn.so")
 
 OMNI_F32, OMNI_BF16 = 0, 1
 OMNI_TUNE_KERNEL, OMNI_TUNE_TARGET_WORKGROUPS, OMNI_TUNE_MIN_PARTITION, OMNI_TUNE_FORCE_PARTITION = 0, 1, 2, 3

@@ -1,43 +1,8 @@
-// Log-sum-exp merge of split-context partitions, KV append, and the debug gather.
+// KV append and the debug gather.
 #pragma once
 #include "common.hpp"
 
 namespace omni {
-
-// One workgroup per (request, KV head).  Requests with a single partition were finalised by the partition kernel.
-// out = sum_j 2^(m_j - M) o_j / sum_j 2^(m_j - M) l_j with M = max_j m_j; partitions with l_j = 0 carry weight 0.
-template <int D>
-__global__ __launch_bounds__(kThreads) void merge_kernel(AttnParams p) {
-    const int b = blockIdx.x / p.Hkv, kvh = blockIdx.x - b * p.Hkv;
-    if (p.context_lens[b] <= 0) return;                 // the partition kernel wrote the zero row
-    const int2 info = p.ws.req_info[b];
-    const int start = info.x, n = info.y;
-    if (n <= 1) return;
-    const int G = p.G;
-    const int head0 = kvh * G;
-    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
-        const int g = idx / D;
-        float M = -INFINITY;
-        for (int jx = 0; jx < n; ++jx) {
-            const float2 ml = p.ws.part_ml[(size_t)(start + jx) * p.Hq + head0 + g];
-            if (ml.y > 0.f) M = fmaxf(M, ml.x);
-        }
-        float num = 0.f, den = 0.f;
-        for (int jx = 0; jx < n; ++jx) {
-            const size_t pi = (size_t)(start + jx) * p.Hq + head0;
-            const float2 ml = p.ws.part_ml[pi + g];
-            if (ml.y > 0.f) {
-                const float w = fast_exp2(ml.x - M);
-                num += w * p.ws.part_o[pi * D + idx];
-                den += w * ml.y;
-            }
-        }
-        const float res = den > 0.f ? num / den : 0.f;
-        const size_t oi = ((size_t)b * p.Hq + head0) * D + idx;
-        if (p.out_bf16) reinterpret_cast<uint16_t *>(p.out)[oi] = float_to_bf16_rne(res);
-        else reinterpret_cast<float *>(p.out)[oi] = res;
-    }
-}
 
 struct AppendParams {
     const void *k_new, *v_new;

@@ -12,12 +12,12 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 // Workspace layout (bytes from the workspace base, all 256-byte aligned):
 //   [0, 256)                 plan words written by item 0: PL, R, T(lo), T(hi)
-//   [256, 256 + 8*B)         per request: first item index, number of partitions (int2)
+//   [256, 256 + 4*B*Hkv)     per (request, KV head): arrival counter of its partitions; zero between calls
 //   ml_off                   per (item, query head): running max (log2 domain) and sum, float2
 //   o_off                    per (item, query head): unnormalised output row, D floats
 struct Workspace {
     int32_t *plan_words;
-    int2 *req_info;
+    int32_t *arrivals;
     float2 *part_ml;
     float *part_o;
 };
@@ -35,7 +35,21 @@ struct AttnParams {
     int Hq, Hkv, G, MB;
     int log2_ps;
     int out_bf16;
+#ifdef OMNI_TRACE
+    long long *trace;                   // development builds only: per-wave phase timestamps
+#endif
 };
+
+// Phase timestamps for development builds (compiled out otherwise): slot `id` of this wave's record.
+#ifdef OMNI_TRACE
+#define OMNI_STAMP(p, id)                                                                              \
+    do {                                                                                               \
+        if ((p).trace && (threadIdx.x & 63) == 0)                                                      \
+            (p).trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + (id)] = wall_clock64(); \
+    } while (0)
+#else
+#define OMNI_STAMP(p, id) do { } while (0)
+#endif
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
@@ -55,17 +69,89 @@ struct CombineSmem {
     float o[kWaves][kMaxGroup][D + 4];
     float m[kWaves][kMaxGroup];
     float l[kWaves][kMaxGroup];
+    int flag;                          // set when this workgroup is the last partition of its (request, KV head) to arrive
 };
 
-// Combine the four waves' (m, l, o) of this item and store: the normalised output when the request has a single
-// partition, else the unnormalised row plus (m, l) for the merge kernel.  Must be called by all 256 threads after the
-// waves have filled `sm` (this function synchronises first).
+// Relaxed device-scope accesses: coherent across the compute dies without a cache-wide fence.
+__device__ __forceinline__ void dev_store(float *ptr, float v) {
+    __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float dev_load(const float *ptr) {
+    return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void store_out(const AttnParams &p, size_t index, float v) {
+    if (p.out_bf16) reinterpret_cast<uint16_t *>(p.out)[index] = float_to_bf16_rne(v);
+    else reinterpret_cast<float *>(p.out)[index] = v;
+}
+
+// One thread: count this workgroup's arrival for the request of `seg`; true if it is the last piece to arrive.
+__device__ __forceinline__ bool count_arrival(const AttnParams &p, const Segment &seg, int kvh) {
+    const int old = __hip_atomic_fetch_add(&p.ws.arrivals[seg.b * p.Hkv + kvh], 1, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+    return old == seg.nparts - 1;
+}
+
+// All 256 threads: log-sum-exp merge of the request's pieces, in slot order, four pieces per round: all loads of a
+// round are issued before any is used, so a round costs one trip to memory, and no load depends on a loaded value.
+// Puts the arrival counter back to zero for the next call.
 template <int D>
-__device__ __forceinline__ void wg_combine_and_store(const CombineSmem<D> &sm, const AttnParams &p, const Item &it,
-                                                     int r, int kvh) {
+__device__ __forceinline__ void merge_request(const AttnParams &p, const Segment &seg, int kvh) {
+    const int G = p.G, head0 = kvh * G, n = seg.nparts;
+    const size_t out0 = ((size_t)seg.b * p.Hq + head0) * D;
+    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+        const int g = idx / D;
+        float M = -INFINITY, num = 0.f, den = 0.f;
+        for (int j0 = 0; j0 < n; j0 += 4) {
+            float mj[4], lj[4], oj[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                lj[u] = 0.f; mj[u] = 0.f; oj[u] = 0.f;
+                if (j0 + u < n) {                                    // uniform
+                    const size_t pi = (size_t)(seg.slot_first + j0 + u) * p.Hq + head0;
+                    mj[u] = dev_load(&p.ws.part_ml[pi + g].x);
+                    lj[u] = dev_load(&p.ws.part_ml[pi + g].y);
+                    oj[u] = dev_load(&p.ws.part_o[pi * D + idx]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (lj[u] > 0.f) {
+                    const float Mn = fmaxf(M, mj[u]);
+                    const float a = fast_exp2(M - Mn);               // 0 while M is still -inf
+                    const float w = fast_exp2(mj[u] - Mn);
+                    num = num * a + w * oj[u];
+                    den = den * a + w * lj[u];
+                    M = Mn;
+                }
+            }
+        }
+        store_out(p, out0 + idx, den > 0.f ? num / den : 0.f);
+    }
+    if (threadIdx.x == 0)
+        __hip_atomic_store(&p.ws.arrivals[seg.b * p.Hkv + kvh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Combine the four waves' (m, l, o) of one segment and finish it.  Must be called by all 256 threads after the waves
+// have filled `sm` (this function synchronises first, and again before it returns so that `sm` may be refilled).
+//   - A request that lies inside one range gets its normalised output row at once.
+//   - Otherwise the unnormalised row and (m, l) go to the segment's workspace slot, and the workgroup that arrives
+//     last for its (request, KV head) performs the log-sum-exp merge over the request's slots, in slot order:
+//         out = sum_j 2^(m_j - M) o_j / sum_j 2^(m_j - M) l_j,  M = max_j m_j,  empty pieces (l_j = 0) skipped.
+//     "Last" is decided by an arrival counter: a workgroup writes its partial rows, waits for the writes to be
+//     acknowledged, then adds one; the workgroup that reads nparts-1 merges and puts the counter back to zero.
+//     Nobody waits for anybody, so the scheme cannot hang; the result does not depend on which workgroup merges.
+//     The partial rows cross between compute dies whose L2 caches are not coherent with each other.  A device-scope
+//     fence would write back and invalidate a whole L2 per workgroup (measured: 4x the kernel time); instead every
+//     access to the partial rows and to the counter is a relaxed device-scope atomic (sc1 loads and stores), which
+//     goes to the coherence point without touching the rest of the cache.
+template <int D>
+__device__ __forceinline__ void wg_combine_and_store(CombineSmem<D> &sm, const AttnParams &p, const Segment &seg,
+                                                     int kvh) {
     __syncthreads();
     const int G = p.G;
     const int head0 = kvh * G;
+    const size_t out0 = ((size_t)seg.b * p.Hq + head0) * D;
     for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
         const int g = idx / D, d = idx - g * D;
         float M = -INFINITY;
@@ -81,18 +167,78 @@ __device__ __forceinline__ void wg_combine_and_store(const CombineSmem<D> &sm, c
                 den += a * sm.l[w][g];
             }
         }
-        if (it.nparts == 1) {
-            const float res = den > 0.f ? num / den : 0.f;
-            const size_t oi = ((size_t)it.b * p.Hq + head0) * D + idx;
-            if (p.out_bf16) reinterpret_cast<uint16_t *>(p.out)[oi] = float_to_bf16_rne(res);
-            else reinterpret_cast<float *>(p.out)[oi] = res;
+        if (seg.nparts == 1) {
+            store_out(p, out0 + idx, den > 0.f ? num / den : 0.f);
         } else {
-            const size_t pi = (size_t)r * p.Hq + head0;
-            p.ws.part_o[pi * D + idx] = num;
-            if (d == 0) p.ws.part_ml[pi + g] = make_float2(M, den);
+            const size_t pi = (size_t)seg.slot * p.Hq + head0;
+            dev_store(&p.ws.part_o[pi * D + idx], num);
+            if (d == 0) {
+                dev_store(&p.ws.part_ml[pi + g].x, M);
+                dev_store(&p.ws.part_ml[pi + g].y, den);
+            }
         }
     }
-    if (threadIdx.x == 0 && kvh == 0 && it.part == 0) p.ws.req_info[it.b] = make_int2(it.start, it.nparts);
+    // The barrier's workgroup-scope release makes every wave wait until its device-scope stores above are
+    // acknowledged, so they are globally visible before the arrival is counted.
+    __syncthreads();
+    if (seg.nparts == 1) return;                                     // uniform
+
+    if (threadIdx.x == 0) sm.flag = count_arrival(p, seg, kvh);
+    __syncthreads();
+    const bool last = sm.flag;
+    __syncthreads();                                                 // flag may be rewritten by the next segment
+    if (last) merge_request<D>(p, seg, kvh);                         // uniform
+}
+
+// blockIdx -> (workgroup index w within its KV head, KV head).  Workgroups are dealt to the eight compute dies
+// round-robin by blockIdx; this mapping gives every die a share of every KV head (a KV head is a fixed 4 KB or 8 KB
+// slice of each page, i.e. a fixed set of address bits) instead of binding each die to one head.
+__device__ __forceinline__ void wg_coords(const AttnParams &p, int *w, int *kvh) {
+    constexpr int kDies = 8;
+    const int bid = blockIdx.x;
+    if (gridDim.x % (kDies * p.Hkv) == 0) {
+        const int x = bid % kDies, y = bid / kDies;
+        *kvh = y % p.Hkv;
+        *w = x + kDies * (y / p.Hkv);
+    } else {
+        *w = bid / p.Hkv;
+        *kvh = bid - *w * p.Hkv;
+    }
+}
+
+// Prologue shared by the partition kernels: build the plan in shared memory, write the all-zero rows of empty
+// requests (first workgroup of each KV head) and the plan words (first workgroup of the grid).
+template <int D>
+__device__ __forceinline__ Plan attn_prologue(const AttnParams &p, PlanSmem *ps, int *E, int w, int kvh) {
+    const Plan pl = plan_build(p.context_lens, p.plan, ps, E, E + p.plan.B + 1, [&](int b) {
+        if (w == 0) {
+            const size_t o0 = ((size_t)b * p.Hq + kvh * p.G) * D;
+            for (int i = 0; i < p.G * D; ++i) store_out(p, o0 + i, 0.f);
+        }
+    });
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const unsigned long long T = ps->total_tokens;
+        p.ws.plan_words[0] = pl.S * kTile; p.ws.plan_words[1] = pl.nranges;
+        p.ws.plan_words[2] = (int)(T & 0xffffffffULL); p.ws.plan_words[3] = (int)(T >> 32);
+    }
+    return pl;
+}
+
+// Drive `process(seg)` over every segment of every range of workgroup w, finishing each with the combine above.
+template <int D, typename Process>
+__device__ __forceinline__ void for_each_segment(const AttnParams &p, const Plan &pl, PlanSmem *ps, const int *E,
+                                                 CombineSmem<D> &sm, int w, int kvh, Process process) {
+    for (int range = w; range < pl.nranges; range += p.plan.nw) {
+        const int start = range * pl.S, end = min(pl.C, start + pl.S);
+        int b = plan_first_request(p.plan, ps, E, start);
+        while (true) {
+            const Segment seg = plan_segment(E, E + p.plan.B + 1, pl, b, range, start, end);
+            process(seg);
+            wg_combine_and_store<D>(sm, p, seg, kvh);
+            if (__builtin_amdgcn_readfirstlane(E[b]) + seg.hi >= end) break;
+            do { ++b; } while (b < p.plan.B - 1 && E[b + 1] == E[b]);       // skip requests that own no tile
+        }
+    }
 }
 
 }  // namespace omni

@@ -1,7 +1,7 @@
 // Matrix-core split-context decode kernel for bf16 q/K/V with head_dim 128 and group size <= 16.
 //
-// One workgroup = one (request, partition, KV head); its four waves take 32-token tiles round-robin and each keeps
-// its own online-softmax state; the states meet in LDS at the end.
+// A workgroup walks the segments of its ranges (see plan.hpp) for one KV head; within a segment its four waves take
+// 32-token tiles round-robin and each keeps its own online-softmax state; the states meet in LDS at the segment's end.
 //
 // Per 32-token tile a wave computes, with v_mfma_f32_16x16x32_bf16 (A: 16 rows x 32 k, B: 32 k x 16 columns;
 // a lane holds row/column lane%16 and the 8 consecutive k of group lane/16):
@@ -43,50 +43,31 @@ __device__ __forceinline__ int slot_token(int j, int r) { return (r < 4) ? 4 * j
 
 template <int PS>
 struct MfmaTileLoader {
-    // lane constants
     const char *kbase, *vbase;       // pool base + KV-head offset
     size_t page_stride;              // bytes between pages
     int koff;                        // byte offset of this lane's K chunk inside a 16-token block
-    int voff;                        // byte offset of this lane's V chunk inside a row
-    int j;
-    const int32_t *bt;               // block-table row of the request
+    int voff;                        // byte offset of this lane's first V row chunk inside a 16-token block
 
-    // Issue the 16 loads of tile `tb` (first token).  Pages whose first token is at or past t1 are replaced by the
-    // tile's first page so that no table entry beyond the request's pages is dereferenced.
-    __device__ __forceinline__ void issue(int tb, int t1, uint4 (&K)[8], uint4 (&V)[8]) const {
-        if constexpr (PS == 16) {
-            const int pi = __builtin_amdgcn_readfirstlane(tb >> 4);
-            const int second = (tb + 16 < t1) ? pi + 1 : pi;
-            const int pg0 = bt[pi], pg1 = bt[second];
-            const char *k0 = kbase + (size_t)pg0 * page_stride + koff;
-            const char *k1 = kbase + (size_t)pg1 * page_stride + koff;
+    // The 8 K loads / 8 V loads of one 32-token tile.  pg0 / pg1 are the physical pages of its first / second 16
+    // tokens (wave-uniform; with 32-token pages only pg0 is used).
+    __device__ __forceinline__ void issue_k(int pg0, int pg1, uint4 (&K)[8]) const {
+        const size_t o0 = (size_t)pg0 * page_stride;
+        const size_t o1 = (PS == 16) ? (size_t)pg1 * page_stride : o0 + 16 * 256;
+        const char *k0 = kbase + o0 + koff, *k1 = kbase + o1 + koff;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                K[kk] = *reinterpret_cast<const uint4 *>(k0 + kk * 64);
-                K[4 + kk] = *reinterpret_cast<const uint4 *>(k1 + kk * 64);
-            }
-            const char *v0 = vbase + (size_t)pg0 * page_stride + voff + (4 * j) * 256;
-            const char *v1 = vbase + (size_t)pg1 * page_stride + voff + (4 * j) * 256;
+        for (int kk = 0; kk < 4; ++kk) {
+            K[kk] = *reinterpret_cast<const uint4 *>(k0 + kk * 64);
+            K[4 + kk] = *reinterpret_cast<const uint4 *>(k1 + kk * 64);
+        }
+    }
+    __device__ __forceinline__ void issue_v(int pg0, int pg1, uint4 (&V)[8]) const {
+        const size_t o0 = (size_t)pg0 * page_stride;
+        const size_t o1 = (PS == 16) ? (size_t)pg1 * page_stride : o0 + 16 * 256;
+        const char *v0 = vbase + o0 + voff, *v1 = vbase + o1 + voff;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                V[r] = *reinterpret_cast<const uint4 *>(v0 + r * 256);
-                V[4 + r] = *reinterpret_cast<const uint4 *>(v1 + r * 256);
-            }
-        } else {
-            const int pi = __builtin_amdgcn_readfirstlane(tb >> 5);
-            const int pg = bt[pi];
-            const char *k0 = kbase + (size_t)pg * page_stride + koff;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                K[kk] = *reinterpret_cast<const uint4 *>(k0 + kk * 64);
-                K[4 + kk] = *reinterpret_cast<const uint4 *>(k0 + 16 * 256 + kk * 64);
-            }
-            const char *v0 = vbase + (size_t)pg * page_stride + voff + (4 * j) * 256;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                V[r] = *reinterpret_cast<const uint4 *>(v0 + r * 256);
-                V[4 + r] = *reinterpret_cast<const uint4 *>(v0 + (16 + r) * 256);
-            }
+        for (int r = 0; r < 4; ++r) {
+            V[r] = *reinterpret_cast<const uint4 *>(v0 + r * 256);
+            V[4 + r] = *reinterpret_cast<const uint4 *>(v1 + r * 256);
         }
     }
 };
@@ -96,9 +77,8 @@ struct MfmaState {
     f32x4_t acc[8];          // acc[e][i] = O^T[dim 32j + 8i + e][head lane%16]
 };
 
-// One 32-token tile: scores, online softmax, weighted V accumulation.
-__device__ __forceinline__ void mfma_tile(const uint4 (&K)[8], uint4 (&V)[8], const uint4 (&Q)[4], MfmaState &st,
-                                          int tb, int t1, int j, float scale_log2) {
+// First half of a 32-token tile: the scores S^T = K Q^T of the tile, in the log2 domain.
+__device__ __forceinline__ void mfma_scores(const uint4 (&K)[8], const uint4 (&Q)[4], float (&sv)[8], float scale_log2) {
     // Scores are rounded before the running max is subtracted (no fused multiply-subtract): s - max is then exactly
     // 0 for the maximal score, and a length-1 context returns its V row bit for bit.
 #pragma clang fp contract(off)
@@ -108,9 +88,13 @@ __device__ __forceinline__ void mfma_tile(const uint4 (&K)[8], uint4 (&V)[8], co
         s0 = mfma_bf16(K[kk], Q[kk], s0);
         s1 = mfma_bf16(K[4 + kk], Q[kk], s1);
     }
-    float sv[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) { sv[i] = s0[i] * scale_log2; sv[4 + i] = s1[i] * scale_log2; }
+}
+
+// Second half: online softmax over the tile's scores and the weighted V accumulation O^T += V^T P^T.
+__device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], MfmaState &st, int tb, int t1, int j) {
+#pragma clang fp contract(off)
     if (tb + 32 > t1) {                                  // ragged last tile (uniform branch)
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
@@ -163,89 +147,218 @@ __device__ __forceinline__ void mfma_tile(const uint4 (&K)[8], uint4 (&V)[8], co
     }
 }
 
+// Barrier that orders shared-memory traffic only: global loads issued before it stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+struct ArrivalSmem {
+    int last[2];     // this workgroup is the last piece to arrive for its first / second shared request
+};
+
 template <int PS>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
+    constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     __shared__ CombineSmem<D> sm;
-    __shared__ int sm_plan[16];
+    __shared__ ArrivalSmem stage;
+    __shared__ PlanSmem ps;
+    extern __shared__ int E[];                               // E[B + 1] tile offsets, then Lc[B] lengths
 
-    const int r = blockIdx.x / p.Hkv, kvh = blockIdx.x - r * p.Hkv;
-    Item it;
-    int R;
-    long long Ttot;
-    const bool have = plan_find(p.context_lens, p.plan, r, sm_plan, &it, &R, &Ttot);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        p.ws.plan_words[0] = have ? it.PL : 0; p.ws.plan_words[1] = R;
-        p.ws.plan_words[2] = (int)(Ttot & 0xffffffffLL); p.ws.plan_words[3] = (int)(Ttot >> 32);
+    int w, kvh;
+    wg_coords(p, &w, &kvh);
+    OMNI_STAMP(p, 0);
+#ifdef OMNI_TRACE
+    if (p.trace && (threadIdx.x & 63) == 0) {
+        unsigned xcc, hwid;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+        p.trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + 8] = ((long long)xcc << 32) | hwid;
     }
-    if (!have) return;
-
+#endif
+    const Plan pl = attn_prologue<D>(p, &ps, E, w, kvh);
+    OMNI_STAMP(p, 1);
+    const int *Lc = E + p.plan.B + 1;
     const int G = p.G;
-    const int plen = piece_len(it.L, it.nparts);
-    const int t0 = it.part * plen;
-    const int t1 = min(it.L, t0 + plen);
-    const int ntiles = (t1 - t0 + kTile - 1) / kTile;
+    const int head0 = kvh * G;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 15, j = lane >> 4;
-
-    // B operand of K Q^T: column = head `col` of the group, k-slots = dims (4kk + j)*8 .. +8
-    uint4 Q[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) Q[kk] = make_uint4(0, 0, 0, 0);
-    if (col < G) {
-        const char *qrow = reinterpret_cast<const char *>(p.q) + ((size_t)it.b * p.Hq + kvh * G + col) * (D * 2);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) Q[kk] = *reinterpret_cast<const uint4 *>(qrow + (4 * kk + j) * 16);
-    }
 
     MfmaTileLoader<PS> ld;
     ld.page_stride = (size_t)p.Hkv * PS * D * 2;
     ld.kbase = reinterpret_cast<const char *>(p.k_cache) + (size_t)kvh * PS * D * 2;
     ld.vbase = reinterpret_cast<const char *>(p.v_cache) + (size_t)kvh * PS * D * 2;
     ld.koff = col * 256 + j * 16;
-    ld.voff = col * 16;
-    ld.j = j;
-    ld.bt = p.block_table + (size_t)it.b * p.MB;
+    ld.voff = col * 16 + (4 * j) * 256;
 
-    MfmaState st;
-    st.m = -INFINITY; st.l = 0.f;
+    for (int range = w; range < pl.nranges; range += p.plan.nw) {
+        const int start = range * pl.S, end = min(pl.C, start + pl.S);
+        const int len = end - start;
+        const int first_b = plan_first_request(p.plan, &ps, E, start);
+
+        // ---- this wave's tiles: tile g = wave + 4*slot of the range, slot = 0 .. nk-1.  Lane s of the wave looks up
+        // everything about slot s (of the current group of 64 slots) once: the request, the tile's index inside the
+        // request and its physical pages.  The tile loop then only picks values out with v_readlane, so neither the
+        // block table nor the plan sits on the critical path between two tiles, also across request boundaries.
+        const int nk = len > wave ? (len - wave + kWaves - 1) / kWaves : 0;
+        int meta_req = 0, meta_tile = 0, meta_pg0 = 0, meta_pg1 = 0;
+        auto fetch_meta = [&](int first_slot) {
+            const int slot = first_slot + lane;
+            if (slot < nk) {
+                const int pos = start + wave + kWaves * slot;
+                int lo = first_b, hi = p.plan.B;                 // E[lo] <= pos < E[hi]
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (E[mid] <= pos) lo = mid; else hi = mid;
+                }
+                const int t = pos - E[lo];
+                const int last_page = (Lc[lo] - 1) >> kLog2Ps;
+                const int32_t *bt = p.block_table + (size_t)lo * p.MB;
+                const int page = (t * kTile) >> kLog2Ps;
+                meta_req = lo; meta_tile = t;
+                if (PS == 16 && page < last_page) {              // both pages exist: one 8-byte read (page is even)
+                    struct alignas(4) PagePair { int first, second; };   // rows of odd length keep only 4-byte alignment
+                    const PagePair pp2 = *reinterpret_cast<const PagePair *>(bt + page);
+                    meta_pg0 = pp2.first; meta_pg1 = pp2.second;
+                } else {                                         // never read beyond the request's pages
+                    meta_pg0 = bt[page]; meta_pg1 = meta_pg0;
+                }
+            }
+        };
+        fetch_meta(0);
+
+        // scalar description of a slot, read from the lane that holds it
+        struct SlotInfo { int req, tile, pg0, pg1; };
+        auto slot_info = [&](int slot) {
+            if ((slot & 63) == 0 && slot > 0) fetch_meta(slot);  // rare: more than 64 tiles per wave in one range
+            const int l = slot & 63;
+            SlotInfo si;
+            si.req = __builtin_amdgcn_readlane(meta_req, l); si.tile = __builtin_amdgcn_readlane(meta_tile, l);
+            si.pg0 = __builtin_amdgcn_readlane(meta_pg0, l); si.pg1 = __builtin_amdgcn_readlane(meta_pg1, l);
+            return si;
+        };
+        auto load_q = [&](int b, uint4 (&Q)[4]) {                // B operand of K Q^T for request b
 #pragma unroll
-    for (int e = 0; e < 8; ++e) st.acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            for (int kk = 0; kk < 4; ++kk) Q[kk] = make_uint4(0, 0, 0, 0);
+            if (col < G) {
+                const char *qrow = reinterpret_cast<const char *>(p.q) + ((size_t)b * p.Hq + head0 + col) * (D * 2);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) Q[kk] = *reinterpret_cast<const uint4 *>(qrow + (4 * kk + j) * 16);
+            }
+        };
 
-    uint4 K0[8], V0[8], K1[8], V1[8];
-    int ti = wave;
-    if (ti < ntiles) {
-        ld.issue(t0 + ti * kTile, t1, K0, V0);
+        // Software pipeline of one wave (single K and V buffers): the K rows of the next tile are requested as soon
+        // as the scores of the current tile have consumed K, its V rows as soon as the accumulation has consumed V,
+        // and the next request's query as soon as the last scores of the current request are done.  The requests
+        // stay in flight across the end-of-segment exchange below.
+        uint4 K[8], V[8], Q[4];
+        int s = 0;                       // next slot to compute; its loads are in flight
+        SlotInfo cur{-1, 0, 0, 0};
+        if (nk > 0) {
+            cur = slot_info(0);
+            ld.issue_k(cur.pg0, cur.pg1, K);
+            load_q(cur.req, Q);
+            ld.issue_v(cur.pg0, cur.pg1, V);
+        }
+        OMNI_STAMP(p, 2);
+        bool stamped = false;
+
+        int nstaged = 0;
+        Segment staged0{}, staged1{};
+        int b = first_b;
         while (true) {
-            const bool more1 = ti + kWaves < ntiles;
-            if (more1) ld.issue(t0 + (ti + kWaves) * kTile, t1, K1, V1);
-            mfma_tile(K0, V0, Q, st, t0 + ti * kTile, t1, j, p.scale_log2);
-            if (!more1) break;
-            ti += kWaves;
-            const bool more0 = ti + kWaves < ntiles;
-            if (more0) ld.issue(t0 + (ti + kWaves) * kTile, t1, K0, V0);
-            mfma_tile(K1, V1, Q, st, t0 + ti * kTile, t1, j, p.scale_log2);
-            if (!more0) break;
-            ti += kWaves;
-        }
-    }
-
-    // the sum is per lane (its 8 token slots per tile): add the four lane groups; m is already common to them
-    st.l += __shfl_xor(st.l, 16);
-    st.l += __shfl_xor(st.l, 32);
-    if (col < G) {
+            const Segment seg = plan_segment(E, Lc, pl, b, range, start, end);
+            MfmaState st;
+            st.m = -INFINITY; st.l = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float4 lo4 = make_float4(st.acc[0][i], st.acc[1][i], st.acc[2][i], st.acc[3][i]);
-            float4 hi4 = make_float4(st.acc[4][i], st.acc[5][i], st.acc[6][i], st.acc[7][i]);
-            *reinterpret_cast<float4 *>(&sm.o[wave][col][32 * j + 8 * i]) = lo4;
-            *reinterpret_cast<float4 *>(&sm.o[wave][col][32 * j + 8 * i + 4]) = hi4;
+            for (int e = 0; e < 8; ++e) st.acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            while (s < nk && cur.req == seg.b) {
+                const bool more = s + 1 < nk;
+                SlotInfo nxt{-1, 0, 0, 0};
+                if (more) nxt = slot_info(s + 1);
+                float sv[8];
+                mfma_scores(K, Q, sv, p.scale_log2);
+                if (!stamped) { OMNI_STAMP(p, 3); stamped = true; }
+                if (more) {
+                    ld.issue_k(nxt.pg0, nxt.pg1, K);
+                    if (nxt.req != seg.b) load_q(nxt.req, Q);
+                }
+                mfma_softmax_pv(sv, V, st, cur.tile * kTile, seg.L, j);
+                if (more) ld.issue_v(nxt.pg0, nxt.pg1, V);
+                ++s; cur = nxt;
+            }
+
+            // ---- end of the segment: the four waves' states meet in LDS
+            st.l += __shfl_xor(st.l, 16);                        // per-lane sums of the four lane groups; m is common
+            st.l += __shfl_xor(st.l, 32);
+            if (col < G) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float4 lo4 = make_float4(st.acc[0][i], st.acc[1][i], st.acc[2][i], st.acc[3][i]);
+                    float4 hi4 = make_float4(st.acc[4][i], st.acc[5][i], st.acc[6][i], st.acc[7][i]);
+                    *reinterpret_cast<float4 *>(&sm.o[wave][col][32 * j + 8 * i]) = lo4;
+                    *reinterpret_cast<float4 *>(&sm.o[wave][col][32 * j + 8 * i + 4]) = hi4;
+                }
+                if (j == 0) { sm.m[wave][col] = st.m; sm.l[wave][col] = st.l; }
+            }
+            if (s >= nk) OMNI_STAMP(p, 7);                       // this wave's last tile is done
+            lds_barrier();
+            const size_t out0 = ((size_t)seg.b * p.Hq + head0) * D;
+            for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+                const int g = idx / D, d = idx - g * D;
+                float M = -INFINITY;
+#pragma unroll
+                for (int ww = 0; ww < kWaves; ++ww) M = fmaxf(M, sm.m[ww][g]);
+                float num = 0.f, den = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < kWaves; ++ww) {
+                    const float mw = sm.m[ww][g];
+                    if (mw > -INFINITY) {
+                        const float a = fast_exp2(mw - M);
+                        num += a * sm.o[ww][g][d];
+                        den += a * sm.l[ww][g];
+                    }
+                }
+                if (seg.nparts == 1) {
+                    store_out(p, out0 + idx, den > 0.f ? num / den : 0.f);       // nobody waits for this store
+                } else {                                                         // nor for these, until the range ends
+                    const size_t pi = (size_t)seg.slot * p.Hq + head0;
+                    dev_store(&p.ws.part_o[pi * D + idx], num);
+                    if (d == 0) {
+                        dev_store(&p.ws.part_ml[pi + g].x, M);
+                        dev_store(&p.ws.part_ml[pi + g].y, den);
+                    }
+                }
+            }
+            if (seg.nparts > 1) {                                // at most two per range: its first and last segment
+                if (nstaged == 0) staged0 = seg; else staged1 = seg;
+                ++nstaged;
+            }
+            lds_barrier();                                       // sm may be refilled
+            if (__builtin_amdgcn_readfirstlane(E[b]) + seg.hi >= end) break;
+            do { ++b; } while (b < p.plan.B - 1 && E[b + 1] == E[b]);    // skip requests that own no tile
         }
-        if (j == 0) { sm.m[wave][col] = st.m; sm.l[wave][col] = st.l; }
+
+        OMNI_STAMP(p, 4);
+        // ---- end of the range: count this workgroup's arrival for the (at most two) requests it shares with other
+        // ranges, and merge those for which it is the last piece to arrive.  The partial rows were stored when their
+        // segments ended; the barrier below is where every wave waits for those stores to be acknowledged.
+        if (nstaged > 0) {
+            __syncthreads();             // every wave has waited for its stores to be acknowledged
+            OMNI_STAMP(p, 5);
+            if (threadIdx.x == 0) stage.last[0] = count_arrival(p, staged0, kvh);
+            if (threadIdx.x == 1 && nstaged == 2) stage.last[1] = count_arrival(p, staged1, kvh);
+            __syncthreads();
+            if (stage.last[0]) merge_request<D>(p, staged0, kvh);
+            if (nstaged == 2 && stage.last[1]) merge_request<D>(p, staged1, kvh);
+            __syncthreads();             // stage.last is rewritten by the next range
+        }
+        OMNI_STAMP(p, 6);
     }
-    wg_combine_and_store<D>(sm, p, it, r, kvh);
 }
 
 }  // namespace omni

@@ -1,7 +1,7 @@
 // Vector-ALU split-context decode kernel: covers fp32 and bf16 KV, head_dim 64 and 128, page sizes 16 and 32, any
-// group size up to GP.  One workgroup = one (request, partition, KV head); each wave streams whole token rows with
-// 16-byte loads (a row of D elements is spread over D*es/16 adjacent lanes), keeps one online-softmax state per lane
-// group, and the states are merged by cross-lane shuffles, then through LDS.
+// group size up to GP.  A workgroup walks the segments of its ranges (see plan.hpp) for one KV head; within a segment
+// each wave streams whole token rows with 16-byte loads (a row of D elements is spread over D*es/16 adjacent lanes),
+// keeps one online-softmax state per lane group, and the states are merged by cross-lane shuffles, then through LDS.
 #pragma once
 #include "common.hpp"
 
@@ -32,27 +32,23 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(AttnParams p) {
     static_assert(LPR <= 64 && (LPR & (LPR - 1)) == 0, "row must fit a wave");
 
     __shared__ CombineSmem<D> sm;
-    __shared__ int sm_plan[16];
+    __shared__ PlanSmem ps;
+    extern __shared__ int E[];                 // B + 1 tile offsets
 
-    const int r = blockIdx.x / p.Hkv, kvh = blockIdx.x - r * p.Hkv;
-    Item it;
-    int R;
-    long long Ttot;
-    const bool have = plan_find(p.context_lens, p.plan, r, sm_plan, &it, &R, &Ttot);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        p.ws.plan_words[0] = have ? it.PL : 0; p.ws.plan_words[1] = R;
-        p.ws.plan_words[2] = (int)(Ttot & 0xffffffffLL); p.ws.plan_words[3] = (int)(Ttot >> 32);
-    }
-    if (!have) return;
-
+    int w, kvh;
+    wg_coords(p, &w, &kvh);
+    const Plan pl = attn_prologue<D>(p, &ps, E, w, kvh);
     const int G = p.G;
-    const int plen = piece_len(it.L, it.nparts);
-    const int t0 = it.part * plen;
-    const int t1 = min(it.L, t0 + plen);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane % LPR, sub = lane / LPR;
     const int ps_mask = (1 << p.log2_ps) - 1;
+    const T *kc = reinterpret_cast<const T *>(p.k_cache);
+    const T *vc = reinterpret_cast<const T *>(p.v_cache);
+
+    for_each_segment<D>(p, pl, &ps, E, sm, w, kvh, [&](const Segment &seg) {
+    const int t0 = seg.lo * kTile;
+    const int t1 = min(seg.L, seg.hi * kTile);
 
     // query rows of the group, this lane's VEC elements of each
     float qf[GP][VEC];
@@ -60,7 +56,7 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(AttnParams p) {
     for (int g = 0; g < GP; ++g) {
         if (g < G) {
             const uint4 raw = *reinterpret_cast<const uint4 *>(
-                reinterpret_cast<const T *>(p.q) + ((size_t)it.b * p.Hq + kvh * G + g) * D + c * VEC);
+                reinterpret_cast<const T *>(p.q) + ((size_t)seg.b * p.Hq + kvh * G + g) * D + c * VEC);
             ElemTraits<T>::unpack(raw, qf[g]);
         } else {
 #pragma unroll
@@ -76,9 +72,7 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(AttnParams p) {
         for (int e = 0; e < VEC; ++e) o[g][e] = 0.f;
     }
 
-    const int32_t *bt = p.block_table + (size_t)it.b * p.MB;
-    const T *kc = reinterpret_cast<const T *>(p.k_cache);
-    const T *vc = reinterpret_cast<const T *>(p.v_cache);
+    const int32_t *bt = p.block_table + (size_t)seg.b * p.MB;
 
     for (int tt = t0 + wave * TPW; tt < t1; tt += kWaves * TPW) {
         const int t = tt + sub;
@@ -144,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(AttnParams p) {
             }
         }
     }
-    wg_combine_and_store<D>(sm, p, it, r, kvh);
+    });
 }
 
 }  // namespace omni

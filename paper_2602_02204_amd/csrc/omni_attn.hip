@@ -16,14 +16,20 @@ using namespace omni;
 
 namespace {
 
-constexpr int kDefaultTargetWorkgroups = 1024;
-constexpr int kDefaultMinPartition = 256;
+constexpr int kDefaultTargetWorkgroups = 512;     // two 4-wave workgroups per compute unit
+constexpr int kDefaultMinPartition = 128;
+constexpr int kMaxBatch = 4096;                      // the plan keeps 2 * batch + 1 words in shared memory
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
 
 }  // namespace
+
+#ifdef OMNI_TRACE
+static long long *g_omni_trace = nullptr;
+extern "C" void omni_dev_set_trace(long long *dev_buf) { g_omni_trace = dev_buf; }
+#endif
 
 struct omni_handle_s {
     omni_attn_desc_t d;
@@ -35,9 +41,9 @@ struct omni_handle_s {
     int kernel = 1;              // 1 = vector ALU, 2 = MFMA
     int G = 1;
     int max_ctx = 0;
-    int r_target = 0;
-    int r_cap = 0;               // bound on (request, partition) pairs
-    size_t off_req = 0, off_ml = 0, off_o = 0, ws_bytes = 0;
+    int nw = 1;                  // workgroups per KV head
+    int r_cap = 0;               // bound on partial-result slots (range index + request index)
+    size_t off_arr = 0, off_ml = 0, off_o = 0, ws_bytes = 0;
     void *ws = nullptr;
     size_t ws_given = 0;
     // profiling aid: event pairs around the partition kernel
@@ -50,18 +56,19 @@ struct omni_handle_s {
         max_ctx = (d.max_context_hint > 0 && d.max_context_hint < cap_ctx) ? d.max_context_hint : (int)(cap_ctx > 0x3fffffe0 ? 0x3fffffe0 : cap_ctx);
         const bool mfma_ok = d.kv_dtype == OMNI_BF16 && d.head_dim == 128;
         kernel = (tune_kernel == 2 && mfma_ok) ? 2 : (tune_kernel == 1 ? 1 : (mfma_ok ? 2 : 1));
-        r_target = (tune_target_wgs + d.num_kv_heads - 1) / d.num_kv_heads;
-        long long cap;
+        nw = tune_target_wgs / d.num_kv_heads;
+        if (nw < 1) nw = 1;
+        long long ranges = nw;
         if (tune_force_partition > 0) {
-            cap = (long long)d.batch * ((max_ctx + tune_force_partition - 1) / tune_force_partition);
-            if (cap < d.batch) cap = d.batch;
-        } else {
-            cap = r_target > d.batch ? r_target : d.batch;
+            const long long tiles = (long long)d.batch * ((max_ctx + kTile - 1) / kTile);
+            const long long s = tune_force_partition / kTile;
+            ranges = (tiles + s - 1) / s;
         }
-        if (cap > 0x7fffffff / (d.num_kv_heads > 0 ? d.num_kv_heads : 1)) cap = 0x7fffffff / d.num_kv_heads;
+        long long cap = ranges + d.batch;
+        if (cap > 0x3fffffff) cap = 0x3fffffff;
         r_cap = (int)cap;
-        off_req = 256;
-        off_ml = align256(off_req + (size_t)d.batch * sizeof(int2));
+        off_arr = 256;
+        off_ml = align256(off_arr + (size_t)d.batch * d.num_kv_heads * sizeof(int32_t));
         off_o = align256(off_ml + (size_t)r_cap * d.num_q_heads * sizeof(float2));
         ws_bytes = align256(off_o + (size_t)r_cap * d.num_q_heads * d.head_dim * sizeof(float));
     }
@@ -97,6 +104,7 @@ omni_status_t omni_create(const omni_attn_desc_t *desc, omni_handle_t *out_handl
     if (desc->head_dim != 64 && desc->head_dim != 128) return OMNI_ERR_UNSUPPORTED;
     if (desc->page_size != 16 && desc->page_size != 32) return OMNI_ERR_UNSUPPORTED;
     if (desc->num_q_heads / desc->num_kv_heads > kMaxGroup) return OMNI_ERR_UNSUPPORTED;
+    if (desc->batch > kMaxBatch) return OMNI_ERR_UNSUPPORTED;
     omni_handle_s *h = new (std::nothrow) omni_handle_s();
     if (!h) return OMNI_ERR_HIP;
     h->d = *desc;
@@ -130,6 +138,8 @@ omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value) {
         default: return OMNI_ERR_SHAPE;
     }
     h->derive();
+    h->ws = nullptr;             // layout may have changed: the caller registers the workspace again
+    h->ws_given = 0;
     return OMNI_OK;
 }
 
@@ -142,6 +152,11 @@ omni_status_t omni_workspace_bytes(omni_handle_t h, size_t *bytes) {
 omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes) {
     if (!h || !dev_ptr) return OMNI_ERR_NULL;
     if (((uintptr_t)dev_ptr & 255) != 0 || bytes < h->ws_bytes) return OMNI_ERR_WORKSPACE;
+    // The arrival counters of the in-kernel merge must start at zero; every call leaves them at zero again.
+    if (hipMemset(reinterpret_cast<char *>(dev_ptr) + h->off_arr, 0, h->off_ml - h->off_arr) != hipSuccess) {
+        (void)hipGetLastError();
+        return OMNI_ERR_HIP;
+    }
     h->ws = dev_ptr;
     h->ws_given = bytes;
     return OMNI_OK;
@@ -151,8 +166,8 @@ omni_status_t omni_get_plan(omni_handle_t h, int32_t *kernel, int32_t *partition
                             int32_t *max_request_parts, int32_t *threads_per_workgroup) {
     if (!h) return OMNI_ERR_NULL;
     if (kernel) *kernel = h->kernel;
-    if (partition_grid) *partition_grid = h->r_cap * h->d.num_kv_heads;
-    if (merge_grid) *merge_grid = h->d.batch * h->d.num_kv_heads;
+    if (partition_grid) *partition_grid = h->nw * h->d.num_kv_heads;
+    if (merge_grid) *merge_grid = 0;             // the merge runs inside the partition kernel
     if (max_request_parts) *max_request_parts = h->r_cap;
     if (threads_per_workgroup) *threads_per_workgroup = kThreads;
     return OMNI_OK;
@@ -163,12 +178,12 @@ omni_status_t omni_get_plan(omni_handle_t h, int32_t *kernel, int32_t *partition
 namespace {
 
 template <typename T, int D>
-void launch_valu(const AttnParams &p, dim3 grid, hipStream_t s) {
-    if (p.G <= 1) decode_valu_kernel<T, D, 1><<<grid, kThreads, 0, s>>>(p);
-    else if (p.G <= 2) decode_valu_kernel<T, D, 2><<<grid, kThreads, 0, s>>>(p);
-    else if (p.G <= 4) decode_valu_kernel<T, D, 4><<<grid, kThreads, 0, s>>>(p);
-    else if (p.G <= 8) decode_valu_kernel<T, D, 8><<<grid, kThreads, 0, s>>>(p);
-    else decode_valu_kernel<T, D, 16><<<grid, kThreads, 0, s>>>(p);
+void launch_valu(const AttnParams &p, dim3 grid, size_t dyn, hipStream_t s) {
+    if (p.G <= 1) decode_valu_kernel<T, D, 1><<<grid, kThreads, dyn, s>>>(p);
+    else if (p.G <= 2) decode_valu_kernel<T, D, 2><<<grid, kThreads, dyn, s>>>(p);
+    else if (p.G <= 4) decode_valu_kernel<T, D, 4><<<grid, kThreads, dyn, s>>>(p);
+    else if (p.G <= 8) decode_valu_kernel<T, D, 8><<<grid, kThreads, dyn, s>>>(p);
+    else decode_valu_kernel<T, D, 16><<<grid, kThreads, dyn, s>>>(p);
 }
 
 }  // namespace
@@ -188,31 +203,35 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void 
     p.block_table = block_table; p.context_lens = context_lens; p.out = out;
     char *ws = reinterpret_cast<char *>(h->ws);
     p.ws.plan_words = reinterpret_cast<int32_t *>(ws);
-    p.ws.req_info = reinterpret_cast<int2 *>(ws + h->off_req);
+    p.ws.arrivals = reinterpret_cast<int32_t *>(ws + h->off_arr);
     p.ws.part_ml = reinterpret_cast<float2 *>(ws + h->off_ml);
     p.ws.part_o = reinterpret_cast<float *>(ws + h->off_o);
     p.plan.B = d.batch;
-    p.plan.r_target = h->r_target;
-    p.plan.pl_min = h->tune_min_partition;
-    p.plan.pl_force = h->tune_force_partition;
+    p.plan.nw = h->nw;
+    p.plan.s_min = h->tune_min_partition / kTile;
+    p.plan.s_force = h->tune_force_partition / kTile;
     p.scale_log2 = scale * kLog2e;
     p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
     p.log2_ps = ilog2(d.page_size);
     p.out_bf16 = d.out_dtype == OMNI_BF16;
+#ifdef OMNI_TRACE
+    p.trace = g_omni_trace;
+#endif
 
-    const dim3 grid((unsigned)(h->r_cap * d.num_kv_heads));
+    const dim3 grid((unsigned)(h->nw * d.num_kv_heads));
+    const size_t dyn = (size_t)(2 * d.batch + 1) * sizeof(int);     // tile offsets and lengths of the plan
     (void)hipGetLastError();
     const bool prof = (size_t)(2 * h->prof_used + 1) < h->prof_events.size();
     if (prof && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
     if (h->kernel == 2) {
-        if (d.page_size == 16) decode_mfma_kernel<16><<<grid, kThreads, 0, s>>>(p);
-        else decode_mfma_kernel<32><<<grid, kThreads, 0, s>>>(p);
+        if (d.page_size == 16) decode_mfma_kernel<16><<<grid, kThreads, dyn, s>>>(p);
+        else decode_mfma_kernel<32><<<grid, kThreads, dyn, s>>>(p);
     } else if (d.kv_dtype == OMNI_BF16) {
-        if (d.head_dim == 128) launch_valu<uint16_t, 128>(p, grid, s);
-        else launch_valu<uint16_t, 64>(p, grid, s);
+        if (d.head_dim == 128) launch_valu<uint16_t, 128>(p, grid, dyn, s);
+        else launch_valu<uint16_t, 64>(p, grid, dyn, s);
     } else {
-        if (d.head_dim == 128) launch_valu<float, 128>(p, grid, s);
-        else launch_valu<float, 64>(p, grid, s);
+        if (d.head_dim == 128) launch_valu<float, 128>(p, grid, dyn, s);
+        else launch_valu<float, 64>(p, grid, dyn, s);
     }
     if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
     if (prof) {
@@ -220,12 +239,6 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void 
         ++h->prof_used;
     }
 
-    // Whether any request was split is known only on the device: the merge always runs; its workgroups return at
-    // once for requests with a single partition.
-    const dim3 mgrid((unsigned)(d.batch * d.num_kv_heads));
-    if (d.head_dim == 128) merge_kernel<128><<<mgrid, kThreads, 0, s>>>(p);
-    else merge_kernel<64><<<mgrid, kThreads, 0, s>>>(p);
-    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
     return OMNI_OK;
 }
 

@@ -1,11 +1,15 @@
-// Device-side split-context plan, recomputed identically by every workgroup.
+// Device-side work decomposition ("stream" split of the context), recomputed identically by every workgroup.
 //
-// The host never sees context_lens (they live on the device and the library never synchronises), so the grid is a
-// host-known bound and each workgroup derives the same plan from the lengths:
-//   PL      partition length in tokens (multiple of 32), chosen so that the number of (request, partition) pairs
-//           R = sum_b max(1, ceil(L_b / PL)) does not exceed R_target when that is possible at all;
-//   item r  -> (request b, partition index, partitions of b, first r of b).
-// Partitions of one request are equalised: a request cut n ways uses pieces of roundup32(ceil(L / n)) tokens.
+// The host never sees context_lens (they live on the device and the library never synchronises), so the launch grid is
+// data-independent: nw workgroups per KV head.  Each workgroup derives the same plan from the lengths:
+//   - request b owns c_b = ceil(L_b / 32) tiles of 32 tokens; the tiles of all requests are laid end to end
+//     (E_b = tiles before request b, C = all tiles);
+//   - the line of C tiles is cut into ranges of S tiles, S = max(s_min, ceil(C / nw)) unless forced, so every range
+//     carries the same number of tiles whatever the mix of request lengths;
+//   - workgroup w of a KV head takes range w (and w + nw, ... if there are more ranges than workgroups).
+// A range crosses request boundaries wherever they fall: it is a list of segments (request, first tile, last tile).
+// A request covered by one range is finished by that workgroup; a request cut by range boundaries yields one partial
+// result per range that touches it, merged by the last of them to arrive.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -14,41 +18,58 @@ namespace omni {
 
 constexpr int kThreads = 256;          // threads per workgroup in every kernel of the attention path
 constexpr int kWaves = kThreads / 64;
-constexpr int kTile = 32;              // token granularity of partitions
+constexpr int kTile = 32;              // tokens per tile: the granularity of ranges and segments
+constexpr int kLog2Tile = 5;
 
 struct PlanParams {
     int B;
-    int r_target;        // (request, partition) pairs the plan aims for; <= B means "never split"
-    int pl_min;          // smallest partition length the plan may pick (multiple of 32)
-    int pl_force;        // > 0: use exactly this partition length
+    int nw;              // workgroups per KV head
+    int s_min;           // smallest range length in tiles the plan may pick (>= 1)
+    int s_force;         // > 0: use exactly this range length in tiles
 };
 
-struct Item {
-    int b, part, nparts, start, L, PL;
+// One piece of one request inside one range.
+struct Segment {
+    int b;               // request
+    int lo, hi;          // tiles [lo, hi) of the request
+    int L;               // context length of the request (tokens)
+    int nparts;          // ranges that touch this request
+    int slot;            // partial-result slot of this segment (range index + request index: unique, and
+                         // consecutive over the ranges of one request)
+    int slot_first;      // slot of the request's first segment
 };
 
 __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-__device__ __forceinline__ int piece_len(int L, int nparts) {
-    int x = ceil_div(L, nparts);
-    return (x + kTile - 1) & ~(kTile - 1);
-}
+// Shared-memory part of the plan.  The dynamic shared memory of the kernel holds E[0..B] (exclusive prefix of tile
+// counts, E[B] = C) followed by Lc[0..B) (context lengths clamped at 0).
+struct PlanSmem {
+    int wave_tot[kWaves];
+    int first_b;         // request holding the first tile of the current range
+    unsigned long long total_tokens;
+};
 
-// Inclusive scan over the 256 threads of the workgroup.  sm needs kWaves ints.  Returns the scan value; *total = sum.
-__device__ __forceinline__ int block_inclusive_scan(int v, int *sm, int *total) {
+struct Plan {
+    int S;               // range length in tiles
+    int C;               // all tiles
+    int nranges;
+};
+
+// Inclusive scan over the 256 threads of the workgroup (two barriers).
+__device__ __forceinline__ int block_inclusive_scan(int v, PlanSmem *ps, int *total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
-        int t = __shfl_up(v, off);
+        const int t = __shfl_up(v, off);
         if (lane >= off) v += t;
     }
-    __syncthreads();                       // sm may still be read from a previous call
-    if (lane == 63) sm[wave] = v;
+    __syncthreads();                       // wave_tot may still be read from the previous round
+    if (lane == 63) ps->wave_tot[wave] = v;
     __syncthreads();
     int add = 0, tot = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-        int s = sm[w];
+        const int s = ps->wave_tot[w];
         if (w < wave) add += s;
         tot += s;
     }
@@ -56,66 +77,63 @@ __device__ __forceinline__ int block_inclusive_scan(int v, int *sm, int *total) 
     return v + add;
 }
 
-// Partition length for this batch.  Every thread returns the same value.  sm needs kWaves*2 ints.
-__device__ __forceinline__ int plan_partition_len(const int32_t *__restrict__ lens, const PlanParams &pp, int *sm,
-                                                  long long *total_tokens) {
-    long long sum = 0;
-    for (int b = threadIdx.x; b < pp.B; b += kThreads) sum += max(lens[b], 0);
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-    long long *sm64 = reinterpret_cast<long long *>(sm);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sm64[threadIdx.x >> 6] = sum;
-    __syncthreads();
-    long long T = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) T += sm64[w];
-    *total_tokens = T;
-    if (pp.pl_force > 0) return pp.pl_force;
-    if (pp.r_target <= pp.B) return 0x3fffffe0;                     // no split: one partition per request
-    long long per = (T + (pp.r_target - pp.B) - 1) / (pp.r_target - pp.B);
-    if (per < pp.pl_min) per = pp.pl_min;
-    per = (per + 127) & ~127LL;                                     // whole 128-token strips (4 waves x 32 tokens)
-    if (per > 0x3fffffe0) per = 0x3fffffe0;
-    return (int)per;
-}
-
-// Find the item with global index r.  All 256 threads must call this (it synchronises).  Returns false when r is
-// beyond the last item.  sm needs 16 ints.  *R_out (optional) receives the number of items.
-__device__ __forceinline__ bool plan_find(const int32_t *__restrict__ lens, const PlanParams &pp, int r, int *sm,
-                                          Item *it, int *R_out, long long *T_out) {
-    long long T;
-    const int PL = plan_partition_len(lens, pp, sm, &T);
-    if (T_out) *T_out = T;
+// Build E[] in shared memory and choose S.  All 256 threads call this.  Requests of length <= 0 own no tile;
+// `zero_row(b)` is invoked for each of them by one thread so that the caller can write their all-zero output.
+template <typename ZeroRow>
+__device__ __forceinline__ Plan plan_build(const int32_t *__restrict__ lens, const PlanParams &pp, PlanSmem *ps, int *E,
+                                           int *Lc, ZeroRow zero_row) {
+    if (threadIdx.x == 0) ps->total_tokens = 0;
     int carry = 0;
-    __syncthreads();
-    if (threadIdx.x == 0) sm[8] = -1;
+    unsigned long long tokens = 0;
     for (int base = 0; base < pp.B; base += kThreads) {
         const int b = base + threadIdx.x;
-        int L = 0, n = 0;
+        int c = 0;
         if (b < pp.B) {
-            L = max(lens[b], 0);
-            n = max(1, ceil_div(L, PL));
+            const int L = lens[b];
+            if (L > 0) { c = (L + kTile - 1) >> kLog2Tile; tokens += (unsigned long long)L; }
+            else zero_row(b);
         }
         int tot;
-        const int incl = block_inclusive_scan(n, sm, &tot) + carry;   // its barriers order the sm[8] init above
-        const int excl = incl - n;
-        if (n > 0 && r >= excl && r < incl) {
-            sm[8] = b; sm[9] = r - excl; sm[10] = n; sm[11] = excl; sm[12] = L;
-        }
+        const int incl = block_inclusive_scan(c, ps, &tot) + carry;
+        if (b < pp.B) { E[b] = incl - c; Lc[b] = c ? lens[b] : 0; }
         carry += tot;
     }
+    if (threadIdx.x == 0) E[pp.B] = carry;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) tokens += __shfl_xor(tokens, off);
+    if ((threadIdx.x & 63) == 0 && tokens) atomicAdd(&ps->total_tokens, tokens);
     __syncthreads();
-    if (R_out) *R_out = carry;
-    if (sm[8] < 0) return false;
-    // the item is the same for every thread: keep it in scalar registers
-    it->b = __builtin_amdgcn_readfirstlane(sm[8]);
-    it->part = __builtin_amdgcn_readfirstlane(sm[9]);
-    it->nparts = __builtin_amdgcn_readfirstlane(sm[10]);
-    it->start = __builtin_amdgcn_readfirstlane(sm[11]);
-    it->L = __builtin_amdgcn_readfirstlane(sm[12]);
-    it->PL = __builtin_amdgcn_readfirstlane(PL);
-    return true;
+    Plan pl;
+    pl.C = __builtin_amdgcn_readfirstlane(carry);
+    int S = pp.s_force > 0 ? pp.s_force : max(pp.s_min, ceil_div(pl.C, pp.nw));
+    pl.S = max(S, 1);
+    pl.nranges = ceil_div(pl.C, pl.S);
+    return pl;
+}
+
+// Request that holds tile `start` (0 <= start < C).  All 256 threads call this; E[] must be complete.
+__device__ __forceinline__ int plan_first_request(const PlanParams &pp, PlanSmem *ps, const int *E, int start) {
+    __syncthreads();                       // previous readers of first_b are done
+    for (int b = threadIdx.x; b < pp.B; b += kThreads)
+        if (E[b] <= start && start < E[b + 1]) ps->first_b = b;     // exactly one request matches
+    __syncthreads();
+    return __builtin_amdgcn_readfirstlane(ps->first_b);
+}
+
+// Segment of request b inside range `range` = tiles [start, end) of the line.
+__device__ __forceinline__ Segment plan_segment(const int *E, const int *Lc, const Plan &pl, int b, int range, int start,
+                                                int end) {
+    Segment s;
+    const int e0 = __builtin_amdgcn_readfirstlane(E[b]), e1 = __builtin_amdgcn_readfirstlane(E[b + 1]);
+    s.b = b;
+    s.lo = max(start, e0) - e0;
+    s.hi = min(end, e1) - e0;
+    s.L = __builtin_amdgcn_readfirstlane(Lc[b]);
+    const int first_range = e0 / pl.S, last_range = (e1 - 1) / pl.S;
+    s.nparts = last_range - first_range + 1;
+    s.slot = range + b;
+    s.slot_first = first_range + b;
+    return s;
 }
 
 }  // namespace omni

@@ -35,7 +35,7 @@ def test_status_strings():
 @pytest.mark.parametrize("over,status", [
     (dict(batch=0), 2), (dict(num_q_heads=7), 2), (dict(num_kv_heads=0), 2), (dict(num_pages=-1), 2),
     (dict(kv_dtype=5), 3), (dict(q_dtype=omni.OMNI_F32), 3), (dict(kv_dtype=omni.OMNI_F32, out_dtype=omni.OMNI_BF16), 3),
-    (dict(head_dim=96), 4), (dict(page_size=8), 4), (dict(num_q_heads=34, num_kv_heads=2), 4),
+    (dict(head_dim=96), 4), (dict(page_size=8), 4), (dict(num_q_heads=34, num_kv_heads=2), 4), (dict(batch=5000), 4),
 ])
 def test_create_rejects(over, status):
     with pytest.raises(omni.OmniError) as e:
@@ -71,7 +71,7 @@ def test_tuning_validation_and_plan():
     h = omni.Handle(**good())
     plan = h.omni_get_plan()
     assert plan["kernel"] == omni.KERNEL_MFMA and plan["threads_per_workgroup"] == 256
-    assert plan["merge_grid"] == 4 * 2 and plan["partition_grid"] == plan["max_request_parts"] * 2
+    assert plan["merge_grid"] == 0 and plan["partition_grid"] == 512 and plan["max_request_parts"] == 256 + 4
     h.omni_set_tuning(omni.OMNI_TUNE_KERNEL, omni.KERNEL_VALU)
     assert h.omni_get_plan()["kernel"] == omni.KERNEL_VALU
     for key, val in [(omni.OMNI_TUNE_KERNEL, 3), (omni.OMNI_TUNE_TARGET_WORKGROUPS, 0),
