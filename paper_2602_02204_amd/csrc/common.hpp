@@ -13,11 +13,14 @@ constexpr float kLog2e = 1.4426950408889634f;
 // Workspace layout (bytes from the workspace base, all 256-byte aligned):
 //   [0, 256)                 plan words written by item 0: PL, R, T(lo), T(hi)
 //   [256, 256 + 4*B*Hkv)     per (request, KV head): arrival counter of its partitions; zero between calls
-//   ml_off                   per (item, query head): running max (log2 domain) and sum, float2
-//   o_off                    per (item, query head): unnormalised output row, D floats
+//   meta_off                 per (range, wave, slot): request, tile index in the request, two physical pages (int4);
+//                            written by the plan kernel, read by the MFMA attention kernel of the same call
+//   ml_off                   per (slot, query head): running max (log2 domain) and sum, float2
+//   o_off                    per (slot, query head): unnormalised output row, D floats
 struct Workspace {
     int32_t *plan_words;
     int32_t *arrivals;
+    int4 *meta;
     float2 *part_ml;
     float *part_o;
 };
@@ -35,6 +38,7 @@ struct AttnParams {
     int Hq, Hkv, G, MB;
     int log2_ps;
     int out_bf16;
+    int slots_cap;                      // tile slots per (range, wave) in Workspace::meta
 #ifdef OMNI_TRACE
     long long *trace;                   // development builds only: per-wave phase timestamps
 #endif
@@ -209,13 +213,14 @@ __device__ __forceinline__ void wg_coords(const AttnParams &p, int *w, int *kvh)
 // Prologue shared by the partition kernels: build the plan in shared memory, write the all-zero rows of empty
 // requests (first workgroup of each KV head) and the plan words (first workgroup of the grid).
 template <int D>
-__device__ __forceinline__ Plan attn_prologue(const AttnParams &p, PlanSmem *ps, int *E, int w, int kvh) {
+__device__ __forceinline__ Plan attn_prologue(const AttnParams &p, PlanSmem *ps, int *E, int w, int kvh,
+                                              int first_len = 0, bool have_first = false) {
     const Plan pl = plan_build(p.context_lens, p.plan, ps, E, E + p.plan.B + 1, [&](int b) {
         if (w == 0) {
             const size_t o0 = ((size_t)b * p.Hq + kvh * p.G) * D;
             for (int i = 0; i < p.G * D; ++i) store_out(p, o0 + i, 0.f);
         }
-    });
+    }, first_len, have_first);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         const unsigned long long T = ps->total_tokens;
         p.ws.plan_words[0] = pl.S * kTile; p.ws.plan_words[1] = pl.nranges;

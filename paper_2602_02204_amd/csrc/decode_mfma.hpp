@@ -147,13 +147,6 @@ __device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], M
     }
 }
 
-// Barrier that orders shared-memory traffic only: global loads issued before it stay in flight across it.
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
 struct ArrivalSmem {
     int last[2];     // this workgroup is the last piece to arrive for its first / second shared request
 };
@@ -161,7 +154,6 @@ struct ArrivalSmem {
 template <int PS>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
-    constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     __shared__ CombineSmem<D> sm;
     __shared__ ArrivalSmem stage;
     __shared__ PlanSmem ps;
@@ -178,15 +170,38 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         p.trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + 8] = ((long long)xcc << 32) | hwid;
     }
 #endif
-    const Plan pl = attn_prologue<D>(p, &ps, E, w, kvh);
-    OMNI_STAMP(p, 1);
-    const int *Lc = E + p.plan.B + 1;
-    const int G = p.G;
-    const int head0 = kvh * G;
-
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 15, j = lane >> 4;
+    const int G = p.G;
+    const int head0 = kvh * G;
+
+    // ---- this wave's tiles: tile g = wave + 4*slot of the range.  The plan kernel has written, for every slot, the
+    // request, the tile's index inside the request and its physical pages; lane s of the wave reads slot s (of the
+    // current group of 64 slots).  The tile loop then only picks values out with v_readlane, so neither the block
+    // table nor the plan sits between two tiles, also across request boundaries.  A slot with request -1 ends the list.
+    int4 meta = make_int4(-1, 0, 0, 0);
+    auto fetch_meta = [&](int range, int first_slot) {
+        const int slot = first_slot + lane;
+        meta = make_int4(-1, 0, 0, 0);
+        if (slot < p.slots_cap) meta = p.ws.meta[((size_t)range * kWaves + wave) * p.slots_cap + slot];
+    };
+    struct SlotInfo { int req, tile, pg0, pg1; };
+    auto slot_info = [&](int range, int slot) {
+        SlotInfo si{-1, 0, 0, 0};
+        if (slot >= p.slots_cap) return si;
+        if ((slot & 63) == 0 && slot > 0) fetch_meta(range, slot);   // rare: more than 64 tiles per wave in a range
+        const int l = slot & 63;
+        si.req = __builtin_amdgcn_readlane(meta.x, l); si.tile = __builtin_amdgcn_readlane(meta.y, l);
+        si.pg0 = __builtin_amdgcn_readlane(meta.z, l); si.pg1 = __builtin_amdgcn_readlane(meta.w, l);
+        return si;
+    };
+
+    // The first loads of the kernel, in the order their results are needed: this thread's context length (for the
+    // plan below), the tile list of the first range, and the request that opens the range (wave 0, slot 0).
+    const int first_len = (int)threadIdx.x < p.plan.B ? p.context_lens[threadIdx.x] : 0;
+    fetch_meta(w, 0);
+    int first_b = p.ws.meta[(size_t)w * kWaves * p.slots_cap].x;
 
     MfmaTileLoader<PS> ld;
     ld.page_stride = (size_t)p.Hkv * PS * D * 2;
@@ -195,91 +210,61 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     ld.koff = col * 256 + j * 16;
     ld.voff = col * 16 + (4 * j) * 256;
 
+    auto load_q = [&](int b, uint4 (&Q)[4]) {                    // B operand of K Q^T for request b
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) Q[kk] = make_uint4(0, 0, 0, 0);
+        if (col < G) {
+            const char *qrow = reinterpret_cast<const char *>(p.q) + ((size_t)b * p.Hq + head0 + col) * (D * 2);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) Q[kk] = *reinterpret_cast<const uint4 *>(qrow + (4 * kk + j) * 16);
+        }
+    };
+
+    // Software pipeline of one wave (single K and V buffers): the K rows of the next tile are requested as soon as
+    // the scores of the current tile have consumed K, its V rows as soon as the accumulation has consumed V, and the
+    // next request's query as soon as the last scores of the current request are done.  The requests stay in flight
+    // across the end-of-segment exchange below.  The first tile is requested before the plan is even rebuilt.
+    uint4 K[8], V[8], Q[4];
+    SlotInfo cur = slot_info(w, 0);
+    if (cur.req >= 0) {
+        ld.issue_k(cur.pg0, cur.pg1, K);
+        load_q(cur.req, Q);
+        ld.issue_v(cur.pg0, cur.pg1, V);
+    }
+    OMNI_STAMP(p, 2);
+
+    // Tile offsets and lengths of all requests (shared memory): needed for the segment bookkeeping only.
+    const Plan pl = attn_prologue<D>(p, &ps, E, w, kvh, first_len, true);
+    const int *Lc = E + p.plan.B + 1;
+    OMNI_STAMP(p, 1);
+    bool stamped = false;
+
     for (int range = w; range < pl.nranges; range += p.plan.nw) {
         const int start = range * pl.S, end = min(pl.C, start + pl.S);
-        const int len = end - start;
-        const int first_b = plan_first_request(p.plan, &ps, E, start);
-
-        // ---- this wave's tiles: tile g = wave + 4*slot of the range, slot = 0 .. nk-1.  Lane s of the wave looks up
-        // everything about slot s (of the current group of 64 slots) once: the request, the tile's index inside the
-        // request and its physical pages.  The tile loop then only picks values out with v_readlane, so neither the
-        // block table nor the plan sits on the critical path between two tiles, also across request boundaries.
-        const int nk = len > wave ? (len - wave + kWaves - 1) / kWaves : 0;
-        int meta_req = 0, meta_tile = 0, meta_pg0 = 0, meta_pg1 = 0;
-        auto fetch_meta = [&](int first_slot) {
-            const int slot = first_slot + lane;
-            if (slot < nk) {
-                const int pos = start + wave + kWaves * slot;
-                int lo = first_b, hi = p.plan.B;                 // E[lo] <= pos < E[hi]
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (E[mid] <= pos) lo = mid; else hi = mid;
-                }
-                const int t = pos - E[lo];
-                const int last_page = (Lc[lo] - 1) >> kLog2Ps;
-                const int32_t *bt = p.block_table + (size_t)lo * p.MB;
-                const int page = (t * kTile) >> kLog2Ps;
-                meta_req = lo; meta_tile = t;
-                if (PS == 16 && page < last_page) {              // both pages exist: one 8-byte read (page is even)
-                    struct alignas(4) PagePair { int first, second; };   // rows of odd length keep only 4-byte alignment
-                    const PagePair pp2 = *reinterpret_cast<const PagePair *>(bt + page);
-                    meta_pg0 = pp2.first; meta_pg1 = pp2.second;
-                } else {                                         // never read beyond the request's pages
-                    meta_pg0 = bt[page]; meta_pg1 = meta_pg0;
-                }
+        int s = 0;                       // slot being computed; its loads are in flight
+        if (range != w) {                // a further range of this workgroup (more ranges than workgroups)
+            fetch_meta(range, 0);
+            first_b = p.ws.meta[(size_t)range * kWaves * p.slots_cap].x;
+            cur = slot_info(range, 0);
+            if (cur.req >= 0) {
+                ld.issue_k(cur.pg0, cur.pg1, K);
+                load_q(cur.req, Q);
+                ld.issue_v(cur.pg0, cur.pg1, V);
             }
-        };
-        fetch_meta(0);
-
-        // scalar description of a slot, read from the lane that holds it
-        struct SlotInfo { int req, tile, pg0, pg1; };
-        auto slot_info = [&](int slot) {
-            if ((slot & 63) == 0 && slot > 0) fetch_meta(slot);  // rare: more than 64 tiles per wave in one range
-            const int l = slot & 63;
-            SlotInfo si;
-            si.req = __builtin_amdgcn_readlane(meta_req, l); si.tile = __builtin_amdgcn_readlane(meta_tile, l);
-            si.pg0 = __builtin_amdgcn_readlane(meta_pg0, l); si.pg1 = __builtin_amdgcn_readlane(meta_pg1, l);
-            return si;
-        };
-        auto load_q = [&](int b, uint4 (&Q)[4]) {                // B operand of K Q^T for request b
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) Q[kk] = make_uint4(0, 0, 0, 0);
-            if (col < G) {
-                const char *qrow = reinterpret_cast<const char *>(p.q) + ((size_t)b * p.Hq + head0 + col) * (D * 2);
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) Q[kk] = *reinterpret_cast<const uint4 *>(qrow + (4 * kk + j) * 16);
-            }
-        };
-
-        // Software pipeline of one wave (single K and V buffers): the K rows of the next tile are requested as soon
-        // as the scores of the current tile have consumed K, its V rows as soon as the accumulation has consumed V,
-        // and the next request's query as soon as the last scores of the current request are done.  The requests
-        // stay in flight across the end-of-segment exchange below.
-        uint4 K[8], V[8], Q[4];
-        int s = 0;                       // next slot to compute; its loads are in flight
-        SlotInfo cur{-1, 0, 0, 0};
-        if (nk > 0) {
-            cur = slot_info(0);
-            ld.issue_k(cur.pg0, cur.pg1, K);
-            load_q(cur.req, Q);
-            ld.issue_v(cur.pg0, cur.pg1, V);
         }
-        OMNI_STAMP(p, 2);
-        bool stamped = false;
 
         int nstaged = 0;
         Segment staged0{}, staged1{};
-        int b = first_b;
+        int b = __builtin_amdgcn_readfirstlane(first_b);
         while (true) {
             const Segment seg = plan_segment(E, Lc, pl, b, range, start, end);
             MfmaState st;
             st.m = -INFINITY; st.l = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) st.acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            while (s < nk && cur.req == seg.b) {
-                const bool more = s + 1 < nk;
-                SlotInfo nxt{-1, 0, 0, 0};
-                if (more) nxt = slot_info(s + 1);
+            while (cur.req == seg.b) {
+                const SlotInfo nxt = slot_info(range, s + 1);
+                const bool more = nxt.req >= 0;
                 float sv[8];
                 mfma_scores(K, Q, sv, p.scale_log2);
                 if (!stamped) { OMNI_STAMP(p, 3); stamped = true; }
@@ -305,7 +290,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 }
                 if (j == 0) { sm.m[wave][col] = st.m; sm.l[wave][col] = st.l; }
             }
-            if (s >= nk) OMNI_STAMP(p, 7);                       // this wave's last tile is done
+            if (cur.req < 0) OMNI_STAMP(p, 7);                   // this wave's last tile is done
             lds_barrier();
             const size_t out0 = ((size_t)seg.b * p.Hq + head0) * D;
             for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {

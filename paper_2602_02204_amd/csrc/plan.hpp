@@ -41,6 +41,13 @@ struct Segment {
 
 __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// Barrier that orders shared-memory traffic only: global loads issued before it stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Shared-memory part of the plan.  The dynamic shared memory of the kernel holds E[0..B] (exclusive prefix of tile
 // counts, E[B] = C) followed by Lc[0..B) (context lengths clamped at 0).
 struct PlanSmem {
@@ -55,7 +62,7 @@ struct Plan {
     int nranges;
 };
 
-// Inclusive scan over the 256 threads of the workgroup (two barriers).
+// Inclusive scan over the 256 threads of the workgroup (two shared-memory barriers).
 __device__ __forceinline__ int block_inclusive_scan(int v, PlanSmem *ps, int *total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
@@ -63,9 +70,9 @@ __device__ __forceinline__ int block_inclusive_scan(int v, PlanSmem *ps, int *to
         const int t = __shfl_up(v, off);
         if (lane >= off) v += t;
     }
-    __syncthreads();                       // wave_tot may still be read from the previous round
+    lds_barrier();                         // wave_tot may still be read from the previous round
     if (lane == 63) ps->wave_tot[wave] = v;
-    __syncthreads();
+    lds_barrier();
     int add = 0, tot = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
@@ -77,32 +84,34 @@ __device__ __forceinline__ int block_inclusive_scan(int v, PlanSmem *ps, int *to
     return v + add;
 }
 
-// Build E[] in shared memory and choose S.  All 256 threads call this.  Requests of length <= 0 own no tile;
-// `zero_row(b)` is invoked for each of them by one thread so that the caller can write their all-zero output.
+// Build E[] and Lc[] in shared memory and choose S.  All 256 threads call this.  Requests of length <= 0 own no
+// tile; `zero_row(b)` is invoked for each of them by one thread so that the caller can write their all-zero output.
+// `first_len` is context_lens[threadIdx.x] if the caller has already loaded it (have_first), so that the load can be
+// issued ahead of other traffic.  Only shared memory is synchronised: global loads in flight are not waited for.
 template <typename ZeroRow>
 __device__ __forceinline__ Plan plan_build(const int32_t *__restrict__ lens, const PlanParams &pp, PlanSmem *ps, int *E,
-                                           int *Lc, ZeroRow zero_row) {
+                                           int *Lc, ZeroRow zero_row, int first_len = 0, bool have_first = false) {
     if (threadIdx.x == 0) ps->total_tokens = 0;
     int carry = 0;
     unsigned long long tokens = 0;
     for (int base = 0; base < pp.B; base += kThreads) {
         const int b = base + threadIdx.x;
-        int c = 0;
+        int c = 0, L = 0;
         if (b < pp.B) {
-            const int L = lens[b];
+            L = (have_first && base == 0) ? first_len : lens[b];
             if (L > 0) { c = (L + kTile - 1) >> kLog2Tile; tokens += (unsigned long long)L; }
             else zero_row(b);
         }
         int tot;
         const int incl = block_inclusive_scan(c, ps, &tot) + carry;
-        if (b < pp.B) { E[b] = incl - c; Lc[b] = c ? lens[b] : 0; }
+        if (b < pp.B) { E[b] = incl - c; Lc[b] = c ? L : 0; }
         carry += tot;
     }
     if (threadIdx.x == 0) E[pp.B] = carry;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) tokens += __shfl_xor(tokens, off);
     if ((threadIdx.x & 63) == 0 && tokens) atomicAdd(&ps->total_tokens, tokens);
-    __syncthreads();
+    lds_barrier();
     Plan pl;
     pl.C = __builtin_amdgcn_readfirstlane(carry);
     int S = pp.s_force > 0 ? pp.s_force : max(pp.s_min, ceil_div(pl.C, pp.nw));
@@ -113,10 +122,10 @@ __device__ __forceinline__ Plan plan_build(const int32_t *__restrict__ lens, con
 
 // Request that holds tile `start` (0 <= start < C).  All 256 threads call this; E[] must be complete.
 __device__ __forceinline__ int plan_first_request(const PlanParams &pp, PlanSmem *ps, const int *E, int start) {
-    __syncthreads();                       // previous readers of first_b are done
+    lds_barrier();                         // previous readers of first_b are done
     for (int b = threadIdx.x; b < pp.B; b += kThreads)
         if (E[b] <= start && start < E[b + 1]) ps->first_b = b;     // exactly one request matches
-    __syncthreads();
+    lds_barrier();
     return __builtin_amdgcn_readfirstlane(ps->first_b);
 }
 
