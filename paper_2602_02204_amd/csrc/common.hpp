@@ -13,14 +13,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 // Workspace layout (bytes from the workspace base, all 256-byte aligned):
 //   [0, 256)                 plan words written by item 0: PL, R, T(lo), T(hi)
 //   [256, 256 + 4*B*Hkv)     per (request, KV head): arrival counter of its partitions; zero between calls
-//   meta_off                 per (range, wave, slot): request, tile index in the request, two physical pages (int4);
-//                            written by the plan kernel, read by the MFMA attention kernel of the same call
 //   ml_off                   per (slot, query head): running max (log2 domain) and sum, float2
 //   o_off                    per (slot, query head): unnormalised output row, D floats
 struct Workspace {
     int32_t *plan_words;
     int32_t *arrivals;
-    int4 *meta;
     float2 *part_ml;
     float *part_o;
 };
@@ -38,7 +35,6 @@ struct AttnParams {
     int Hq, Hkv, G, MB;
     int log2_ps;
     int out_bf16;
-    int slots_cap;                      // tile slots per (range, wave) in Workspace::meta
 #ifdef OMNI_TRACE
     long long *trace;                   // development builds only: per-wave phase timestamps
 #endif

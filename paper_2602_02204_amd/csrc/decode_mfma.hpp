@@ -154,6 +154,7 @@ struct ArrivalSmem {
 template <int PS>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
+    constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     __shared__ CombineSmem<D> sm;
     __shared__ ArrivalSmem stage;
     __shared__ PlanSmem ps;
@@ -176,33 +177,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     const int G = p.G;
     const int head0 = kvh * G;
 
-    // ---- this wave's tiles: tile g = wave + 4*slot of the range.  The plan kernel has written, for every slot, the
-    // request, the tile's index inside the request and its physical pages; lane s of the wave reads slot s (of the
-    // current group of 64 slots).  The tile loop then only picks values out with v_readlane, so neither the block
-    // table nor the plan sits between two tiles, also across request boundaries.  A slot with request -1 ends the list.
-    int4 meta = make_int4(-1, 0, 0, 0);
-    auto fetch_meta = [&](int range, int first_slot) {
-        const int slot = first_slot + lane;
-        meta = make_int4(-1, 0, 0, 0);
-        if (slot < p.slots_cap) meta = p.ws.meta[((size_t)range * kWaves + wave) * p.slots_cap + slot];
-    };
-    struct SlotInfo { int req, tile, pg0, pg1; };
-    auto slot_info = [&](int range, int slot) {
-        SlotInfo si{-1, 0, 0, 0};
-        if (slot >= p.slots_cap) return si;
-        if ((slot & 63) == 0 && slot > 0) fetch_meta(range, slot);   // rare: more than 64 tiles per wave in a range
-        const int l = slot & 63;
-        si.req = __builtin_amdgcn_readlane(meta.x, l); si.tile = __builtin_amdgcn_readlane(meta.y, l);
-        si.pg0 = __builtin_amdgcn_readlane(meta.z, l); si.pg1 = __builtin_amdgcn_readlane(meta.w, l);
-        return si;
-    };
-
-    // The first loads of the kernel, in the order their results are needed: this thread's context length (for the
-    // plan below), the tile list of the first range, and the request that opens the range (wave 0, slot 0).
-    const int first_len = (int)threadIdx.x < p.plan.B ? p.context_lens[threadIdx.x] : 0;
-    fetch_meta(w, 0);
-    int first_b = p.ws.meta[(size_t)w * kWaves * p.slots_cap].x;
-
     MfmaTileLoader<PS> ld;
     ld.page_stride = (size_t)p.Hkv * PS * D * 2;
     ld.kbase = reinterpret_cast<const char *>(p.k_cache) + (size_t)kvh * PS * D * 2;
@@ -220,42 +194,76 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         }
     };
 
-    // Software pipeline of one wave (single K and V buffers): the K rows of the next tile are requested as soon as
-    // the scores of the current tile have consumed K, its V rows as soon as the accumulation has consumed V, and the
-    // next request's query as soon as the last scores of the current request are done.  The requests stay in flight
-    // across the end-of-segment exchange below.  The first tile is requested before the plan is even rebuilt.
-    uint4 K[8], V[8], Q[4];
-    SlotInfo cur = slot_info(w, 0);
-    if (cur.req >= 0) {
-        ld.issue_k(cur.pg0, cur.pg1, K);
-        load_q(cur.req, Q);
-        ld.issue_v(cur.pg0, cur.pg1, V);
-    }
-    OMNI_STAMP(p, 2);
-
-    // Tile offsets and lengths of all requests (shared memory): needed for the segment bookkeeping only.
-    const Plan pl = attn_prologue<D>(p, &ps, E, w, kvh, first_len, true);
+    // Tile offsets and lengths of all requests, in shared memory.
+    const Plan pl = attn_prologue<D>(p, &ps, E, w, kvh);
     const int *Lc = E + p.plan.B + 1;
     OMNI_STAMP(p, 1);
     bool stamped = false;
 
     for (int range = w; range < pl.nranges; range += p.plan.nw) {
         const int start = range * pl.S, end = min(pl.C, start + pl.S);
-        int s = 0;                       // slot being computed; its loads are in flight
-        if (range != w) {                // a further range of this workgroup (more ranges than workgroups)
-            fetch_meta(range, 0);
-            first_b = p.ws.meta[(size_t)range * kWaves * p.slots_cap].x;
-            cur = slot_info(range, 0);
-            if (cur.req >= 0) {
-                ld.issue_k(cur.pg0, cur.pg1, K);
-                load_q(cur.req, Q);
-                ld.issue_v(cur.pg0, cur.pg1, V);
+        const int len = end - start;
+        const int first_b = plan_first_request(p.plan, &ps, E, start);
+
+        // ---- this wave's tiles: tile g = wave + 4*slot of the range, slot = 0 .. nk-1.  Lane s of the wave looks up
+        // everything about slot s (of the current group of 64 slots) once: the request, the tile's index inside the
+        // request and its physical pages.  The tile loop then only picks values out with v_readlane, so neither the
+        // block table nor the plan sits between two tiles, also across request boundaries.
+        const int nk = len > wave ? (len - wave + kWaves - 1) / kWaves : 0;
+        int4 meta = make_int4(-1, 0, 0, 0);                      // request, tile in request, page of tokens 0-15, 16-31
+        auto fetch_meta = [&](int first_slot) {
+            const int slot = first_slot + lane;
+            meta = make_int4(-1, 0, 0, 0);
+            if (slot < nk) {
+                const int pos = start + wave + kWaves * slot;
+                int lo = first_b, hi = p.plan.B;                 // E[lo] <= pos < E[hi]
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (E[mid] <= pos) lo = mid; else hi = mid;
+                }
+                const int t = pos - E[lo];
+                const int last_page = (Lc[lo] - 1) >> kLog2Ps;
+                const int32_t *bt = p.block_table + (size_t)lo * p.MB;
+                const int page = (t * kTile) >> kLog2Ps;
+                meta.x = lo; meta.y = t;
+                if (PS == 16 && page < last_page) {              // both pages exist: one 8-byte read (page is even)
+                    struct alignas(4) PagePair { int first, second; };   // rows of odd length keep 4-byte alignment
+                    const PagePair pp2 = *reinterpret_cast<const PagePair *>(bt + page);
+                    meta.z = pp2.first; meta.w = pp2.second;
+                } else {                                         // never read beyond the request's pages
+                    meta.z = bt[page]; meta.w = meta.z;
+                }
             }
+        };
+        fetch_meta(0);
+        struct SlotInfo { int req, tile, pg0, pg1; };
+        auto slot_info = [&](int slot) {
+            SlotInfo si{-1, 0, 0, 0};
+            if (slot >= nk) return si;
+            if ((slot & 63) == 0 && slot > 0) fetch_meta(slot);  // rare: more than 64 tiles per wave in a range
+            const int l = slot & 63;
+            si.req = __builtin_amdgcn_readlane(meta.x, l); si.tile = __builtin_amdgcn_readlane(meta.y, l);
+            si.pg0 = __builtin_amdgcn_readlane(meta.z, l); si.pg1 = __builtin_amdgcn_readlane(meta.w, l);
+            return si;
+        };
+
+        // Software pipeline of one wave (single K and V buffers): the K rows of the next tile are requested as soon
+        // as the scores of the current tile have consumed K, its V rows as soon as the accumulation has consumed V,
+        // and the next request's query as soon as the last scores of the current request are done.  The requests
+        // stay in flight across the end-of-segment exchange below.
+        uint4 K[8], V[8], Q[4];
+        int s = 0;                       // slot being computed; its loads are in flight
+        SlotInfo cur = slot_info(0);
+        if (cur.req >= 0) {
+            ld.issue_k(cur.pg0, cur.pg1, K);
+            load_q(cur.req, Q);
+            ld.issue_v(cur.pg0, cur.pg1, V);
         }
+        OMNI_STAMP(p, 2);
 
         int nstaged = 0;
         Segment staged0{}, staged1{};
-        int b = __builtin_amdgcn_readfirstlane(first_b);
+        int b = first_b;
         while (true) {
             const Segment seg = plan_segment(E, Lc, pl, b, range, start, end);
             MfmaState st;
@@ -263,7 +271,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
 #pragma unroll
             for (int e = 0; e < 8; ++e) st.acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             while (cur.req == seg.b) {
-                const SlotInfo nxt = slot_info(range, s + 1);
+                const SlotInfo nxt = slot_info(s + 1);
                 const bool more = nxt.req >= 0;
                 float sv[8];
                 mfma_scores(K, Q, sv, p.scale_log2);

@@ -10,7 +10,6 @@
 #include "omni_attn.h"
 #include "aux_kernels.hpp"
 #include "decode_mfma.hpp"
-#include "plan_kernel.hpp"
 #include "decode_valu.hpp"
 
 using namespace omni;
@@ -44,9 +43,7 @@ struct omni_handle_s {
     int max_ctx = 0;
     int nw = 1;                  // workgroups per KV head
     int r_cap = 0;               // bound on partial-result slots (range index + request index)
-    size_t off_arr = 0, off_meta = 0, off_ml = 0, off_o = 0, ws_bytes = 0;
-    int slots_cap = 1;           // tile slots per (range, wave) in the planner's tile lists
-    int ranges_cap = 1;          // ranges whose tile lists the workspace holds
+    size_t off_arr = 0, off_ml = 0, off_o = 0, ws_bytes = 0;
     void *ws = nullptr;
     size_t ws_given = 0;
     // profiling aid: event pairs around the partition kernel
@@ -67,21 +64,11 @@ struct omni_handle_s {
             const long long s = tune_force_partition / kTile;
             ranges = (tiles + s - 1) / s;
         }
-        {   // tile lists written by the plan kernel: bound the range length S by what the description allows
-            const long long tiles = (long long)d.batch * ((max_ctx + kTile - 1) / kTile);
-            long long s_cap = tune_force_partition > 0 ? tune_force_partition / kTile : (tiles + nw - 1) / nw;
-            const long long s_min = tune_min_partition / kTile;
-            if (tune_force_partition <= 0 && s_cap < s_min) s_cap = s_min;
-            if (s_cap < 1) s_cap = 1;
-            slots_cap = (int)((s_cap + kWaves - 1) / kWaves);
-            ranges_cap = (int)(ranges > nw ? ranges : nw);
-        }
         long long cap = ranges + d.batch;
         if (cap > 0x3fffffff) cap = 0x3fffffff;
         r_cap = (int)cap;
         off_arr = 256;
-        off_meta = align256(off_arr + (size_t)d.batch * d.num_kv_heads * sizeof(int32_t));
-        off_ml = align256(off_meta + (kernel == 2 ? (size_t)ranges_cap * kWaves * slots_cap * sizeof(int4) : 0));
+        off_ml = align256(off_arr + (size_t)d.batch * d.num_kv_heads * sizeof(int32_t));
         off_o = align256(off_ml + (size_t)r_cap * d.num_q_heads * sizeof(float2));
         ws_bytes = align256(off_o + (size_t)r_cap * d.num_q_heads * d.head_dim * sizeof(float));
     }
@@ -166,7 +153,7 @@ omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes) {
     if (!h || !dev_ptr) return OMNI_ERR_NULL;
     if (((uintptr_t)dev_ptr & 255) != 0 || bytes < h->ws_bytes) return OMNI_ERR_WORKSPACE;
     // The arrival counters of the in-kernel merge must start at zero; every call leaves them at zero again.
-    if (hipMemset(reinterpret_cast<char *>(dev_ptr) + h->off_arr, 0, h->off_meta - h->off_arr) != hipSuccess) {
+    if (hipMemset(reinterpret_cast<char *>(dev_ptr) + h->off_arr, 0, h->off_ml - h->off_arr) != hipSuccess) {
         (void)hipGetLastError();
         return OMNI_ERR_HIP;
     }
@@ -217,7 +204,6 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void 
     char *ws = reinterpret_cast<char *>(h->ws);
     p.ws.plan_words = reinterpret_cast<int32_t *>(ws);
     p.ws.arrivals = reinterpret_cast<int32_t *>(ws + h->off_arr);
-    p.ws.meta = reinterpret_cast<int4 *>(ws + h->off_meta);
     p.ws.part_ml = reinterpret_cast<float2 *>(ws + h->off_ml);
     p.ws.part_o = reinterpret_cast<float *>(ws + h->off_o);
     p.plan.B = d.batch;
@@ -228,7 +214,6 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void 
     p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
     p.log2_ps = ilog2(d.page_size);
     p.out_bf16 = d.out_dtype == OMNI_BF16;
-    p.slots_cap = h->slots_cap;
 #ifdef OMNI_TRACE
     p.trace = g_omni_trace;
 #endif
@@ -237,14 +222,8 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void 
     const size_t dyn = (size_t)(2 * d.batch + 1) * sizeof(int);     // tile offsets and lengths of the plan
     (void)hipGetLastError();
     const bool prof = (size_t)(2 * h->prof_used + 1) < h->prof_events.size();
-    if (prof && h->kernel != 2 && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
+    if (prof && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
     if (h->kernel == 2) {
-        // the plan kernel writes the tile lists outside the profiled region: the event pair brackets the attention kernel
-        const dim3 pgrid((unsigned)h->nw);
-        if (d.page_size == 16) plan_kernel<16><<<pgrid, kThreads, dyn, s>>>(p, h->nw);
-        else plan_kernel<32><<<pgrid, kThreads, dyn, s>>>(p, h->nw);
-        if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
-        if (prof && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
         if (d.page_size == 16) decode_mfma_kernel<16><<<grid, kThreads, dyn, s>>>(p);
         else decode_mfma_kernel<32><<<grid, kThreads, dyn, s>>>(p);
     } else if (d.kv_dtype == OMNI_BF16) {
