@@ -130,6 +130,19 @@ omni_status_t omni_kv_append(omni_handle_t h,
                              const void *k_new, const void *v_new, void *k_cache, void *v_cache,
                              const int32_t *block_table, const int32_t *positions, void *stream);
 
+/*
+ * One decode iteration of an autoregressive stage for the whole batch (Section 3.1: "one batched forward step for
+ * each iteration"; Section 2.2: the AR decoding loop adds one token per request): exactly omni_kv_append with
+ * positions[b] = context_lens[b] - 1 (requests of length 0 are skipped) followed by omni_paged_decode_attn, but as
+ * one kernel launch where the hardware path allows it: the workgroup that will read a request's last tile first
+ * writes the new K/V row into that page.  Same results, bit for bit, as the two separate calls.
+ * Errors: NULL, WORKSPACE, HIP.
+ */
+omni_status_t omni_decode_step(omni_handle_t h,
+                               const void *q, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                               const int32_t *block_table, const int32_t *context_lens,
+                               float scale, void *out, void *stream);
+
 /* Host-known part of the launch plan: which kernel (OMNI_TUNE_KERNEL value actually used), the data-independent
  * grid (workgroups) of the attention kernel, the grid of a separate merge kernel (0: the merge runs inside the
  * attention kernel, in the workgroup that finishes a request's last piece), the number of partial-result slots the

@@ -19,7 +19,7 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = (
     "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_set_workspace",
-    "omni_paged_decode_attn", "omni_kv_append", "omni_get_plan", "omni_status_string",
+    "omni_paged_decode_attn", "omni_kv_append", "omni_decode_step", "omni_get_plan", "omni_status_string",
     "omni_debug_last_plan", "omni_debug_gather", "omni_debug_profile_begin", "omni_debug_profile_end",
 )
 
@@ -55,6 +55,7 @@ def lib():
         L.omni_set_workspace.argtypes = [vp, vp, C.c_size_t]
         L.omni_paged_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_kv_append.argtypes = [vp] * 8
+        L.omni_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_get_plan.argtypes = [vp] + [i32p] * 5
         L.omni_status_string.argtypes = [C.c_int]; L.omni_status_string.restype = C.c_char_p
         L.omni_debug_last_plan.argtypes = [vp, i32p, vp]
@@ -137,6 +138,12 @@ class Handle:
     def omni_kv_append(self, k_new, v_new, k_cache, v_cache, block_table, positions, stream=None) -> None:
         _ck(lib().omni_kv_append(self._h, _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
                                  _ptr(positions), _stream(stream)), "omni_kv_append")
+
+    def omni_decode_step(self, q, k_new, v_new, k_cache, v_cache, block_table, context_lens, scale, out,
+                         stream=None) -> None:
+        _ck(lib().omni_decode_step(self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                   _ptr(block_table), _ptr(context_lens), C.c_float(float(scale)), _ptr(out),
+                                   _stream(stream)), "omni_decode_step")
 
     def omni_get_plan(self) -> dict:
         v = [C.c_int32() for _ in range(5)]

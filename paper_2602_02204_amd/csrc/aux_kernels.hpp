@@ -10,6 +10,7 @@ struct AppendParams {
     const int32_t *block_table, *positions;
     int B, Hkv, MB, log2_ps;
     int row_vecs;                    // 16-byte vectors per row (D * elem_size / 16)
+    int positions_are_lengths;       // positions[] holds context lengths: append at length - 1
 };
 
 // One thread per 16 bytes of one (request, KV head) row; K and V rows are copied bit for bit.
@@ -20,7 +21,7 @@ __global__ __launch_bounds__(kThreads) void kv_append_kernel(AppendParams p) {
     const int c = (int)(idx % p.row_vecs);
     const long long row = idx / p.row_vecs;
     const int g = (int)(row % p.Hkv), b = (int)(row / p.Hkv);
-    const int pos = p.positions[b];
+    const int pos = p.positions[b] - (p.positions_are_lengths ? 1 : 0);
     if (pos < 0) return;
     const int page = p.block_table[(size_t)b * p.MB + (pos >> p.log2_ps)];
     const int slot = pos & ((1 << p.log2_ps) - 1);

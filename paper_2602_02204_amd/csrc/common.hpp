@@ -26,6 +26,8 @@ struct AttnParams {
     const void *q;
     const void *k_cache;
     const void *v_cache;
+    const void *k_new;                  // fused decode step only (else null): rows to append at context_lens[b] - 1
+    const void *v_new;
     const int32_t *block_table;
     const int32_t *context_lens;
     void *out;
@@ -92,44 +94,63 @@ __device__ __forceinline__ bool count_arrival(const AttnParams &p, const Segment
     return old == seg.nparts - 1;
 }
 
-// All 256 threads: log-sum-exp merge of the request's pieces, in slot order, four pieces per round: all loads of a
-// round are issued before any is used, so a round costs one trip to memory, and no load depends on a loaded value.
-// Puts the arrival counter back to zero for the next call.
-template <int D>
-__device__ __forceinline__ void merge_request(const AttnParams &p, const Segment &seg, int kvh) {
+// All 256 threads: log-sum-exp merge of the request's pieces, in slot order.  Every thread owns up to kMergeIdx
+// output elements; the loads of kRound pieces for all of them are issued before any is used, so a round costs one
+// trip to memory, and no load depends on a loaded value.  Puts the arrival counter back to zero for the next
+// call.
+template <int D, int kMergeIdx, int kRound>
+__device__ __forceinline__ void merge_request_impl(const AttnParams &p, const Segment &seg, int kvh) {
     const int G = p.G, head0 = kvh * G, n = seg.nparts;
     const size_t out0 = ((size_t)seg.b * p.Hq + head0) * D;
-    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
-        const int g = idx / D;
-        float M = -INFINITY, num = 0.f, den = 0.f;
-        for (int j0 = 0; j0 < n; j0 += 4) {
-            float mj[4], lj[4], oj[4];
+    float M[kMergeIdx], num[kMergeIdx], den[kMergeIdx];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                lj[u] = 0.f; mj[u] = 0.f; oj[u] = 0.f;
-                if (j0 + u < n) {                                    // uniform
+    for (int i = 0; i < kMergeIdx; ++i) { M[i] = -INFINITY; num[i] = 0.f; den[i] = 0.f; }
+    for (int j0 = 0; j0 < n; j0 += kRound) {
+        float mj[kMergeIdx][kRound], lj[kMergeIdx][kRound], oj[kMergeIdx][kRound];
+#pragma unroll
+        for (int i = 0; i < kMergeIdx; ++i) {
+            const int idx = threadIdx.x + i * kThreads;
+            const int g = idx / D;
+#pragma unroll
+            for (int u = 0; u < kRound; ++u) {
+                lj[i][u] = 0.f; mj[i][u] = 0.f; oj[i][u] = 0.f;
+                if (idx < G * D && j0 + u < n) {
                     const size_t pi = (size_t)(seg.slot_first + j0 + u) * p.Hq + head0;
-                    mj[u] = dev_load(&p.ws.part_ml[pi + g].x);
-                    lj[u] = dev_load(&p.ws.part_ml[pi + g].y);
-                    oj[u] = dev_load(&p.ws.part_o[pi * D + idx]);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (lj[u] > 0.f) {
-                    const float Mn = fmaxf(M, mj[u]);
-                    const float a = fast_exp2(M - Mn);               // 0 while M is still -inf
-                    const float w = fast_exp2(mj[u] - Mn);
-                    num = num * a + w * oj[u];
-                    den = den * a + w * lj[u];
-                    M = Mn;
+                    mj[i][u] = dev_load(&p.ws.part_ml[pi + g].x);
+                    lj[i][u] = dev_load(&p.ws.part_ml[pi + g].y);
+                    oj[i][u] = dev_load(&p.ws.part_o[pi * D + idx]);
                 }
             }
         }
-        store_out(p, out0 + idx, den > 0.f ? num / den : 0.f);
+#pragma unroll
+        for (int i = 0; i < kMergeIdx; ++i) {
+#pragma unroll
+            for (int u = 0; u < kRound; ++u) {
+                if (lj[i][u] > 0.f) {
+                    const float Mn = fmaxf(M[i], mj[i][u]);
+                    const float a = fast_exp2(M[i] - Mn);            // 0 while M is still -inf
+                    const float w = fast_exp2(mj[i][u] - Mn);
+                    num[i] = num[i] * a + w * oj[i][u];
+                    den[i] = den[i] * a + w * lj[i][u];
+                    M[i] = Mn;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kMergeIdx; ++i) {
+        const int idx = threadIdx.x + i * kThreads;
+        if (idx < G * D) store_out(p, out0 + idx, den[i] > 0.f ? num[i] / den[i] : 0.f);
     }
     if (threadIdx.x == 0)
         __hip_atomic_store(&p.ws.arrivals[seg.b * p.Hkv + kvh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int D>
+__device__ __forceinline__ void merge_request(const AttnParams &p, const Segment &seg, int kvh) {
+    // up to 8 heads: 4 (or 2) output elements per thread, four pieces per round; up to 16 heads: twice the elements, two pieces
+    if (p.G * D <= 4 * kThreads) merge_request_impl<D, 4, 4>(p, seg, kvh);
+    else merge_request_impl<D, kMaxGroup * D / kThreads, 2>(p, seg, kvh);
 }
 
 // Combine the four waves' (m, l, o) of one segment and finish it.  Must be called by all 256 threads after the waves

@@ -38,6 +38,8 @@ __device__ __forceinline__ uint32_t dword_of(const uint4 &v, int w) {
     return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w));
 }
 
+constexpr int kAppendFlag = 1 << 30;   // in a slot's tile word: the tile holds the token to append (fused decode step)
+
 // token of k-slot r (0..7) of lane group j inside a 32-token tile
 __device__ __forceinline__ int slot_token(int j, int r) { return (r < 4) ? 4 * j + r : 16 + 4 * j + (r - 4); }
 
@@ -225,7 +227,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 const int last_page = (Lc[lo] - 1) >> kLog2Ps;
                 const int32_t *bt = p.block_table + (size_t)lo * p.MB;
                 const int page = (t * kTile) >> kLog2Ps;
-                meta.x = lo; meta.y = t;
+                meta.x = lo;
+                meta.y = t | ((p.k_new != nullptr && t == ((Lc[lo] - 1) >> kLog2Tile)) ? kAppendFlag : 0);
                 if (PS == 16 && page < last_page) {              // both pages exist: one 8-byte read (page is even)
                     struct alignas(4) PagePair { int first, second; };   // rows of odd length keep 4-byte alignment
                     const PagePair pp2 = *reinterpret_cast<const PagePair *>(bt + page);
@@ -236,15 +239,33 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             }
         };
         fetch_meta(0);
-        struct SlotInfo { int req, tile, pg0, pg1; };
+        struct SlotInfo { int req, tile, pg0, pg1; bool append; };
         auto slot_info = [&](int slot) {
-            SlotInfo si{-1, 0, 0, 0};
+            SlotInfo si{-1, 0, 0, 0, false};
             if (slot >= nk) return si;
             if ((slot & 63) == 0 && slot > 0) fetch_meta(slot);  // rare: more than 64 tiles per wave in a range
             const int l = slot & 63;
-            si.req = __builtin_amdgcn_readlane(meta.x, l); si.tile = __builtin_amdgcn_readlane(meta.y, l);
+            const int ty = __builtin_amdgcn_readlane(meta.y, l);
+            si.req = __builtin_amdgcn_readlane(meta.x, l); si.tile = ty & ~kAppendFlag; si.append = (ty & kAppendFlag) != 0;
             si.pg0 = __builtin_amdgcn_readlane(meta.z, l); si.pg1 = __builtin_amdgcn_readlane(meta.w, l);
             return si;
+        };
+        // Fused decode step: the tile that holds the request's last token gets the new K/V row written into its page
+        // (a bit copy, lanes 0-15 the K row, lanes 16-31 the V row) before the tile is requested; the wave waits for
+        // the write to be acknowledged, so the loads that follow see it.
+        auto append_row = [&](const SlotInfo &si) {
+            const int pos = Lc[si.req] - 1;
+            const int pg = (PS == 16 && (pos & 16)) ? si.pg1 : si.pg0;
+            const size_t row = (size_t)pg * ld.page_stride + (size_t)(pos & (PS - 1)) * (D * 2);
+            if (lane < 32) {
+                const bool is_v = lane >= 16;
+                const char *src = reinterpret_cast<const char *>(is_v ? p.v_new : p.k_new) +
+                                  ((size_t)si.req * p.Hkv + kvh) * (D * 2) + (lane & 15) * 16;
+                char *dst = const_cast<char *>(is_v ? ld.vbase : ld.kbase) + row + (lane & 15) * 16;
+                *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_s_waitcnt(0);           // all counters: the row is in memory before the tile is read
         };
 
         // Software pipeline of one wave (single K and V buffers): the K rows of the next tile are requested as soon
@@ -255,6 +276,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         int s = 0;                       // slot being computed; its loads are in flight
         SlotInfo cur = slot_info(0);
         if (cur.req >= 0) {
+            if (cur.append) append_row(cur);
             ld.issue_k(cur.pg0, cur.pg1, K);
             load_q(cur.req, Q);
             ld.issue_v(cur.pg0, cur.pg1, V);
@@ -277,6 +299,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 mfma_scores(K, Q, sv, p.scale_log2);
                 if (!stamped) { OMNI_STAMP(p, 3); stamped = true; }
                 if (more) {
+                    if (nxt.append) append_row(nxt);
                     ld.issue_k(nxt.pg0, nxt.pg1, K);
                     if (nxt.req != seg.b) load_q(nxt.req, Q);
                 }

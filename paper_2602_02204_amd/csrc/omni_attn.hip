@@ -190,9 +190,14 @@ void launch_valu(const AttnParams &p, dim3 grid, size_t dyn, hipStream_t s) {
 
 extern "C" {
 
-omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
-                                     const int32_t *block_table, const int32_t *context_lens, float scale, void *out,
-                                     void *stream) {
+static omni_status_t launch_append(omni_handle_t h, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                                   const int32_t *block_table, const int32_t *positions, int positions_are_lengths,
+                                   void *stream);
+
+// The attention launch shared by omni_paged_decode_attn (k_new = v_new = null) and omni_decode_step.
+static omni_status_t launch_attention(omni_handle_t h, const void *q, const void *k_new, const void *v_new,
+                                      const void *k_cache, const void *v_cache, const int32_t *block_table,
+                                      const int32_t *context_lens, float scale, void *out, void *stream) {
     if (!h || !q || !k_cache || !v_cache || !block_table || !context_lens || !out) return OMNI_ERR_NULL;
     if (!h->ws || h->ws_given < h->ws_bytes) return OMNI_ERR_WORKSPACE;
     const omni_attn_desc_t &d = h->d;
@@ -200,6 +205,7 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void 
 
     AttnParams p;
     p.q = q; p.k_cache = k_cache; p.v_cache = v_cache;
+    p.k_new = k_new; p.v_new = v_new;
     p.block_table = block_table; p.context_lens = context_lens; p.out = out;
     char *ws = reinterpret_cast<char *>(h->ws);
     p.ws.plan_words = reinterpret_cast<int32_t *>(ws);
@@ -242,8 +248,33 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void 
     return OMNI_OK;
 }
 
+omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
+                                     const int32_t *block_table, const int32_t *context_lens, float scale, void *out,
+                                     void *stream) {
+    return launch_attention(h, q, nullptr, nullptr, k_cache, v_cache, block_table, context_lens, scale, out, stream);
+}
+
+omni_status_t omni_decode_step(omni_handle_t h, const void *q, const void *k_new, const void *v_new, void *k_cache,
+                               void *v_cache, const int32_t *block_table, const int32_t *context_lens, float scale,
+                               void *out, void *stream) {
+    if (!h || !k_new || !v_new) return OMNI_ERR_NULL;
+    if (h->kernel == 2)          // the MFMA kernel writes the new rows itself, just before it reads their tiles
+        return launch_attention(h, q, k_new, v_new, k_cache, v_cache, block_table, context_lens, scale, out, stream);
+    if (!q || !k_cache || !v_cache || !block_table || !context_lens || !out) return OMNI_ERR_NULL;
+    if (!h->ws || h->ws_given < h->ws_bytes) return OMNI_ERR_WORKSPACE;
+    const omni_status_t st = launch_append(h, k_new, v_new, k_cache, v_cache, block_table, context_lens, 1, stream);
+    if (st != OMNI_OK) return st;
+    return launch_attention(h, q, nullptr, nullptr, k_cache, v_cache, block_table, context_lens, scale, out, stream);
+}
+
 omni_status_t omni_kv_append(omni_handle_t h, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
                              const int32_t *block_table, const int32_t *positions, void *stream) {
+    return launch_append(h, k_new, v_new, k_cache, v_cache, block_table, positions, 0, stream);
+}
+
+static omni_status_t launch_append(omni_handle_t h, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                                   const int32_t *block_table, const int32_t *positions, int positions_are_lengths,
+                                   void *stream) {
     if (!h || !k_new || !v_new || !k_cache || !v_cache || !block_table || !positions) return OMNI_ERR_NULL;
     const omni_attn_desc_t &d = h->d;
     AppendParams p;
@@ -251,6 +282,7 @@ omni_status_t omni_kv_append(omni_handle_t h, const void *k_new, const void *v_n
     p.block_table = block_table; p.positions = positions;
     p.B = d.batch; p.Hkv = d.num_kv_heads; p.MB = d.max_blocks_per_seq; p.log2_ps = ilog2(d.page_size);
     p.row_vecs = d.head_dim * (d.kv_dtype == OMNI_BF16 ? 2 : 4) / 16;
+    p.positions_are_lengths = positions_are_lengths;
     const long long total = (long long)p.B * p.Hkv * p.row_vecs;
     const dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
     (void)hipGetLastError();

@@ -157,6 +157,41 @@ def test_kv_append_and_gather_bit_exact(dtype, D, ps):
     assert np.max(np.abs(got - oracle_out(wl))) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("name,kw", [("thinker", dict(batch=10)), ("talker", dict(batch=40)), ("mixed", dict(batch=20, len_div=4))])
+@pytest.mark.parametrize("kernel", [omni.KERNEL_MFMA, omni.KERNEL_VALU], ids=["mfma", "valu"])
+@pytest.mark.parametrize("force_pl", [0, 64], ids=["plan", "pl64"])
+def test_decode_step_equals_append_then_attention(name, kw, kernel, force_pl):
+    """omni_decode_step == omni_kv_append at context_lens - 1 followed by omni_paged_decode_attn: same pool bits, same
+    output bits; and both match the oracle's append + attention."""
+    wl = W.make(name, append=True, **kw)
+    lens = wl.context_lens.copy()
+    lens[0] = 0                                        # an empty request: nothing is appended for it
+    wl.context_lens = lens
+    wl.positions = (lens - 1).astype(np.int32)
+    tuning = {omni.OMNI_TUNE_KERNEL: kernel}
+    if force_pl:
+        tuning[omni.OMNI_TUNE_FORCE_PARTITION] = force_pl
+    two = DeviceBatch(wl, tuning=tuning)
+    two.context_lens.copy_(torch.from_numpy(lens).cuda())
+    two.positions.copy_(torch.from_numpy(wl.positions).cuda())
+    two.append()
+    out_two = two.attend().copy()
+    one = DeviceBatch(wl, tuning=tuning)
+    one.context_lens.copy_(torch.from_numpy(lens).cuda())
+    one.out.fill_(float("nan"))
+    one.h.omni_decode_step(one.q, one.k_new, one.v_new, one.k_cache, one.v_cache, one.block_table, one.context_lens,
+                           float(wl.scale), one.out)
+    torch.cuda.synchronize()
+    out_one = one.out.float().cpu().numpy().astype(np.float64)
+    as_bytes = lambda a: a.view(np.uint8)
+    assert np.array_equal(as_bytes(bits_of(one.k_cache)), as_bytes(bits_of(two.k_cache)))
+    assert np.array_equal(as_bytes(bits_of(one.v_cache)), as_bytes(bits_of(two.v_cache)))
+    assert np.array_equal(out_one, out_two)
+    oracle.kv_append(wl.k_new, wl.v_new, wl.k_cache, wl.v_cache, wl.block_table, wl.positions, wl.dtype)
+    assert np.array_equal(as_bytes(bits_of(one.k_cache)), as_bytes(wl.k_cache))
+    assert np.max(np.abs(out_one - oracle_out(wl))) <= TOL[wl.dtype]
+
+
 @pytest.mark.parametrize("kernel", [omni.KERNEL_MFMA, omni.KERNEL_VALU], ids=["mfma", "valu"])
 def test_bit_identical_rerun_and_page_permutation(kernel):
     wl = W.make("thinker", batch=6)
