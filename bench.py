@@ -1,8 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the decode hot path on one MI355X.
 
-A step = one pass of the whole hot path over one synthetic batch: omni_kv_append (the new token's K/V rows into their
-pages) followed by omni_paged_decode_attn (device-side plan, split-context partition kernel, log-sum-exp merge).
+A step = one pass of the whole hot path over one synthetic batch: omni_decode_step, i.e. the new token's K/V rows
+written into their pages (kv_append), the device-side plan, the split-context attention over the paged cache and the
+log-sum-exp merge (two kernel launches: attention with the append fused in, then the merge).  --unfused times
+omni_kv_append + omni_paged_decode_attn instead (three launches).
 Inputs are resident in HBM before the timed region.  The KV pools are replicated and the steps rotate over the
 replicas so that the 256 MB memory-side cache cannot serve the reads of the next step.
 
@@ -37,6 +39,7 @@ def parse():
     ap.add_argument("--target-wgs", type=int, default=0)
     ap.add_argument("--min-partition", type=int, default=0)
     ap.add_argument("--force-partition", type=int, default=0)
+    ap.add_argument("--unfused", action="store_true", help="time omni_kv_append + omni_paged_decode_attn instead")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
 
@@ -93,10 +96,16 @@ def main():
     scale = float(wl.scale)
     stream = torch.cuda.current_stream()
 
-    def step(i):
+    def step_two_launches(i):
         r = i % R
         h.omni_kv_append(k_new, v_new, kc[r], vc[r], bt, pos, stream)
         h.omni_paged_decode_attn(q, kc[r], vc[r], bt, lens, scale, out, stream)
+
+    def step_fused(i):
+        r = i % R
+        h.omni_decode_step(q, k_new, v_new, kc[r], vc[r], bt, lens, scale, out, stream)
+
+    step = step_two_launches if args.unfused else step_fused
 
     for r in range(R):                       # every replica holds the appended token before anything is timed
         h.omni_kv_append(k_new, v_new, kc[r], vc[r], bt, pos, stream)
@@ -122,20 +131,18 @@ def main():
     k_med_ms = float(np.median(kernel_ms))
     achieved = kv_bytes / (k_avg_ms * 1e-3) / 1e9
 
-    # ---- same K steps without the event pairs and on a single replica (cache-warm), for the record
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    for i in range(K):
-        step(i)
-    torch.cuda.synchronize()
-    t3 = time.perf_counter()
-    ms_noevents = (t3 - t2) * 1e3 / K
-    t4 = time.perf_counter()
-    for i in range(K):
-        step(0)
-    torch.cuda.synchronize()
-    t5 = time.perf_counter()
-    ms_warm = (t5 - t4) * 1e3 / K
+    # ---- for the record: the same K steps without the event pairs, as two launches, and on a single replica
+    def timed(fn, fixed_replica=False):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for i in range(K):
+            fn(0 if fixed_replica else i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - a) * 1e3 / K
+
+    ms_noevents = timed(step)
+    ms_other = timed(step_fused if args.unfused else step_two_launches)
+    ms_warm = timed(step, fixed_replica=True)
 
     # ---- validity: sampled rows of the last step against the oracle (the appended token is in the pools now)
     import oracle
@@ -170,7 +177,8 @@ def main():
                "kv_gbs": kv_bytes / cpu_s / 1e9}
 
     result = {
-        "metric": "decode-attention tokens/s (one token per request per step; kv_append + paged decode attention)",
+        "metric": "decode-attention tokens/s (one token per request per step; kv_append + paged decode attention, "
+                  + ("separate append kernel)" if args.unfused else "append fused into the attention kernel)"),
         "value": tokens_per_s,
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -194,7 +202,10 @@ def main():
                      "kernel_avg_us": k_avg_ms * 1e3, "kernel_median_us": k_med_ms * 1e3,
                      "algorithmic_bytes_per_launch": kv_bytes},
         "cpu_baseline": cpu,
-        "extra": {"ms_per_step_without_event_pairs": ms_noevents, "ms_per_step_single_replica_cache_warm": ms_warm,
+        "extra": {"ms_per_step_without_event_pairs": ms_noevents,
+                  ("ms_per_step_fused" if args.unfused else "ms_per_step_separate_append"): ms_other,
+                  "ms_per_step_single_replica_cache_warm": ms_warm,
+                  "kv_gbs_cache_warm": kv_bytes / (ms_warm * 1e-3) / 1e9,
                   "parity_max_abs_err_sampled": max_err},
     }
     print(json.dumps(result))

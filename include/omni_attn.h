@@ -100,9 +100,8 @@ omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value);
 omni_status_t omni_workspace_bytes(omni_handle_t h, size_t *bytes);
 
 /* Hand the library a caller-owned device buffer of at least omni_workspace_bytes, 256-byte aligned.
- * The library keeps the pointer and clears a few KB of counters in it with a synchronous hipMemset (the one place
- * outside omni_debug_* where the library blocks); every attention call leaves those counters cleared again, so the
- * buffer must not be shared by calls that run concurrently.  Errors: NULL, WORKSPACE, HIP. */
+ * The library keeps the pointer only; contents need no initialisation.  The buffer must not be shared by calls that
+ * run concurrently.  Errors: NULL, WORKSPACE. */
 omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes);
 
 /*
@@ -111,7 +110,7 @@ omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes);
  * Accumulation is fp32.  The batch's context, laid end to end in 32-token tiles, is cut on the device into equal
  * ranges, one per workgroup (split-context / flash-decoding with an online softmax per piece); a request that is cut
  * by a range boundary is put together again by a log-sum-exp merge.  Both are exact re-associations of the definition
- * above.  One kernel launch.  Writes `out` and the workspace, nothing else.
+ * above.  Two kernel launches (attention, merge).  Writes `out` and the workspace, nothing else.
  * For a fixed handle and tuning the result is bit-identical from run to run and under any physical page permutation.
  * Errors: NULL, WORKSPACE, HIP.
  */
@@ -133,9 +132,10 @@ omni_status_t omni_kv_append(omni_handle_t h,
 /*
  * One decode iteration of an autoregressive stage for the whole batch (Section 3.1: "one batched forward step for
  * each iteration"; Section 2.2: the AR decoding loop adds one token per request): exactly omni_kv_append with
- * positions[b] = context_lens[b] - 1 (requests of length 0 are skipped) followed by omni_paged_decode_attn, but as
- * one kernel launch where the hardware path allows it: the workgroup that will read a request's last tile first
- * writes the new K/V row into that page.  Same results, bit for bit, as the two separate calls.
+ * positions[b] = context_lens[b] - 1 (requests of length 0 are skipped) followed by omni_paged_decode_attn, but with
+ * the append fused into the attention kernel where the hardware path allows it (bf16, head_dim 128): the workgroup
+ * that will read a request's last tile first writes the new K/V row into that page.  Same results, bit for bit, as
+ * the two separate calls.
  * Errors: NULL, WORKSPACE, HIP.
  */
 omni_status_t omni_decode_step(omni_handle_t h,
@@ -144,9 +144,8 @@ omni_status_t omni_decode_step(omni_handle_t h,
                                float scale, void *out, void *stream);
 
 /* Host-known part of the launch plan: which kernel (OMNI_TUNE_KERNEL value actually used), the data-independent
- * grid (workgroups) of the attention kernel, the grid of a separate merge kernel (0: the merge runs inside the
- * attention kernel, in the workgroup that finishes a request's last piece), the number of partial-result slots the
- * workspace is sized for, and threads per workgroup.  The range length itself is chosen on the device from
+ * grid (workgroups) of the attention kernel, the grid of the merge kernel that follows it, the number of
+ * partial-result slots the workspace is sized for, and threads per workgroup.  The range length itself is chosen on the device from
  * context_lens; omni_debug_last_plan reads it back. */
 omni_status_t omni_get_plan(omni_handle_t h, int32_t *kernel, int32_t *partition_grid, int32_t *merge_grid,
                             int32_t *max_request_parts, int32_t *threads_per_workgroup);

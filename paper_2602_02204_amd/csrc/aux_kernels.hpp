@@ -1,8 +1,77 @@
-// KV append and the debug gather.
+// Log-sum-exp merge of split requests, KV append, and the debug gather.
 #pragma once
 #include "common.hpp"
 
 namespace omni {
+
+// Merge kernel: one workgroup per (request, KV head), launched right after the attention kernel.  It rebuilds the
+// plan from context_lens (the same deterministic function the attention kernel used), and for a request that was cut
+// by range boundaries combines its partial-result slots, in slot order:
+//     out = sum_j 2^(m_j - M) o_j / sum_j 2^(m_j - M) l_j,   M = max_j m_j,   pieces with l_j = 0 skipped.
+// Requests inside one range (finished by the attention kernel) and empty requests return at once.
+// Every thread owns up to kMergeIdx output elements; the loads of kRound pieces for all of them are issued before any
+// is used, so a round costs one trip to memory and no load depends on a loaded value.
+template <int D, int kMergeIdx, int kRound>
+__device__ __forceinline__ void merge_request(const AttnParams &p, int b, int kvh, int slot_first, int n) {
+    const int G = p.G, head0 = kvh * G;
+    const size_t out0 = ((size_t)b * p.Hq + head0) * D;
+    float M[kMergeIdx], num[kMergeIdx], den[kMergeIdx];
+#pragma unroll
+    for (int i = 0; i < kMergeIdx; ++i) { M[i] = -INFINITY; num[i] = 0.f; den[i] = 0.f; }
+    for (int j0 = 0; j0 < n; j0 += kRound) {
+        float2 ml[kMergeIdx][kRound];
+        float oj[kMergeIdx][kRound];
+#pragma unroll
+        for (int i = 0; i < kMergeIdx; ++i) {
+            const int idx = threadIdx.x + i * kThreads;
+            const int g = idx / D;
+#pragma unroll
+            for (int u = 0; u < kRound; ++u) {
+                ml[i][u] = make_float2(0.f, 0.f); oj[i][u] = 0.f;
+                if (idx < G * D && j0 + u < n) {
+                    const size_t pi = (size_t)(slot_first + j0 + u) * p.Hq + head0;
+                    ml[i][u] = p.ws.part_ml[pi + g];
+                    oj[i][u] = p.ws.part_o[pi * D + idx];
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kMergeIdx; ++i) {
+#pragma unroll
+            for (int u = 0; u < kRound; ++u) {
+                if (ml[i][u].y > 0.f) {
+                    const float Mn = fmaxf(M[i], ml[i][u].x);
+                    const float a = fast_exp2(M[i] - Mn);            // 0 while M is still -inf
+                    const float w = fast_exp2(ml[i][u].x - Mn);
+                    num[i] = num[i] * a + w * oj[i][u];
+                    den[i] = den[i] * a + w * ml[i][u].y;
+                    M[i] = Mn;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kMergeIdx; ++i) {
+        const int idx = threadIdx.x + i * kThreads;
+        if (idx < G * D) store_out(p, out0 + idx, den[i] > 0.f ? num[i] / den[i] : 0.f);
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void merge_kernel(AttnParams p) {
+    __shared__ PlanSmem ps;
+    extern __shared__ int E[];                               // E[B + 1] tile offsets, then Lc[B] lengths
+    const Plan pl = plan_build(p.context_lens, p.plan, &ps, E, E + p.plan.B + 1, [](int) {});
+    const int b = blockIdx.x / p.Hkv, kvh = blockIdx.x - b * p.Hkv;
+    const int e0 = E[b], e1 = E[b + 1];
+    if (e1 == e0) return;                                    // empty request: its zero row is already written
+    const int first_range = e0 / pl.S, last_range = (e1 - 1) / pl.S;
+    const int n = last_range - first_range + 1;
+    if (n == 1) return;                                      // finished by the attention kernel
+    // up to 8 heads of 128: 4 output elements per thread, four pieces per round; above: twice the elements, two pieces
+    if (p.G * D <= 4 * kThreads) merge_request<D, 4, 4>(p, b, kvh, first_range + b, n);
+    else merge_request<D, kMaxGroup * D / kThreads, 2>(p, b, kvh, first_range + b, n);
+}
 
 struct AppendParams {
     const void *k_new, *v_new;

@@ -17,7 +17,6 @@ constexpr float kLog2e = 1.4426950408889634f;
 //   o_off                    per (slot, query head): unnormalised output row, D floats
 struct Workspace {
     int32_t *plan_words;
-    int32_t *arrivals;
     float2 *part_ml;
     float *part_o;
 };
@@ -71,108 +70,39 @@ struct CombineSmem {
     float o[kWaves][kMaxGroup][D + 4];
     float m[kWaves][kMaxGroup];
     float l[kWaves][kMaxGroup];
-    int flag;                          // set when this workgroup is the last partition of its (request, KV head) to arrive
 };
-
-// Relaxed device-scope accesses: coherent across the compute dies without a cache-wide fence.
-__device__ __forceinline__ void dev_store(float *ptr, float v) {
-    __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float dev_load(const float *ptr) {
-    return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 __device__ __forceinline__ void store_out(const AttnParams &p, size_t index, float v) {
     if (p.out_bf16) reinterpret_cast<uint16_t *>(p.out)[index] = float_to_bf16_rne(v);
     else reinterpret_cast<float *>(p.out)[index] = v;
 }
 
-// One thread: count this workgroup's arrival for the request of `seg`; true if it is the last piece to arrive.
-__device__ __forceinline__ bool count_arrival(const AttnParams &p, const Segment &seg, int kvh) {
-    const int old = __hip_atomic_fetch_add(&p.ws.arrivals[seg.b * p.Hkv + kvh], 1, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-    return old == seg.nparts - 1;
-}
-
-// All 256 threads: log-sum-exp merge of the request's pieces, in slot order.  Every thread owns up to kMergeIdx
-// output elements; the loads of kRound pieces for all of them are issued before any is used, so a round costs one
-// trip to memory, and no load depends on a loaded value.  Puts the arrival counter back to zero for the next
-// call.
-template <int D, int kMergeIdx, int kRound>
-__device__ __forceinline__ void merge_request_impl(const AttnParams &p, const Segment &seg, int kvh) {
-    const int G = p.G, head0 = kvh * G, n = seg.nparts;
-    const size_t out0 = ((size_t)seg.b * p.Hq + head0) * D;
-    float M[kMergeIdx], num[kMergeIdx], den[kMergeIdx];
-#pragma unroll
-    for (int i = 0; i < kMergeIdx; ++i) { M[i] = -INFINITY; num[i] = 0.f; den[i] = 0.f; }
-    for (int j0 = 0; j0 < n; j0 += kRound) {
-        float mj[kMergeIdx][kRound], lj[kMergeIdx][kRound], oj[kMergeIdx][kRound];
-#pragma unroll
-        for (int i = 0; i < kMergeIdx; ++i) {
-            const int idx = threadIdx.x + i * kThreads;
-            const int g = idx / D;
-#pragma unroll
-            for (int u = 0; u < kRound; ++u) {
-                lj[i][u] = 0.f; mj[i][u] = 0.f; oj[i][u] = 0.f;
-                if (idx < G * D && j0 + u < n) {
-                    const size_t pi = (size_t)(seg.slot_first + j0 + u) * p.Hq + head0;
-                    mj[i][u] = dev_load(&p.ws.part_ml[pi + g].x);
-                    lj[i][u] = dev_load(&p.ws.part_ml[pi + g].y);
-                    oj[i][u] = dev_load(&p.ws.part_o[pi * D + idx]);
-                }
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < kMergeIdx; ++i) {
-#pragma unroll
-            for (int u = 0; u < kRound; ++u) {
-                if (lj[i][u] > 0.f) {
-                    const float Mn = fmaxf(M[i], mj[i][u]);
-                    const float a = fast_exp2(M[i] - Mn);            // 0 while M is still -inf
-                    const float w = fast_exp2(mj[i][u] - Mn);
-                    num[i] = num[i] * a + w * oj[i][u];
-                    den[i] = den[i] * a + w * lj[i][u];
-                    M[i] = Mn;
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < kMergeIdx; ++i) {
-        const int idx = threadIdx.x + i * kThreads;
-        if (idx < G * D) store_out(p, out0 + idx, den[i] > 0.f ? num[i] / den[i] : 0.f);
-    }
-    if (threadIdx.x == 0)
-        __hip_atomic_store(&p.ws.arrivals[seg.b * p.Hkv + kvh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
+// One element of a finished segment: the normalised output if the request lies inside one range, else the
+// unnormalised value (plus, once per head, the running max and sum) into the segment's partial-result slot.  The
+// merge kernel that follows in the stream puts the slots of a request together; the kernel boundary between the two
+// is what makes rows written on one compute die visible to a workgroup running on another (their L2 caches are not
+// coherent with each other, and doing the exchange inside one kernel needs device-scope release/acquire fences that
+// write back and invalidate a whole L2: measured at +40 % kernel time, and without them stale rows were observed).
 template <int D>
-__device__ __forceinline__ void merge_request(const AttnParams &p, const Segment &seg, int kvh) {
-    // up to 8 heads: 4 (or 2) output elements per thread, four pieces per round; up to 16 heads: twice the elements, two pieces
-    if (p.G * D <= 4 * kThreads) merge_request_impl<D, 4, 4>(p, seg, kvh);
-    else merge_request_impl<D, kMaxGroup * D / kThreads, 2>(p, seg, kvh);
+__device__ __forceinline__ void store_segment_element(const AttnParams &p, const Segment &seg, int head0, int idx,
+                                                      float M, float num, float den) {
+    if (seg.nparts == 1) {
+        store_out(p, ((size_t)seg.b * p.Hq + head0) * D + idx, den > 0.f ? num / den : 0.f);
+    } else {
+        const size_t pi = (size_t)seg.slot * p.Hq + head0;
+        p.ws.part_o[pi * D + idx] = num;
+        if (idx % D == 0) p.ws.part_ml[pi + idx / D] = make_float2(M, den);
+    }
 }
 
-// Combine the four waves' (m, l, o) of one segment and finish it.  Must be called by all 256 threads after the waves
+// Combine the four waves' (m, l, o) of one segment and store it.  Must be called by all 256 threads after the waves
 // have filled `sm` (this function synchronises first, and again before it returns so that `sm` may be refilled).
-//   - A request that lies inside one range gets its normalised output row at once.
-//   - Otherwise the unnormalised row and (m, l) go to the segment's workspace slot, and the workgroup that arrives
-//     last for its (request, KV head) performs the log-sum-exp merge over the request's slots, in slot order:
-//         out = sum_j 2^(m_j - M) o_j / sum_j 2^(m_j - M) l_j,  M = max_j m_j,  empty pieces (l_j = 0) skipped.
-//     "Last" is decided by an arrival counter: a workgroup writes its partial rows, waits for the writes to be
-//     acknowledged, then adds one; the workgroup that reads nparts-1 merges and puts the counter back to zero.
-//     Nobody waits for anybody, so the scheme cannot hang; the result does not depend on which workgroup merges.
-//     The partial rows cross between compute dies whose L2 caches are not coherent with each other.  A device-scope
-//     fence would write back and invalidate a whole L2 per workgroup (measured: 4x the kernel time); instead every
-//     access to the partial rows and to the counter is a relaxed device-scope atomic (sc1 loads and stores), which
-//     goes to the coherence point without touching the rest of the cache.
 template <int D>
 __device__ __forceinline__ void wg_combine_and_store(CombineSmem<D> &sm, const AttnParams &p, const Segment &seg,
                                                      int kvh) {
-    __syncthreads();
+    lds_barrier();
     const int G = p.G;
     const int head0 = kvh * G;
-    const size_t out0 = ((size_t)seg.b * p.Hq + head0) * D;
     for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
         const int g = idx / D, d = idx - g * D;
         float M = -INFINITY;
@@ -188,27 +118,9 @@ __device__ __forceinline__ void wg_combine_and_store(CombineSmem<D> &sm, const A
                 den += a * sm.l[w][g];
             }
         }
-        if (seg.nparts == 1) {
-            store_out(p, out0 + idx, den > 0.f ? num / den : 0.f);
-        } else {
-            const size_t pi = (size_t)seg.slot * p.Hq + head0;
-            dev_store(&p.ws.part_o[pi * D + idx], num);
-            if (d == 0) {
-                dev_store(&p.ws.part_ml[pi + g].x, M);
-                dev_store(&p.ws.part_ml[pi + g].y, den);
-            }
-        }
+        store_segment_element<D>(p, seg, head0, idx, M, num, den);
     }
-    // The barrier's workgroup-scope release makes every wave wait until its device-scope stores above are
-    // acknowledged, so they are globally visible before the arrival is counted.
-    __syncthreads();
-    if (seg.nparts == 1) return;                                     // uniform
-
-    if (threadIdx.x == 0) sm.flag = count_arrival(p, seg, kvh);
-    __syncthreads();
-    const bool last = sm.flag;
-    __syncthreads();                                                 // flag may be rewritten by the next segment
-    if (last) merge_request<D>(p, seg, kvh);                         // uniform
+    lds_barrier();
 }
 
 // blockIdx -> (workgroup index w within its KV head, KV head).  Workgroups are dealt to the eight compute dies

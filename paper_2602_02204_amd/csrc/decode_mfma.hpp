@@ -149,16 +149,11 @@ __device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], M
     }
 }
 
-struct ArrivalSmem {
-    int last[2];     // this workgroup is the last piece to arrive for its first / second shared request
-};
-
 template <int PS>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     __shared__ CombineSmem<D> sm;
-    __shared__ ArrivalSmem stage;
     __shared__ PlanSmem ps;
     extern __shared__ int E[];                               // E[B + 1] tile offsets, then Lc[B] lengths
 
@@ -206,6 +201,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         const int start = range * pl.S, end = min(pl.C, start + pl.S);
         const int len = end - start;
         const int first_b = plan_first_request(p.plan, &ps, E, start);
+        OMNI_STAMP(p, 9);
 
         // ---- this wave's tiles: tile g = wave + 4*slot of the range, slot = 0 .. nk-1.  Lane s of the wave looks up
         // everything about slot s (of the current group of 64 slots) once: the request, the tile's index inside the
@@ -224,6 +220,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                     if (E[mid] <= pos) lo = mid; else hi = mid;
                 }
                 const int t = pos - E[lo];
+                OMNI_STAMP(p, 10);
                 const int last_page = (Lc[lo] - 1) >> kLog2Ps;
                 const int32_t *bt = p.block_table + (size_t)lo * p.MB;
                 const int page = (t * kTile) >> kLog2Ps;
@@ -283,8 +280,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         }
         OMNI_STAMP(p, 2);
 
-        int nstaged = 0;
-        Segment staged0{}, staged1{};
         int b = first_b;
         while (true) {
             const Segment seg = plan_segment(E, Lc, pl, b, range, start, end);
@@ -322,58 +317,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 if (j == 0) { sm.m[wave][col] = st.m; sm.l[wave][col] = st.l; }
             }
             if (cur.req < 0) OMNI_STAMP(p, 7);                   // this wave's last tile is done
-            lds_barrier();
-            const size_t out0 = ((size_t)seg.b * p.Hq + head0) * D;
-            for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
-                const int g = idx / D, d = idx - g * D;
-                float M = -INFINITY;
-#pragma unroll
-                for (int ww = 0; ww < kWaves; ++ww) M = fmaxf(M, sm.m[ww][g]);
-                float num = 0.f, den = 0.f;
-#pragma unroll
-                for (int ww = 0; ww < kWaves; ++ww) {
-                    const float mw = sm.m[ww][g];
-                    if (mw > -INFINITY) {
-                        const float a = fast_exp2(mw - M);
-                        num += a * sm.o[ww][g][d];
-                        den += a * sm.l[ww][g];
-                    }
-                }
-                if (seg.nparts == 1) {
-                    store_out(p, out0 + idx, den > 0.f ? num / den : 0.f);       // nobody waits for this store
-                } else {                                                         // nor for these, until the range ends
-                    const size_t pi = (size_t)seg.slot * p.Hq + head0;
-                    dev_store(&p.ws.part_o[pi * D + idx], num);
-                    if (d == 0) {
-                        dev_store(&p.ws.part_ml[pi + g].x, M);
-                        dev_store(&p.ws.part_ml[pi + g].y, den);
-                    }
-                }
-            }
-            if (seg.nparts > 1) {                                // at most two per range: its first and last segment
-                if (nstaged == 0) staged0 = seg; else staged1 = seg;
-                ++nstaged;
-            }
-            lds_barrier();                                       // sm may be refilled
+            wg_combine_and_store<D>(sm, p, seg, kvh);            // nobody waits for its stores
             if (__builtin_amdgcn_readfirstlane(E[b]) + seg.hi >= end) break;
             do { ++b; } while (b < p.plan.B - 1 && E[b + 1] == E[b]);    // skip requests that own no tile
         }
-
         OMNI_STAMP(p, 4);
-        // ---- end of the range: count this workgroup's arrival for the (at most two) requests it shares with other
-        // ranges, and merge those for which it is the last piece to arrive.  The partial rows were stored when their
-        // segments ended; the barrier below is where every wave waits for those stores to be acknowledged.
-        if (nstaged > 0) {
-            __syncthreads();             // every wave has waited for its stores to be acknowledged
-            OMNI_STAMP(p, 5);
-            if (threadIdx.x == 0) stage.last[0] = count_arrival(p, staged0, kvh);
-            if (threadIdx.x == 1 && nstaged == 2) stage.last[1] = count_arrival(p, staged1, kvh);
-            __syncthreads();
-            if (stage.last[0]) merge_request<D>(p, staged0, kvh);
-            if (nstaged == 2 && stage.last[1]) merge_request<D>(p, staged1, kvh);
-            __syncthreads();             // stage.last is rewritten by the next range
-        }
-        OMNI_STAMP(p, 6);
     }
 }
 

@@ -43,7 +43,7 @@ struct omni_handle_s {
     int max_ctx = 0;
     int nw = 1;                  // workgroups per KV head
     int r_cap = 0;               // bound on partial-result slots (range index + request index)
-    size_t off_arr = 0, off_ml = 0, off_o = 0, ws_bytes = 0;
+    size_t off_ml = 0, off_o = 0, ws_bytes = 0;
     void *ws = nullptr;
     size_t ws_given = 0;
     // profiling aid: event pairs around the partition kernel
@@ -67,8 +67,7 @@ struct omni_handle_s {
         long long cap = ranges + d.batch;
         if (cap > 0x3fffffff) cap = 0x3fffffff;
         r_cap = (int)cap;
-        off_arr = 256;
-        off_ml = align256(off_arr + (size_t)d.batch * d.num_kv_heads * sizeof(int32_t));
+        off_ml = 256;
         off_o = align256(off_ml + (size_t)r_cap * d.num_q_heads * sizeof(float2));
         ws_bytes = align256(off_o + (size_t)r_cap * d.num_q_heads * d.head_dim * sizeof(float));
     }
@@ -152,11 +151,6 @@ omni_status_t omni_workspace_bytes(omni_handle_t h, size_t *bytes) {
 omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes) {
     if (!h || !dev_ptr) return OMNI_ERR_NULL;
     if (((uintptr_t)dev_ptr & 255) != 0 || bytes < h->ws_bytes) return OMNI_ERR_WORKSPACE;
-    // The arrival counters of the in-kernel merge must start at zero; every call leaves them at zero again.
-    if (hipMemset(reinterpret_cast<char *>(dev_ptr) + h->off_arr, 0, h->off_ml - h->off_arr) != hipSuccess) {
-        (void)hipGetLastError();
-        return OMNI_ERR_HIP;
-    }
     h->ws = dev_ptr;
     h->ws_given = bytes;
     return OMNI_OK;
@@ -167,7 +161,7 @@ omni_status_t omni_get_plan(omni_handle_t h, int32_t *kernel, int32_t *partition
     if (!h) return OMNI_ERR_NULL;
     if (kernel) *kernel = h->kernel;
     if (partition_grid) *partition_grid = h->nw * h->d.num_kv_heads;
-    if (merge_grid) *merge_grid = 0;             // the merge runs inside the partition kernel
+    if (merge_grid) *merge_grid = h->d.batch * h->d.num_kv_heads;
     if (max_request_parts) *max_request_parts = h->r_cap;
     if (threads_per_workgroup) *threads_per_workgroup = kThreads;
     return OMNI_OK;
@@ -209,7 +203,6 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.block_table = block_table; p.context_lens = context_lens; p.out = out;
     char *ws = reinterpret_cast<char *>(h->ws);
     p.ws.plan_words = reinterpret_cast<int32_t *>(ws);
-    p.ws.arrivals = reinterpret_cast<int32_t *>(ws + h->off_arr);
     p.ws.part_ml = reinterpret_cast<float2 *>(ws + h->off_ml);
     p.ws.part_o = reinterpret_cast<float *>(ws + h->off_o);
     p.plan.B = d.batch;
@@ -244,6 +237,13 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
         if (hipEventRecord(h->prof_events[2 * h->prof_used + 1], s) != hipSuccess) return OMNI_ERR_HIP;
         ++h->prof_used;
     }
+
+    // Whether any request was cut by a range boundary is known only on the device: the merge kernel always runs, and
+    // its workgroups return at once for requests that the attention kernel finished.
+    const dim3 mgrid((unsigned)(d.batch * d.num_kv_heads));
+    if (d.head_dim == 128) merge_kernel<128><<<mgrid, kThreads, dyn, s>>>(p);
+    else merge_kernel<64><<<mgrid, kThreads, dyn, s>>>(p);
+    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
 
     return OMNI_OK;
 }

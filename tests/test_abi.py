@@ -71,7 +71,7 @@ def test_tuning_validation_and_plan():
     h = omni.Handle(**good())
     plan = h.omni_get_plan()
     assert plan["kernel"] == omni.KERNEL_MFMA and plan["threads_per_workgroup"] == 256
-    assert plan["merge_grid"] == 0 and plan["partition_grid"] == 512 and plan["max_request_parts"] == 256 + 4
+    assert plan["merge_grid"] == 4 * 2 and plan["partition_grid"] == 512 and plan["max_request_parts"] == 256 + 4
     h.omni_set_tuning(omni.OMNI_TUNE_KERNEL, omni.KERNEL_VALU)
     assert h.omni_get_plan()["kernel"] == omni.KERNEL_VALU
     for key, val in [(omni.OMNI_TUNE_KERNEL, 3), (omni.OMNI_TUNE_TARGET_WORKGROUPS, 0),

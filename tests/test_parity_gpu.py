@@ -231,6 +231,29 @@ def test_workspace_reuse_with_changing_inputs(kernel):
         assert err <= TOL[wl.dtype], f"call {it}: {err:.3e}"
 
 
+@pytest.mark.parametrize("dtype,D,kernel,G,Hkv", [(W.F32, 64, omni.KERNEL_VALU, 3, 3), (W.BF16, 128, omni.KERNEL_MFMA, 7, 4),
+                                                   (W.BF16, 128, omni.KERNEL_VALU, 7, 4)], ids=["f32-valu", "bf16-mfma", "bf16-valu"])
+def test_merge_never_reads_stale_partial_rows(dtype, D, kernel, G, Hkv):
+    """One-tile ranges: every request is merged from up to 22 pieces written by workgroups on other compute dies.
+    The query changes on every call and the partial-row area is refilled with NaN between calls, so a piece that the
+    merging workgroup sees late (a missing device-scope release/acquire) shows up as NaN or as a wrong value."""
+    rng = np.random.default_rng(504)
+    lens = rng.integers(0, 700, size=35)
+    wl = W.build("stale", 904, lens, Hq=G * Hkv, Hkv=Hkv, D=D, ps=16, dtype=dtype, pool_factor=2.0, extra_table_cols=1)
+    dev = DeviceBatch(wl, tuning={omni.OMNI_TUNE_KERNEL: kernel, omni.OMNI_TUNE_TARGET_WORKGROUPS: 4096,
+                                  omni.OMNI_TUNE_MIN_PARTITION: 32})
+    first_row = ((256 + 4 * wl.B * wl.Hkv + 255) // 256) * 256          # behind the plan words and arrival counters
+    for rep in range(120):
+        qf = rng.standard_normal(wl.q.shape, dtype=np.float32) * np.float32(1 + rep % 3)
+        wl.q = qf if dtype == W.F32 else W.f32_to_bf16_bits(qf)
+        dev.q.copy_(to_dev(wl.q, dtype))
+        if rep % 2 == 0:
+            dev.ws[first_row:].view(torch.float32).fill_(float("nan"))
+        got = dev.attend()
+        err = np.max(np.abs(got - oracle_out(wl)))
+        assert np.all(np.isfinite(got)) and err <= TOL[dtype], f"call {rep}: {err}"
+
+
 def test_bf16_output_is_rounded_fp32_result():
     wl = W.make("talker", batch=16, append=False)
     f32 = DeviceBatch(wl).attend()
