@@ -24,6 +24,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the attention kernel on the thinker workload (seed 1), from two rocprofv3 counter runs
+# (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000, the factors a plain 1 GiB copy gives); see
+# profiles/decode_mfma_kernel_thinker_hbm_traffic.txt.  Not measured by this script: null for any other workload.
+MEASURED_TRAFFIC_BYTES = {("thinker", 1): 300.2e6}
+EVENT_STRIDE = 8                # one timed step in eight carries the HIP event pair around the attention kernel
 
 
 def parse():
@@ -40,6 +45,10 @@ def parse():
     ap.add_argument("--min-partition", type=int, default=0)
     ap.add_argument("--force-partition", type=int, default=0)
     ap.add_argument("--unfused", action="store_true", help="time omni_kv_append + omni_paged_decode_attn instead")
+    ap.add_argument("--timed-only", action="store_true",
+                    help="skip the extra record-keeping loops, so that a profiler sees only warm-up and timed steps")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy, so that a counter run has a kernel of known traffic in it")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
 
@@ -115,9 +124,10 @@ def main():
     plan = h.omni_debug_last_plan()
     plan.update(h.omni_get_plan())
 
-    # ---- timed region: exactly K steps; the library records an event pair around the partition kernel of each step
+    # ---- timed region: exactly K steps; the library records an event pair around the attention kernel of every
+    # EVENT_STRIDE-th step (a pair costs a few microseconds of stream time, so not around every step)
     K = args.steps
-    h.omni_debug_profile_begin(K)
+    h.omni_debug_profile_begin((K + EVENT_STRIDE - 1) // EVENT_STRIDE, EVENT_STRIDE)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
@@ -140,9 +150,19 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - a) * 1e3 / K
 
-    ms_noevents = timed(step)
-    ms_other = timed(step_fused if args.unfused else step_two_launches)
-    ms_warm = timed(step, fixed_replica=True)
+    ms_noevents = ms_other = ms_warm = None
+    if not args.timed_only:
+        ms_noevents = timed(step)
+        ms_other = timed(step_fused if args.unfused else step_two_launches)
+        ms_warm = timed(step, fixed_replica=True)
+
+    if args.calibrate_copy:                  # 1 GiB read + 1 GiB written per copy: the yardstick for FETCH_SIZE / WRITE_SIZE
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- validity: sampled rows of the last step against the oracle (the appended token is in the pools now)
     import oracle
@@ -164,7 +184,7 @@ def main():
         oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, wl.scale, wl.dtype,
                                  pairs=[(0, 0)])
         reps, spent, used = 0, 0.0, 1
-        while reps < 1 or (spent < 4.0 and reps < 5):
+        while reps < 1 or (spent < 1.5 and reps < 25):     # about 20 core-seconds of oracle work
             c0 = time.perf_counter()
             _, used = oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens,
                                                wl.scale, wl.dtype, return_threads=True)
@@ -197,15 +217,17 @@ def main():
                    "pool_replicas": R, "plan": plan},
         "kv_gbs_per_step": kv_bytes / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, wl.seed)) if plan["kernel"] == 2 else None,
                      "kernel": "decode_mfma_kernel" if plan["kernel"] == 2 else "decode_valu_kernel",
                      "kernel_avg_us": k_avg_ms * 1e3, "kernel_median_us": k_med_ms * 1e3,
+                     "kernel_launches_timed": len(kernel_ms),
                      "algorithmic_bytes_per_launch": kv_bytes},
         "cpu_baseline": cpu,
         "extra": {"ms_per_step_without_event_pairs": ms_noevents,
                   ("ms_per_step_fused" if args.unfused else "ms_per_step_separate_append"): ms_other,
                   "ms_per_step_single_replica_cache_warm": ms_warm,
-                  "kv_gbs_cache_warm": kv_bytes / (ms_warm * 1e-3) / 1e9,
+                  "kv_gbs_cache_warm": kv_bytes / (ms_warm * 1e-3) / 1e9 if ms_warm else None,
                   "parity_max_abs_err_sampled": max_err},
     }
     print(json.dumps(result))

@@ -163,12 +163,14 @@ omni_status_t omni_debug_last_plan(omni_handle_t h, int32_t host_out[4], void *s
 omni_status_t omni_debug_gather(omni_handle_t h, const void *cache, const int32_t *block_table,
                                 const int32_t *context_lens, int32_t request, void *dense_out, void *stream);
 
-/* Profiling aid for the benchmark.  After omni_debug_profile_begin(h, capacity) every omni_paged_decode_attn call
- * records a HIP event pair around its partition kernel (the kernel that reads the KV cache) on the caller's stream,
- * up to `capacity` calls; later calls are not recorded.  omni_debug_profile_end synchronises the recorded events,
- * writes the elapsed milliseconds of each recorded launch to host_ms[0 .. *count) (host_ms must hold `capacity`
- * floats), destroys the events and switches recording off.  Errors: NULL, SHAPE (capacity <= 0), HIP. */
-omni_status_t omni_debug_profile_begin(omni_handle_t h, int32_t capacity);
+/* Profiling aid for the benchmark.  After omni_debug_profile_begin(h, capacity, stride) every stride-th attention
+ * call (omni_paged_decode_attn or omni_decode_step; the first one included) records a HIP event pair around its
+ * attention kernel (the kernel that reads the KV cache) on the caller's stream, until `capacity` pairs are used.
+ * An event pair costs a few microseconds of stream time, hence the stride.  omni_debug_profile_end synchronises the
+ * recorded events, writes the elapsed milliseconds of each recorded launch to host_ms[0 .. *count) (host_ms must hold
+ * `capacity` floats), destroys the events and switches recording off.  Errors: NULL, SHAPE (capacity or stride <= 0),
+ * HIP. */
+omni_status_t omni_debug_profile_begin(omni_handle_t h, int32_t capacity, int32_t stride);
 omni_status_t omni_debug_profile_end(omni_handle_t h, float *host_ms, int32_t *count);
 
 #ifdef __cplusplus

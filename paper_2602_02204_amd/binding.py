@@ -60,7 +60,7 @@ def lib():
         L.omni_status_string.argtypes = [C.c_int]; L.omni_status_string.restype = C.c_char_p
         L.omni_debug_last_plan.argtypes = [vp, i32p, vp]
         L.omni_debug_gather.argtypes = [vp, vp, vp, vp, C.c_int32, vp, vp]
-        L.omni_debug_profile_begin.argtypes = [vp, C.c_int32]
+        L.omni_debug_profile_begin.argtypes = [vp, C.c_int32, C.c_int32]
         L.omni_debug_profile_end.argtypes = [vp, C.POINTER(C.c_float), i32p]
         for name in EXPORTS:
             if name not in ("omni_destroy", "omni_status_string"):
@@ -160,9 +160,9 @@ class Handle:
         _ck(lib().omni_debug_gather(self._h, _ptr(cache), _ptr(block_table), _ptr(context_lens), int(request),
                                     _ptr(dense_out), _stream(stream)), "omni_debug_gather")
 
-    def omni_debug_profile_begin(self, capacity: int) -> None:
+    def omni_debug_profile_begin(self, capacity: int, stride: int = 1) -> None:
         self._prof_cap = int(capacity)
-        _ck(lib().omni_debug_profile_begin(self._h, int(capacity)), "omni_debug_profile_begin")
+        _ck(lib().omni_debug_profile_begin(self._h, int(capacity), int(stride)), "omni_debug_profile_begin")
 
     def omni_debug_profile_end(self) -> list:
         buf = (C.c_float * self._prof_cap)()

@@ -48,7 +48,7 @@ struct omni_handle_s {
     size_t ws_given = 0;
     // profiling aid: event pairs around the partition kernel
     std::vector<hipEvent_t> prof_events;
-    int prof_used = 0;
+    int prof_used = 0, prof_stride = 1, prof_calls = 0;
 
     void derive() {
         G = d.num_q_heads / d.num_kv_heads;
@@ -220,7 +220,7 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     const dim3 grid((unsigned)(h->nw * d.num_kv_heads));
     const size_t dyn = (size_t)(2 * d.batch + 1) * sizeof(int);     // tile offsets and lengths of the plan
     (void)hipGetLastError();
-    const bool prof = (size_t)(2 * h->prof_used + 1) < h->prof_events.size();
+    const bool prof = (size_t)(2 * h->prof_used + 1) < h->prof_events.size() && (h->prof_calls++ % h->prof_stride) == 0;
     if (prof && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
     if (h->kernel == 2) {
         if (d.page_size == 16) decode_mfma_kernel<16><<<grid, kThreads, dyn, s>>>(p);
@@ -302,9 +302,11 @@ omni_status_t omni_debug_last_plan(omni_handle_t h, int32_t host_out[4], void *s
     return OMNI_OK;
 }
 
-omni_status_t omni_debug_profile_begin(omni_handle_t h, int32_t capacity) {
+omni_status_t omni_debug_profile_begin(omni_handle_t h, int32_t capacity, int32_t stride) {
     if (!h) return OMNI_ERR_NULL;
-    if (capacity <= 0) return OMNI_ERR_SHAPE;
+    if (capacity <= 0 || stride <= 0) return OMNI_ERR_SHAPE;
+    h->prof_stride = stride;
+    h->prof_calls = 0;
     for (hipEvent_t e : h->prof_events) (void)hipEventDestroy(e);
     h->prof_events.clear();
     h->prof_used = 0;
