@@ -110,8 +110,8 @@ class Handle:
         self._ws = None
 
     def close(self):
-        if getattr(self, "_h", None) is not None and self._h:
-            lib().omni_destroy(self._h)
+        if getattr(self, "_h", None) is not None and self._h and _lib is not None:
+            _lib.omni_destroy(self._h)
             self._h = C.c_void_p()
 
     __del__ = close
