@@ -61,7 +61,14 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void merge_kernel(AttnParams p) {
     __shared__ PlanSmem ps;
     extern __shared__ int E[];                               // E[B + 1] tile offsets, then Lc[B] lengths
-    const Plan pl = plan_build(p.context_lens, p.plan, &ps, E, E + p.plan.B + 1, [](int) {});
+    Plan pl;
+    if (p.plan.B <= kWavePlanMax) {                          // every wave plans for itself: no barrier
+        WavePlan wp;
+        unsigned long long T;
+        pl = plan_build_wave(p.context_lens, p.plan, E, E + p.plan.B + 1, &wp, false, [](int) {}, T);
+    } else {
+        pl = plan_build(p.context_lens, p.plan, &ps, E, E + p.plan.B + 1, [](int) {});
+    }
     const int b = blockIdx.x / p.Hkv, kvh = blockIdx.x - b * p.Hkv;
     const int e0 = E[b], e1 = E[b + 1];
     if (e1 == e0) return;                                    // empty request: its zero row is already written

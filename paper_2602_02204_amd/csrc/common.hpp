@@ -46,7 +46,7 @@ struct AttnParams {
 #define OMNI_STAMP(p, id)                                                                              \
     do {                                                                                               \
         if ((p).trace && (threadIdx.x & 63) == 0)                                                      \
-            (p).trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + (id)] = wall_clock64(); \
+            (p).trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 32 + (id)] = wall_clock64(); \
     } while (0)
 #else
 #define OMNI_STAMP(p, id) do { } while (0)
@@ -95,12 +95,11 @@ __device__ __forceinline__ void store_segment_element(const AttnParams &p, const
     }
 }
 
-// Combine the four waves' (m, l, o) of one segment and store it.  Must be called by all 256 threads after the waves
-// have filled `sm` (this function synchronises first, and again before it returns so that `sm` may be refilled).
+// Combine the four waves' (m, l, o) of one segment and store it: the part between the barriers.  All 256 threads
+// call it once the waves' states in `sm` are visible.
 template <int D>
-__device__ __forceinline__ void wg_combine_and_store(CombineSmem<D> &sm, const AttnParams &p, const Segment &seg,
-                                                     int kvh) {
-    lds_barrier();
+__device__ __forceinline__ void wg_combine_segment(const CombineSmem<D> &sm, const AttnParams &p, const Segment &seg,
+                                                   int kvh) {
     const int G = p.G;
     const int head0 = kvh * G;
     for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
@@ -120,6 +119,15 @@ __device__ __forceinline__ void wg_combine_and_store(CombineSmem<D> &sm, const A
         }
         store_segment_element<D>(p, seg, head0, idx, M, num, den);
     }
+}
+
+// The same with the synchronisation around it: waits until the waves have filled `sm`, and returns when `sm` may be
+// refilled.
+template <int D>
+__device__ __forceinline__ void wg_combine_and_store(CombineSmem<D> &sm, const AttnParams &p, const Segment &seg,
+                                                     int kvh) {
+    lds_barrier();
+    wg_combine_segment<D>(sm, p, seg, kvh);
     lds_barrier();
 }
 

@@ -149,11 +149,14 @@ __device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], M
     }
 }
 
-template <int PS>
+// RING = number of finished segments whose per-wave states may wait in shared memory before the workgroup meets to
+// combine them.  With 2, a range that holds the end of one request and the start of the next is processed without a
+// stop in the middle: the waves only meet at the end of the range (or after every second segment).
+template <int PS, int RING>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
-    __shared__ CombineSmem<D> sm;
+    __shared__ CombineSmem<D> sm[RING];
     __shared__ PlanSmem ps;
     extern __shared__ int E[];                               // E[B + 1] tile offsets, then Lc[B] lengths
 
@@ -165,7 +168,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         unsigned xcc, hwid;
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
-        p.trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 16 + 8] = ((long long)xcc << 32) | hwid;
+        p.trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 32 + 8] = ((long long)xcc << 32) | hwid;
     }
 #endif
     const int lane = threadIdx.x & 63;
@@ -192,15 +195,31 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     };
 
     // Tile offsets and lengths of all requests, in shared memory.
-    const Plan pl = attn_prologue<D>(p, &ps, E, w, kvh);
     const int *Lc = E + p.plan.B + 1;
+    const bool wave_plan = p.plan.B <= kWavePlanMax;         // small batch: every wave plans for itself, no barrier
+    WavePlan wp{0, 0, 0, 0};
+    Plan pl;
+    if (wave_plan) {
+        unsigned long long T = 0;
+        const bool first = blockIdx.x == 0 && wave == 0;
+        pl = plan_build_wave(p.context_lens, p.plan, E, E + p.plan.B + 1, &wp, w == 0 && wave == 0, [&](int b) {
+            const size_t o0 = ((size_t)b * p.Hq + head0) * D;
+            for (int i = 0; i < G * D; ++i) store_out(p, o0 + i, 0.f);
+        }, T);
+        if (first && lane == 0) {
+            p.ws.plan_words[0] = pl.S * kTile; p.ws.plan_words[1] = pl.nranges;
+            p.ws.plan_words[2] = (int)(T & 0xffffffffULL); p.ws.plan_words[3] = (int)(T >> 32);
+        }
+    } else {
+        pl = attn_prologue<D>(p, &ps, E, w, kvh);
+    }
     OMNI_STAMP(p, 1);
     bool stamped = false;
 
     for (int range = w; range < pl.nranges; range += p.plan.nw) {
         const int start = range * pl.S, end = min(pl.C, start + pl.S);
         const int len = end - start;
-        const int first_b = plan_first_request(p.plan, &ps, E, start);
+        const int first_b = wave_plan ? wave_first_request(wp, start) : plan_first_request(p.plan, &ps, E, start);
         OMNI_STAMP(p, 9);
 
         // ---- this wave's tiles: tile g = wave + 4*slot of the range, slot = 0 .. nk-1.  Lane s of the wave looks up
@@ -281,6 +300,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         OMNI_STAMP(p, 2);
 
         int b = first_b;
+        int npend = 0;                   // finished segments waiting in sm[0 .. npend)
+        Segment pend[RING];
         while (true) {
             const Segment seg = plan_segment(E, Lc, pl, b, range, start, end);
             MfmaState st;
@@ -293,6 +314,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 float sv[8];
                 mfma_scores(K, Q, sv, p.scale_log2);
                 if (!stamped) { OMNI_STAMP(p, 3); stamped = true; }
+                OMNI_STAMP(p, 16 + (s < 15 ? s : 15));
                 if (more) {
                     if (nxt.append) append_row(nxt);
                     ld.issue_k(nxt.pg0, nxt.pg1, K);
@@ -303,22 +325,35 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 ++s; cur = nxt;
             }
 
-            // ---- end of the segment: the four waves' states meet in LDS
+            // ---- end of the segment: the wave leaves its state in LDS and goes on; the workgroup meets to combine
+            // the waiting segments when the ring is full or the range ends
             st.l += __shfl_xor(st.l, 16);                        // per-lane sums of the four lane groups; m is common
             st.l += __shfl_xor(st.l, 32);
+            CombineSmem<D> &my = sm[npend];
             if (col < G) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float4 lo4 = make_float4(st.acc[0][i], st.acc[1][i], st.acc[2][i], st.acc[3][i]);
                     float4 hi4 = make_float4(st.acc[4][i], st.acc[5][i], st.acc[6][i], st.acc[7][i]);
-                    *reinterpret_cast<float4 *>(&sm.o[wave][col][32 * j + 8 * i]) = lo4;
-                    *reinterpret_cast<float4 *>(&sm.o[wave][col][32 * j + 8 * i + 4]) = hi4;
+                    *reinterpret_cast<float4 *>(&my.o[wave][col][32 * j + 8 * i]) = lo4;
+                    *reinterpret_cast<float4 *>(&my.o[wave][col][32 * j + 8 * i + 4]) = hi4;
                 }
-                if (j == 0) { sm.m[wave][col] = st.m; sm.l[wave][col] = st.l; }
+                if (j == 0) { my.m[wave][col] = st.m; my.l[wave][col] = st.l; }
             }
             if (cur.req < 0) OMNI_STAMP(p, 7);                   // this wave's last tile is done
-            wg_combine_and_store<D>(sm, p, seg, kvh);            // nobody waits for its stores
-            if (__builtin_amdgcn_readfirstlane(E[b]) + seg.hi >= end) break;
+#pragma unroll
+            for (int r = 0; r < RING; ++r) if (r == npend) pend[r] = seg;
+            ++npend;
+            const bool last = __builtin_amdgcn_readfirstlane(E[b]) + seg.hi >= end;
+            if (last || npend == RING) {
+                lds_barrier();
+#pragma unroll
+                for (int r = 0; r < RING; ++r)
+                    if (r < npend) wg_combine_segment<D>(sm[r], p, pend[r], kvh);    // nobody waits for its stores
+                lds_barrier();
+                npend = 0;
+            }
+            if (last) break;
             do { ++b; } while (b < p.plan.B - 1 && E[b + 1] == E[b]);    // skip requests that own no tile
         }
         OMNI_STAMP(p, 4);

@@ -223,8 +223,15 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     const bool prof = (size_t)(2 * h->prof_used + 1) < h->prof_events.size() && (h->prof_calls++ % h->prof_stride) == 0;
     if (prof && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
     if (h->kernel == 2) {
-        if (d.page_size == 16) decode_mfma_kernel<16><<<grid, kThreads, dyn, s>>>(p);
-        else decode_mfma_kernel<32><<<grid, kThreads, dyn, s>>>(p);
+        // Two segment buffers per workgroup as long as two workgroups still fit the 160 KB of a compute unit.
+        const bool ring2 = 2 * (2 * sizeof(CombineSmem<128>) + dyn + 256) <= 160 * 1024;
+        if (d.page_size == 16) {
+            if (ring2) decode_mfma_kernel<16, 2><<<grid, kThreads, dyn, s>>>(p);
+            else decode_mfma_kernel<16, 1><<<grid, kThreads, dyn, s>>>(p);
+        } else {
+            if (ring2) decode_mfma_kernel<32, 2><<<grid, kThreads, dyn, s>>>(p);
+            else decode_mfma_kernel<32, 1><<<grid, kThreads, dyn, s>>>(p);
+        }
     } else if (d.kv_dtype == OMNI_BF16) {
         if (d.head_dim == 128) launch_valu<uint16_t, 128>(p, grid, dyn, s);
         else launch_valu<uint16_t, 64>(p, grid, dyn, s);

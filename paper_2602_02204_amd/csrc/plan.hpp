@@ -120,6 +120,71 @@ __device__ __forceinline__ Plan plan_build(const int32_t *__restrict__ lens, con
     return pl;
 }
 
+// ---- Plan without workgroup barriers, for batches of up to kWavePlanMax requests.
+// Every wave loads all the lengths itself (lane l holds requests 4l .. 4l+3), scans them with cross-lane shuffles and
+// writes E[] and Lc[] to shared memory.  The waves of a workgroup store identical values to the same words, so a wave
+// may read the arrays as soon as its own stores are done: no wave waits for another before its first table read.
+constexpr int kWavePlanMax = 256;
+
+struct WavePlan {
+    int i0, i1, i2, i3;  // tiles up to and including request 4*lane + i (requests beyond the batch own no tile)
+};
+
+// `zero_row(b)` is called for each request of length <= 0 if `zero_rows`; `total_tokens` receives the sum of the
+// lengths (in every lane).
+template <typename ZeroRow>
+__device__ __forceinline__ Plan plan_build_wave(const int32_t *__restrict__ lens, const PlanParams &pp, int *E, int *Lc,
+                                                WavePlan *wp, bool zero_rows, ZeroRow zero_row,
+                                                unsigned long long &total_tokens) {
+    const int lane = threadIdx.x & 63;
+    int L[4], c[4], incl[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int b = 4 * lane + i;
+        L[i] = b < pp.B ? lens[b] : 0;
+    }
+    int run = 0;
+    unsigned long long tokens = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int b = 4 * lane + i;
+        if (L[i] > 0) { c[i] = (L[i] + kTile - 1) >> kLog2Tile; tokens += (unsigned long long)L[i]; }
+        else { c[i] = 0; L[i] = 0; if (zero_rows && b < pp.B) zero_row(b); }
+        run += c[i];
+        incl[i] = run;
+    }
+    int scan = run;                              // inclusive scan of the lanes' totals
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(scan, off);
+        if (lane >= off) scan += t;
+    }
+    const int before = scan - run;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int b = 4 * lane + i;
+        incl[i] += before;
+        if (b < pp.B) { E[b] = incl[i] - c[i]; Lc[b] = L[i]; }
+    }
+    wp->i0 = incl[0]; wp->i1 = incl[1]; wp->i2 = incl[2]; wp->i3 = incl[3];
+    Plan pl;
+    pl.C = __builtin_amdgcn_readlane(scan, 63);
+    if (lane == 0) E[pp.B] = pl.C;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) tokens += __shfl_xor(tokens, off);
+    total_tokens = tokens;
+    int S = pp.s_force > 0 ? pp.s_force : max(pp.s_min, ceil_div(pl.C, pp.nw));
+    pl.S = max(S, 1);
+    pl.nranges = ceil_div(pl.C, pl.S);
+    return pl;
+}
+
+// Request that holds tile `start` (0 <= start < C): the number of requests that end at or before it.
+__device__ __forceinline__ int wave_first_request(const WavePlan &wp, int start) {
+    return __popcll(__ballot(wp.i0 <= start)) + __popcll(__ballot(wp.i1 <= start)) +
+           __popcll(__ballot(wp.i2 <= start)) + __popcll(__ballot(wp.i3 <= start));
+}
+
 // Request that holds tile `start` (0 <= start < C).  All 256 threads call this; E[] must be complete.
 __device__ __forceinline__ int plan_first_request(const PlanParams &pp, PlanSmem *ps, const int *E, int start) {
     lds_barrier();                         // previous readers of first_b are done
