@@ -156,6 +156,24 @@ def main():
         ms_other = timed(step_fused if args.unfused else step_two_launches)
         ms_warm = timed(step, fixed_replica=True)
 
+    # ---- the memory system's ceiling for a kernel of this size: a plain streaming read of one replica's K and V pools
+    # (pool bytes >= the algorithmic bytes: it also reads the unused tail slots), timed with event pairs like the
+    # attention kernel, over rotating replicas
+    ceiling = None
+    if not args.timed_only:
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(40)]
+        for i in range(8):
+            omni.omni_debug_stream_read(kc[i % R], vc[i % R], sink, stream)
+        for i, (a, b) in enumerate(evs):
+            a.record(stream)
+            omni.omni_debug_stream_read(kc[i % R], vc[i % R], sink, stream)
+            b.record(stream)
+        torch.cuda.synchronize()
+        us = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e3
+        ceiling = {"kernel": "stream_read_kernel", "bytes": pool_bytes, "avg_us": us, "GB/s": pool_bytes / us / 1e3,
+                   "attention_vs_stream_read": (kv_bytes / (k_avg_ms * 1e3)) / (pool_bytes / us)}
+
     if args.calibrate_copy:                  # 1 GiB read + 1 GiB written per copy: the yardstick for FETCH_SIZE / WRITE_SIZE
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -222,7 +240,8 @@ def main():
                      "kernel": "decode_mfma_kernel" if plan["kernel"] == 2 else "decode_valu_kernel",
                      "kernel_avg_us": k_avg_ms * 1e3, "kernel_median_us": k_med_ms * 1e3,
                      "kernel_launches_timed": len(kernel_ms),
-                     "algorithmic_bytes_per_launch": kv_bytes},
+                     "algorithmic_bytes_per_launch": kv_bytes,
+                     "stream_read_ceiling": ceiling},
         "cpu_baseline": cpu,
         "extra": {"ms_per_step_without_event_pairs": ms_noevents,
                   ("ms_per_step_fused" if args.unfused else "ms_per_step_separate_append"): ms_other,

@@ -163,6 +163,14 @@ omni_status_t omni_debug_last_plan(omni_handle_t h, int32_t host_out[4], void *s
 omni_status_t omni_debug_gather(omni_handle_t h, const void *cache, const int32_t *block_table,
                                 const int32_t *context_lens, int32_t request, void *dense_out, void *stream);
 
+/* Measurement aid: a plain streaming read of a_bytes at a followed by b_bytes at b (device pointers, 16-byte aligned,
+ * sizes multiples of 16; b may be null with b_bytes = 0), launched on `stream` like the attention kernel.  `sink`
+ * points at 4 writable device bytes.  Timed on buffers of the KV pool's size it gives the memory system's ceiling for a
+ * kernel of the attention kernel's duration, the figure the attention kernel's bandwidth is compared with.
+ * Errors: OMNI_ERR_NULL, OMNI_ERR_SHAPE (alignment), OMNI_ERR_HIP. */
+omni_status_t omni_debug_stream_read(const void *a, size_t a_bytes, const void *b, size_t b_bytes, void *sink,
+                                     void *stream);
+
 /* Profiling aid for the benchmark.  After omni_debug_profile_begin(h, capacity, stride) every stride-th attention
  * call (omni_paged_decode_attn or omni_decode_step; the first one included) records a HIP event pair around its
  * attention kernel (the kernel that reads the KV cache) on the caller's stream, until `capacity` pairs are used.

@@ -20,7 +20,8 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 EXPORTS = (
     "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_set_workspace",
     "omni_paged_decode_attn", "omni_kv_append", "omni_decode_step", "omni_get_plan", "omni_status_string",
-    "omni_debug_last_plan", "omni_debug_gather", "omni_debug_profile_begin", "omni_debug_profile_end",
+    "omni_debug_last_plan", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
+    "omni_debug_profile_end",
 )
 
 
@@ -60,6 +61,7 @@ def lib():
         L.omni_status_string.argtypes = [C.c_int]; L.omni_status_string.restype = C.c_char_p
         L.omni_debug_last_plan.argtypes = [vp, i32p, vp]
         L.omni_debug_gather.argtypes = [vp, vp, vp, vp, C.c_int32, vp, vp]
+        L.omni_debug_stream_read.argtypes = [vp, C.c_size_t, vp, C.c_size_t, vp, vp]
         L.omni_debug_profile_begin.argtypes = [vp, C.c_int32, C.c_int32]
         L.omni_debug_profile_end.argtypes = [vp, C.POINTER(C.c_float), i32p]
         for name in EXPORTS:
@@ -67,6 +69,13 @@ def lib():
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
+
+
+def omni_debug_stream_read(a, b, sink, stream=None) -> None:
+    """Plain streaming read of tensors a and b (b may be None); sink is a device tensor of at least 4 bytes."""
+    nbytes = lambda t: 0 if t is None else t.numel() * t.element_size()
+    _ck(lib().omni_debug_stream_read(_ptr(a), nbytes(a), _ptr(b) if b is not None else None, nbytes(b), _ptr(sink),
+                                     _stream(stream)), "omni_debug_stream_read")
 
 
 def status_string(status: int) -> str:

@@ -361,4 +361,16 @@ omni_status_t omni_debug_gather(omni_handle_t h, const void *cache, const int32_
     return OMNI_OK;
 }
 
+omni_status_t omni_debug_stream_read(const void *a, size_t a_bytes, const void *b, size_t b_bytes, void *sink,
+                                     void *stream) {
+    if (!a || !sink || (b_bytes && !b)) return OMNI_ERR_NULL;
+    if (((a_bytes | b_bytes) & 15) || ((uintptr_t)a & 15) || ((uintptr_t)b & 15)) return OMNI_ERR_SHAPE;
+    (void)hipGetLastError();
+    stream_read_kernel<<<2 * 256, kThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(
+        reinterpret_cast<const uint4 *>(a), a_bytes / 16, reinterpret_cast<const uint4 *>(b), b_bytes / 16,
+        reinterpret_cast<unsigned *>(sink));
+    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+    return OMNI_OK;
+}
+
 }  // extern "C"
