@@ -9,51 +9,47 @@ namespace omni {
 // by range boundaries combines its partial-result slots, in slot order:
 //     out = sum_j 2^(m_j - M) o_j / sum_j 2^(m_j - M) l_j,   M = max_j m_j,   pieces with l_j = 0 skipped.
 // Requests inside one range (finished by the attention kernel) and empty requests return at once.
-// Every thread owns up to kMergeIdx output elements; the loads of kRound pieces for all of them are issued before any
-// is used, so a round costs one trip to memory and no load depends on a loaded value.
-template <int D, int kMergeIdx, int kRound>
+// Every thread owns four consecutive output elements (one 16-byte load per piece); the loads of kRound pieces are
+// issued before any is used, so a round costs one trip to memory and no load depends on a loaded value.
+template <int D, int kRound>
 __device__ __forceinline__ void merge_request(const AttnParams &p, int b, int kvh, int slot_first, int n) {
     const int G = p.G, head0 = kvh * G;
     const size_t out0 = ((size_t)b * p.Hq + head0) * D;
-    float M[kMergeIdx], num[kMergeIdx], den[kMergeIdx];
-#pragma unroll
-    for (int i = 0; i < kMergeIdx; ++i) { M[i] = -INFINITY; num[i] = 0.f; den[i] = 0.f; }
-    for (int j0 = 0; j0 < n; j0 += kRound) {
-        float2 ml[kMergeIdx][kRound];
-        float oj[kMergeIdx][kRound];
-#pragma unroll
-        for (int i = 0; i < kMergeIdx; ++i) {
-            const int idx = threadIdx.x + i * kThreads;
-            const int g = idx / D;
+    for (int idx = 4 * threadIdx.x; idx < G * D; idx += 4 * kThreads) {       // one pass up to 1024 elements
+        const int g = idx / D;
+        float M = -INFINITY, den = 0.f;
+        float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j0 = 0; j0 < n; j0 += kRound) {
+            float2 ml[kRound];
+            float4 oj[kRound];
 #pragma unroll
             for (int u = 0; u < kRound; ++u) {
-                ml[i][u] = make_float2(0.f, 0.f); oj[i][u] = 0.f;
-                if (idx < G * D && j0 + u < n) {
+                ml[u] = make_float2(0.f, 0.f); oj[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (j0 + u < n) {
                     const size_t pi = (size_t)(slot_first + j0 + u) * p.Hq + head0;
-                    ml[i][u] = p.ws.part_ml[pi + g];
-                    oj[i][u] = p.ws.part_o[pi * D + idx];
+                    ml[u] = p.ws.part_ml[pi + g];
+                    oj[u] = *reinterpret_cast<const float4 *>(p.ws.part_o + pi * D + idx);
                 }
             }
-        }
-#pragma unroll
-        for (int i = 0; i < kMergeIdx; ++i) {
+            OMNI_STAMP(p, 22);
 #pragma unroll
             for (int u = 0; u < kRound; ++u) {
-                if (ml[i][u].y > 0.f) {
-                    const float Mn = fmaxf(M[i], ml[i][u].x);
-                    const float a = fast_exp2(M[i] - Mn);            // 0 while M is still -inf
-                    const float w = fast_exp2(ml[i][u].x - Mn);
-                    num[i] = num[i] * a + w * oj[i][u];
-                    den[i] = den[i] * a + w * ml[i][u].y;
-                    M[i] = Mn;
+                if (ml[u].y > 0.f) {
+                    const float Mn = fmaxf(M, ml[u].x);
+                    const float a = fast_exp2(M - Mn);               // 0 while M is still -inf
+                    const float w = fast_exp2(ml[u].x - Mn);
+                    num.x = num.x * a + w * oj[u].x; num.y = num.y * a + w * oj[u].y;
+                    num.z = num.z * a + w * oj[u].z; num.w = num.w * a + w * oj[u].w;
+                    den = den * a + w * ml[u].y;
+                    M = Mn;
                 }
             }
         }
-    }
-#pragma unroll
-    for (int i = 0; i < kMergeIdx; ++i) {
-        const int idx = threadIdx.x + i * kThreads;
-        if (idx < G * D) store_out(p, out0 + idx, den[i] > 0.f ? num[i] / den[i] : 0.f);
+        const bool live = den > 0.f;
+        store_out(p, out0 + idx + 0, live ? num.x / den : 0.f);
+        store_out(p, out0 + idx + 1, live ? num.y / den : 0.f);
+        store_out(p, out0 + idx + 2, live ? num.z / den : 0.f);
+        store_out(p, out0 + idx + 3, live ? num.w / den : 0.f);
     }
 }
 
@@ -61,6 +57,7 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void merge_kernel(AttnParams p) {
     __shared__ PlanSmem ps;
     extern __shared__ int E[];                               // E[B + 1] tile offsets, then Lc[B] lengths
+    OMNI_STAMP(p, 20);
     Plan pl;
     if (p.plan.B <= kWavePlanMax) {                          // every wave plans for itself: no barrier
         WavePlan wp;
@@ -75,9 +72,12 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(AttnParams p) {
     const int first_range = e0 / pl.S, last_range = (e1 - 1) / pl.S;
     const int n = last_range - first_range + 1;
     if (n == 1) return;                                      // finished by the attention kernel
-    // up to 8 heads of 128: 4 output elements per thread, four pieces per round; above: twice the elements, two pieces
-    if (p.G * D <= 4 * kThreads) merge_request<D, 4, 4>(p, b, kvh, first_range + b, n);
-    else merge_request<D, kMaxGroup * D / kThreads, 2>(p, b, kvh, first_range + b, n);
+    OMNI_STAMP(p, 21);
+    // 4, 8 or 16 pieces per round, so that a request cut into many pieces still costs few dependent trips to memory
+    if (n <= 4) merge_request<D, 4>(p, b, kvh, first_range + b, n);
+    else if (n <= 8) merge_request<D, 8>(p, b, kvh, first_range + b, n);
+    else merge_request<D, 16>(p, b, kvh, first_range + b, n);
+    OMNI_STAMP(p, 23);
 }
 
 struct AppendParams {

@@ -21,6 +21,15 @@ struct Workspace {
     float *part_o;
 };
 
+// Shared memory of the matrix-core kernel behind the plan's arrays: `ring_depth` slots, each holding the four waves'
+// online-softmax states of one finished segment as o[wave][G][D + 4] floats followed by m[wave][16] and l[wave][16].
+struct MfmaLds {
+    int ring_off;                       // bytes from the start of dynamic shared memory
+    int slot_floats;
+    int ring_depth;                     // 1 .. 4
+    int total;                          // bytes of dynamic shared memory
+};
+
 struct AttnParams {
     const void *q;
     const void *k_cache;
@@ -36,6 +45,7 @@ struct AttnParams {
     int Hq, Hkv, G, MB;
     int log2_ps;
     int out_bf16;
+    MfmaLds lds;                        // matrix-core kernel only
 #ifdef OMNI_TRACE
     long long *trace;                   // development builds only: per-wave phase timestamps
 #endif

@@ -149,16 +149,58 @@ __device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], M
     }
 }
 
-// RING = number of finished segments whose per-wave states may wait in shared memory before the workgroup meets to
-// combine them.  With 2, a range that holds the end of one request and the start of the next is processed without a
-// stop in the middle: the waves only meet at the end of the range (or after every second segment).
-template <int PS, int RING>
+constexpr int kMaxRing = 4;
+
+// Shared-memory layout for a batch of B requests and G query heads per KV head: as many ring slots (up to four) as
+// fit while two workgroups still share the 160 KB of a compute unit; at least one fits for every supported B and G.
+inline MfmaLds mfma_lds_layout(int B, int G) {
+    constexpr int D = 128;
+    MfmaLds L;
+    L.ring_off = ((2 * B + 1) * 4 + 15) & ~15;
+    L.slot_floats = kWaves * G * (D + 4) + 2 * kWaves * kMaxGroup;
+    const int budget = 80 * 1024 - 512 - L.ring_off;            // 512 B for the kernel's static variables
+    const int depth = budget / (L.slot_floats * 4);
+    L.ring_depth = depth > kMaxRing ? kMaxRing : (depth < 1 ? 1 : depth);
+    L.total = L.ring_off + L.ring_depth * L.slot_floats * 4;
+    return L;
+}
+
+// Combine the four waves' (m, l, o) of one finished segment held in a ring slot and store the result.  All threads
+// call it between barriers.
+template <int D>
+__device__ __forceinline__ void mfma_combine_segment(const float *slot, const AttnParams &p, const Segment &seg, int kvh) {
+    const int G = p.G, head0 = kvh * G;
+    const float *sm_m = slot + kWaves * G * (D + 4), *sm_l = sm_m + kWaves * kMaxGroup;
+    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+        const int g = idx / D, d = idx - g * D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm_m[w * kMaxGroup + g]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float mw = sm_m[w * kMaxGroup + g];
+            if (mw > -INFINITY) {
+                const float a = fast_exp2(mw - M);
+                num += a * slot[(w * G + g) * (D + 4) + d];
+                den += a * sm_l[w * kMaxGroup + g];
+            }
+        }
+        store_segment_element<D>(p, seg, head0, idx, M, num, den);
+    }
+}
+
+// Finished segments wait in a ring of shared-memory slots (their per-wave states) until the workgroup meets to
+// combine them: when the ring is full or the range ends.  A range that holds the end of one request and the start of
+// the next is thus processed without a stop in the middle.
+template <int PS>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
-    __shared__ CombineSmem<D> sm[RING];
     __shared__ PlanSmem ps;
-    extern __shared__ int E[];                               // E[B + 1] tile offsets, then Lc[B] lengths
+    extern __shared__ __align__(16) int E[];                 // E[B + 1] tile offsets, then Lc[B] lengths, then the ring
+    float *ring = reinterpret_cast<float *>(reinterpret_cast<char *>(E) + p.lds.ring_off);
+    const int RING = p.lds.ring_depth, slot_floats = p.lds.slot_floats;
 
     int w, kvh;
     wg_coords(p, &w, &kvh);
@@ -300,8 +342,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         OMNI_STAMP(p, 2);
 
         int b = first_b;
-        int npend = 0;                   // finished segments waiting in sm[0 .. npend)
-        Segment pend[RING];
+        int npend = 0;                   // finished segments waiting in ring slots 0 .. npend-1
+        int pend0 = 0, pend1 = 0, pend2 = 0, pend3 = 0;          // their requests
         while (true) {
             const Segment seg = plan_segment(E, Lc, pl, b, range, start, end);
             MfmaState st;
@@ -329,27 +371,35 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             // the waiting segments when the ring is full or the range ends
             st.l += __shfl_xor(st.l, 16);                        // per-lane sums of the four lane groups; m is common
             st.l += __shfl_xor(st.l, 32);
-            CombineSmem<D> &my = sm[npend];
+            float *slot = ring + (size_t)npend * slot_floats;
             if (col < G) {
+                float *orow = slot + (wave * G + col) * (D + 4);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float4 lo4 = make_float4(st.acc[0][i], st.acc[1][i], st.acc[2][i], st.acc[3][i]);
                     float4 hi4 = make_float4(st.acc[4][i], st.acc[5][i], st.acc[6][i], st.acc[7][i]);
-                    *reinterpret_cast<float4 *>(&my.o[wave][col][32 * j + 8 * i]) = lo4;
-                    *reinterpret_cast<float4 *>(&my.o[wave][col][32 * j + 8 * i + 4]) = hi4;
+                    *reinterpret_cast<float4 *>(orow + 32 * j + 8 * i) = lo4;
+                    *reinterpret_cast<float4 *>(orow + 32 * j + 8 * i + 4) = hi4;
                 }
-                if (j == 0) { my.m[wave][col] = st.m; my.l[wave][col] = st.l; }
+                if (j == 0) {
+                    float *sm_m = slot + kWaves * G * (D + 4);
+                    sm_m[wave * kMaxGroup + col] = st.m; sm_m[kWaves * kMaxGroup + wave * kMaxGroup + col] = st.l;
+                }
             }
             if (cur.req < 0) OMNI_STAMP(p, 7);                   // this wave's last tile is done
-#pragma unroll
-            for (int r = 0; r < RING; ++r) if (r == npend) pend[r] = seg;
+            if (npend == 0) pend0 = b; else if (npend == 1) pend1 = b; else if (npend == 2) pend2 = b; else pend3 = b;
             ++npend;
             const bool last = __builtin_amdgcn_readfirstlane(E[b]) + seg.hi >= end;
             if (last || npend == RING) {
                 lds_barrier();
 #pragma unroll
-                for (int r = 0; r < RING; ++r)
-                    if (r < npend) wg_combine_segment<D>(sm[r], p, pend[r], kvh);    // nobody waits for its stores
+                for (int r = 0; r < kMaxRing; ++r) {
+                    if (r < npend) {
+                        const int rb = r == 0 ? pend0 : (r == 1 ? pend1 : (r == 2 ? pend2 : pend3));
+                        const Segment sg = plan_segment(E, Lc, pl, rb, range, start, end);
+                        mfma_combine_segment<D>(ring + (size_t)r * slot_floats, p, sg, kvh);   // nobody waits for its stores
+                    }
+                }
                 lds_barrier();
                 npend = 0;
             }

@@ -44,6 +44,8 @@ struct omni_handle_s {
     int nw = 1;                  // workgroups per KV head
     int r_cap = 0;               // bound on partial-result slots (range index + request index)
     size_t off_ml = 0, off_o = 0, ws_bytes = 0;
+    MfmaLds lds{};               // shared-memory layout of the matrix-core kernel
+    bool lds_attr_set = false;   // the kernel has been told how much dynamic shared memory it may get
     void *ws = nullptr;
     size_t ws_given = 0;
     // profiling aid: event pairs around the partition kernel
@@ -58,6 +60,8 @@ struct omni_handle_s {
         kernel = (tune_kernel == 2 && mfma_ok) ? 2 : (tune_kernel == 1 ? 1 : (mfma_ok ? 2 : 1));
         nw = tune_target_wgs / d.num_kv_heads;
         if (nw < 1) nw = 1;
+        lds = mfma_lds_layout(d.batch, G);
+        lds_attr_set = false;
         long long ranges = nw;
         if (tune_force_partition > 0) {
             const long long tiles = (long long)d.batch * ((max_ctx + kTile - 1) / kTile);
@@ -213,6 +217,7 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
     p.log2_ps = ilog2(d.page_size);
     p.out_bf16 = d.out_dtype == OMNI_BF16;
+    p.lds = h->lds;
 #ifdef OMNI_TRACE
     p.trace = g_omni_trace;
 #endif
@@ -223,15 +228,17 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     const bool prof = (size_t)(2 * h->prof_used + 1) < h->prof_events.size() && (h->prof_calls++ % h->prof_stride) == 0;
     if (prof && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
     if (h->kernel == 2) {
-        // Two segment buffers per workgroup as long as two workgroups still fit the 160 KB of a compute unit.
-        const bool ring2 = 2 * (2 * sizeof(CombineSmem<128>) + dyn + 256) <= 160 * 1024;
-        if (d.page_size == 16) {
-            if (ring2) decode_mfma_kernel<16, 2><<<grid, kThreads, dyn, s>>>(p);
-            else decode_mfma_kernel<16, 1><<<grid, kThreads, dyn, s>>>(p);
-        } else {
-            if (ring2) decode_mfma_kernel<32, 2><<<grid, kThreads, dyn, s>>>(p);
-            else decode_mfma_kernel<32, 1><<<grid, kThreads, dyn, s>>>(p);
+        const void *fn = d.page_size == 16 ? reinterpret_cast<const void *>(&decode_mfma_kernel<16>)
+                                           : reinterpret_cast<const void *>(&decode_mfma_kernel<32>);
+        if (!h->lds_attr_set) {          // more than the default 64 KB of dynamic shared memory
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, h->lds.total) != hipSuccess) {
+                (void)hipGetLastError();
+                return OMNI_ERR_HIP;
+            }
+            h->lds_attr_set = true;
         }
+        if (d.page_size == 16) decode_mfma_kernel<16><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
+        else decode_mfma_kernel<32><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
     } else if (d.kv_dtype == OMNI_BF16) {
         if (d.head_dim == 128) launch_valu<uint16_t, 128>(p, grid, dyn, s);
         else launch_valu<uint16_t, 64>(p, grid, dyn, s);
