@@ -165,28 +165,49 @@ inline MfmaLds mfma_lds_layout(int B, int G) {
     return L;
 }
 
-// Combine the four waves' (m, l, o) of one finished segment held in a ring slot and store the result.  All threads
-// call it between barriers.
+// Combine the four waves' (m, l, o) of one finished segment held in a ring slot and store the result: the
+// normalised output if the request lies inside one range, else the unnormalised values (plus, once per head, the
+// running max and sum) into the segment's partial-result slot.  Every thread owns four consecutive output
+// elements.  All threads call it between barriers.
 template <int D>
 __device__ __forceinline__ void mfma_combine_segment(const float *slot, const AttnParams &p, const Segment &seg, int kvh) {
     const int G = p.G, head0 = kvh * G;
     const float *sm_m = slot + kWaves * G * (D + 4), *sm_l = sm_m + kWaves * kMaxGroup;
-    for (int idx = threadIdx.x; idx < G * D; idx += kThreads) {
+    for (int idx = 4 * threadIdx.x; idx < G * D; idx += 4 * kThreads) {
         const int g = idx / D, d = idx - g * D;
         float M = -INFINITY;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm_m[w * kMaxGroup + g]);
-        float num = 0.f, den = 0.f;
+        float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+        float den = 0.f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
             const float mw = sm_m[w * kMaxGroup + g];
             if (mw > -INFINITY) {
                 const float a = fast_exp2(mw - M);
-                num += a * slot[(w * G + g) * (D + 4) + d];
+                const float4 o = *reinterpret_cast<const float4 *>(slot + (w * G + g) * (D + 4) + d);
+                num.x += a * o.x; num.y += a * o.y; num.z += a * o.z; num.w += a * o.w;
                 den += a * sm_l[w * kMaxGroup + g];
             }
         }
-        store_segment_element<D>(p, seg, head0, idx, M, num, den);
+        if (seg.nparts == 1) {
+            const size_t o0 = ((size_t)seg.b * p.Hq + head0) * D + idx;
+            const bool live = den > 0.f;
+            const float4 r = make_float4(live ? num.x / den : 0.f, live ? num.y / den : 0.f, live ? num.z / den : 0.f,
+                                         live ? num.w / den : 0.f);
+            if (p.out_bf16) {
+                uint2 pk;
+                pk.x = (uint32_t)float_to_bf16_rne(r.x) | ((uint32_t)float_to_bf16_rne(r.y) << 16);
+                pk.y = (uint32_t)float_to_bf16_rne(r.z) | ((uint32_t)float_to_bf16_rne(r.w) << 16);
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(p.out) + o0) = pk;
+            } else {
+                *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.out) + o0) = r;
+            }
+        } else {
+            const size_t pi = (size_t)seg.slot * p.Hq + head0;
+            *reinterpret_cast<float4 *>(p.ws.part_o + pi * D + idx) = num;
+            if (d == 0) p.ws.part_ml[pi + g] = make_float2(M, den);
+        }
     }
 }
 
