@@ -31,7 +31,6 @@ __device__ __forceinline__ void merge_request(const AttnParams &p, int b, int kv
                     oj[u] = *reinterpret_cast<const float4 *>(p.ws.part_o + pi * D + idx);
                 }
             }
-            OMNI_STAMP(p, 22);
 #pragma unroll
             for (int u = 0; u < kRound; ++u) {
                 if (ml[u].y > 0.f) {
@@ -57,7 +56,6 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void merge_kernel(AttnParams p) {
     __shared__ PlanSmem ps;
     extern __shared__ int E[];                               // E[B + 1] tile offsets, then Lc[B] lengths
-    OMNI_STAMP(p, 20);
     Plan pl;
     if (p.plan.B <= kWavePlanMax) {                          // every wave plans for itself: no barrier
         WavePlan wp;
@@ -72,12 +70,10 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(AttnParams p) {
     const int first_range = e0 / pl.S, last_range = (e1 - 1) / pl.S;
     const int n = last_range - first_range + 1;
     if (n == 1) return;                                      // finished by the attention kernel
-    OMNI_STAMP(p, 21);
     // 4, 8 or 16 pieces per round, so that a request cut into many pieces still costs few dependent trips to memory
     if (n <= 4) merge_request<D, 4>(p, b, kvh, first_range + b, n);
     else if (n <= 8) merge_request<D, 8>(p, b, kvh, first_range + b, n);
     else merge_request<D, 16>(p, b, kvh, first_range + b, n);
-    OMNI_STAMP(p, 23);
 }
 
 struct AppendParams {
