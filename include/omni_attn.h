@@ -35,6 +35,8 @@
  *                       this step; 0 is legal and yields an all-zero output row
  *   positions           [batch] int32; token index at which omni_kv_append writes; < 0 skips the request
  * Query head h reads KV head h / (num_q_heads / num_kv_heads).  No mask, bias, window or soft-cap.
+ * Alignment: q, out, k_new, v_new, k_cache and v_cache must be 16-byte aligned (rows are moved in 16-byte pieces);
+ * the int32 arrays 4-byte aligned.  A misaligned pointer is reported as OMNI_ERR_SHAPE.
  */
 #ifndef OMNI_ATTN_H
 #define OMNI_ATTN_H

@@ -24,6 +24,8 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
 
+bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
 }  // namespace
 
 #ifdef OMNI_TRACE
@@ -198,6 +200,9 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
                                       const int32_t *context_lens, float scale, void *out, void *stream) {
     if (!h || !q || !k_cache || !v_cache || !block_table || !context_lens || !out) return OMNI_ERR_NULL;
     if (!h->ws || h->ws_given < h->ws_bytes) return OMNI_ERR_WORKSPACE;
+    if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(out, 16) ||
+        misaligned(k_new, 16) || misaligned(v_new, 16) || misaligned(block_table, 4) || misaligned(context_lens, 4))
+        return OMNI_ERR_SHAPE;
     const omni_attn_desc_t &d = h->d;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
@@ -290,6 +295,9 @@ static omni_status_t launch_append(omni_handle_t h, const void *k_new, const voi
                                    const int32_t *block_table, const int32_t *positions, int positions_are_lengths,
                                    void *stream) {
     if (!h || !k_new || !v_new || !k_cache || !v_cache || !block_table || !positions) return OMNI_ERR_NULL;
+    if (misaligned(k_new, 16) || misaligned(v_new, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) ||
+        misaligned(block_table, 4) || misaligned(positions, 4))
+        return OMNI_ERR_SHAPE;
     const omni_attn_desc_t &d = h->d;
     AppendParams p;
     p.k_new = k_new; p.v_new = v_new; p.k_cache = k_cache; p.v_cache = v_cache;

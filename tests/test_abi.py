@@ -65,6 +65,8 @@ def test_workspace_and_null_argument_errors_without_touching_the_gpu():
     assert L.omni_kv_append(h._h, None, 256, 256, 256, 256, 256, None) == 1
     assert L.omni_kv_append(None, 256, 256, 256, 256, 256, 256, None) == 1
     assert L.omni_debug_gather(h._h, 256, 256, 256, 99, 256, None) == 2
+    assert L.omni_kv_append(h._h, 256 + 8, 256, 256, 256, 256, 256, None) == 2        # rows move in 16-byte pieces
+    assert L.omni_kv_append(h._h, 256, 256, 256, 256, 256 + 2, 256, None) == 2        # int32 array off by 2 bytes
 
 
 def test_tuning_validation_and_plan():
