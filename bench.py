@@ -150,11 +150,38 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - a) * 1e3 / K
 
-    ms_noevents = ms_other = ms_warm = None
+    ms_noevents = ms_other = ms_warm = ms_graph = host_us_graph = host_us_eager = None
     if not args.timed_only:
         ms_noevents = timed(step)
         ms_other = timed(step_fused if args.unfused else step_two_launches)
         ms_warm = timed(step, fixed_replica=True)
+        # the same steps recorded once as a HIP graph (one step per pool replica) and replayed: what is left of the
+        # step time when the host issues one call per R steps instead of one per kernel
+        gs = torch.cuda.Stream()
+        for r in range(R):
+            h.omni_decode_step(q, k_new, v_new, kc[r], vc[r], bt, lens, scale, out, gs)
+        torch.cuda.synchronize()
+        with omni.Graph(gs) as graph:
+            for r in range(R):
+                h.omni_decode_step(q, k_new, v_new, kc[r], vc[r], bt, lens, scale, out, gs)
+        for _ in range(3):
+            graph.launch()
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(max(1, K // R)):
+            graph.launch()
+        issued = time.perf_counter()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - a) * 1e3 / (max(1, K // R) * R)
+        host_us_graph = (issued - a) * 1e6 / (max(1, K // R) * R)
+        graph.close()
+        # host time to issue a step eagerly (python + ctypes + two launches), GPU idle-free queue not awaited
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for i in range(64):
+            step(i)
+        host_us_eager = (time.perf_counter() - a) * 1e6 / 64
+        torch.cuda.synchronize()
 
     # ---- the memory system's ceiling for a kernel of this size: a plain streaming read of one replica's K and V pools
     # (pool bytes >= the algorithmic bytes: it also reads the unused tail slots), timed with event pairs like the
@@ -246,6 +273,8 @@ def main():
         "extra": {"ms_per_step_without_event_pairs": ms_noevents,
                   ("ms_per_step_fused" if args.unfused else "ms_per_step_separate_append"): ms_other,
                   "ms_per_step_single_replica_cache_warm": ms_warm,
+                  "ms_per_step_replayed_as_hip_graph": ms_graph,
+                  "host_us_to_issue_a_step_eager": host_us_eager, "host_us_to_issue_a_step_in_graph": host_us_graph,
                   "kv_gbs_cache_warm": kv_bytes / (ms_warm * 1e-3) / 1e9 if ms_warm else None,
                   "parity_max_abs_err_sampled": max_err},
     }

@@ -154,6 +154,26 @@ omni_status_t omni_get_plan(omni_handle_t h, int32_t *kernel, int32_t *partition
 
 const char *omni_status_string(omni_status_t s);
 
+/*
+ * Execution graphs (Section 3.3 lists execution-graph compilation among the engine's options and Section 4 credits
+ * it with the largest gains of the autoregressive stages).  Every launch above has a grid that does not depend on
+ * device data, allocates nothing and never synchronises, so a sequence of omni_decode_step / omni_paged_decode_attn /
+ * omni_kv_append calls (for instance one per layer) can be recorded once and replayed with one host call per token:
+ *   omni_graph_begin(stream);  ... calls on `stream` ...;  omni_graph_end(stream, &g);  omni_graph_launch(g, stream);
+ * The graph replays the recorded pointers and scalar arguments (scale); the CONTENTS of q, context_lens, block_table,
+ * k_new / v_new and the pools may change between replays.  `stream` must be a created stream (not NULL: the null
+ * stream cannot be captured).  Between begin and end the calling thread must make no synchronising or allocating HIP call on any
+ * stream, and each handle used must have run once on this device before (its first launch configures the kernel).
+ * A graph is replayed on one stream at a time (the handles' workspaces are in it).  omni_graph_end returns the
+ * instantiated graph; omni_graph_destroy(NULL) is a no-op.
+ * Errors: NULL, UNSUPPORTED (null stream), HIP (capture or instantiation failed; the capture is ended and dropped).
+ */
+typedef struct omni_graph_s *omni_graph_t;
+omni_status_t omni_graph_begin(void *stream);
+omni_status_t omni_graph_end(void *stream, omni_graph_t *out_graph);
+omni_status_t omni_graph_launch(omni_graph_t g, void *stream);
+void omni_graph_destroy(omni_graph_t g);
+
 /* ---- test / debugging aids: these synchronise the stream and copy to HOST memory ---- */
 
 /* After an omni_paged_decode_attn call on `stream`: host_out[0] = range length (tokens) the device chose,

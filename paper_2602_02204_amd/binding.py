@@ -21,7 +21,7 @@ EXPORTS = (
     "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_set_workspace",
     "omni_paged_decode_attn", "omni_kv_append", "omni_decode_step", "omni_get_plan", "omni_status_string",
     "omni_debug_last_plan", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
-    "omni_debug_profile_end",
+    "omni_debug_profile_end", "omni_graph_begin", "omni_graph_end", "omni_graph_launch", "omni_graph_destroy",
 )
 
 
@@ -64,8 +64,12 @@ def lib():
         L.omni_debug_stream_read.argtypes = [vp, C.c_size_t, vp, C.c_size_t, vp, vp]
         L.omni_debug_profile_begin.argtypes = [vp, C.c_int32, C.c_int32]
         L.omni_debug_profile_end.argtypes = [vp, C.POINTER(C.c_float), i32p]
+        L.omni_graph_begin.argtypes = [vp]
+        L.omni_graph_end.argtypes = [vp, C.POINTER(vp)]
+        L.omni_graph_launch.argtypes = [vp, vp]
+        L.omni_graph_destroy.argtypes = [vp]; L.omni_graph_destroy.restype = None
         for name in EXPORTS:
-            if name not in ("omni_destroy", "omni_status_string"):
+            if name not in ("omni_destroy", "omni_status_string", "omni_graph_destroy"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -76,6 +80,39 @@ def omni_debug_stream_read(a, b, sink, stream=None) -> None:
     nbytes = lambda t: 0 if t is None else t.numel() * t.element_size()
     _ck(lib().omni_debug_stream_read(_ptr(a), nbytes(a), _ptr(b) if b is not None else None, nbytes(b), _ptr(sink),
                                      _stream(stream)), "omni_debug_stream_read")
+
+
+class Graph:
+    """A recorded sequence of library calls on one stream: `with Graph(stream) as g: ...calls...`, then g.launch()."""
+
+    def __init__(self, stream):
+        self._stream = stream
+        self._g = None
+
+    def __enter__(self):
+        _ck(lib().omni_graph_begin(_stream(self._stream)), "omni_graph_begin")
+        return self
+
+    def __exit__(self, exc_type, exc, tb):
+        g = C.c_void_p()
+        status = lib().omni_graph_end(_stream(self._stream), C.byref(g))      # ends the capture also after an error
+        if exc_type is None:
+            _ck(status, "omni_graph_end")
+            self._g = g
+        elif g:
+            lib().omni_graph_destroy(g)
+        return False
+
+    def launch(self, stream=None) -> None:
+        _ck(lib().omni_graph_launch(self._g, _stream(stream if stream is not None else self._stream)), "omni_graph_launch")
+
+    def close(self) -> None:
+        if self._g is not None and _lib is not None:
+            _lib.omni_graph_destroy(self._g)
+        self._g = None
+
+    def __del__(self):
+        self.close()
 
 
 def status_string(status: int) -> str:

@@ -388,4 +388,59 @@ omni_status_t omni_debug_stream_read(const void *a, size_t a_bytes, const void *
     return OMNI_OK;
 }
 
+struct omni_graph_s {
+    hipGraphExec_t exec = nullptr;
+};
+
+omni_status_t omni_graph_begin(void *stream) {
+    if (!stream) return OMNI_ERR_UNSUPPORTED;
+    (void)hipGetLastError();
+    if (hipStreamBeginCapture(reinterpret_cast<hipStream_t>(stream), hipStreamCaptureModeThreadLocal) != hipSuccess) {
+        (void)hipGetLastError();
+        return OMNI_ERR_HIP;
+    }
+    return OMNI_OK;
+}
+
+omni_status_t omni_graph_end(void *stream, omni_graph_t *out_graph) {
+    if (out_graph) *out_graph = nullptr;
+    if (!stream) return OMNI_ERR_UNSUPPORTED;
+    hipGraph_t graph = nullptr;
+    const hipError_t e = hipStreamEndCapture(reinterpret_cast<hipStream_t>(stream), &graph);   // always ends the capture
+    if (!out_graph) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return OMNI_ERR_NULL;
+    }
+    if (e != hipSuccess || !graph) {
+        (void)hipGetLastError();
+        if (graph) (void)hipGraphDestroy(graph);
+        return OMNI_ERR_HIP;
+    }
+    omni_graph_s *g = new (std::nothrow) omni_graph_s();
+    if (!g || hipGraphInstantiate(&g->exec, graph, nullptr, nullptr, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipGraphDestroy(graph);
+        delete g;
+        return OMNI_ERR_HIP;
+    }
+    (void)hipGraphDestroy(graph);
+    *out_graph = g;
+    return OMNI_OK;
+}
+
+omni_status_t omni_graph_launch(omni_graph_t g, void *stream) {
+    if (!g || !g->exec) return OMNI_ERR_NULL;
+    if (hipGraphLaunch(g->exec, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) {
+        (void)hipGetLastError();
+        return OMNI_ERR_HIP;
+    }
+    return OMNI_OK;
+}
+
+void omni_graph_destroy(omni_graph_t g) {
+    if (!g) return;
+    if (g->exec) (void)hipGraphExecDestroy(g->exec);
+    delete g;
+}
+
 }  // extern "C"
