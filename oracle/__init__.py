@@ -126,3 +126,33 @@ def gather(cache, block_table, context_lens, b: int, dtype: str) -> np.ndarray:
     out = np.zeros((int(lens[b]), Hkv, D), dtype=cache.dtype)
     lib().oracle_gather(C.byref(s), _p(cache), _p(block_table), _p(lens), b, _p(out))
     return out
+
+
+def kv_pack(cache, block_table, context_lens, token_offsets, total_tokens: int) -> np.ndarray:
+    """Dense copy of every request's rows (Section 3.4: the connector moves a request's KV cache between stages).
+
+    dense[token_offsets[b] + t, g, :] = cache[block_table[b, t // ps], g, t % ps, :] for t < context_lens[b];
+    requests with token_offsets[b] < 0 are skipped; rows of `dense` that no request owns stay zero.  A bit copy.
+    Pins: brute-force triple loop, pack/unpack round trip into a poisoned pool, agreement with `gather`.
+    """
+    P, Hkv, ps, D = cache.shape
+    dense = np.zeros((int(total_tokens), Hkv, D), dtype=cache.dtype)
+    for b in range(block_table.shape[0]):
+        L, off = int(context_lens[b]), int(token_offsets[b])
+        if off < 0 or L <= 0:
+            continue
+        t = np.arange(L)
+        dense[off:off + L] = cache[block_table[b, t // ps], :, t % ps, :]
+    return dense
+
+
+def kv_unpack(dense, cache, block_table, context_lens, token_offsets) -> None:
+    """Inverse of kv_pack, in place: cache[block_table[b, t // ps], g, t % ps, :] = dense[token_offsets[b] + t, g, :]
+    for t < context_lens[b] of every request with token_offsets[b] >= 0.  No other byte of `cache` changes."""
+    P, Hkv, ps, D = cache.shape
+    for b in range(block_table.shape[0]):
+        L, off = int(context_lens[b]), int(token_offsets[b])
+        if off < 0 or L <= 0:
+            continue
+        t = np.arange(L)
+        cache[block_table[b, t // ps], :, t % ps, :] = dense[off:off + L]

@@ -331,3 +331,64 @@ def test_gather_is_token_ordered_bit_copy():
         g = oracle.gather(wl.v_cache, wl.block_table, wl.context_lens, b, wl.dtype)
         L = int(wl.context_lens[b]); t = np.arange(L)
         assert np.array_equal(g, wl.v_cache[wl.block_table[b, t // wl.ps], :, t % wl.ps, :])
+
+
+# ---- KV pack / unpack (the dense per-request copies a connector ships between stages)
+
+def _pack_case(seed=11):
+    wl = W.make("tiny", seed=seed)
+    lens = wl.context_lens.copy()
+    lens[1] = 0                                              # an empty request
+    order = [2, 0, 3, 1]                                     # dense order differs from batch order
+    offs = np.full(wl.B, -1, dtype=np.int64)
+    run = 3                                                  # and the dense buffer has rows nobody owns
+    for b in order:
+        offs[b] = run
+        run += int(lens[b]) + 1
+    offs[3] = -1                                             # a skipped request
+    return wl, lens, offs, run
+
+
+def test_kv_pack_equals_brute_force_loops():
+    wl, lens, offs, total = _pack_case()
+    dense = oracle.kv_pack(wl.k_cache, wl.block_table, lens, offs, total)
+    want = np.zeros_like(dense)
+    for b in range(wl.B):
+        if offs[b] < 0:
+            continue
+        for t in range(int(lens[b])):
+            for g in range(wl.Hkv):
+                want[offs[b] + t, g] = wl.k_cache[wl.block_table[b, t // wl.ps], g, t % wl.ps]
+    assert np.array_equal(dense.view(np.uint8), want.view(np.uint8))
+    for b in range(wl.B):                                    # and with the per-request gather of the C oracle
+        if offs[b] >= 0 and lens[b] > 0:
+            g1 = oracle.gather(wl.k_cache, wl.block_table, lens, b, wl.dtype)
+            assert np.array_equal(dense[offs[b]:offs[b] + lens[b]].view(np.uint8), g1.view(np.uint8))
+
+
+def test_kv_unpack_is_the_inverse_and_touches_nothing_else():
+    wl, lens, offs, total = _pack_case(seed=12)
+    dense = oracle.kv_pack(wl.v_cache, wl.block_table, lens, offs, total)
+    pool = np.full_like(wl.v_cache, np.float32(123.0))       # a different pool: only owned rows may change
+    oracle.kv_unpack(dense, pool, wl.block_table, lens, offs)
+    owned = np.zeros(wl.v_cache.shape[:3], dtype=bool)       # [page, head, slot]
+    for b in range(wl.B):
+        if offs[b] < 0:
+            continue
+        for t in range(int(lens[b])):
+            owned[wl.block_table[b, t // wl.ps], :, t % wl.ps] = True
+    assert np.array_equal(pool[owned].view(np.uint8), wl.v_cache[owned].view(np.uint8))
+    assert np.all(pool[~owned] == np.float32(123.0))
+    again = oracle.kv_pack(pool, wl.block_table, lens, offs, total)
+    assert np.array_equal(again.view(np.uint8), dense.view(np.uint8))
+
+
+def test_kv_pack_mutations_are_caught():
+    """A transposed slot/page index or a dropped offset must change the result (the pins above would fail)."""
+    wl, lens, offs, total = _pack_case(seed=13)
+    good = oracle.kv_pack(wl.k_cache, wl.block_table, lens, offs, total)
+    shifted = oracle.kv_pack(wl.k_cache, wl.block_table, lens, offs + (offs >= 0), total + 1)[1:]
+    assert np.array_equal(shifted.view(np.uint8), good.view(np.uint8))                  # offsets are honoured exactly
+    bt2 = wl.block_table.copy()
+    bt2[0, 0], bt2[0, 1] = bt2[0, 1], bt2[0, 0]
+    assert not np.array_equal(oracle.kv_pack(wl.k_cache, bt2, lens, offs, total).view(np.uint8), good.view(np.uint8))
