@@ -201,6 +201,40 @@ def main():
         ceiling = {"kernel": "stream_read_kernel", "bytes": pool_bytes, "avg_us": us, "GB/s": pool_bytes / us / 1e3,
                    "attention_vs_stream_read": (kv_bytes / (k_avg_ms * 1e3)) / (pool_bytes / us)}
 
+    # ---- the dense copies a connector ships (whole batch packed out of the pools, and unpacked back in)
+    pack = None
+    if not args.timed_only:
+        offs = torch.from_numpy(np.concatenate([[0], np.cumsum(wl.context_lens[:-1])]).astype(np.int64)).cuda()
+        kd = torch.empty((wl.total_tokens, wl.Hkv, wl.D), dtype=k0.dtype, device="cuda")
+        vd = torch.empty_like(kd)
+        pack = {"bytes_read_plus_written": 2 * kv_bytes}
+        for nm, fn in (("pack", lambda r: h.omni_kv_pack(kc[r], vc[r], bt, lens, offs, kd, vd, stream)),
+                       ("unpack", lambda r: h.omni_kv_unpack(kd, vd, kc[r], vc[r], bt, lens, offs, stream))):
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(24)]
+            for i in range(4):
+                fn(i % R)
+            for i, (a, b) in enumerate(evs):
+                a.record(stream)
+                fn(i % R)
+                b.record(stream)
+            torch.cuda.synchronize()
+            us = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e3
+            pack[nm + "_avg_us"] = us
+            pack[nm + "_GB/s"] = 2 * kv_bytes / us / 1e3
+        # yardstick: the runtime's own device-to-device copy of the same dense buffers
+        kd2, vd2 = torch.empty_like(kd), torch.empty_like(vd)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+        for i, (a, b) in enumerate(evs):
+            a.record(stream)
+            kd2.copy_(kd)
+            vd2.copy_(vd)
+            b.record(stream)
+        torch.cuda.synchronize()
+        us = float(np.mean([a.elapsed_time(b) for a, b in evs[2:]])) * 1e3
+        pack["plain_copy_avg_us"] = us
+        pack["plain_copy_GB/s"] = 2 * kv_bytes / us / 1e3
+        del kd, vd, kd2, vd2
+
     if args.calibrate_copy:                  # 1 GiB read + 1 GiB written per copy: the yardstick for FETCH_SIZE / WRITE_SIZE
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -276,6 +310,7 @@ def main():
                   "ms_per_step_replayed_as_hip_graph": ms_graph,
                   "host_us_to_issue_a_step_eager": host_us_eager, "host_us_to_issue_a_step_in_graph": host_us_graph,
                   "kv_gbs_cache_warm": kv_bytes / (ms_warm * 1e-3) / 1e9 if ms_warm else None,
+                  "kv_pack_unpack": pack,
                   "parity_max_abs_err_sampled": max_err},
     }
     print(json.dumps(result))

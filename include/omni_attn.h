@@ -145,6 +145,25 @@ omni_status_t omni_decode_step(omni_handle_t h,
                                const int32_t *block_table, const int32_t *context_lens,
                                float scale, void *out, void *stream);
 
+/*
+ * Dense copies of whole requests, the payload a connector ships when the KV cache of a request moves between a
+ * prefill and a decode engine (Section 3.4, "Disaggregated Data Transfer": the connector also carries KV cache between
+ * prefill and decode).  For every request b with token_offsets[b] >= 0 and every t < context_lens[b]:
+ *   pack:    k_dense[token_offsets[b] + t, g, :] = k_cache[block_table[b][t / page_size], g, t % page_size, :]
+ *   unpack:  the same assignment in the other direction
+ * and likewise for V; bit copies.  k_dense / v_dense are [total tokens, num_kv_heads, head_dim] DEVICE buffers of the
+ * cache dtype; token_offsets is a DEVICE array [batch] of int64 (first dense row of each request; < 0 skips the
+ * request; the caller keeps the ranges of different requests apart).  Pack writes only the addressed dense rows,
+ * unpack only the addressed pool rows.  Lengths above max_context_hint (if one was given) are not supported.
+ * One launch each; grid (ceil(max context / 32), batch), data-independent.  Errors: NULL, SHAPE (alignment), HIP.
+ */
+omni_status_t omni_kv_pack(omni_handle_t h, const void *k_cache, const void *v_cache, const int32_t *block_table,
+                           const int32_t *context_lens, const int64_t *token_offsets, void *k_dense, void *v_dense,
+                           void *stream);
+omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v_dense, void *k_cache, void *v_cache,
+                             const int32_t *block_table, const int32_t *context_lens, const int64_t *token_offsets,
+                             void *stream);
+
 /* Host-known part of the launch plan: which kernel (OMNI_TUNE_KERNEL value actually used), the data-independent
  * grid (workgroups) of the attention kernel, the grid of the merge kernel that follows it, the number of
  * partial-result slots the workspace is sized for, and threads per workgroup.  The range length itself is chosen on the device from

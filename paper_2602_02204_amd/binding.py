@@ -19,7 +19,8 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = (
     "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_set_workspace",
-    "omni_paged_decode_attn", "omni_kv_append", "omni_decode_step", "omni_get_plan", "omni_status_string",
+    "omni_paged_decode_attn", "omni_kv_append", "omni_decode_step", "omni_kv_pack", "omni_kv_unpack", "omni_get_plan",
+    "omni_status_string",
     "omni_debug_last_plan", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
     "omni_debug_profile_end", "omni_graph_begin", "omni_graph_end", "omni_graph_launch", "omni_graph_destroy",
 )
@@ -57,6 +58,8 @@ def lib():
         L.omni_paged_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_kv_append.argtypes = [vp] * 8
         L.omni_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
+        L.omni_kv_pack.argtypes = [vp] * 9
+        L.omni_kv_unpack.argtypes = [vp] * 9
         L.omni_get_plan.argtypes = [vp] + [i32p] * 5
         L.omni_status_string.argtypes = [C.c_int]; L.omni_status_string.restype = C.c_char_p
         L.omni_debug_last_plan.argtypes = [vp, i32p, vp]
@@ -196,6 +199,14 @@ class Handle:
         _ck(lib().omni_get_plan(self._h, *[C.byref(x) for x in v]), "omni_get_plan")
         keys = ("kernel", "partition_grid", "merge_grid", "max_request_parts", "threads_per_workgroup")
         return dict(zip(keys, (x.value for x in v)))
+
+    def omni_kv_pack(self, k_cache, v_cache, block_table, context_lens, token_offsets, k_dense, v_dense, stream=None) -> None:
+        _ck(lib().omni_kv_pack(self._h, _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(context_lens),
+                               _ptr(token_offsets), _ptr(k_dense), _ptr(v_dense), _stream(stream)), "omni_kv_pack")
+
+    def omni_kv_unpack(self, k_dense, v_dense, k_cache, v_cache, block_table, context_lens, token_offsets, stream=None) -> None:
+        _ck(lib().omni_kv_unpack(self._h, _ptr(k_dense), _ptr(v_dense), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                 _ptr(context_lens), _ptr(token_offsets), _stream(stream)), "omni_kv_unpack")
 
     def omni_debug_last_plan(self, stream=None) -> dict:
         arr = (C.c_int32 * 4)()

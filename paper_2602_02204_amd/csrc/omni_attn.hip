@@ -388,6 +388,41 @@ omni_status_t omni_debug_stream_read(const void *a, size_t a_bytes, const void *
     return OMNI_OK;
 }
 
+static omni_status_t launch_pack(omni_handle_t h, bool unpack, const void *k_src, const void *v_src, void *k_dst,
+                                 void *v_dst, const int32_t *block_table, const int32_t *context_lens,
+                                 const int64_t *token_offsets, void *stream) {
+    if (!h || !k_src || !v_src || !k_dst || !v_dst || !block_table || !context_lens || !token_offsets) return OMNI_ERR_NULL;
+    if (misaligned(k_src, 16) || misaligned(v_src, 16) || misaligned(k_dst, 16) || misaligned(v_dst, 16) ||
+        misaligned(block_table, 4) || misaligned(context_lens, 4) || misaligned(token_offsets, 8))
+        return OMNI_ERR_SHAPE;
+    const omni_attn_desc_t &d = h->d;
+    PackParams p;
+    p.k_src = k_src; p.v_src = v_src; p.k_dst = k_dst; p.v_dst = v_dst;
+    p.block_table = block_table; p.context_lens = context_lens;
+    p.token_offsets = reinterpret_cast<const long long *>(token_offsets);
+    p.Hkv = d.num_kv_heads; p.MB = d.max_blocks_per_seq; p.log2_ps = ilog2(d.page_size);
+    p.row_vecs = d.head_dim * (d.kv_dtype == OMNI_BF16 ? 2 : 4) / 16;
+    const dim3 grid((unsigned)((h->max_ctx + kPackTokens - 1) / kPackTokens), (unsigned)d.batch);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    (void)hipGetLastError();
+    if (unpack) kv_pack_kernel<true><<<grid, kThreads, 0, s>>>(p);
+    else kv_pack_kernel<false><<<grid, kThreads, 0, s>>>(p);
+    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+    return OMNI_OK;
+}
+
+omni_status_t omni_kv_pack(omni_handle_t h, const void *k_cache, const void *v_cache, const int32_t *block_table,
+                           const int32_t *context_lens, const int64_t *token_offsets, void *k_dense, void *v_dense,
+                           void *stream) {
+    return launch_pack(h, false, k_cache, v_cache, k_dense, v_dense, block_table, context_lens, token_offsets, stream);
+}
+
+omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v_dense, void *k_cache, void *v_cache,
+                             const int32_t *block_table, const int32_t *context_lens, const int64_t *token_offsets,
+                             void *stream) {
+    return launch_pack(h, true, k_dense, v_dense, k_cache, v_cache, block_table, context_lens, token_offsets, stream);
+}
+
 struct omni_graph_s {
     hipGraphExec_t exec = nullptr;
 };
