@@ -124,6 +124,21 @@ def test_random_shapes(seed):
             assert np.all(np.isfinite(got)) and err <= TOL[dtype], f"seed {seed} kernel {kernel} tw {tw}: {err:.3e}"
 
 
+@pytest.mark.parametrize("B,G,Hkv,top", [(257, 7, 4, 300), (1000, 8, 2, 120), (4096, 16, 1, 70), (4096, 4, 2, 40)])
+def test_large_batches(B, G, Hkv, top):
+    """Batches above 256 requests take the workgroup-wide plan; 4096 is the largest batch a handle accepts (with 16
+    heads per KV head the ring of segment slots shrinks to what still fits beside the plan)."""
+    rng = np.random.default_rng(B + G)
+    lens = rng.integers(0, top, size=B)
+    lens[rng.integers(0, B, size=B // 50 + 1)] = 0
+    wl = W.build("big", 4000 + B + G, lens, Hq=G * Hkv, Hkv=Hkv, D=128, ps=16, dtype=W.BF16, pool_factor=1.3)
+    ref = oracle_out(wl)
+    for kernel in kernels_for(wl):
+        got = DeviceBatch(wl, tuning={omni.OMNI_TUNE_KERNEL: kernel, omni.OMNI_TUNE_MIN_PARTITION: 32}).attend()
+        err = np.max(np.abs(got - ref))
+        assert np.all(np.isfinite(got)) and err <= TOL[wl.dtype], f"B {B} kernel {kernel}: {err:.3e}"
+
+
 def test_large_scores_and_peaked_softmax():
     # keys 6x larger: |scores| reach ~60, the softmax is nearly one-hot; the running-max rescale must hold up
     wl = W.build("peaked", 77, [700, 33, 1500], Hq=14, Hkv=2, D=128, ps=16, dtype=W.BF16)
