@@ -37,6 +37,9 @@ def lib():
         L.oracle_merge.argtypes = [C.c_int32, C.c_int32] + [C.c_void_p] * 4
         L.oracle_kv_append.restype = None
         L.oracle_kv_append.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 6
+        L.oracle_paged_prefill_attn.restype = C.c_int
+        L.oracle_paged_prefill_attn.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 7 + [C.c_float, C.c_void_p, C.c_void_p,
+                                                                                        C.c_int64, C.c_int32]
         L.oracle_gather.restype = None
         L.oracle_gather.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 3 + [C.c_int32, C.c_void_p]
         _lib = L
@@ -156,3 +159,45 @@ def kv_unpack(dense, cache, block_table, context_lens, token_offsets) -> None:
             continue
         t = np.arange(L)
         cache[block_table[b, t // ps], :, t % ps, :] = dense[off:off + L]
+
+
+def paged_prefill_attn(q, k_cache, v_cache, block_table, context_lens, q_lens, q_offsets, scale, dtype: str,
+                       rows: Optional[Sequence[Tuple[int, int, int]]] = None, num_threads: int = 0) -> np.ndarray:
+    """Multi-token (chunk) queries, causal inside the chunk: fp64 [Tq, Hq, D], or [len(rows), D] for (b, i, h) triples.
+
+    q is [Tq, Hq, D]; request b's chunk is rows q_offsets[b] .. +q_lens[b]; its query i sits at position
+    context_lens[b] - q_lens[b] + i and attends to every token up to and including itself.
+    """
+    _check(q, dtype, "q"); _check(k_cache, dtype, "k_cache"); _check(v_cache, dtype, "v_cache")
+    Tq, Hq, D = q.shape
+    P, Hkv, ps, D2 = k_cache.shape
+    assert D == D2 and Hq % Hkv == 0
+    s = _Shape(block_table.shape[0], Hq, Hkv, D, ps, block_table.shape[1], _DT[dtype], _DT[dtype])
+    bt = np.ascontiguousarray(block_table, dtype=np.int32)
+    lens = np.ascontiguousarray(context_lens, dtype=np.int32)
+    ql = np.ascontiguousarray(q_lens, dtype=np.int32)
+    qo = np.ascontiguousarray(q_offsets, dtype=np.int64)
+    if rows is not None:
+        r = np.ascontiguousarray(np.asarray(rows, dtype=np.int32).reshape(-1, 3))
+        out = np.zeros((len(r), D), dtype=np.float64)
+        lib().oracle_paged_prefill_attn(C.byref(s), _p(q), _p(k_cache), _p(v_cache), _p(bt), _p(lens), _p(ql), _p(qo),
+                                        C.c_float(scale), _p(out), _p(r), len(r), num_threads)
+    else:
+        out = np.zeros((Tq, Hq, D), dtype=np.float64)
+        lib().oracle_paged_prefill_attn(C.byref(s), _p(q), _p(k_cache), _p(v_cache), _p(bt), _p(lens), _p(ql), _p(qo),
+                                        C.c_float(scale), _p(out), None, 0, num_threads)
+    return out
+
+
+def kv_append_chunk(k_new, v_new, k_cache, v_cache, block_table, context_lens, q_lens, q_offsets) -> None:
+    """Bit copy of every chunk token's K/V rows into the pools: row q_offsets[b] + i of k_new / v_new [Tq, Hkv, D]
+    goes to position context_lens[b] - q_lens[b] + i of request b.  Requests with q_lens[b] <= 0 are skipped."""
+    P, Hkv, ps, D = k_cache.shape
+    for b in range(block_table.shape[0]):
+        n, L = int(q_lens[b]), int(context_lens[b])
+        if n <= 0:
+            continue
+        t = np.arange(L - n, L)
+        src = slice(int(q_offsets[b]), int(q_offsets[b]) + n)
+        k_cache[block_table[b, t // ps], :, t % ps, :] = k_new[src]
+        v_cache[block_table[b, t // ps], :, t % ps, :] = v_new[src]

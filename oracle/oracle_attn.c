@@ -213,3 +213,81 @@ void oracle_gather(const oracle_shape_t *s, const void *cache, const int32_t *bl
             memcpy((char *)dense_out + (size_t)dst * es, (const char *)cache + (size_t)src * es, row);
         }
 }
+
+/*
+ * Multi-token queries over the paged cache (chunked prefill: Section 2.2 and Section 3.3 name chunked prefill among
+ * the AR engine's scheduling features; a Talker prefill consumes the Thinker's hidden states in one such pass).
+ * Request b contributes q_lens[b] query rows, stored at rows q_offsets[b] .. q_offsets[b] + q_lens[b] - 1 of
+ * q [Tq, Hq, D]; query i of the chunk sits at position p = context_lens[b] - q_lens[b] + i of the request and attends
+ * to tokens 0 .. p (causal inside the chunk, everything before it), context_lens[b] counting the chunk's own tokens:
+ *
+ *     out[q_offsets[b] + i, h, :] = sum_{t <= p} softmax_t(scale * q_row . k_t) v_t
+ *
+ * With q_lens[b] = 1 this is the decode definition above.  `rows` (optional) lists nrows triples (b, i, h) to compute
+ * instead of everything; out is then [nrows, D], else [Tq, Hq, D].  Returns the number of threads used.
+ * Pins: equals oracle_paged_decode_attn for one-token chunks; dense causal brute force in numpy; rows after a
+ * query's position never influence it (NaN poison); the first token of a request returns its own V row.
+ */
+int oracle_paged_prefill_attn(const oracle_shape_t *s, const void *q, const void *k_cache, const void *v_cache,
+                              const int32_t *block_table, const int32_t *context_lens, const int32_t *q_lens,
+                              const int64_t *q_offsets, float scale, double *out, const int32_t *rows, int64_t nrows,
+                              int32_t num_threads)
+{
+    int G = s->Hq / s->Hkv;
+    int64_t total = nrows;
+    int64_t *first = NULL;          /* without `rows`: prefix of q_lens, to enumerate (b, i) */
+    if (!rows) {
+        first = (int64_t *)malloc(sizeof(int64_t) * (size_t)(s->B + 1));
+        first[0] = 0;
+        for (int b = 0; b < s->B; ++b) first[b + 1] = first[b] + (q_lens[b] > 0 ? q_lens[b] : 0);
+        total = first[s->B] * s->Hq;
+    }
+    int used = 1;
+#ifdef _OPENMP
+    if (num_threads > 0) omp_set_num_threads(num_threads);
+    #pragma omp parallel
+    {
+        #pragma omp single
+        used = omp_get_num_threads();
+    }
+    #pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int64_t r = 0; r < total; ++r) {
+        int b, i, h;
+        if (rows) { b = rows[3 * r]; i = rows[3 * r + 1]; h = rows[3 * r + 2]; }
+        else {
+            int64_t row = r / s->Hq;
+            h = (int)(r % s->Hq);
+            b = 0;
+            while (first[b + 1] <= row) ++b;
+            i = (int)(row - first[b]);
+        }
+        int g = h / G;
+        int n = context_lens[b] - q_lens[b] + i + 1;              /* tokens 0 .. p */
+        int64_t qoff = ((q_offsets[b] + i) * s->Hq + h) * s->D;
+        double *o = rows ? out + r * s->D : out + ((q_offsets[b] + i) * s->Hq + h) * s->D;
+        for (int d = 0; d < s->D; ++d) o[d] = 0.0;
+        if (n <= 0) continue;
+        double *sc = (double *)malloc(sizeof(double) * (size_t)n);
+        double m = -INFINITY;
+        for (int t = 0; t < n; ++t) {
+            int64_t koff = row_offset(s, block_table, b, g, t);
+            double acc = 0.0;
+            for (int d = 0; d < s->D; ++d)
+                acc += widen(q, qoff + d, s->q_dtype) * widen(k_cache, koff + d, s->kv_dtype);
+            sc[t] = (double)scale * acc;
+            if (sc[t] > m) m = sc[t];
+        }
+        double l = 0.0;
+        for (int t = 0; t < n; ++t) {
+            double p = exp(sc[t] - m);
+            l += p;
+            int64_t voff = row_offset(s, block_table, b, g, t);
+            for (int d = 0; d < s->D; ++d) o[d] += p * widen(v_cache, voff + d, s->kv_dtype);
+        }
+        for (int d = 0; d < s->D; ++d) o[d] /= l;
+        free(sc);
+    }
+    free(first);
+    return used;
+}

@@ -226,3 +226,52 @@ def make(name: str, seed: Optional[int] = None, *, append: Optional[bool] = None
         return build(name, seed, lens, Hq=32, Hkv=8, D=128, ps=32, dtype=BF16,
                      pool_factor=2.0, v_std=0.5, append=bool(append), rng=rng)
     raise KeyError(name)
+
+
+@dataclass
+class Chunk:
+    """Multi-token queries for a batch (chunked prefill): request b brings q_lens[b] new tokens, the last
+    q_lens[b] of its context_lens[b] tokens.  q / k_new / v_new hold the chunk rows of all requests back to back."""
+    q_lens: np.ndarray              # [B] int32
+    q_offsets: np.ndarray           # [B] int64: first row of request b in q / out / k_new / v_new
+    total: int                      # rows in q
+    q: np.ndarray                   # [total, Hq, D]
+    k_new: np.ndarray               # [total, Hkv, D]: the K rows of the chunk tokens (taken out of the pool)
+    v_new: np.ndarray
+
+    @property
+    def max_q_len(self) -> int:
+        return int(self.q_lens.max()) if self.q_lens.size else 0
+
+
+def add_chunk(wl: Workload, q_lens: Sequence[int], seed: int, *, in_cache: bool = True, gap: int = 0) -> Chunk:
+    """Turn the last q_lens[b] tokens of every request of ``wl`` into a chunk of new tokens.
+
+    Query rows are drawn from ``seed``.  The chunk's K/V rows are copied out of the pools into k_new / v_new; with
+    ``in_cache=False`` their pool slots are poisoned with NaN afterwards (they are "not appended yet").  ``gap`` leaves
+    that many unused rows between the requests' row ranges.
+    """
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    ql = np.minimum(np.asarray(q_lens, dtype=np.int64), wl.context_lens.astype(np.int64))
+    ql = np.maximum(ql, 0)
+    offs = np.zeros(wl.B, dtype=np.int64)
+    run = 0
+    for b in range(wl.B):
+        offs[b] = run
+        run += int(ql[b]) + gap
+    total = max(run, 1)
+    q = _draw(rng, (total, wl.Hq, wl.D), wl.dtype)
+    k_new = np.zeros((total, wl.Hkv, wl.D), dtype=wl.np_dtype())
+    v_new = np.zeros_like(k_new)
+    for b in range(wl.B):
+        n, L = int(ql[b]), int(wl.context_lens[b])
+        if n <= 0:
+            continue
+        t = np.arange(L - n, L)
+        pages, slots = wl.block_table[b, t // wl.ps], t % wl.ps
+        k_new[offs[b]:offs[b] + n] = wl.k_cache[pages, :, slots, :]
+        v_new[offs[b]:offs[b] + n] = wl.v_cache[pages, :, slots, :]
+        if not in_cache:
+            wl.k_cache[pages, :, slots, :] = _poison((n, wl.Hkv, wl.D), wl.dtype)
+            wl.v_cache[pages, :, slots, :] = _poison((n, wl.Hkv, wl.D), wl.dtype)
+    return Chunk(ql.astype(np.int32), offs, int(total), q, k_new, v_new)

@@ -392,3 +392,86 @@ def test_kv_pack_mutations_are_caught():
     bt2 = wl.block_table.copy()
     bt2[0, 0], bt2[0, 1] = bt2[0, 1], bt2[0, 0]
     assert not np.array_equal(oracle.kv_pack(wl.k_cache, bt2, lens, offs, total).view(np.uint8), good.view(np.uint8))
+
+
+# ---- multi-token (chunk) queries: causal inside the chunk
+
+def _chunk_case(seed=21, dtype=None):
+    lens = [37, 5, 64, 1, 90]
+    wl = W.build("chunk", seed, lens, Hq=6, Hkv=2, D=64, ps=16, dtype=dtype or W.F32, pool_factor=1.5)
+    ch = W.add_chunk(wl, [7, 5, 1, 1, 33], seed + 1, gap=2)
+    return wl, ch
+
+
+def test_chunk_of_one_token_is_the_decode_definition():
+    wl = W.make("tiny")
+    ch = W.add_chunk(wl, [1] * wl.B, 3)
+    ch.q[:] = wl.q                                           # same query rows as the decode batch
+    got = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                                    ch.q_offsets, wl.scale, wl.dtype)
+    ref = oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, wl.scale, wl.dtype)
+    assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_chunk_equals_dense_causal_brute_force(dtype):
+    wl, ch = _chunk_case(dtype=dtype)
+    got = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                                    ch.q_offsets, wl.scale, wl.dtype)
+    to64 = (lambda a: a.astype(np.float64)) if dtype == W.F32 else (lambda a: W.bf16_bits_to_f32(a).astype(np.float64))
+    G = wl.G
+    for b in range(wl.B):
+        L, n = int(wl.context_lens[b]), int(ch.q_lens[b])
+        K = to64(oracle.gather(wl.k_cache, wl.block_table, wl.context_lens, b, wl.dtype))      # [L, Hkv, D]
+        V = to64(oracle.gather(wl.v_cache, wl.block_table, wl.context_lens, b, wl.dtype))
+        Q = to64(ch.q[ch.q_offsets[b]:ch.q_offsets[b] + n])                                     # [n, Hq, D]
+        Kh, Vh = np.repeat(K, G, axis=1), np.repeat(V, G, axis=1)                               # [L, Hq, D]
+        S = np.einsum("ihd,thd->hit", Q, Kh) * float(wl.scale)                                  # [Hq, n, L]
+        pos = (L - n + np.arange(n))[None, :, None]
+        S = np.where(np.arange(L)[None, None, :] <= pos, S, -np.inf)
+        Pm = np.exp(S - S.max(axis=2, keepdims=True))
+        Pm /= Pm.sum(axis=2, keepdims=True)
+        want = np.einsum("hit,thd->ihd", Pm, Vh)
+        assert np.max(np.abs(got[ch.q_offsets[b]:ch.q_offsets[b] + n] - want)) < 1e-12, b
+
+
+def test_chunk_rows_after_a_query_never_reach_it_and_first_token_returns_its_v_row():
+    wl, ch = _chunk_case(seed=31)
+    args = (wl.block_table, wl.context_lens, ch.q_lens, ch.q_offsets, wl.scale, wl.dtype)
+    b, i, h = 4, 10, 5                                       # position 90 - 33 + 10 = 67: 22 later rows exist
+    ref = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, *args, rows=[(b, i, h)])
+    kc, vc = wl.k_cache.copy(), wl.v_cache.copy()
+    for t in range(67 + 1, 90):
+        kc[wl.block_table[b, t // wl.ps], :, t % wl.ps, :] = np.nan
+        vc[wl.block_table[b, t // wl.ps], :, t % wl.ps, :] = np.nan
+    got = oracle.paged_prefill_attn(ch.q, kc, vc, *args, rows=[(b, i, h)])
+    assert np.array_equal(got, ref) and np.all(np.isfinite(ref))
+    kc[wl.block_table[b, 67 // wl.ps], :, 67 % wl.ps, :] = np.nan          # its own position does count
+    assert not np.all(np.isfinite(oracle.paged_prefill_attn(ch.q, kc, vc, *args, rows=[(b, i, h)])))
+    # request 1 is all chunk (5 of 5 tokens): its first query sees only token 0
+    first = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, *args, rows=[(1, 0, 3)])
+    assert np.array_equal(first[0], wl.v_cache[wl.block_table[1, 0], 3 // wl.G, 0, :].astype(np.float64))
+    # rows in the sampled form equal the rows of the full form
+    full = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, *args)
+    assert np.array_equal(full[ch.q_offsets[b] + i, h], ref[0])
+    assert np.all(full[ch.q_offsets[0] + 7:ch.q_offsets[1]] == 0)          # gap rows between requests stay zero
+
+
+def test_kv_append_chunk_writes_exactly_the_chunk_rows():
+    lens = [37, 5, 64, 1, 90]
+    wl = W.build("chunk", 41, lens, Hq=6, Hkv=2, D=64, ps=16, dtype=W.BF16, pool_factor=1.5)
+    full_k, full_v = wl.k_cache.copy(), wl.v_cache.copy()
+    ch = W.add_chunk(wl, [7, 5, 0, 1, 33], 42, in_cache=False, gap=1)
+    changed = (wl.k_cache != full_k).any(axis=(1, 3)).sum()
+    assert changed == 7 + 5 + 0 + 1 + 33                     # that many (page, slot) rows were taken out
+    oracle.kv_append_chunk(ch.k_new, ch.v_new, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                           ch.q_offsets)
+    assert np.array_equal(wl.k_cache, full_k) and np.array_equal(wl.v_cache, full_v)
+    # one token per request is the single-token append
+    wl1 = W.build("chunk", 41, lens, Hq=6, Hkv=2, D=64, ps=16, dtype=W.BF16, pool_factor=1.5, append=True)
+    k2, v2 = wl1.k_cache.copy(), wl1.v_cache.copy()
+    oracle.kv_append(wl1.k_new, wl1.v_new, wl1.k_cache, wl1.v_cache, wl1.block_table, wl1.positions, wl1.dtype)
+    oracle.kv_append_chunk(wl1.k_new, wl1.v_new, k2, v2, wl1.block_table, wl1.context_lens, np.ones(5, np.int32),
+                           np.arange(5, dtype=np.int64))
+    assert np.array_equal(k2.view(np.uint8), wl1.k_cache.view(np.uint8))
+    assert np.array_equal(v2.view(np.uint8), wl1.v_cache.view(np.uint8))
