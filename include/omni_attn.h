@@ -164,6 +164,31 @@ omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v
                              const int32_t *block_table, const int32_t *context_lens, const int64_t *token_offsets,
                              void *stream);
 
+/*
+ * Multi-token queries over the paged cache (chunked prefill, which Section 2.2 and Section 3.3 list among the AR
+ * engine's features; also how a stage consumes a whole sequence of upstream hidden states in one pass).  Request b
+ * brings q_lens[b] new tokens, the LAST q_lens[b] of its context_lens[b] tokens; their query rows are rows
+ * q_offsets[b] .. q_offsets[b] + q_lens[b] - 1 of q [total rows, num_q_heads, head_dim] and their results go to the
+ * same rows of out.  Query i of the chunk sits at position p = context_lens[b] - q_lens[b] + i and attends to tokens
+ * 0 .. p: causal inside the chunk, everything before it.  With q_lens[b] = 1 this is omni_paged_decode_attn.
+ *   out[q_offsets[b] + i, h, :] = sum_{t <= p} softmax_t(scale * q[q_offsets[b] + i, h, :] . K_t) V_t
+ * The chunk's K/V rows must be in the pools already (omni_kv_append_chunk).  q_lens [batch] int32 and q_offsets
+ * [batch] int64 are DEVICE arrays; max_q_len is a HOST upper bound on q_lens (it sizes the grid; longer chunks are
+ * cut off).  Rows of out that no request owns are not written; requests with q_lens[b] <= 0 are skipped.
+ * bf16 q/K/V with head_dim 128 only (matrix-core kernel; fp32 accumulation): else OMNI_ERR_UNSUPPORTED.
+ * One launch, no workspace.  Errors: NULL, SHAPE (max_q_len <= 0, alignment), UNSUPPORTED, HIP.
+ */
+omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
+                                      const int32_t *block_table, const int32_t *context_lens, const int32_t *q_lens,
+                                      const int64_t *q_offsets, int32_t max_q_len, float scale, void *out, void *stream);
+
+/* The multi-token form of omni_kv_append: row q_offsets[b] + i of k_new / v_new [total rows, num_kv_heads, head_dim]
+ * is copied, bit for bit, to position context_lens[b] - q_lens[b] + i of request b, for i < q_lens[b].  Any dtype
+ * the handle supports.  max_q_len as above.  Errors: NULL, SHAPE, HIP. */
+omni_status_t omni_kv_append_chunk(omni_handle_t h, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                                   const int32_t *block_table, const int32_t *context_lens, const int32_t *q_lens,
+                                   const int64_t *q_offsets, int32_t max_q_len, void *stream);
+
 /* Host-known part of the launch plan: which kernel (OMNI_TUNE_KERNEL value actually used), the data-independent
  * grid (workgroups) of the attention kernel, the grid of the merge kernel that follows it, the number of
  * partial-result slots the workspace is sized for, and threads per workgroup.  The range length itself is chosen on the device from

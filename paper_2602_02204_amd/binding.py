@@ -19,7 +19,7 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = (
     "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_set_workspace",
-    "omni_paged_decode_attn", "omni_kv_append", "omni_decode_step", "omni_kv_pack", "omni_kv_unpack", "omni_get_plan",
+    "omni_paged_decode_attn", "omni_kv_append", "omni_decode_step", "omni_kv_pack", "omni_kv_unpack", "omni_paged_prefill_attn", "omni_kv_append_chunk", "omni_get_plan",
     "omni_status_string",
     "omni_debug_last_plan", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
     "omni_debug_profile_end", "omni_graph_begin", "omni_graph_end", "omni_graph_launch", "omni_graph_destroy",
@@ -60,6 +60,8 @@ def lib():
         L.omni_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_kv_pack.argtypes = [vp] * 9
         L.omni_kv_unpack.argtypes = [vp] * 9
+        L.omni_paged_prefill_attn.argtypes = [vp] * 8 + [C.c_int32, C.c_float, vp, vp]
+        L.omni_kv_append_chunk.argtypes = [vp] * 9 + [C.c_int32, vp]
         L.omni_get_plan.argtypes = [vp] + [i32p] * 5
         L.omni_status_string.argtypes = [C.c_int]; L.omni_status_string.restype = C.c_char_p
         L.omni_debug_last_plan.argtypes = [vp, i32p, vp]
@@ -207,6 +209,18 @@ class Handle:
     def omni_kv_unpack(self, k_dense, v_dense, k_cache, v_cache, block_table, context_lens, token_offsets, stream=None) -> None:
         _ck(lib().omni_kv_unpack(self._h, _ptr(k_dense), _ptr(v_dense), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
                                  _ptr(context_lens), _ptr(token_offsets), _stream(stream)), "omni_kv_unpack")
+
+    def omni_paged_prefill_attn(self, q, k_cache, v_cache, block_table, context_lens, q_lens, q_offsets, max_q_len: int,
+                                scale: float, out, stream=None) -> None:
+        _ck(lib().omni_paged_prefill_attn(self._h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                          _ptr(context_lens), _ptr(q_lens), _ptr(q_offsets), int(max_q_len),
+                                          C.c_float(scale), _ptr(out), _stream(stream)), "omni_paged_prefill_attn")
+
+    def omni_kv_append_chunk(self, k_new, v_new, k_cache, v_cache, block_table, context_lens, q_lens, q_offsets,
+                             max_q_len: int, stream=None) -> None:
+        _ck(lib().omni_kv_append_chunk(self._h, _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                       _ptr(context_lens), _ptr(q_lens), _ptr(q_offsets), int(max_q_len), _stream(stream)),
+            "omni_kv_append_chunk")
 
     def omni_debug_last_plan(self, stream=None) -> dict:
         arr = (C.c_int32 * 4)()

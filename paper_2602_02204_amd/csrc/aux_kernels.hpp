@@ -130,6 +130,8 @@ struct PackParams {
     void *k_dst, *v_dst;             // pack: the dense buffers; unpack: the pools
     const int32_t *block_table, *context_lens;
     const long long *token_offsets;  // first dense row of each request; < 0: skip the request
+    const int32_t *q_lens;           // null: whole requests; else only the last q_lens[b] tokens of each request move,
+                                     // and dense row token_offsets[b] holds the first of them
     int Hkv, MB, log2_ps, row_vecs;
 };
 
@@ -145,10 +147,12 @@ constexpr int kPackTokens = 32;      // tokens per workgroup
 template <bool kUnpack>
 __global__ __launch_bounds__(kThreads) void kv_pack_kernel(PackParams p) {
     constexpr int kU = 2;                                    // pieces of K and of V a thread keeps in flight
-    const int b = blockIdx.y, t0 = blockIdx.x * kPackTokens;
+    const int b = blockIdx.y;
     const int L = p.context_lens[b];
-    const long long off = p.token_offsets[b];
-    if (off < 0 || t0 >= L) return;
+    const int first = p.q_lens ? L - max(0, min(p.q_lens[b], L)) : 0;      // first token that moves
+    const int t0 = first + blockIdx.x * kPackTokens;
+    const long long off = p.token_offsets[b] - first;                      // dense row of token 0 (may be virtual)
+    if (p.token_offsets[b] < 0 || t0 >= L) return;
     const int log2_rv = 31 - __clz(p.row_vecs);              // row_vecs is 8, 16 or 32
     const int vecs_per_token = p.Hkv << log2_rv;
     const int total = min(kPackTokens, L - t0) * vecs_per_token;

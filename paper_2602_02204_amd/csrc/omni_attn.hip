@@ -11,6 +11,7 @@
 #include "aux_kernels.hpp"
 #include "decode_mfma.hpp"
 #include "decode_valu.hpp"
+#include "prefill_mfma.hpp"
 
 using namespace omni;
 
@@ -390,7 +391,8 @@ omni_status_t omni_debug_stream_read(const void *a, size_t a_bytes, const void *
 
 static omni_status_t launch_pack(omni_handle_t h, bool unpack, const void *k_src, const void *v_src, void *k_dst,
                                  void *v_dst, const int32_t *block_table, const int32_t *context_lens,
-                                 const int64_t *token_offsets, void *stream) {
+                                 const int64_t *token_offsets, void *stream, const int32_t *q_lens = nullptr,
+                                 int max_tokens = 0) {
     if (!h || !k_src || !v_src || !k_dst || !v_dst || !block_table || !context_lens || !token_offsets) return OMNI_ERR_NULL;
     if (misaligned(k_src, 16) || misaligned(v_src, 16) || misaligned(k_dst, 16) || misaligned(v_dst, 16) ||
         misaligned(block_table, 4) || misaligned(context_lens, 4) || misaligned(token_offsets, 8))
@@ -400,9 +402,11 @@ static omni_status_t launch_pack(omni_handle_t h, bool unpack, const void *k_src
     p.k_src = k_src; p.v_src = v_src; p.k_dst = k_dst; p.v_dst = v_dst;
     p.block_table = block_table; p.context_lens = context_lens;
     p.token_offsets = reinterpret_cast<const long long *>(token_offsets);
+    p.q_lens = q_lens;
     p.Hkv = d.num_kv_heads; p.MB = d.max_blocks_per_seq; p.log2_ps = ilog2(d.page_size);
     p.row_vecs = d.head_dim * (d.kv_dtype == OMNI_BF16 ? 2 : 4) / 16;
-    const dim3 grid((unsigned)((h->max_ctx + kPackTokens - 1) / kPackTokens), (unsigned)d.batch);
+    const int span = q_lens ? max_tokens : h->max_ctx;                     // tokens per request the grid must cover
+    const dim3 grid((unsigned)((span + kPackTokens - 1) / kPackTokens), (unsigned)d.batch);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     (void)hipGetLastError();
     if (unpack) kv_pack_kernel<true><<<grid, kThreads, 0, s>>>(p);
@@ -421,6 +425,45 @@ omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v
                              const int32_t *block_table, const int32_t *context_lens, const int64_t *token_offsets,
                              void *stream) {
     return launch_pack(h, true, k_dense, v_dense, k_cache, v_cache, block_table, context_lens, token_offsets, stream);
+}
+
+omni_status_t omni_kv_append_chunk(omni_handle_t h, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                                   const int32_t *block_table, const int32_t *context_lens, const int32_t *q_lens,
+                                   const int64_t *q_offsets, int32_t max_q_len, void *stream) {
+    if (!q_lens) return OMNI_ERR_NULL;
+    if (max_q_len <= 0) return OMNI_ERR_SHAPE;
+    if (misaligned(q_lens, 4)) return OMNI_ERR_SHAPE;
+    return launch_pack(h, true, k_new, v_new, k_cache, v_cache, block_table, context_lens, q_offsets, stream, q_lens,
+                       max_q_len);
+}
+
+omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
+                                      const int32_t *block_table, const int32_t *context_lens, const int32_t *q_lens,
+                                      const int64_t *q_offsets, int32_t max_q_len, float scale, void *out, void *stream) {
+    if (!h || !q || !k_cache || !v_cache || !block_table || !context_lens || !q_lens || !q_offsets || !out)
+        return OMNI_ERR_NULL;
+    const omni_attn_desc_t &d = h->d;
+    if (!(d.kv_dtype == OMNI_BF16 && d.head_dim == 128)) return OMNI_ERR_UNSUPPORTED;
+    if (max_q_len <= 0) return OMNI_ERR_SHAPE;
+    if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(out, 16) ||
+        misaligned(block_table, 4) || misaligned(context_lens, 4) || misaligned(q_lens, 4) || misaligned(q_offsets, 8))
+        return OMNI_ERR_SHAPE;
+    PrefillParams p;
+    p.q = q; p.k_cache = k_cache; p.v_cache = v_cache;
+    p.block_table = block_table; p.context_lens = context_lens; p.q_lens = q_lens;
+    p.q_offsets = reinterpret_cast<const long long *>(q_offsets);
+    p.out = out;
+    p.scale_log2 = scale * kLog2e;
+    p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
+    p.out_bf16 = d.out_dtype == OMNI_BF16;
+    const int qb = prefill_tokens_per_block(h->G);
+    const dim3 grid((unsigned)((max_q_len + qb - 1) / qb), (unsigned)d.num_kv_heads, (unsigned)d.batch);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    (void)hipGetLastError();
+    if (d.page_size == 16) prefill_mfma_kernel<16><<<grid, kThreads, 0, s>>>(p);
+    else prefill_mfma_kernel<32><<<grid, kThreads, 0, s>>>(p);
+    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+    return OMNI_OK;
 }
 
 struct omni_graph_s {

@@ -1,0 +1,248 @@
+// Matrix-core attention kernel for multi-token queries over the paged cache (chunked prefill): bf16 q/K/V,
+// head_dim 128, group size <= 16.  Query i of request b's chunk sits at position p = L_b - n_b + i and attends to
+// tokens 0 .. p (causal inside the chunk).
+//
+// A workgroup (4 waves, one per SIMD) owns one (request, KV head, block of query tokens).  Its "columns" are the
+// (query token, query head of the group) pairs of that block; a wave owns 64 of them = four 16-column MFMA blocks.
+// The same transposed products as in the decode kernel are used, per 32-token tile and per column block:
+//   S^T = K Q^T     (A = K rows from shared memory, B = the block's queries, held in registers for the whole kernel)
+//   O^T += V^T P^T  (A = V transposed in registers, B = the softmax weights as bf16 hi + lo)
+// so every lane owns one column: running max, sum and rescale never cross lanes except two max exchanges per tile.
+// What differs from decode is reuse: a K/V tile is fetched once per workgroup into shared memory (double buffered,
+// one barrier per tile) and feeds 16 column blocks, and the 8x8 in-lane transpose of V is done once per wave and
+// tile for its four blocks.  That makes the path a dense contraction (bound: matrix cores), not a stream.
+#pragma once
+#include "decode_mfma.hpp"
+
+namespace omni {
+
+constexpr int kPrefillBlocks = 4;                     // 16-column MFMA blocks per wave
+constexpr int kPrefillCols = 16 * kPrefillBlocks;     // (token, head) pairs per wave
+constexpr int kPrefillRowBytes = 256 + 16;            // a 256-byte K or V row plus padding: conflict-free LDS reads
+
+struct PrefillParams {
+    const void *q;                    // [Tq, Hq, D] bf16
+    const void *k_cache, *v_cache;
+    const int32_t *block_table, *context_lens, *q_lens;
+    const long long *q_offsets;
+    void *out;                        // [Tq, Hq, D]
+    float scale_log2;
+    int Hq, Hkv, G, MB;
+    int out_bf16;
+};
+
+// Query tokens per wave and per workgroup for a group of G heads.
+__host__ __device__ inline int prefill_tokens_per_wave(int G) { return kPrefillCols / G; }
+__host__ __device__ inline int prefill_tokens_per_block(int G) { return kWaves * prefill_tokens_per_wave(G); }
+
+template <int PS>
+__global__ __launch_bounds__(kThreads, 1) void prefill_mfma_kernel(PrefillParams p) {
+    constexpr int D = 128;
+    constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
+    constexpr int kTileBytes = kTile * kPrefillRowBytes;         // one K or V tile in shared memory
+    __shared__ __align__(16) char smem[2][2][kTileBytes];        // [buffer][K, V]
+
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int G = p.G, head0 = kvh * G;
+    const int L = p.context_lens[b];
+    const int n_q = min(p.q_lens[b], L);
+    const int TW = prefill_tokens_per_wave(G), QB = kWaves * TW;
+    const int q0 = blockIdx.x * QB;                              // first query token of this workgroup
+    if (n_q <= 0 || q0 >= n_q) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = lane & 15, j = lane >> 4;
+    const long long q_row0 = p.q_offsets[b];
+    const int pos0 = L - n_q;                                    // position of the chunk's first token
+    const int wg_last = min(n_q, q0 + QB) - 1;                   // last query token of the workgroup
+    const int n_tiles = (pos0 + wg_last) / kTile + 1;            // tiles that hold tokens 0 .. position of wg_last
+
+    // ---- this lane's four columns: query token, head, position; and the queries as MFMA B operands
+    int pos[kPrefillBlocks];                                     // -1: padding column (never stored)
+    uint4 Q[kPrefillBlocks][4];
+    int wave_max_pos = -1;
+#pragma unroll
+    for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+        const int c = cb * 16 + col;
+        const int tl = c / G, g = c - tl * G;
+        const int qi = q0 + wave * TW + tl;                      // query token inside the chunk
+        const bool live = tl < TW && qi < n_q;
+        pos[cb] = live ? pos0 + qi : -1;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) Q[cb][kk] = make_uint4(0, 0, 0, 0);
+        if (live) {
+            const char *qrow = reinterpret_cast<const char *>(p.q) + ((size_t)(q_row0 + qi) * p.Hq + head0 + g) * (D * 2);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) Q[cb][kk] = *reinterpret_cast<const uint4 *>(qrow + (4 * kk + j) * 16);
+        }
+        wave_max_pos = max(wave_max_pos, pos[cb]);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) wave_max_pos = max(wave_max_pos, __shfl_xor(wave_max_pos, off));
+    // the smallest live position of the wave: tiles that end at or before it need no mask
+    int wave_min_pos = 0x7fffffff;
+#pragma unroll
+    for (int cb = 0; cb < kPrefillBlocks; ++cb) wave_min_pos = min(wave_min_pos, pos[cb] >= 0 ? pos[cb] : 0x7fffffff);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) wave_min_pos = min(wave_min_pos, __shfl_xor(wave_min_pos, off));
+
+    // ---- staging: thread t moves pieces t and t + 256 of the 512 16-byte pieces of a K tile (and of a V tile);
+    // piece = 16 * token + chunk, so the first piece lies in tokens 0-15 and the second in tokens 16-31
+    const size_t page_stride = (size_t)p.Hkv * PS * D * 2;
+    const char *kbase = reinterpret_cast<const char *>(p.k_cache) + (size_t)kvh * PS * D * 2;
+    const char *vbase = reinterpret_cast<const char *>(p.v_cache) + (size_t)kvh * PS * D * 2;
+    const int32_t *bt = p.block_table + (size_t)b * p.MB;
+    const int st_tok = threadIdx.x >> 4, st_chunk = threadIdx.x & 15;       // token 0..15 (+16 for the second piece)
+    const int lds_off0 = st_tok * kPrefillRowBytes + st_chunk * 16;
+    const int lds_off1 = (16 + st_tok) * kPrefillRowBytes + st_chunk * 16;
+    uint4 sk0, sk1, sv0, sv1;
+    auto fetch_tile = [&](int tile) __attribute__((always_inline)) {
+        const int tb = tile * kTile;
+        const int t_a = tb + st_tok, t_b = tb + 16 + st_tok;
+        sk0 = sk1 = sv0 = sv1 = make_uint4(0, 0, 0, 0);                     // rows beyond the context are zero
+        if (t_a < L) {
+            const int pg = bt[t_a >> kLog2Ps];
+            const size_t o = (size_t)pg * page_stride + (size_t)(t_a & (PS - 1)) * 256 + st_chunk * 16;
+            sk0 = *reinterpret_cast<const uint4 *>(kbase + o);
+            sv0 = *reinterpret_cast<const uint4 *>(vbase + o);
+        }
+        if (t_b < L) {
+            const int pg = bt[t_b >> kLog2Ps];
+            const size_t o = (size_t)pg * page_stride + (size_t)(t_b & (PS - 1)) * 256 + st_chunk * 16;
+            sk1 = *reinterpret_cast<const uint4 *>(kbase + o);
+            sv1 = *reinterpret_cast<const uint4 *>(vbase + o);
+        }
+    };
+    auto stage_tile = [&](int buf) __attribute__((always_inline)) {
+        *reinterpret_cast<uint4 *>(&smem[buf][0][lds_off0]) = sk0;
+        *reinterpret_cast<uint4 *>(&smem[buf][0][lds_off1]) = sk1;
+        *reinterpret_cast<uint4 *>(&smem[buf][1][lds_off0]) = sv0;
+        *reinterpret_cast<uint4 *>(&smem[buf][1][lds_off1]) = sv1;
+    };
+
+    // ---- per-column online-softmax state
+    float m[kPrefillBlocks], l[kPrefillBlocks];
+    f32x4_t acc[kPrefillBlocks][8];
+#pragma unroll
+    for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+        m[cb] = -INFINITY; l[cb] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[cb][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
+    fetch_tile(0);
+    stage_tile(0);
+    lds_barrier();
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int buf = tile & 1;
+        const bool more = tile + 1 < n_tiles;
+        if (more) fetch_tile(tile + 1);                          // in flight while this tile is computed
+        const int tb = tile * kTile;
+        if (tb <= wave_max_pos) {                                // the tile holds tokens some column of this wave sees
+            const char *ks = smem[buf][0], *vs = smem[buf][1];
+            uint4 K[8], V[8];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                K[kk] = *reinterpret_cast<const uint4 *>(ks + col * kPrefillRowBytes + (4 * kk + j) * 16);
+                K[4 + kk] = *reinterpret_cast<const uint4 *>(ks + (16 + col) * kPrefillRowBytes + (4 * kk + j) * 16);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                V[r] = *reinterpret_cast<const uint4 *>(vs + (4 * j + r) * kPrefillRowBytes + col * 16);
+                V[4 + r] = *reinterpret_cast<const uint4 *>(vs + (16 + 4 * j + r) * kPrefillRowBytes + col * 16);
+            }
+            const bool need_mask = tb + kTile - 1 > wave_min_pos;
+            uint4 Ph[kPrefillBlocks], Pl[kPrefillBlocks];
+#pragma unroll
+            for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+#pragma clang fp contract(off)
+                float sv[8];
+                mfma_scores(K, Q[cb], sv, p.scale_log2);
+                if (need_mask) {
+#pragma unroll
+                    for (int r = 0; r < 8; ++r)
+                        if (tb + slot_token(j, r) > pos[cb]) sv[r] = -INFINITY;
+                }
+                float tmax = sv[0];
+#pragma unroll
+                for (int r = 1; r < 8; ++r) tmax = fmaxf(tmax, sv[r]);
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+                // a column whose tokens are all masked so far keeps a finite stand-in, so that exp2 sees -inf - finite
+                const float mn = fmaxf(fmaxf(m[cb], tmax), -1e30f);
+                const float alpha = fast_exp2(m[cb] - mn);
+                float pw[8], psum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(sv[r] - mn); psum += pw[r]; }
+                l[cb] = l[cb] * alpha + psum;
+                m[cb] = mn;
+                uint32_t hi[4], lo[4];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    hi[w] = pack_bf16x2(pw[2 * w], pw[2 * w + 1]);
+                    const float r0 = pw[2 * w] - bf16_bits_to_float(hi[w] & 0xffffu);
+                    const float r1 = pw[2 * w + 1] - __uint_as_float(hi[w] & 0xffff0000u);
+                    lo[w] = pack_bf16x2(r0, r1);
+                }
+                Ph[cb] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                Pl[cb] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                if (__any(alpha != 1.f)) {                       // the running max moved for some column of the block
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[cb][e] *= alpha;
+                }
+            }
+            // O^T += V^T P^T: the transposed V operand is built once and feeds all four column blocks
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int w = e >> 1;
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                uint4 A;
+                A.x = __builtin_amdgcn_perm(dword_of(V[1], w), dword_of(V[0], w), sel);
+                A.y = __builtin_amdgcn_perm(dword_of(V[3], w), dword_of(V[2], w), sel);
+                A.z = __builtin_amdgcn_perm(dword_of(V[5], w), dword_of(V[4], w), sel);
+                A.w = __builtin_amdgcn_perm(dword_of(V[7], w), dword_of(V[6], w), sel);
+#pragma unroll
+                for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+                    acc[cb][e] = mfma_bf16(A, Ph[cb], acc[cb][e]);
+                    acc[cb][e] = mfma_bf16(A, Pl[cb], acc[cb][e]);
+                }
+            }
+        }
+        if (more) stage_tile(buf ^ 1);
+        lds_barrier();
+    }
+
+    // ---- normalise and store: a lane holds, for each of its columns, dims 32j + 8i + e (e = 0..7 contiguous)
+#pragma unroll
+    for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+        float lsum = l[cb];
+        lsum += __shfl_xor(lsum, 16);                            // the four lane groups hold disjoint tokens
+        lsum += __shfl_xor(lsum, 32);
+        if (pos[cb] < 0) continue;
+        const int c = cb * 16 + col;
+        const int tl = c / G, g = c - tl * G;
+        const size_t row = ((size_t)(q_row0 + q0 + wave * TW + tl) * p.Hq + head0 + g) * D;
+        const float inv = 1.f / lsum;                            // every live column saw its own position: lsum > 0
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = acc[cb][e][i] * inv;
+            const size_t at = row + 32 * j + 8 * i;
+            if (p.out_bf16) {
+                uint4 pk;
+                pk.x = (uint32_t)float_to_bf16_rne(o[0]) | ((uint32_t)float_to_bf16_rne(o[1]) << 16);
+                pk.y = (uint32_t)float_to_bf16_rne(o[2]) | ((uint32_t)float_to_bf16_rne(o[3]) << 16);
+                pk.z = (uint32_t)float_to_bf16_rne(o[4]) | ((uint32_t)float_to_bf16_rne(o[5]) << 16);
+                pk.w = (uint32_t)float_to_bf16_rne(o[6]) | ((uint32_t)float_to_bf16_rne(o[7]) << 16);
+                *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.out) + at) = pk;
+            } else {
+                float *dst = reinterpret_cast<float *>(p.out) + at;
+                *reinterpret_cast<float4 *>(dst) = make_float4(o[0], o[1], o[2], o[3]);
+                *reinterpret_cast<float4 *>(dst + 4) = make_float4(o[4], o[5], o[6], o[7]);
+            }
+        }
+    }
+}
+
+}  // namespace omni

@@ -1,0 +1,128 @@
+"""omni_paged_prefill_attn / omni_kv_append_chunk through the C ABI against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_02204_amd import binding as omni
+from paper_2602_02204_amd import workloads as W
+from gpu_util import TOL, DeviceBatch, bits_of, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def as_bytes(a: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(a).view(np.uint8)
+
+
+class ChunkOnDevice:
+    def __init__(self, dev: DeviceBatch, ch: W.Chunk, out_dtype=torch.float32):
+        wl = dev.wl
+        self.q = to_dev(ch.q, wl.dtype)
+        self.k_new, self.v_new = to_dev(ch.k_new, wl.dtype), to_dev(ch.v_new, wl.dtype)
+        self.q_lens = torch.from_numpy(ch.q_lens).cuda()
+        self.q_offsets = torch.from_numpy(ch.q_offsets).cuda()
+        self.out = torch.full((ch.total, wl.Hq, wl.D), float("nan"), dtype=out_dtype, device="cuda")
+
+
+def run_chunk(wl, ch, max_q_len=None, out_dtype=W.F32):
+    """Append the chunk's rows, then attend; returns (DeviceBatch, fp64 output with NaN in rows nobody owns)."""
+    dev = DeviceBatch(wl, out_dtype=out_dtype)
+    c = ChunkOnDevice(dev, ch, torch.float32 if out_dtype == W.F32 else torch.bfloat16)
+    mq = max_q_len or max(ch.max_q_len, 1)
+    dev.h.omni_kv_append_chunk(c.k_new, c.v_new, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens,
+                               c.q_lens, c.q_offsets, mq)
+    dev.h.omni_paged_prefill_attn(c.q, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens, c.q_lens,
+                                  c.q_offsets, mq, float(wl.scale), c.out)
+    torch.cuda.synchronize()
+    return dev, c.out.float().cpu().numpy().astype(np.float64)
+
+
+def check_chunk(wl, ch, label="", **kw):
+    dev, got = run_chunk(wl, ch, **kw)
+    oracle.kv_append_chunk(ch.k_new, ch.v_new, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                           ch.q_offsets)
+    assert np.array_equal(as_bytes(bits_of(dev.k_cache)), as_bytes(wl.k_cache)), label      # the append is a bit copy
+    assert np.array_equal(as_bytes(bits_of(dev.v_cache)), as_bytes(wl.v_cache)), label
+    ref = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                                    ch.q_offsets, wl.scale, wl.dtype)
+    owned = np.zeros(ch.total, dtype=bool)
+    for b in range(wl.B):
+        owned[ch.q_offsets[b]:ch.q_offsets[b] + ch.q_lens[b]] = True
+    assert np.all(np.isnan(got[~owned])), f"{label}: rows nobody owns were written"
+    err = np.max(np.abs(got[owned] - ref[owned])) if owned.any() else 0.0
+    assert np.all(np.isfinite(got[owned])) and err <= TOL[wl.dtype], f"{label}: max|err| {err:.3e}"
+    return got, ref
+
+
+@pytest.mark.parametrize("G,Hkv,ps", [(7, 4, 16), (8, 2, 16), (4, 8, 32), (16, 1, 16), (1, 2, 16), (3, 2, 32), (5, 1, 16)])
+def test_chunks_of_many_shapes(G, Hkv, ps):
+    lens = [300, 64, 1, 0, 33, 257, 96, 40]
+    q_lens = [300, 1, 1, 0, 17, 100, 37, 40]                 # whole prompt, one token, nothing, ragged pieces
+    wl = W.build("chunk", 700 + G, lens, Hq=G * Hkv, Hkv=Hkv, D=128, ps=ps, dtype=W.BF16, pool_factor=1.5)
+    ch = W.add_chunk(wl, q_lens, 800 + G, in_cache=False, gap=3)
+    got, ref = check_chunk(wl, ch, label=f"G{G} Hkv{Hkv} ps{ps}")
+    # request 0 is all chunk: its first query sees only token 0 and returns that V row exactly
+    v0 = W.bf16_bits_to_f32(wl.v_cache[wl.block_table[0, 0], :, 0, :]).astype(np.float64)
+    assert np.array_equal(got[ch.q_offsets[0]], np.repeat(v0, G, axis=0))
+
+
+def test_one_token_chunks_agree_with_the_decode_call():
+    wl = W.make("talker", batch=24, len_div=2, append=False)
+    ch = W.add_chunk(wl, [1] * wl.B, 5)
+    ch.q[:] = wl.q
+    got, ref = check_chunk(wl, ch, label="decode")
+    dec = DeviceBatch(wl).attend()
+    assert np.max(np.abs(got - dec)) <= 2 * TOL[wl.dtype]
+    assert np.array_equal(ref, oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens,
+                                                        wl.scale, wl.dtype))
+
+
+def test_chunk_longer_than_max_q_len_hint_is_cut_and_bf16_output_rounds():
+    wl = W.build("chunk", 900, [200, 150], Hq=8, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    ch = W.add_chunk(wl, [64, 150], 901, in_cache=True)
+    dev, got = run_chunk(wl, ch, out_dtype=W.BF16)
+    ref = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                                    ch.q_offsets, wl.scale, wl.dtype)
+    rounded = W.bf16_bits_to_f32(W.f32_to_bf16_bits(ref.astype(np.float32))).astype(np.float64)
+    ulp = np.maximum(np.abs(rounded), 2.0 ** -126) * 2.0 ** -7
+    assert np.all(np.abs(got - rounded) <= ulp + 2e-3)
+
+
+def test_peaked_softmax_and_large_scores_in_a_chunk():
+    wl = W.build("chunk", 910, [500, 90], Hq=14, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    kf = W.bf16_bits_to_f32(wl.k_cache) * np.float32(6.0)
+    wl.k_cache = np.where(np.isnan(kf), W.BF16_NAN_BITS, W.f32_to_bf16_bits(np.nan_to_num(kf))).astype(np.uint16)
+    ch = W.add_chunk(wl, [130, 90], 911, in_cache=False)
+    check_chunk(wl, ch, label="peaked")
+
+
+def test_full_size_prefill_chunk_sampled_rows():
+    """Eight thinker-sized requests, each with a 512-token chunk at the end of a 512..4096-token context."""
+    wl = W.make("thinker", batch=8, append=False)
+    ch = W.add_chunk(wl, [512] * wl.B, 77, in_cache=False)
+    dev, got = run_chunk(wl, ch)
+    oracle.kv_append_chunk(ch.k_new, ch.v_new, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                           ch.q_offsets)
+    assert np.array_equal(as_bytes(bits_of(dev.k_cache)), as_bytes(wl.k_cache))
+    rng = np.random.default_rng(3)
+    rows = [(int(b), int(i), int(h)) for b, i, h in zip(rng.integers(0, wl.B, 24), rng.integers(0, 512, 24),
+                                                        rng.integers(0, wl.Hq, 24))]
+    rows += [(0, 0, 0), (wl.B - 1, 511, wl.Hq - 1)]
+    ref = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                                    ch.q_offsets, wl.scale, wl.dtype, rows=rows)
+    for r, (b, i, h) in enumerate(rows):
+        assert np.max(np.abs(got[ch.q_offsets[b] + i, h] - ref[r])) <= TOL[wl.dtype], (b, i, h)
+    assert np.all(np.isfinite(got))
+
+
+def test_prefill_argument_errors():
+    h = omni.Handle(batch=2, num_q_heads=4, num_kv_heads=2, head_dim=64, page_size=16, num_pages=8,
+                    max_blocks_per_seq=4, kv_dtype=omni.OMNI_F32)
+    L = omni.lib()
+    assert L.omni_paged_prefill_attn(h._h, 256, 256, 256, 256, 256, 256, 256, 8, 1.0, 256, None) == 4     # fp32 / D=64
+    hb = omni.Handle(batch=2, num_q_heads=4, num_kv_heads=2, head_dim=128, page_size=16, num_pages=8,
+                     max_blocks_per_seq=4, kv_dtype=omni.OMNI_BF16)
+    assert L.omni_paged_prefill_attn(hb._h, 256, 256, 256, 256, 256, 256, 256, 0, 1.0, 256, None) == 2
+    assert L.omni_paged_prefill_attn(hb._h, 256, 256, 256, 256, 256, None, 256, 8, 1.0, 256, None) == 1
+    assert L.omni_kv_append_chunk(hb._h, 256, 256, 256, 256, 256, 256, 256, 256 + 4, 8, None) == 2        # int64 array off by 4
