@@ -16,9 +16,10 @@
 
 namespace omni {
 
-constexpr int kPrefillBlocks = 4;                     // 16-column MFMA blocks per wave
+constexpr int kPrefillBlocks = 2;                     // 16-column MFMA blocks per wave
 constexpr int kPrefillCols = 16 * kPrefillBlocks;     // (token, head) pairs per wave
 constexpr int kPrefillRowBytes = 256 + 16;            // a 256-byte K or V row plus padding: conflict-free LDS reads
+constexpr float kPrefillSlack = 8.f;                  // log2 units a score may exceed a column's reference maximum
 
 struct PrefillParams {
     const void *q;                    // [Tq, Hq, D] bf16
@@ -36,7 +37,7 @@ __host__ __device__ inline int prefill_tokens_per_wave(int G) { return kPrefillC
 __host__ __device__ inline int prefill_tokens_per_block(int G) { return kWaves * prefill_tokens_per_wave(G); }
 
 template <int PS>
-__global__ __launch_bounds__(kThreads, 1) void prefill_mfma_kernel(PrefillParams p) {
+__global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(PrefillParams p) {
     constexpr int D = 128;
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     constexpr int kTileBytes = kTile * kPrefillRowBytes;         // one K or V tile in shared memory
@@ -130,6 +131,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_kernel(PrefillParams
         for (int e = 0; e < 8; ++e) acc[cb][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
 
+    float tmax_lane[kPrefillBlocks];
     fetch_tile(0);
     stage_tile(0);
     lds_barrier();
@@ -152,30 +154,50 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_kernel(PrefillParams
                 V[4 + r] = *reinterpret_cast<const uint4 *>(vs + (16 + 4 * j + r) * kPrefillRowBytes + col * 16);
             }
             const bool need_mask = tb + kTile - 1 > wave_min_pos;
+            // Scores of both column blocks, masked where a token lies after the column's position.
+            float sv[kPrefillBlocks][8];
+            bool over = false;
+#pragma unroll
+            for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+                mfma_scores(K, Q[cb], sv[cb], p.scale_log2);
+                if (need_mask) {
+#pragma unroll
+                    for (int r = 0; r < 8; ++r)
+                        if (tb + slot_token(j, r) > pos[cb]) sv[cb][r] = -INFINITY;
+                }
+                float lmax = sv[cb][0];
+#pragma unroll
+                for (int r = 1; r < 8; ++r) lmax = fmaxf(lmax, sv[cb][r]);
+                over = over || lmax > m[cb] + kPrefillSlack;
+                tmax_lane[cb] = lmax;
+            }
+            // The reference m of a column is moved (and its sums rescaled) only when a score exceeds it by more than
+            // the slack: any common reference gives the same softmax, and 2^slack times the weights is far from
+            // overflow.  After a column's first tiles this is rare, so the exchange between the four lane groups of
+            // a column and the rescale of 32 accumulators leave the common path.
+            if (__any(over)) {
+#pragma unroll
+                for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+                    float tmax = tmax_lane[cb];
+                    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+                    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+                    // a column whose tokens are all masked so far keeps a finite stand-in: exp2 then sees -inf - finite
+                    const float mn = fmaxf(fmaxf(m[cb], tmax), -1e30f);
+                    const float alpha = fast_exp2(m[cb] - mn);
+                    l[cb] *= alpha;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[cb][e] *= alpha;
+                    m[cb] = mn;
+                }
+            }
             uint4 Ph[kPrefillBlocks], Pl[kPrefillBlocks];
 #pragma unroll
             for (int cb = 0; cb < kPrefillBlocks; ++cb) {
 #pragma clang fp contract(off)
-                float sv[8];
-                mfma_scores(K, Q[cb], sv, p.scale_log2);
-                if (need_mask) {
-#pragma unroll
-                    for (int r = 0; r < 8; ++r)
-                        if (tb + slot_token(j, r) > pos[cb]) sv[r] = -INFINITY;
-                }
-                float tmax = sv[0];
-#pragma unroll
-                for (int r = 1; r < 8; ++r) tmax = fmaxf(tmax, sv[r]);
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-                // a column whose tokens are all masked so far keeps a finite stand-in, so that exp2 sees -inf - finite
-                const float mn = fmaxf(fmaxf(m[cb], tmax), -1e30f);
-                const float alpha = fast_exp2(m[cb] - mn);
                 float pw[8], psum = 0.f;
 #pragma unroll
-                for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(sv[r] - mn); psum += pw[r]; }
-                l[cb] = l[cb] * alpha + psum;
-                m[cb] = mn;
+                for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(sv[cb][r] - m[cb]); psum += pw[r]; }
+                l[cb] += psum;
                 uint32_t hi[4], lo[4];
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
@@ -186,10 +208,6 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_kernel(PrefillParams
                 }
                 Ph[cb] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
                 Pl[cb] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-                if (__any(alpha != 1.f)) {                       // the running max moved for some column of the block
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[cb][e] *= alpha;
-                }
             }
             // O^T += V^T P^T: the transposed V operand is built once and feeds all four column blocks
 #pragma unroll
