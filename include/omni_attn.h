@@ -176,7 +176,8 @@ omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v
  * [batch] int64 are DEVICE arrays; max_q_len is a HOST upper bound on q_lens (it sizes the grid; longer chunks are
  * cut off).  Rows of out that no request owns are not written; requests with q_lens[b] <= 0 are skipped.
  * bf16 q/K/V with head_dim 128 only (matrix-core kernel; fp32 accumulation): else OMNI_ERR_UNSUPPORTED.
- * One launch, no workspace.  Errors: NULL, SHAPE (max_q_len <= 0, alignment), UNSUPPORTED, HIP.
+ * scale must be positive.  One launch, no workspace.
+ * Errors: NULL, SHAPE (max_q_len <= 0, scale <= 0, alignment), UNSUPPORTED, HIP.
  */
 omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
                                       const int32_t *block_table, const int32_t *context_lens, const int32_t *q_lens,

@@ -444,7 +444,7 @@ omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void
         return OMNI_ERR_NULL;
     const omni_attn_desc_t &d = h->d;
     if (!(d.kv_dtype == OMNI_BF16 && d.head_dim == 128)) return OMNI_ERR_UNSUPPORTED;
-    if (max_q_len <= 0) return OMNI_ERR_SHAPE;
+    if (max_q_len <= 0 || !(scale > 0.f)) return OMNI_ERR_SHAPE;
     if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(out, 16) ||
         misaligned(block_table, 4) || misaligned(context_lens, 4) || misaligned(q_lens, 4) || misaligned(q_offsets, 8))
         return OMNI_ERR_SHAPE;
@@ -460,8 +460,8 @@ omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void
     const dim3 grid((unsigned)((max_q_len + qb - 1) / qb), (unsigned)d.num_kv_heads, (unsigned)d.batch);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     (void)hipGetLastError();
-    if (d.page_size == 16) prefill_mfma_kernel<16><<<grid, kThreads, 0, s>>>(p);
-    else prefill_mfma_kernel<32><<<grid, kThreads, 0, s>>>(p);
+    if (d.page_size == 16) prefill_mfma_kernel<16><<<grid, kPrefillThreads, 0, s>>>(p);
+    else prefill_mfma_kernel<32><<<grid, kPrefillThreads, 0, s>>>(p);
     if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
     return OMNI_OK;
 }

@@ -2,20 +2,23 @@
 // head_dim 128, group size <= 16.  Query i of request b's chunk sits at position p = L_b - n_b + i and attends to
 // tokens 0 .. p (causal inside the chunk).
 //
-// A workgroup (4 waves, one per SIMD) owns one (request, KV head, block of query tokens).  Its "columns" are the
-// (query token, query head of the group) pairs of that block; a wave owns 64 of them = four 16-column MFMA blocks.
+// A workgroup (8 waves, two per SIMD) owns one (request, KV head, block of query tokens).  Its "columns" are the
+// (query token, query head of the group) pairs of that block; a wave owns 32 of them = two 16-column MFMA blocks.
 // The same transposed products as in the decode kernel are used, per 32-token tile and per column block:
 //   S^T = K Q^T     (A = K rows from shared memory, B = the block's queries, held in registers for the whole kernel)
 //   O^T += V^T P^T  (A = V transposed in registers, B = the softmax weights as bf16 hi + lo)
 // so every lane owns one column: running max, sum and rescale never cross lanes except two max exchanges per tile.
 // What differs from decode is reuse: a K/V tile is fetched once per workgroup into shared memory (double buffered,
 // one barrier per tile) and feeds 16 column blocks, and the 8x8 in-lane transpose of V is done once per wave and
-// tile for its four blocks.  That makes the path a dense contraction (bound: matrix cores), not a stream.
+// tile for its two blocks.  That makes the path a dense contraction, not a stream; with the softmax arithmetic on
+// the vector ALUs (no packed fp32 here) about as long as the matrix-core work, both units bound it.
 #pragma once
 #include "decode_mfma.hpp"
 
 namespace omni {
 
+constexpr int kPrefillThreads = 512;                  // 8 waves = 2 per SIMD share one K/V tile in shared memory
+constexpr int kPrefillWaves = kPrefillThreads / 64;
 constexpr int kPrefillBlocks = 2;                     // 16-column MFMA blocks per wave
 constexpr int kPrefillCols = 16 * kPrefillBlocks;     // (token, head) pairs per wave
 constexpr int kPrefillRowBytes = 256 + 16;            // a 256-byte K or V row plus padding: conflict-free LDS reads
@@ -34,10 +37,10 @@ struct PrefillParams {
 
 // Query tokens per wave and per workgroup for a group of G heads.
 __host__ __device__ inline int prefill_tokens_per_wave(int G) { return kPrefillCols / G; }
-__host__ __device__ inline int prefill_tokens_per_block(int G) { return kWaves * prefill_tokens_per_wave(G); }
+__host__ __device__ inline int prefill_tokens_per_block(int G) { return kPrefillWaves * prefill_tokens_per_wave(G); }
 
 template <int PS>
-__global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(PrefillParams p) {
+__global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(PrefillParams p) {
     constexpr int D = 128;
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     constexpr int kTileBytes = kTile * kPrefillRowBytes;         // one K or V tile in shared memory
@@ -47,7 +50,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(PrefillParams
     const int G = p.G, head0 = kvh * G;
     const int L = p.context_lens[b];
     const int n_q = min(p.q_lens[b], L);
-    const int TW = prefill_tokens_per_wave(G), QB = kWaves * TW;
+    const int TW = prefill_tokens_per_wave(G), QB = kPrefillWaves * TW;
     const int q0 = blockIdx.x * QB;                              // first query token of this workgroup
     if (n_q <= 0 || q0 >= n_q) return;
     const int lane = threadIdx.x & 63;
@@ -87,38 +90,28 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(PrefillParams
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) wave_min_pos = min(wave_min_pos, __shfl_xor(wave_min_pos, off));
 
-    // ---- staging: thread t moves pieces t and t + 256 of the 512 16-byte pieces of a K tile (and of a V tile);
-    // piece = 16 * token + chunk, so the first piece lies in tokens 0-15 and the second in tokens 16-31
+    // ---- staging: thread t moves piece t of the 512 16-byte pieces of a K tile and of a V tile
+    // (piece = 16 * token + chunk)
     const size_t page_stride = (size_t)p.Hkv * PS * D * 2;
     const char *kbase = reinterpret_cast<const char *>(p.k_cache) + (size_t)kvh * PS * D * 2;
     const char *vbase = reinterpret_cast<const char *>(p.v_cache) + (size_t)kvh * PS * D * 2;
     const int32_t *bt = p.block_table + (size_t)b * p.MB;
-    const int st_tok = threadIdx.x >> 4, st_chunk = threadIdx.x & 15;       // token 0..15 (+16 for the second piece)
-    const int lds_off0 = st_tok * kPrefillRowBytes + st_chunk * 16;
-    const int lds_off1 = (16 + st_tok) * kPrefillRowBytes + st_chunk * 16;
-    uint4 sk0, sk1, sv0, sv1;
+    const int st_tok = threadIdx.x >> 4, st_chunk = threadIdx.x & 15;       // token 0..31 of the tile
+    const int lds_off = st_tok * kPrefillRowBytes + st_chunk * 16;
+    uint4 sk, sv_;
     auto fetch_tile = [&](int tile) __attribute__((always_inline)) {
-        const int tb = tile * kTile;
-        const int t_a = tb + st_tok, t_b = tb + 16 + st_tok;
-        sk0 = sk1 = sv0 = sv1 = make_uint4(0, 0, 0, 0);                     // rows beyond the context are zero
-        if (t_a < L) {
-            const int pg = bt[t_a >> kLog2Ps];
-            const size_t o = (size_t)pg * page_stride + (size_t)(t_a & (PS - 1)) * 256 + st_chunk * 16;
-            sk0 = *reinterpret_cast<const uint4 *>(kbase + o);
-            sv0 = *reinterpret_cast<const uint4 *>(vbase + o);
-        }
-        if (t_b < L) {
-            const int pg = bt[t_b >> kLog2Ps];
-            const size_t o = (size_t)pg * page_stride + (size_t)(t_b & (PS - 1)) * 256 + st_chunk * 16;
-            sk1 = *reinterpret_cast<const uint4 *>(kbase + o);
-            sv1 = *reinterpret_cast<const uint4 *>(vbase + o);
+        const int t = tile * kTile + st_tok;
+        sk = sv_ = make_uint4(0, 0, 0, 0);                                  // rows beyond the context are zero
+        if (t < L) {
+            const int pg = bt[t >> kLog2Ps];
+            const size_t o = (size_t)pg * page_stride + (size_t)(t & (PS - 1)) * 256 + st_chunk * 16;
+            sk = *reinterpret_cast<const uint4 *>(kbase + o);
+            sv_ = *reinterpret_cast<const uint4 *>(vbase + o);
         }
     };
     auto stage_tile = [&](int buf) __attribute__((always_inline)) {
-        *reinterpret_cast<uint4 *>(&smem[buf][0][lds_off0]) = sk0;
-        *reinterpret_cast<uint4 *>(&smem[buf][0][lds_off1]) = sk1;
-        *reinterpret_cast<uint4 *>(&smem[buf][1][lds_off0]) = sv0;
-        *reinterpret_cast<uint4 *>(&smem[buf][1][lds_off1]) = sv1;
+        *reinterpret_cast<uint4 *>(&smem[buf][0][lds_off]) = sk;
+        *reinterpret_cast<uint4 *>(&smem[buf][1][lds_off]) = sv_;
     };
 
     // ---- per-column online-softmax state
@@ -131,7 +124,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(PrefillParams
         for (int e = 0; e < 8; ++e) acc[cb][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
 
-    float tmax_lane[kPrefillBlocks];
+    float tmax_lane[kPrefillBlocks], raw_limit[kPrefillBlocks];      // raw_limit: raw score above which m must move
+#pragma unroll
+    for (int cb = 0; cb < kPrefillBlocks; ++cb) raw_limit[cb] = -INFINITY;
+    const float inv_scale_log2 = 1.f / p.scale_log2;
     fetch_tile(0);
     stage_tile(0);
     lds_barrier();
@@ -154,12 +150,21 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(PrefillParams
                 V[4 + r] = *reinterpret_cast<const uint4 *>(vs + (16 + 4 * j + r) * kPrefillRowBytes + col * 16);
             }
             const bool need_mask = tb + kTile - 1 > wave_min_pos;
-            // Scores of both column blocks, masked where a token lies after the column's position.
+            // Raw scores q.k of both column blocks, masked where a token lies after the column's position.  The
+            // softmax scale is applied inside the exponent (one fused multiply-add per score): scale > 0, so the
+            // order of scores is that of the raw dot products.
             float sv[kPrefillBlocks][8];
             bool over = false;
 #pragma unroll
             for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-                mfma_scores(K, Q[cb], sv[cb], p.scale_log2);
+                f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    s0 = mfma_bf16(K[kk], Q[cb][kk], s0);
+                    s1 = mfma_bf16(K[4 + kk], Q[cb][kk], s1);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { sv[cb][i] = s0[i]; sv[cb][4 + i] = s1[i]; }
                 if (need_mask) {
 #pragma unroll
                     for (int r = 0; r < 8; ++r)
@@ -168,13 +173,13 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(PrefillParams
                 float lmax = sv[cb][0];
 #pragma unroll
                 for (int r = 1; r < 8; ++r) lmax = fmaxf(lmax, sv[cb][r]);
-                over = over || lmax > m[cb] + kPrefillSlack;
+                over = over || lmax > raw_limit[cb];
                 tmax_lane[cb] = lmax;
             }
-            // The reference m of a column is moved (and its sums rescaled) only when a score exceeds it by more than
-            // the slack: any common reference gives the same softmax, and 2^slack times the weights is far from
-            // overflow.  After a column's first tiles this is rare, so the exchange between the four lane groups of
-            // a column and the rescale of 32 accumulators leave the common path.
+            // The reference m of a column (log2 domain) is moved, and its sums rescaled, only when a score exceeds it
+            // by more than the slack: any common reference gives the same softmax, and 2^slack times the weights is
+            // far from overflow.  After a column's first tiles this is rare, so the exchange between the four lane
+            // groups of a column and the rescale of 32 accumulators leave the common path.
             if (__any(over)) {
 #pragma unroll
                 for (int cb = 0; cb < kPrefillBlocks; ++cb) {
@@ -182,21 +187,21 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_mfma_kernel(PrefillParams
                     tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
                     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
                     // a column whose tokens are all masked so far keeps a finite stand-in: exp2 then sees -inf - finite
-                    const float mn = fmaxf(fmaxf(m[cb], tmax), -1e30f);
+                    const float mn = fmaxf(fmaxf(m[cb], tmax * p.scale_log2), -1e30f);
                     const float alpha = fast_exp2(m[cb] - mn);
                     l[cb] *= alpha;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) acc[cb][e] *= alpha;
                     m[cb] = mn;
+                    raw_limit[cb] = (mn + kPrefillSlack) * inv_scale_log2;
                 }
             }
             uint4 Ph[kPrefillBlocks], Pl[kPrefillBlocks];
 #pragma unroll
             for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-#pragma clang fp contract(off)
                 float pw[8], psum = 0.f;
 #pragma unroll
-                for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(sv[cb][r] - m[cb]); psum += pw[r]; }
+                for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(fmaf(sv[cb][r], p.scale_log2, -m[cb])); psum += pw[r]; }
                 l[cb] += psum;
                 uint32_t hi[4], lo[4];
 #pragma unroll

@@ -62,9 +62,10 @@ def test_chunks_of_many_shapes(G, Hkv, ps):
     wl = W.build("chunk", 700 + G, lens, Hq=G * Hkv, Hkv=Hkv, D=128, ps=ps, dtype=W.BF16, pool_factor=1.5)
     ch = W.add_chunk(wl, q_lens, 800 + G, in_cache=False, gap=3)
     got, ref = check_chunk(wl, ch, label=f"G{G} Hkv{Hkv} ps{ps}")
-    # request 0 is all chunk: its first query sees only token 0 and returns that V row exactly
+    # request 0 is all chunk: its first query sees only token 0 and returns that V row (the weight is exp2 of a
+    # rounding residue: 1 to within a few ulp)
     v0 = W.bf16_bits_to_f32(wl.v_cache[wl.block_table[0, 0], :, 0, :]).astype(np.float64)
-    assert np.array_equal(got[ch.q_offsets[0]], np.repeat(v0, G, axis=0))
+    assert np.max(np.abs(got[ch.q_offsets[0]] - np.repeat(v0, G, axis=0))) <= 1e-5
 
 
 def test_one_token_chunks_agree_with_the_decode_call():
