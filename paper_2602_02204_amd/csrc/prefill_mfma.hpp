@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         for (int e = 0; e < 8; ++e) acc[cb][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
 
-    float tmax_lane[kPrefillBlocks], raw_limit[kPrefillBlocks];      // raw_limit: raw score above which m must move
+    float raw_limit[kPrefillBlocks];                                 // raw score above which a column's m must move
 #pragma unroll
     for (int cb = 0; cb < kPrefillBlocks; ++cb) raw_limit[cb] = -INFINITY;
     const float inv_scale_log2 = 1.f / p.scale_log2;
@@ -150,40 +150,50 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
                 V[4 + r] = *reinterpret_cast<const uint4 *>(vs + (16 + 4 * j + r) * kPrefillRowBytes + col * 16);
             }
             const bool need_mask = tb + kTile - 1 > wave_min_pos;
-            // Raw scores q.k of both column blocks, masked where a token lies after the column's position.  The
+            // Raw scores q.k of the column blocks: all their MFMAs are issued before the first result is read, so the
+            // matrix cores work on the later blocks while the vector ALUs do the softmax of the earlier ones.  The
             // softmax scale is applied inside the exponent (one fused multiply-add per score): scale > 0, so the
             // order of scores is that of the raw dot products.
-            float sv[kPrefillBlocks][8];
-            bool over = false;
+            f32x4_t s0[kPrefillBlocks], s1[kPrefillBlocks];
 #pragma unroll
             for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-                f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+                s0[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f}; s1[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    s0 = mfma_bf16(K[kk], Q[cb][kk], s0);
-                    s1 = mfma_bf16(K[4 + kk], Q[cb][kk], s1);
+                    s0[cb] = mfma_bf16(K[kk], Q[cb][kk], s0[cb]);
+                    s1[cb] = mfma_bf16(K[4 + kk], Q[cb][kk], s1[cb]);
                 }
+            }
+            // The transposed V operands of the tile (8x8 in-lane transposes), shared by the column blocks.
+            uint4 A[8];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { sv[cb][i] = s0[i]; sv[cb][4 + i] = s1[i]; }
-                if (need_mask) {
+            for (int e = 0; e < 8; ++e) {
+                const int w = e >> 1;
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                A[e].x = __builtin_amdgcn_perm(dword_of(V[1], w), dword_of(V[0], w), sel);
+                A[e].y = __builtin_amdgcn_perm(dword_of(V[3], w), dword_of(V[2], w), sel);
+                A[e].z = __builtin_amdgcn_perm(dword_of(V[5], w), dword_of(V[4], w), sel);
+                A[e].w = __builtin_amdgcn_perm(dword_of(V[7], w), dword_of(V[6], w), sel);
+            }
+#pragma unroll
+            for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+                float sv[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { sv[i] = s0[cb][i]; sv[4 + i] = s1[cb][i]; }
+                if (need_mask) {                                 // tokens after the column's position
 #pragma unroll
                     for (int r = 0; r < 8; ++r)
-                        if (tb + slot_token(j, r) > pos[cb]) sv[cb][r] = -INFINITY;
+                        if (tb + slot_token(j, r) > pos[cb]) sv[r] = -INFINITY;
                 }
-                float lmax = sv[cb][0];
+                float lmax = sv[0];
 #pragma unroll
-                for (int r = 1; r < 8; ++r) lmax = fmaxf(lmax, sv[cb][r]);
-                over = over || lmax > raw_limit[cb];
-                tmax_lane[cb] = lmax;
-            }
-            // The reference m of a column (log2 domain) is moved, and its sums rescaled, only when a score exceeds it
-            // by more than the slack: any common reference gives the same softmax, and 2^slack times the weights is
-            // far from overflow.  After a column's first tiles this is rare, so the exchange between the four lane
-            // groups of a column and the rescale of 32 accumulators leave the common path.
-            if (__any(over)) {
-#pragma unroll
-                for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-                    float tmax = tmax_lane[cb];
+                for (int r = 1; r < 8; ++r) lmax = fmaxf(lmax, sv[r]);
+                // The reference m of a column (log2 domain) is moved, and its sums rescaled, only when a score exceeds
+                // it by more than the slack: any common reference gives the same softmax, and 2^slack times the
+                // weights is far from overflow.  After a column's first tiles this is rare, so the exchange between
+                // the four lane groups of a column and the rescale of 32 accumulators leave the common path.
+                if (__any(lmax > raw_limit[cb])) {
+                    float tmax = lmax;
                     tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
                     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
                     // a column whose tokens are all masked so far keeps a finite stand-in: exp2 then sees -inf - finite
@@ -195,13 +205,9 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
                     m[cb] = mn;
                     raw_limit[cb] = (mn + kPrefillSlack) * inv_scale_log2;
                 }
-            }
-            uint4 Ph[kPrefillBlocks], Pl[kPrefillBlocks];
-#pragma unroll
-            for (int cb = 0; cb < kPrefillBlocks; ++cb) {
                 float pw[8], psum = 0.f;
 #pragma unroll
-                for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(fmaf(sv[cb][r], p.scale_log2, -m[cb])); psum += pw[r]; }
+                for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(fmaf(sv[r], p.scale_log2, -m[cb])); psum += pw[r]; }
                 l[cb] += psum;
                 uint32_t hi[4], lo[4];
 #pragma unroll
@@ -211,24 +217,12 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
                     const float r1 = pw[2 * w + 1] - __uint_as_float(hi[w] & 0xffff0000u);
                     lo[w] = pack_bf16x2(r0, r1);
                 }
-                Ph[cb] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-                Pl[cb] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-            }
-            // O^T += V^T P^T: the transposed V operand is built once and feeds all four column blocks
+                const uint4 Ph = make_uint4(hi[0], hi[1], hi[2], hi[3]), Pl = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                // O^T += V^T P^T for this block; the next block's softmax follows while these MFMAs run
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int w = e >> 1;
-                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-                uint4 A;
-                A.x = __builtin_amdgcn_perm(dword_of(V[1], w), dword_of(V[0], w), sel);
-                A.y = __builtin_amdgcn_perm(dword_of(V[3], w), dword_of(V[2], w), sel);
-                A.z = __builtin_amdgcn_perm(dword_of(V[5], w), dword_of(V[4], w), sel);
-                A.w = __builtin_amdgcn_perm(dword_of(V[7], w), dword_of(V[6], w), sel);
+                for (int e = 0; e < 8; ++e) acc[cb][e] = mfma_bf16(A[e], Ph, acc[cb][e]);
 #pragma unroll
-                for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-                    acc[cb][e] = mfma_bf16(A, Ph[cb], acc[cb][e]);
-                    acc[cb][e] = mfma_bf16(A, Pl[cb], acc[cb][e]);
-                }
+                for (int e = 0; e < 8; ++e) acc[cb][e] = mfma_bf16(A[e], Pl, acc[cb][e]);
             }
         }
         if (more) stage_tile(buf ^ 1);
