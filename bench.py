@@ -235,6 +235,45 @@ def main():
         pack["plain_copy_GB/s"] = 2 * kv_bytes / us / 1e3
         del kd, vd, kd2, vd2
 
+    # ---- multi-token queries (chunked prefill) on the matrix cores: 32 thinker-shaped requests, each with a chunk of
+    # 512 new tokens at the end of its context; useful flops = 4 * D * Hq per (query, visible token) pair
+    prefill = None
+    if not args.timed_only and wl.dtype == W.BF16 and wl.D == 128:
+        pw = W.make(wl.name, batch=min(32, wl.B), append=False)
+        ch = W.add_chunk(pw, [512] * pw.B, 77, in_cache=True)
+        ph = omni.Handle(batch=pw.B, num_q_heads=pw.Hq, num_kv_heads=pw.Hkv, head_dim=pw.D, page_size=pw.ps,
+                         num_pages=pw.P, max_blocks_per_seq=pw.MB, kv_dtype=kvd, out_dtype=omni.OMNI_F32)
+        pq, pk, pv = to_dev(ch.q, pw.dtype), to_dev(pw.k_cache, pw.dtype), to_dev(pw.v_cache, pw.dtype)
+        pbt, plens = torch.from_numpy(pw.block_table).cuda(), torch.from_numpy(pw.context_lens).cuda()
+        pql, pqo = torch.from_numpy(ch.q_lens).cuda(), torch.from_numpy(ch.q_offsets).cuda()
+        pout = torch.empty((ch.total, pw.Hq, pw.D), dtype=torch.float32, device="cuda")
+        Lh, nh = pw.context_lens.astype(np.int64), ch.q_lens.astype(np.int64)
+        pairs = int(np.sum(nh * (Lh - nh) + nh * (nh + 1) // 2))
+        flops = 4.0 * pw.D * pw.Hq * pairs
+        run = lambda: ph.omni_paged_prefill_attn(pq, pk, pv, pbt, plens, pql, pqo, ch.max_q_len, float(pw.scale), pout, stream)
+        for _ in range(3):
+            run()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        for a, b in evs:
+            a.record(stream)
+            run()
+            b.record(stream)
+        torch.cuda.synchronize()
+        us = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e3
+        rows = [(0, 0, 0), (pw.B - 1, 511, pw.Hq - 1), (pw.B // 2, 255, 3)]
+        import oracle as _oracle
+        pref = _oracle.paged_prefill_attn(ch.q, pw.k_cache, pw.v_cache, pw.block_table, pw.context_lens, ch.q_lens,
+                                          ch.q_offsets, pw.scale, pw.dtype, rows=rows)
+        pgot = pout.cpu().numpy().astype(np.float64)
+        perr = float(max(np.max(np.abs(pgot[ch.q_offsets[b] + i, hh] - pref[r])) for r, (b, i, hh) in enumerate(rows)))
+        if not (perr <= 2e-3):
+            print(f"bench.py: prefill parity check failed, max|err|={perr:.3e}", file=sys.stderr)
+            sys.exit(1)
+        prefill = {"kernel": "prefill_mfma_kernel", "workload": f"{pw.B} {pw.name}-shaped requests, chunk of 512 tokens each",
+                   "query_token_pairs": pairs, "useful_flops": flops, "avg_us": us, "TFLOP/s": flops / us / 1e6,
+                   "peak_TFLOP/s": 2500.0, "frac": flops / us / 1e6 / 2500.0, "parity_max_abs_err_sampled": perr}
+        del pq, pk, pv, pout
+
     if args.calibrate_copy:                  # 1 GiB read + 1 GiB written per copy: the yardstick for FETCH_SIZE / WRITE_SIZE
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -311,6 +350,7 @@ def main():
                   "host_us_to_issue_a_step_eager": host_us_eager, "host_us_to_issue_a_step_in_graph": host_us_graph,
                   "kv_gbs_cache_warm": kv_bytes / (ms_warm * 1e-3) / 1e9 if ms_warm else None,
                   "kv_pack_unpack": pack,
+                  "prefill_chunk": prefill,
                   "parity_max_abs_err_sampled": max_err},
     }
     print(json.dumps(result))
