@@ -40,6 +40,11 @@ def lib():
         L.oracle_paged_prefill_attn.restype = C.c_int
         L.oracle_paged_prefill_attn.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 7 + [C.c_float, C.c_void_p, C.c_void_p,
                                                                                         C.c_int64, C.c_int32]
+        L.oracle_fp8_e4m3_decode.restype = C.c_double
+        L.oracle_fp8_e4m3_decode.argtypes = [C.c_uint8]
+        L.oracle_paged_decode_attn_fp8.restype = C.c_int
+        L.oracle_paged_decode_attn_fp8.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 7 + [C.c_float, C.c_void_p,
+                                                                                           C.c_void_p, C.c_int32, C.c_int32]
         L.oracle_gather.restype = None
         L.oracle_gather.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 3 + [C.c_int32, C.c_void_p]
         _lib = L
@@ -201,3 +206,36 @@ def kv_append_chunk(k_new, v_new, k_cache, v_cache, block_table, context_lens, q
         src = slice(int(q_offsets[b]), int(q_offsets[b]) + n)
         k_cache[block_table[b, t // ps], :, t % ps, :] = k_new[src]
         v_cache[block_table[b, t // ps], :, t % ps, :] = v_new[src]
+
+
+def fp8_e4m3_decode(byte: int) -> float:
+    """Value of one OCP E4M3 byte (NaN for 0x7f / 0xff)."""
+    return float(lib().oracle_fp8_e4m3_decode(int(byte) & 0xff))
+
+
+def paged_decode_attn_fp8(q, k_cache, v_cache, k_scale, v_scale, block_table, context_lens, scale,
+                          pairs: Optional[Sequence[Tuple[int, int]]] = None, num_threads: int = 0) -> np.ndarray:
+    """Decode attention over an 8-bit (E4M3) KV cache with one fp32 scale per (page, KV head); q is bf16 bits.
+
+    k_cache / v_cache are uint8 [P, Hkv, ps, D]; k_scale / v_scale float32 [P, Hkv].  fp64 [B, Hq, D] (or
+    [len(pairs), D])."""
+    _check(q, "bf16", "q")
+    assert k_cache.dtype == np.uint8 and v_cache.dtype == np.uint8 and k_cache.flags.c_contiguous
+    B, Hq, D = q.shape
+    P, Hkv, ps, D2 = k_cache.shape
+    assert D == D2 and Hq % Hkv == 0 and k_scale.shape == (P, Hkv) and v_scale.shape == (P, Hkv)
+    s = _Shape(B, Hq, Hkv, D, ps, block_table.shape[1], _DT["bf16"], 2)
+    bt = np.ascontiguousarray(block_table, dtype=np.int32)
+    lens = np.ascontiguousarray(context_lens, dtype=np.int32)
+    ks = np.ascontiguousarray(k_scale, dtype=np.float32)
+    vs = np.ascontiguousarray(v_scale, dtype=np.float32)
+    if pairs is not None:
+        pr = np.ascontiguousarray(np.asarray(pairs, dtype=np.int32).reshape(-1, 2))
+        out = np.zeros((len(pr), D), dtype=np.float64)
+        lib().oracle_paged_decode_attn_fp8(C.byref(s), _p(q), _p(k_cache), _p(v_cache), _p(ks), _p(vs), _p(bt), _p(lens),
+                                           C.c_float(scale), _p(out), _p(pr), len(pr), num_threads)
+    else:
+        out = np.zeros((B, Hq, D), dtype=np.float64)
+        lib().oracle_paged_decode_attn_fp8(C.byref(s), _p(q), _p(k_cache), _p(v_cache), _p(ks), _p(vs), _p(bt), _p(lens),
+                                           C.c_float(scale), _p(out), None, 0, num_threads)
+    return out

@@ -291,3 +291,74 @@ int oracle_paged_prefill_attn(const oracle_shape_t *s, const void *q, const void
     free(first);
     return used;
 }
+
+/*
+ * Quantised KV cache (8-bit floating point with one scale per page and KV head).  The stored byte is an OCP
+ * "E4M3" number: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits; exponent 0 holds subnormals m/8 * 2^-6;
+ * there is no infinity and only the all-ones exponent with all-ones mantissa is NaN, so the largest finite value is
+ * 1.75 * 2^8 = 448.  A cache element stands for   decode(byte) * scale[page, kv head].
+ * The attention itself is the definition at the top of this file, taken over the de-quantised rows.
+ * Pins: the decode against an independent conversion routine for all 256 bytes; with power-of-two scales the result
+ * equals, bit for bit, the fp32 oracle run on the de-quantised pools; general scales to 1e-12.
+ */
+double oracle_fp8_e4m3_decode(uint8_t byte)
+{
+    int sign = byte >> 7, e = (byte >> 3) & 15, mant = byte & 7;
+    double v;
+    if (e == 15 && mant == 7) return NAN;
+    if (e == 0) v = ldexp((double)mant / 8.0, -6);
+    else v = ldexp(1.0 + (double)mant / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+/* out[b, h, :] for every (b, h), or for the npairs listed pairs; k_scale / v_scale are [P, Hkv] fp32. */
+int oracle_paged_decode_attn_fp8(const oracle_shape_t *s, const void *q, const uint8_t *k_cache, const uint8_t *v_cache,
+                                 const float *k_scale, const float *v_scale, const int32_t *block_table,
+                                 const int32_t *context_lens, float scale, double *out, const int32_t *pairs,
+                                 int32_t npairs, int32_t num_threads)
+{
+    int G = s->Hq / s->Hkv;
+    int64_t total = pairs ? npairs : (int64_t)s->B * s->Hq;
+    int used = 1;
+#ifdef _OPENMP
+    if (num_threads > 0) omp_set_num_threads(num_threads);
+    #pragma omp parallel
+    {
+        #pragma omp single
+        used = omp_get_num_threads();
+    }
+    #pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int64_t r = 0; r < total; ++r) {
+        int b = pairs ? pairs[2 * r] : (int)(r / s->Hq);
+        int h = pairs ? pairs[2 * r + 1] : (int)(r % s->Hq);
+        int g = h / G, n = context_lens[b];
+        double *o = out + r * s->D;
+        for (int d = 0; d < s->D; ++d) o[d] = 0.0;
+        if (n <= 0) continue;
+        int64_t qoff = ((int64_t)b * s->Hq + h) * s->D;
+        double *sc = (double *)malloc(sizeof(double) * (size_t)n);
+        double m = -INFINITY;
+        for (int t = 0; t < n; ++t) {
+            int64_t page = block_table[(int64_t)b * s->MB + t / s->ps];
+            int64_t koff = row_offset(s, block_table, b, g, t);
+            double ks = (double)k_scale[page * s->Hkv + g], acc = 0.0;
+            for (int d = 0; d < s->D; ++d)
+                acc += widen(q, qoff + d, s->q_dtype) * (oracle_fp8_e4m3_decode(k_cache[koff + d]) * ks);
+            sc[t] = (double)scale * acc;
+            if (sc[t] > m) m = sc[t];
+        }
+        double l = 0.0;
+        for (int t = 0; t < n; ++t) {
+            double p = exp(sc[t] - m);
+            l += p;
+            int64_t page = block_table[(int64_t)b * s->MB + t / s->ps];
+            int64_t voff = row_offset(s, block_table, b, g, t);
+            double vs = (double)v_scale[page * s->Hkv + g];
+            for (int d = 0; d < s->D; ++d) o[d] += p * (oracle_fp8_e4m3_decode(v_cache[voff + d]) * vs);
+        }
+        for (int d = 0; d < s->D; ++d) o[d] /= l;
+        free(sc);
+    }
+    return used;
+}

@@ -275,3 +275,42 @@ def add_chunk(wl: Workload, q_lens: Sequence[int], seed: int, *, in_cache: bool 
             wl.k_cache[pages, :, slots, :] = _poison((n, wl.Hkv, wl.D), wl.dtype)
             wl.v_cache[pages, :, slots, :] = _poison((n, wl.Hkv, wl.D), wl.dtype)
     return Chunk(ql.astype(np.int32), offs, int(total), q, k_new, v_new)
+
+
+FP8_NAN_BYTE = np.uint8(0x7F)
+FP8_MAX = 448.0
+
+
+@dataclass
+class Fp8Pools:
+    """The K/V pools of a workload re-encoded as 8-bit E4M3 bytes with one fp32 scale per (page, KV head)."""
+    k_cache: np.ndarray             # [P, Hkv, ps, D] uint8; slots no live token owns hold the NaN byte
+    v_cache: np.ndarray
+    k_scale: np.ndarray             # [P, Hkv] float32
+    v_scale: np.ndarray
+
+    @property
+    def kv_bytes_per_token_head(self) -> int:
+        return 2 * self.k_cache.shape[-1]
+
+
+def quantize_fp8(wl: Workload, *, power_of_two_scales: bool = False) -> Fp8Pools:
+    """Encode the pools of ``wl`` (bf16 or fp32) in E4M3: scale = largest live magnitude of the (page, head) / 448
+    (rounded up to a power of two on request; 1 for an all-dead page), bytes by the library's round-to-nearest cast."""
+    import torch
+
+    def one(cache):
+        x = cache.astype(np.float32) if cache.dtype == np.float32 else bf16_bits_to_f32(cache)
+        live = ~np.isnan(x)
+        amax = np.where(live, np.abs(x), 0.0).max(axis=(2, 3))                       # [P, Hkv]
+        scale = np.where(amax > 0, amax / FP8_MAX, 1.0).astype(np.float32)
+        if power_of_two_scales:
+            scale = np.exp2(np.ceil(np.log2(scale))).astype(np.float32)
+        y = np.where(live, x / scale[:, :, None, None], 0.0).astype(np.float32)
+        b = torch.from_numpy(y).to(torch.float8_e4m3fn).view(torch.uint8).numpy().copy()
+        b[~live] = FP8_NAN_BYTE
+        return b, scale
+
+    k8, ks = one(wl.k_cache)
+    v8, vs = one(wl.v_cache)
+    return Fp8Pools(k8, v8, ks, vs)

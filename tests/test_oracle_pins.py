@@ -475,3 +475,59 @@ def test_kv_append_chunk_writes_exactly_the_chunk_rows():
                            np.arange(5, dtype=np.int64))
     assert np.array_equal(k2.view(np.uint8), wl1.k_cache.view(np.uint8))
     assert np.array_equal(v2.view(np.uint8), wl1.v_cache.view(np.uint8))
+
+
+# ---- 8-bit (E4M3) KV cache with per-(page, head) scales
+
+def test_fp8_decode_matches_an_independent_conversion_for_all_bytes():
+    import torch
+    ref = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    for b in range(256):
+        got = oracle.fp8_e4m3_decode(b)
+        assert (math.isnan(got) and math.isnan(ref[b])) or got == ref[b], b
+    assert oracle.fp8_e4m3_decode(0x7E) == 448.0 and oracle.fp8_e4m3_decode(0x01) == 2.0 ** -9
+    assert oracle.fp8_e4m3_decode(0x38) == 1.0 and oracle.fp8_e4m3_decode(0xB8) == -1.0
+
+
+def _dequantized(wl, f8):
+    """fp32 pools holding decode(byte) * scale, by the library's own cast (NaN bytes stay NaN)."""
+    import torch
+    def one(c8, sc):
+        x = torch.from_numpy(c8).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+        return (x * sc[:, :, None, None]).astype(np.float32)
+    return one(f8.k_cache, f8.k_scale), one(f8.v_cache, f8.v_scale)
+
+
+def test_fp8_attention_with_power_of_two_scales_is_the_fp32_oracle_on_dequantised_pools():
+    wl = W.build("f8", 51, [37, 5, 64, 1, 0, 90], Hq=6, Hkv=2, D=64, ps=16, dtype=W.BF16, pool_factor=1.5)
+    f8 = W.quantize_fp8(wl, power_of_two_scales=True)
+    got = oracle.paged_decode_attn_fp8(wl.q, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                                       wl.context_lens, wl.scale)
+    kd, vd = _dequantized(wl, f8)                            # exact: a 4-bit significand times a power of two
+    qf = W.bf16_bits_to_f32(wl.q)
+    ref = oracle.paged_decode_attn(qf, kd, vd, wl.block_table, wl.context_lens, wl.scale, W.F32)
+    assert np.array_equal(got, ref)
+    assert np.all(got[4] == 0)                               # the empty request
+
+
+def test_fp8_attention_with_general_scales_and_quantisation_error_is_small():
+    wl = W.build("f8", 52, [200, 33, 64], Hq=8, Hkv=2, D=128, ps=32, dtype=W.BF16)
+    f8 = W.quantize_fp8(wl)
+    assert f8.k_cache.dtype == np.uint8 and np.all(f8.k_scale > 0)
+    got = oracle.paged_decode_attn_fp8(wl.q, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                                       wl.context_lens, wl.scale)
+    import torch
+    kd = torch.from_numpy(f8.k_cache).view(torch.float8_e4m3fn).to(torch.float64).numpy() * f8.k_scale.astype(np.float64)[:, :, None, None]
+    vd = torch.from_numpy(f8.v_cache).view(torch.float8_e4m3fn).to(torch.float64).numpy() * f8.v_scale.astype(np.float64)[:, :, None, None]
+    qf = W.bf16_bits_to_f32(wl.q).astype(np.float64)
+    for b in range(wl.B):                                    # dense brute force on the de-quantised rows, fp64
+        L = int(wl.context_lens[b]); t = np.arange(L)
+        K = kd[wl.block_table[b, t // wl.ps], :, t % wl.ps, :]; V = vd[wl.block_table[b, t // wl.ps], :, t % wl.ps, :]
+        Kh, Vh = np.repeat(K, wl.G, axis=1), np.repeat(V, wl.G, axis=1)
+        S = np.einsum("hd,thd->ht", qf[b], Kh) * float(wl.scale)
+        Pm = np.exp(S - S.max(axis=1, keepdims=True)); Pm /= Pm.sum(axis=1, keepdims=True)
+        assert np.max(np.abs(got[b] - np.einsum("ht,thd->hd", Pm, Vh))) < 1e-12
+    # and it is attention over a quantised copy of the bf16 pools: close to the bf16 result, not equal to it
+    ref16 = oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, wl.scale, wl.dtype)
+    d = np.max(np.abs(got - ref16))
+    assert 1e-5 < d < 0.2
