@@ -58,7 +58,11 @@ typedef enum {
     OMNI_ERR_HIP = 6            /* the HIP runtime reported an error at launch */
 } omni_status_t;
 
-typedef enum { OMNI_F32 = 0, OMNI_BF16 = 1 } omni_dtype_t;
+typedef enum {
+    OMNI_F32 = 0,
+    OMNI_BF16 = 1,
+    OMNI_FP8_E4M3 = 2           /* kv_dtype only: OCP 8-bit float (1-4-3, bias 7, max 448, no infinity), see omni_paged_decode_attn_fp8 */
+} omni_dtype_t;
 
 /* Problem description, fixed for the lifetime of a handle.  Set struct_size = sizeof(omni_attn_desc_t). */
 typedef struct {
@@ -70,7 +74,7 @@ typedef struct {
     int32_t  page_size;             /* 16 or 32 tokens */
     int32_t  num_pages;             /* P, pages in each pool */
     int32_t  max_blocks_per_seq;    /* row length of block_table */
-    int32_t  q_dtype;               /* omni_dtype_t; must equal kv_dtype */
+    int32_t  q_dtype;               /* omni_dtype_t; must equal kv_dtype, except OMNI_BF16 queries over an OMNI_FP8_E4M3 cache */
     int32_t  kv_dtype;              /* omni_dtype_t */
     int32_t  out_dtype;             /* omni_dtype_t; OMNI_BF16 only with bf16 q/kv */
     int32_t  max_context_hint;      /* upper bound on any context_lens[b] if the caller knows one; <= 0: max_blocks_per_seq*page_size */
@@ -120,6 +124,24 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h,
                                      const void *q, const void *k_cache, const void *v_cache,
                                      const int32_t *block_table, const int32_t *context_lens,
                                      float scale, void *out, void *stream);
+
+/*
+ * The same attention over a quantised KV cache (the paper lists quantised attention only among its diffusion engine's
+ * options, Section 3.3; here it halves the bytes the decode path streams).  The handle is created with
+ * kv_dtype = OMNI_FP8_E4M3, q_dtype = OMNI_BF16, head_dim 128.  k_cache / v_cache hold one E4M3 byte per element in
+ * the same [num_pages, num_kv_heads, page_size, head_dim] layout; k_scale / v_scale are DEVICE arrays
+ * [num_pages, num_kv_heads] of fp32, and element (page, g, slot, d) stands for decode(byte) * scale[page, g].
+ * Bytes are widened exactly to bf16 in registers, products and sums are fp32, the K scale joins the softmax scale and
+ * the V scale the softmax weights.  NaN bytes in slots no live token owns never reach the result.
+ * omni_kv_append, omni_kv_pack and omni_kv_unpack move the bytes of such a cache like any other (scales are the
+ * caller's); omni_paged_decode_attn, omni_decode_step and omni_paged_prefill_attn return OMNI_ERR_UNSUPPORTED for it.
+ * Errors: NULL, SHAPE (alignment), UNSUPPORTED (handle is not an fp8 one), WORKSPACE, HIP.
+ */
+omni_status_t omni_paged_decode_attn_fp8(omni_handle_t h,
+                                         const void *q, const void *k_cache, const void *v_cache,
+                                         const float *k_scale, const float *v_scale,
+                                         const int32_t *block_table, const int32_t *context_lens,
+                                         float scale, void *out, void *stream);
 
 /*
  * Autoregressive decoding adds one token per request per iteration (Section 2.2, the AR decoding loop): copy, bit for

@@ -13,13 +13,13 @@ from typing import Optional
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("OMNI_ATTN_LIB") or os.path.join(_HERE, "libomni_attn.so")
 
-OMNI_F32, OMNI_BF16 = 0, 1
+OMNI_F32, OMNI_BF16, OMNI_FP8_E4M3 = 0, 1, 2
 OMNI_TUNE_KERNEL, OMNI_TUNE_TARGET_WORKGROUPS, OMNI_TUNE_MIN_PARTITION, OMNI_TUNE_FORCE_PARTITION = 0, 1, 2, 3
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = (
     "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_set_workspace",
-    "omni_paged_decode_attn", "omni_kv_append", "omni_decode_step", "omni_kv_pack", "omni_kv_unpack", "omni_paged_prefill_attn", "omni_kv_append_chunk", "omni_get_plan",
+    "omni_paged_decode_attn", "omni_paged_decode_attn_fp8", "omni_kv_append", "omni_decode_step", "omni_kv_pack", "omni_kv_unpack", "omni_paged_prefill_attn", "omni_kv_append_chunk", "omni_get_plan",
     "omni_status_string",
     "omni_debug_last_plan", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
     "omni_debug_profile_end", "omni_graph_begin", "omni_graph_end", "omni_graph_launch", "omni_graph_destroy",
@@ -56,6 +56,7 @@ def lib():
         L.omni_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
         L.omni_set_workspace.argtypes = [vp, vp, C.c_size_t]
         L.omni_paged_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
+        L.omni_paged_decode_attn_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_kv_append.argtypes = [vp] * 8
         L.omni_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_kv_pack.argtypes = [vp] * 9
@@ -185,6 +186,12 @@ class Handle:
         _ck(lib().omni_paged_decode_attn(self._h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
                                          _ptr(context_lens), C.c_float(float(scale)), _ptr(out), _stream(stream)),
             "omni_paged_decode_attn")
+
+    def omni_paged_decode_attn_fp8(self, q, k_cache, v_cache, k_scale, v_scale, block_table, context_lens, scale, out,
+                                   stream=None) -> None:
+        _ck(lib().omni_paged_decode_attn_fp8(self._h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale), _ptr(v_scale),
+                                             _ptr(block_table), _ptr(context_lens), C.c_float(float(scale)), _ptr(out),
+                                             _stream(stream)), "omni_paged_decode_attn_fp8")
 
     def omni_kv_append(self, k_new, v_new, k_cache, v_cache, block_table, positions, stream=None) -> None:
         _ck(lib().omni_kv_append(self._h, _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),

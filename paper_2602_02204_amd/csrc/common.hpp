@@ -34,6 +34,8 @@ struct AttnParams {
     const void *q;
     const void *k_cache;
     const void *v_cache;
+    const float *k_scale;               // 8-bit KV cache only (else null): [P, Hkv] scales of the K and V pools
+    const float *v_scale;
     const void *k_new;                  // fused decode step only (else null): rows to append at context_lens[b] - 1
     const void *v_new;
     const int32_t *block_table;

@@ -74,6 +74,71 @@ struct MfmaTileLoader {
     }
 };
 
+// 8 E4M3 bytes (two dwords, dims ascending) -> 8 bf16 (exact: 4 significant bits fit in 8).
+__device__ __forceinline__ uint4 fp8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
+    uint4 r;
+    r.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false));
+    r.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true));
+    r.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false));
+    r.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true));
+    return r;
+}
+
+// Loads of one 32-token tile of an 8-bit KV cache (128-byte rows).  K: a lane (token = lane%16, group j) takes the 32
+// bytes of dims 32j .. 32j+31 as two 16-byte loads, and MFMA step kk of group j uses dims 32j + 8kk .. +8 (the query
+// operand is bound the same way).  V: a lane (chunk = lane%16, group j) takes 8 bytes = dims 8*chunk .. +8 of rows
+// 4j .. 4j+3 and 16+4j .. 16+4j+3.  The scales of the tile's pages ride along.
+template <int PS>
+struct Mfma8TileLoader {
+    const char *kbase, *vbase;
+    const float *k_scale, *v_scale;  // already offset by the KV head
+    size_t page_stride;
+    int Hkv, koff, voff;
+
+    __device__ __forceinline__ void issue_k(int pg0, int pg1, uint4 (&Kr)[4], float (&ks)[2]) const {
+        const int pgb = (PS == 16) ? pg1 : pg0;
+        const char *k0 = kbase + (size_t)pg0 * page_stride + koff;
+        const char *k1 = (PS == 16) ? kbase + (size_t)pg1 * page_stride + koff : k0 + 16 * 128;
+        Kr[0] = *reinterpret_cast<const uint4 *>(k0);
+        Kr[1] = *reinterpret_cast<const uint4 *>(k0 + 16);
+        Kr[2] = *reinterpret_cast<const uint4 *>(k1);
+        Kr[3] = *reinterpret_cast<const uint4 *>(k1 + 16);
+        ks[0] = k_scale[(size_t)pg0 * Hkv];
+        ks[1] = k_scale[(size_t)pgb * Hkv];
+    }
+    __device__ __forceinline__ void issue_v(int pg0, int pg1, uint2 (&Vr)[8], float (&vs)[2]) const {
+        const int pgb = (PS == 16) ? pg1 : pg0;
+        const char *v0 = vbase + (size_t)pg0 * page_stride + voff;
+        const char *v1 = (PS == 16) ? vbase + (size_t)pg1 * page_stride + voff : v0 + 16 * 128;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            Vr[r] = *reinterpret_cast<const uint2 *>(v0 + r * 128);
+            Vr[4 + r] = *reinterpret_cast<const uint2 *>(v1 + r * 128);
+        }
+        vs[0] = v_scale[(size_t)pg0 * Hkv];
+        vs[1] = v_scale[(size_t)pgb * Hkv];
+    }
+};
+
+// Scores of a tile of an 8-bit cache: bytes are widened to bf16 right before each MFMA step; the K scale of each
+// 16-token half joins the softmax scale.
+__device__ __forceinline__ void mfma_scores_fp8(const uint4 (&Kr)[4], const uint4 (&Q)[4], float (&sv)[8],
+                                                float scale_log2, const float (&ks)[2]) {
+#pragma clang fp contract(off)
+    f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        const uint4 &a = Kr[kk >> 1], &b = Kr[2 + (kk >> 1)];
+        const uint4 A0 = (kk & 1) ? fp8x8_to_bf16x8(a.z, a.w) : fp8x8_to_bf16x8(a.x, a.y);
+        const uint4 A1 = (kk & 1) ? fp8x8_to_bf16x8(b.z, b.w) : fp8x8_to_bf16x8(b.x, b.y);
+        s0 = mfma_bf16(A0, Q[kk], s0);
+        s1 = mfma_bf16(A1, Q[kk], s1);
+    }
+    const float c0 = ks[0] * scale_log2, c1 = ks[1] * scale_log2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { sv[i] = s0[i] * c0; sv[4 + i] = s1[i] * c1; }
+}
+
 struct MfmaState {
     float m, l;
     f32x4_t acc[8];          // acc[e][i] = O^T[dim 32j + 8i + e][head lane%16]
@@ -95,7 +160,11 @@ __device__ __forceinline__ void mfma_scores(const uint4 (&K)[8], const uint4 (&Q
 }
 
 // Second half: online softmax over the tile's scores and the weighted V accumulation O^T += V^T P^T.
-__device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], MfmaState &st, int tb, int t1, int j) {
+// `vs0` / `vs1` scale the weights of the tile's first / second 16 tokens on their way into the product (the V scales of
+// an 8-bit cache; 1 otherwise): the sum of weights stays unscaled.
+template <bool kScaled = false>
+__device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], MfmaState &st, int tb, int t1, int j,
+                                                float vs0 = 1.f, float vs1 = 1.f) {
 #pragma clang fp contract(off)
     if (tb + 32 > t1) {                                  // ragged last tile (uniform branch)
 #pragma unroll
@@ -118,6 +187,10 @@ __device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], M
     for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(sv[r] - mn); psum += pw[r]; }
     st.l = st.l * alpha + psum;
     st.m = mn;
+    if (kScaled) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { pw[r] *= vs0; pw[4 + r] *= vs1; }
+    }
     uint4 Ph, Pl;
     {
         uint32_t h[4], lo[4];
@@ -214,9 +287,11 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
 // Finished segments wait in a ring of shared-memory slots (their per-wave states) until the workgroup meets to
 // combine them: when the ring is full or the range ends.  A range that holds the end of one request and the start of
 // the next is thus processed without a stop in the middle.
-template <int PS>
+// KV8: the pools hold 8-bit E4M3 bytes with one scale per (page, KV head); queries stay bf16.
+template <int PS, bool KV8 = false>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
+    constexpr int ES = KV8 ? 1 : 2;                          // bytes per cache element
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     __shared__ PlanSmem ps;
     extern __shared__ __align__(16) int E[];                 // E[B + 1] tile offsets, then Lc[B] lengths, then the ring
@@ -241,11 +316,17 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     const int head0 = kvh * G;
 
     MfmaTileLoader<PS> ld;
-    ld.page_stride = (size_t)p.Hkv * PS * D * 2;
-    ld.kbase = reinterpret_cast<const char *>(p.k_cache) + (size_t)kvh * PS * D * 2;
-    ld.vbase = reinterpret_cast<const char *>(p.v_cache) + (size_t)kvh * PS * D * 2;
+    ld.page_stride = (size_t)p.Hkv * PS * D * ES;
+    ld.kbase = reinterpret_cast<const char *>(p.k_cache) + (size_t)kvh * PS * D * ES;
+    ld.vbase = reinterpret_cast<const char *>(p.v_cache) + (size_t)kvh * PS * D * ES;
     ld.koff = col * 256 + j * 16;
     ld.voff = col * 16 + (4 * j) * 256;
+    Mfma8TileLoader<PS> ld8;
+    ld8.page_stride = ld.page_stride; ld8.kbase = ld.kbase; ld8.vbase = ld.vbase;
+    ld8.k_scale = KV8 ? p.k_scale + kvh : nullptr; ld8.v_scale = KV8 ? p.v_scale + kvh : nullptr;
+    ld8.Hkv = p.Hkv;
+    ld8.koff = col * 128 + j * 32;
+    ld8.voff = col * 8 + (4 * j) * 128;
 
     auto load_q = [&](int b, uint4 (&Q)[4]) {                    // B operand of K Q^T for request b
 #pragma unroll
@@ -253,7 +334,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         if (col < G) {
             const char *qrow = reinterpret_cast<const char *>(p.q) + ((size_t)b * p.Hq + head0 + col) * (D * 2);
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) Q[kk] = *reinterpret_cast<const uint4 *>(qrow + (4 * kk + j) * 16);
+            for (int kk = 0; kk < 4; ++kk)                      // dims of step kk: (4kk + j) * 8 .., or 32j + 8kk .. (KV8)
+                Q[kk] = *reinterpret_cast<const uint4 *>(qrow + (KV8 ? 4 * j + kk : 4 * kk + j) * 16);
         }
     };
 
@@ -336,7 +418,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             const int pos = Lc[si.req] - 1;
             const int pg = (PS == 16 && (pos & 16)) ? si.pg1 : si.pg0;
             const size_t row = (size_t)pg * ld.page_stride + (size_t)(pos & (PS - 1)) * (D * 2);
-            if (lane < 32) {
+            if (!KV8 && lane < 32) {                             // the fused append exists for 16-bit caches only
                 const bool is_v = lane >= 16;
                 const char *src = reinterpret_cast<const char *>(is_v ? p.v_new : p.k_new) +
                                   ((size_t)si.req * p.Hkv + kvh) * (D * 2) + (lane & 15) * 16;
@@ -351,14 +433,23 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         // as the scores of the current tile have consumed K, its V rows as soon as the accumulation has consumed V,
         // and the next request's query as soon as the last scores of the current request are done.  The requests
         // stay in flight across the end-of-segment exchange below.
-        uint4 K[8], V[8], Q[4];
+        uint4 K[KV8 ? 1 : 8], V[8], Q[4];
+        uint4 Kr[KV8 ? 4 : 1];           // 8-bit cache: the raw bytes of a tile and the scales of its two pages
+        uint2 Vr[KV8 ? 8 : 1];
+        float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
+        auto issue_k = [&](int pg0, int pg1) __attribute__((always_inline)) {
+            if constexpr (KV8) ld8.issue_k(pg0, pg1, Kr, ks); else ld.issue_k(pg0, pg1, K);
+        };
+        auto issue_v = [&](int pg0, int pg1) __attribute__((always_inline)) {
+            if constexpr (KV8) ld8.issue_v(pg0, pg1, Vr, vs); else ld.issue_v(pg0, pg1, V);
+        };
         int s = 0;                       // slot being computed; its loads are in flight
         SlotInfo cur = slot_info(0);
         if (cur.req >= 0) {
             if (cur.append) append_row(cur);
-            ld.issue_k(cur.pg0, cur.pg1, K);
+            issue_k(cur.pg0, cur.pg1);
             load_q(cur.req, Q);
-            ld.issue_v(cur.pg0, cur.pg1, V);
+            issue_v(cur.pg0, cur.pg1);
         }
         OMNI_STAMP(p, 2);
 
@@ -375,16 +466,25 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 const SlotInfo nxt = slot_info(s + 1);
                 const bool more = nxt.req >= 0;
                 float sv[8];
-                mfma_scores(K, Q, sv, p.scale_log2);
+                if constexpr (KV8) mfma_scores_fp8(Kr, Q, sv, p.scale_log2, ks);
+                else mfma_scores(K, Q, sv, p.scale_log2);
                 if (!stamped) { OMNI_STAMP(p, 3); stamped = true; }
                 OMNI_STAMP(p, 16 + (s < 15 ? s : 15));
                 if (more) {
                     if (nxt.append) append_row(nxt);
-                    ld.issue_k(nxt.pg0, nxt.pg1, K);
+                    issue_k(nxt.pg0, nxt.pg1);
                     if (nxt.req != seg.b) load_q(nxt.req, Q);
                 }
-                mfma_softmax_pv(sv, V, st, cur.tile * kTile, seg.L, j);
-                if (more) ld.issue_v(nxt.pg0, nxt.pg1, V);
+                if constexpr (KV8) {
+                    const float v0 = vs[0], v1 = vs[1];          // of the current tile: the next V request replaces them
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) V[r] = fp8x8_to_bf16x8(Vr[r].x, Vr[r].y);
+                    if (more) issue_v(nxt.pg0, nxt.pg1);         // the raw V bytes are consumed: request the next ones
+                    mfma_softmax_pv<true>(sv, V, st, cur.tile * kTile, seg.L, j, v0, v1);
+                } else {
+                    mfma_softmax_pv(sv, V, st, cur.tile * kTile, seg.L, j);
+                    if (more) issue_v(nxt.pg0, nxt.pg1);
+                }
                 ++s; cur = nxt;
             }
 

@@ -27,6 +27,8 @@ int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
 
 bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
+int elem_bytes(int dtype) { return dtype == OMNI_F32 ? 4 : (dtype == OMNI_BF16 ? 2 : 1); }
+
 }  // namespace
 
 #ifdef OMNI_TRACE
@@ -59,8 +61,9 @@ struct omni_handle_s {
         G = d.num_q_heads / d.num_kv_heads;
         const long long cap_ctx = (long long)d.max_blocks_per_seq * d.page_size;
         max_ctx = (d.max_context_hint > 0 && d.max_context_hint < cap_ctx) ? d.max_context_hint : (int)(cap_ctx > 0x3fffffe0 ? 0x3fffffe0 : cap_ctx);
-        const bool mfma_ok = d.kv_dtype == OMNI_BF16 && d.head_dim == 128;
-        kernel = (tune_kernel == 2 && mfma_ok) ? 2 : (tune_kernel == 1 ? 1 : (mfma_ok ? 2 : 1));
+        const bool fp8 = d.kv_dtype == OMNI_FP8_E4M3;
+        const bool mfma_ok = (d.kv_dtype == OMNI_BF16 || fp8) && d.head_dim == 128;
+        kernel = fp8 ? 2 : ((tune_kernel == 2 && mfma_ok) ? 2 : (tune_kernel == 1 ? 1 : (mfma_ok ? 2 : 1)));
         nw = tune_target_wgs / d.num_kv_heads;
         if (nw < 1) nw = 1;
         lds = mfma_lds_layout(d.batch, G);
@@ -104,9 +107,11 @@ omni_status_t omni_create(const omni_attn_desc_t *desc, omni_handle_t *out_handl
         return OMNI_ERR_SHAPE;
     if (desc->num_q_heads % desc->num_kv_heads != 0) return OMNI_ERR_SHAPE;
     auto known = [](int t) { return t == OMNI_F32 || t == OMNI_BF16; };
-    if (!known(desc->q_dtype) || !known(desc->kv_dtype) || !known(desc->out_dtype)) return OMNI_ERR_DTYPE;
-    if (desc->q_dtype != desc->kv_dtype) return OMNI_ERR_DTYPE;
-    if (desc->out_dtype == OMNI_BF16 && desc->kv_dtype != OMNI_BF16) return OMNI_ERR_DTYPE;
+    const bool fp8 = desc->kv_dtype == OMNI_FP8_E4M3;
+    if (!known(desc->q_dtype) || !(known(desc->kv_dtype) || fp8) || !known(desc->out_dtype)) return OMNI_ERR_DTYPE;
+    if (fp8 ? desc->q_dtype != OMNI_BF16 : desc->q_dtype != desc->kv_dtype) return OMNI_ERR_DTYPE;
+    if (desc->out_dtype == OMNI_BF16 && desc->q_dtype != OMNI_BF16) return OMNI_ERR_DTYPE;
+    if (fp8 && desc->head_dim != 128) return OMNI_ERR_UNSUPPORTED;
     if (desc->head_dim != 64 && desc->head_dim != 128) return OMNI_ERR_UNSUPPORTED;
     if (desc->page_size != 16 && desc->page_size != 32) return OMNI_ERR_UNSUPPORTED;
     if (desc->num_q_heads / desc->num_kv_heads > kMaxGroup) return OMNI_ERR_UNSUPPORTED;
@@ -130,7 +135,9 @@ omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value) {
     switch (key) {
         case OMNI_TUNE_KERNEL:
             if (value < 0 || value > 2) return OMNI_ERR_SHAPE;
-            if (value == 2 && !(h->d.kv_dtype == OMNI_BF16 && h->d.head_dim == 128)) return OMNI_ERR_UNSUPPORTED;
+            if (value == 2 && !(h->d.kv_dtype == OMNI_BF16 && h->d.head_dim == 128) && h->d.kv_dtype != OMNI_FP8_E4M3)
+                return OMNI_ERR_UNSUPPORTED;
+            if (value == 1 && h->d.kv_dtype == OMNI_FP8_E4M3) return OMNI_ERR_UNSUPPORTED;
             h->tune_kernel = value; break;
         case OMNI_TUNE_TARGET_WORKGROUPS:
             if (value <= 0) return OMNI_ERR_SHAPE;
@@ -198,8 +205,12 @@ static omni_status_t launch_append(omni_handle_t h, const void *k_new, const voi
 // The attention launch shared by omni_paged_decode_attn (k_new = v_new = null) and omni_decode_step.
 static omni_status_t launch_attention(omni_handle_t h, const void *q, const void *k_new, const void *v_new,
                                       const void *k_cache, const void *v_cache, const int32_t *block_table,
-                                      const int32_t *context_lens, float scale, void *out, void *stream) {
+                                      const int32_t *context_lens, float scale, void *out, void *stream,
+                                      const float *k_scale = nullptr, const float *v_scale = nullptr) {
     if (!h || !q || !k_cache || !v_cache || !block_table || !context_lens || !out) return OMNI_ERR_NULL;
+    const bool fp8 = h->d.kv_dtype == OMNI_FP8_E4M3;
+    if (fp8 != (k_scale != nullptr) || (fp8 && (k_new || v_new))) return OMNI_ERR_UNSUPPORTED;
+    if (fp8 && (!v_scale || misaligned(k_scale, 4) || misaligned(v_scale, 4))) return v_scale ? OMNI_ERR_SHAPE : OMNI_ERR_NULL;
     if (!h->ws || h->ws_given < h->ws_bytes) return OMNI_ERR_WORKSPACE;
     if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(out, 16) ||
         misaligned(k_new, 16) || misaligned(v_new, 16) || misaligned(block_table, 4) || misaligned(context_lens, 4))
@@ -210,6 +221,7 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     AttnParams p;
     p.q = q; p.k_cache = k_cache; p.v_cache = v_cache;
     p.k_new = k_new; p.v_new = v_new;
+    p.k_scale = k_scale; p.v_scale = v_scale;
     p.block_table = block_table; p.context_lens = context_lens; p.out = out;
     char *ws = reinterpret_cast<char *>(h->ws);
     p.ws.plan_words = reinterpret_cast<int32_t *>(ws);
@@ -234,8 +246,10 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     const bool prof = (size_t)(2 * h->prof_used + 1) < h->prof_events.size() && (h->prof_calls++ % h->prof_stride) == 0;
     if (prof && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
     if (h->kernel == 2) {
-        const void *fn = d.page_size == 16 ? reinterpret_cast<const void *>(&decode_mfma_kernel<16>)
-                                           : reinterpret_cast<const void *>(&decode_mfma_kernel<32>);
+        const void *fn = fp8 ? (d.page_size == 16 ? reinterpret_cast<const void *>(&decode_mfma_kernel<16, true>)
+                                                  : reinterpret_cast<const void *>(&decode_mfma_kernel<32, true>))
+                             : (d.page_size == 16 ? reinterpret_cast<const void *>(&decode_mfma_kernel<16, false>)
+                                                  : reinterpret_cast<const void *>(&decode_mfma_kernel<32, false>));
         if (!h->lds_attr_set) {          // more than the default 64 KB of dynamic shared memory
             if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, h->lds.total) != hipSuccess) {
                 (void)hipGetLastError();
@@ -243,8 +257,13 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
             }
             h->lds_attr_set = true;
         }
-        if (d.page_size == 16) decode_mfma_kernel<16><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
-        else decode_mfma_kernel<32><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
+        if (fp8) {
+            if (d.page_size == 16) decode_mfma_kernel<16, true><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
+            else decode_mfma_kernel<32, true><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
+        } else {
+            if (d.page_size == 16) decode_mfma_kernel<16, false><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
+            else decode_mfma_kernel<32, false><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
+        }
     } else if (d.kv_dtype == OMNI_BF16) {
         if (d.head_dim == 128) launch_valu<uint16_t, 128>(p, grid, dyn, s);
         else launch_valu<uint16_t, 64>(p, grid, dyn, s);
@@ -272,6 +291,15 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void 
                                      const int32_t *block_table, const int32_t *context_lens, float scale, void *out,
                                      void *stream) {
     return launch_attention(h, q, nullptr, nullptr, k_cache, v_cache, block_table, context_lens, scale, out, stream);
+}
+
+omni_status_t omni_paged_decode_attn_fp8(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
+                                         const float *k_scale, const float *v_scale, const int32_t *block_table,
+                                         const int32_t *context_lens, float scale, void *out, void *stream) {
+    if (!h || !k_scale || !v_scale) return OMNI_ERR_NULL;
+    if (h->d.kv_dtype != OMNI_FP8_E4M3) return OMNI_ERR_UNSUPPORTED;
+    return launch_attention(h, q, nullptr, nullptr, k_cache, v_cache, block_table, context_lens, scale, out, stream,
+                            k_scale, v_scale);
 }
 
 omni_status_t omni_decode_step(omni_handle_t h, const void *q, const void *k_new, const void *v_new, void *k_cache,
@@ -304,7 +332,7 @@ static omni_status_t launch_append(omni_handle_t h, const void *k_new, const voi
     p.k_new = k_new; p.v_new = v_new; p.k_cache = k_cache; p.v_cache = v_cache;
     p.block_table = block_table; p.positions = positions;
     p.B = d.batch; p.Hkv = d.num_kv_heads; p.MB = d.max_blocks_per_seq; p.log2_ps = ilog2(d.page_size);
-    p.row_vecs = d.head_dim * (d.kv_dtype == OMNI_BF16 ? 2 : 4) / 16;
+    p.row_vecs = d.head_dim * elem_bytes(d.kv_dtype) / 16;
     p.positions_are_lengths = positions_are_lengths;
     const long long total = (long long)p.B * p.Hkv * p.row_vecs;
     const dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
@@ -368,7 +396,7 @@ omni_status_t omni_debug_gather(omni_handle_t h, const void *cache, const int32_
     GatherParams p;
     p.cache = cache; p.block_table = block_table; p.context_lens = context_lens; p.dense_out = dense_out;
     p.request = request; p.Hkv = d.num_kv_heads; p.MB = d.max_blocks_per_seq; p.log2_ps = ilog2(d.page_size);
-    p.row_vecs = d.head_dim * (d.kv_dtype == OMNI_BF16 ? 2 : 4) / 16;
+    p.row_vecs = d.head_dim * elem_bytes(d.kv_dtype) / 16;
     const long long total = (long long)h->max_ctx * p.Hkv * p.row_vecs;
     const dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
     (void)hipGetLastError();
@@ -404,7 +432,7 @@ static omni_status_t launch_pack(omni_handle_t h, bool unpack, const void *k_src
     p.token_offsets = reinterpret_cast<const long long *>(token_offsets);
     p.q_lens = q_lens;
     p.Hkv = d.num_kv_heads; p.MB = d.max_blocks_per_seq; p.log2_ps = ilog2(d.page_size);
-    p.row_vecs = d.head_dim * (d.kv_dtype == OMNI_BF16 ? 2 : 4) / 16;
+    p.row_vecs = d.head_dim * elem_bytes(d.kv_dtype) / 16;
     const int span = q_lens ? max_tokens : h->max_ctx;                     // tokens per request the grid must cover
     const dim3 grid((unsigned)((span + kPackTokens - 1) / kPackTokens), (unsigned)d.batch);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);

@@ -20,7 +20,7 @@ def good(**over):
 def test_library_exports_every_declared_symbol():
     text = open(os.path.join(ROOT, "include", "omni_attn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(omni_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(omni_[a-z0-9_]+)\s*\(", text))
     assert declared == set(omni.EXPORTS)
     L = omni.lib()
     for name in declared:
@@ -88,3 +88,18 @@ def test_tuning_validation_and_plan():
     assert f32.omni_get_plan()["kernel"] == omni.KERNEL_VALU
     with pytest.raises(omni.OmniError):
         f32.omni_set_tuning(omni.OMNI_TUNE_KERNEL, omni.KERNEL_MFMA)
+
+
+def test_fp8_cache_descriptions():
+    h = omni.Handle(**good(kv_dtype=omni.OMNI_FP8_E4M3, q_dtype=omni.OMNI_BF16))
+    plan = h.omni_get_plan()
+    assert plan["kernel"] == omni.KERNEL_MFMA
+    with pytest.raises(omni.OmniError) as e:
+        omni.Handle(**good(kv_dtype=omni.OMNI_FP8_E4M3, q_dtype=omni.OMNI_F32))
+    assert e.value.status == 3
+    with pytest.raises(omni.OmniError) as e:
+        omni.Handle(**good(kv_dtype=omni.OMNI_FP8_E4M3, q_dtype=omni.OMNI_BF16, head_dim=64))
+    assert e.value.status == 4
+    with pytest.raises(omni.OmniError) as e:
+        omni.Handle(**good(kv_dtype=3))
+    assert e.value.status == 3
