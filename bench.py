@@ -274,6 +274,48 @@ def main():
                    "peak_TFLOP/s": 2500.0, "frac": flops / us / 1e6 / 2500.0, "parity_max_abs_err_sampled": perr}
         del pq, pk, pv, pout
 
+    # ---- the same batch over an 8-bit (E4M3) KV cache with per-page scales: half the bytes per token
+    fp8 = None
+    if not args.timed_only and wl.dtype == W.BF16 and wl.D == 128:
+        wl8 = W.make(args.workload, seed=args.seed, append=False)       # the same batch with every token in the pools
+        f8 = W.quantize_fp8(wl8)
+        h8 = omni.Handle(batch=wl.B, num_q_heads=wl.Hq, num_kv_heads=wl.Hkv, head_dim=wl.D, page_size=wl.ps,
+                         num_pages=wl.P, max_blocks_per_seq=wl.MB, kv_dtype=omni.OMNI_FP8_E4M3, q_dtype=omni.OMNI_BF16,
+                         out_dtype=omni.OMNI_F32)
+        ws8 = h8.alloc_workspace()
+        k8 = [torch.from_numpy(f8.k_cache).cuda()]
+        v8 = [torch.from_numpy(f8.v_cache).cuda()]
+        R8 = max(2, int(np.ceil((1 << 30) / max(kv_bytes // 2, 1))))
+        k8 += [k8[0].clone() for _ in range(R8 - 1)]
+        v8 += [v8[0].clone() for _ in range(R8 - 1)]
+        ks8, vs8 = torch.from_numpy(f8.k_scale).cuda(), torch.from_numpy(f8.v_scale).cuda()
+        out8 = torch.empty_like(out)
+        step8 = lambda i: h8.omni_paged_decode_attn_fp8(q, k8[i % R8], v8[i % R8], ks8, vs8, bt, lens, scale, out8, stream)
+        for i in range(args.warmup):
+            step8(i)
+        h8.omni_debug_profile_begin((K + EVENT_STRIDE - 1) // EVENT_STRIDE, EVENT_STRIDE)
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for i in range(K):
+            step8(i)
+        torch.cuda.synchronize()
+        ms8 = (time.perf_counter() - a) * 1e3 / K
+        kern8 = float(np.mean(h8.omni_debug_profile_end())) * 1e3
+        import oracle as _oracle
+        pr8 = [(0, 0), (wl.B - 1, wl.Hq - 1), (wl.B // 2, 3)]
+        ref8 = _oracle.paged_decode_attn_fp8(wl8.q, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl8.block_table,
+                                             wl8.context_lens, wl8.scale, pairs=pr8)
+        got8 = out8.cpu().numpy().astype(np.float64)
+        err8 = float(max(np.max(np.abs(got8[b, hh] - ref8[i])) for i, (b, hh) in enumerate(pr8)))
+        if not (err8 <= 2e-3):
+            print(f"bench.py: fp8 parity check failed, max|err|={err8:.3e}", file=sys.stderr)
+            sys.exit(1)
+        fp8 = {"kv_bytes_per_step": kv_bytes // 2, "ms_per_step": ms8, "tokens_per_s": wl.B / (ms8 * 1e-3),
+               "kernel_avg_us": kern8, "kernel_GB/s": kv_bytes / 2 / kern8 / 1e3,
+               "kernel_frac_of_hbm_peak": kv_bytes / 2 / kern8 / 1e3 / HBM_PEAK_GBS, "pool_replicas": R8,
+               "parity_max_abs_err_sampled": err8, "note": "attention + merge only (no append in the step)"}
+        del k8, v8
+
     if args.calibrate_copy:                  # 1 GiB read + 1 GiB written per copy: the yardstick for FETCH_SIZE / WRITE_SIZE
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -351,6 +393,7 @@ def main():
                   "kv_gbs_cache_warm": kv_bytes / (ms_warm * 1e-3) / 1e9 if ms_warm else None,
                   "kv_pack_unpack": pack,
                   "prefill_chunk": prefill,
+                  "fp8_kv_cache": fp8,
                   "parity_max_abs_err_sampled": max_err},
     }
     print(json.dumps(result))
