@@ -11,10 +11,11 @@ constexpr int kMaxGroup = 16;          // query heads per KV head the kernels co
 constexpr float kLog2e = 1.4426950408889634f;
 
 // Workspace layout (bytes from the workspace base, all 256-byte aligned):
-//   [0, 256)                 plan words written by item 0: PL, R, T(lo), T(hi)
-//   [256, 256 + 4*B*Hkv)     per (request, KV head): arrival counter of its partitions; zero between calls
-//   ml_off                   per (slot, query head): running max (log2 domain) and sum, float2
+//   [0, 256)                 plan words written by the first workgroup: range length in tokens, number of ranges,
+//                            total context tokens (low, high word)
+//   256                      per (slot, query head): running max (log2 domain) and sum, float2
 //   o_off                    per (slot, query head): unnormalised output row, D floats
+// A slot is one piece of one request (range index + request index); nothing in the workspace needs initialising.
 struct Workspace {
     int32_t *plan_words;
     float2 *part_ml;

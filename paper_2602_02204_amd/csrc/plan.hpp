@@ -9,7 +9,7 @@
 //   - workgroup w of a KV head takes range w (and w + nw, ... if there are more ranges than workgroups).
 // A range crosses request boundaries wherever they fall: it is a list of segments (request, first tile, last tile).
 // A request covered by one range is finished by that workgroup; a request cut by range boundaries yields one partial
-// result per range that touches it, merged by the last of them to arrive.
+// result per range that touches it, put together by the merge kernel that follows.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
