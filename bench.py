@@ -260,7 +260,9 @@ def main():
             b.record(stream)
         torch.cuda.synchronize()
         us = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e3
-        rows = [(0, 0, 0), (pw.B - 1, 511, pw.Hq - 1), (pw.B // 2, 255, 3)]
+        live = [b for b in range(pw.B) if ch.q_lens[b] > 0]
+        rows = [(live[0], 0, 0), (live[-1], int(ch.q_lens[live[-1]]) - 1, pw.Hq - 1),
+                (live[len(live) // 2], int(ch.q_lens[live[len(live) // 2]]) // 2, 3)]
         import oracle as _oracle
         pref = _oracle.paged_prefill_attn(ch.q, pw.k_cache, pw.v_cache, pw.block_table, pw.context_lens, ch.q_lens,
                                           ch.q_offsets, pw.scale, pw.dtype, rows=rows)
@@ -351,7 +353,17 @@ def main():
             spent += time.perf_counter() - c0
             reps += 1
         cpu_s = spent / reps
+        # the same oracle on one thread, on a slice of the batch (the first 8 requests)
+        nb = min(8, wl.B)
+        one_pairs = [(b, hh) for b in range(nb) for hh in range(wl.Hq)]
+        c0 = time.perf_counter()
+        oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, wl.scale, wl.dtype,
+                                 pairs=one_pairs, num_threads=1)
+        one_s = time.perf_counter() - c0
+        one_tokens = float(wl.context_lens[:nb].astype(np.int64).sum())
         cpu = {"value": wl.B / cpu_s, "unit": "tokens/s", "cores": int(used), "kind": "oracle",
+               "single_thread_tokens_per_s": nb / one_s,
+               "single_thread_sample": f"first {nb} requests ({int(one_tokens)} context tokens) in {one_s:.2f} s on 1 thread",
                "sample": f"whole {wl.name} batch ({wl.B} requests, {wl.total_tokens} context tokens), "
                          f"{reps} pass(es) of {cpu_s:.2f} s, fp64, OpenMP over (request, head)",
                "kv_gbs": kv_bytes / cpu_s / 1e9}

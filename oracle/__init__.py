@@ -182,8 +182,14 @@ def paged_prefill_attn(q, k_cache, v_cache, block_table, context_lens, q_lens, q
     lens = np.ascontiguousarray(context_lens, dtype=np.int32)
     ql = np.ascontiguousarray(q_lens, dtype=np.int32)
     qo = np.ascontiguousarray(q_offsets, dtype=np.int64)
+    for b in range(block_table.shape[0]):                    # the C code trusts these
+        if ql[b] > 0 and (ql[b] > lens[b] or qo[b] < 0 or qo[b] + ql[b] > Tq):
+            raise ValueError(f"request {b}: chunk of {ql[b]} rows at {qo[b]} does not fit (context {lens[b]}, {Tq} rows)")
     if rows is not None:
         r = np.ascontiguousarray(np.asarray(rows, dtype=np.int32).reshape(-1, 3))
+        for b, i, h in r:
+            if not (0 <= b < block_table.shape[0] and 0 <= i < ql[b] and 0 <= h < Hq):
+                raise ValueError(f"row ({b}, {i}, {h}) is outside the chunks")
         out = np.zeros((len(r), D), dtype=np.float64)
         lib().oracle_paged_prefill_attn(C.byref(s), _p(q), _p(k_cache), _p(v_cache), _p(bt), _p(lens), _p(ql), _p(qo),
                                         C.c_float(scale), _p(out), _p(r), len(r), num_threads)

@@ -531,3 +531,13 @@ def test_fp8_attention_with_general_scales_and_quantisation_error_is_small():
     ref16 = oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, wl.scale, wl.dtype)
     d = np.max(np.abs(got - ref16))
     assert 1e-5 < d < 0.2
+
+
+def test_chunk_oracle_rejects_rows_outside_the_chunks():
+    wl, ch = _chunk_case(seed=61)
+    args = (ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens, ch.q_offsets, wl.scale, wl.dtype)
+    with pytest.raises(ValueError):
+        oracle.paged_prefill_attn(*args, rows=[(0, 7, 0)])              # request 0 has 7 chunk rows: 0..6
+    with pytest.raises(ValueError):
+        oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens,
+                                  ch.q_lens + 100, ch.q_offsets, wl.scale, wl.dtype)
