@@ -21,8 +21,17 @@ constexpr int kPrefillThreads = 512;                  // 8 waves = 2 per SIMD sh
 constexpr int kPrefillWaves = kPrefillThreads / 64;
 constexpr int kPrefillBlocks = 2;                     // 16-column MFMA blocks per wave
 constexpr int kPrefillCols = 16 * kPrefillBlocks;     // (token, head) pairs per wave
-constexpr int kPrefillRowBytes = 256 + 16;            // a 256-byte K or V row plus padding: conflict-free LDS reads
+constexpr int kPrefillRowBytes = 256 + 16;            // a 256-byte K row plus padding: conflict-free 16-byte LDS reads
+constexpr int kPrefillVRowBytes = 256 + 32;           // V rows: conflict-free 8-byte transposing reads (4 rows x 32 B)
 constexpr float kPrefillSlack = 8.f;                  // log2 units a score may exceed a column's reference maximum
+
+// Transposing 64-bit read from shared memory (see its use below for the lane arrangement).
+__device__ __forceinline__ uint2 lds_read_tr16_b64(const char *p) {
+    typedef short short4_t __attribute__((ext_vector_type(4)));
+    const short4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (short4_t __attribute__((address_space(3))) *)(const __attribute__((address_space(3))) char *)p);
+    return __builtin_bit_cast(uint2, v);
+}
 
 struct PrefillParams {
     const void *q;                    // [Tq, Hq, D] bf16
@@ -43,7 +52,7 @@ template <int PS>
 __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(PrefillParams p) {
     constexpr int D = 128;
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
-    constexpr int kTileBytes = kTile * kPrefillRowBytes;         // one K or V tile in shared memory
+    constexpr int kTileBytes = kTile * kPrefillVRowBytes;        // room for one K or V tile in shared memory
     __shared__ __align__(16) char smem[2][2][kTileBytes];        // [buffer][K, V]
 
     const int b = blockIdx.z, kvh = blockIdx.y;
@@ -98,6 +107,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     const int32_t *bt = p.block_table + (size_t)b * p.MB;
     const int st_tok = threadIdx.x >> 4, st_chunk = threadIdx.x & 15;       // token 0..31 of the tile
     const int lds_off = st_tok * kPrefillRowBytes + st_chunk * 16;
+    const int lds_off_v = st_tok * kPrefillVRowBytes + st_chunk * 16;
     uint4 sk, sv_;
     auto fetch_tile = [&](int tile) __attribute__((always_inline)) {
         const int t = tile * kTile + st_tok;
@@ -111,7 +121,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     };
     auto stage_tile = [&](int buf) __attribute__((always_inline)) {
         *reinterpret_cast<uint4 *>(&smem[buf][0][lds_off]) = sk;
-        *reinterpret_cast<uint4 *>(&smem[buf][1][lds_off]) = sv_;
+        *reinterpret_cast<uint4 *>(&smem[buf][1][lds_off_v]) = sv_;
     };
 
     // ---- per-column online-softmax state
@@ -138,16 +148,11 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         const int tb = tile * kTile;
         if (tb <= wave_max_pos) {                                // the tile holds tokens some column of this wave sees
             const char *ks = smem[buf][0], *vs = smem[buf][1];
-            uint4 K[8], V[8];
+            uint4 K[8];
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
                 K[kk] = *reinterpret_cast<const uint4 *>(ks + col * kPrefillRowBytes + (4 * kk + j) * 16);
                 K[4 + kk] = *reinterpret_cast<const uint4 *>(ks + (16 + col) * kPrefillRowBytes + (4 * kk + j) * 16);
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                V[r] = *reinterpret_cast<const uint4 *>(vs + (4 * j + r) * kPrefillRowBytes + col * 16);
-                V[4 + r] = *reinterpret_cast<const uint4 *>(vs + (16 + 4 * j + r) * kPrefillRowBytes + col * 16);
             }
             const bool need_mask = tb + kTile - 1 > wave_min_pos;
             // Raw scores q.k of the column blocks: all their MFMAs are issued before the first result is read, so the
@@ -164,16 +169,21 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
                     s1[cb] = mfma_bf16(K[4 + kk], Q[cb][kk], s1[cb]);
                 }
             }
-            // The transposed V operands of the tile (8x8 in-lane transposes), shared by the column blocks.
+            // The V^T operands of the tile, shared by the column blocks, come transposed out of shared memory: in a
+            // transposing 8-byte read the 16 lanes of a group each name four consecutive 16-bit values (lane 4k + q:
+            // dims 4q .. 4q+3 of token k of the group's four tokens) and lane i receives value i of each token, i.e.
+            // one output dim for four tokens.  Two reads (tokens 4j .. 4j+3 and 16+4j .. 16+4j+3, exactly the tokens
+            // whose weights this lane group holds) make the operand of one 16-dim block of output rows.
             uint4 A[8];
+            {
+                const char *v_lo = vs + (4 * j + (col >> 2)) * kPrefillVRowBytes + (col & 3) * 8;
+                const char *v_hi = v_lo + 16 * kPrefillVRowBytes;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int w = e >> 1;
-                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-                A[e].x = __builtin_amdgcn_perm(dword_of(V[1], w), dword_of(V[0], w), sel);
-                A[e].y = __builtin_amdgcn_perm(dword_of(V[3], w), dword_of(V[2], w), sel);
-                A[e].z = __builtin_amdgcn_perm(dword_of(V[5], w), dword_of(V[4], w), sel);
-                A[e].w = __builtin_amdgcn_perm(dword_of(V[7], w), dword_of(V[6], w), sel);
+                for (int eb = 0; eb < 8; ++eb) {
+                    const uint2 a0 = lds_read_tr16_b64(v_lo + eb * 32);
+                    const uint2 a1 = lds_read_tr16_b64(v_hi + eb * 32);
+                    A[eb] = make_uint4(a0.x, a0.y, a1.x, a1.y);
+                }
             }
 #pragma unroll
             for (int cb = 0; cb < kPrefillBlocks; ++cb) {
@@ -229,7 +239,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         lds_barrier();
     }
 
-    // ---- normalise and store: a lane holds, for each of its columns, dims 32j + 8i + e (e = 0..7 contiguous)
+    // ---- normalise and store: a lane holds, for each of its columns, dims 16 eb + 4j .. + 3 of every 16-dim block eb
 #pragma unroll
     for (int cb = 0; cb < kPrefillBlocks; ++cb) {
         float lsum = l[cb];
@@ -241,22 +251,16 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         const size_t row = ((size_t)(q_row0 + q0 + wave * TW + tl) * p.Hq + head0 + g) * D;
         const float inv = 1.f / lsum;                            // every live column saw its own position: lsum > 0
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float o[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = acc[cb][e][i] * inv;
-            const size_t at = row + 32 * j + 8 * i;
+        for (int eb = 0; eb < 8; ++eb) {                         // acc[cb][eb][i] = O^T[dim 16 eb + 4 j + i][column]
+            const float o0 = acc[cb][eb][0] * inv, o1 = acc[cb][eb][1] * inv, o2 = acc[cb][eb][2] * inv, o3 = acc[cb][eb][3] * inv;
+            const size_t at = row + 16 * eb + 4 * j;
             if (p.out_bf16) {
-                uint4 pk;
-                pk.x = (uint32_t)float_to_bf16_rne(o[0]) | ((uint32_t)float_to_bf16_rne(o[1]) << 16);
-                pk.y = (uint32_t)float_to_bf16_rne(o[2]) | ((uint32_t)float_to_bf16_rne(o[3]) << 16);
-                pk.z = (uint32_t)float_to_bf16_rne(o[4]) | ((uint32_t)float_to_bf16_rne(o[5]) << 16);
-                pk.w = (uint32_t)float_to_bf16_rne(o[6]) | ((uint32_t)float_to_bf16_rne(o[7]) << 16);
-                *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.out) + at) = pk;
+                uint2 pk;
+                pk.x = (uint32_t)float_to_bf16_rne(o0) | ((uint32_t)float_to_bf16_rne(o1) << 16);
+                pk.y = (uint32_t)float_to_bf16_rne(o2) | ((uint32_t)float_to_bf16_rne(o3) << 16);
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(p.out) + at) = pk;
             } else {
-                float *dst = reinterpret_cast<float *>(p.out) + at;
-                *reinterpret_cast<float4 *>(dst) = make_float4(o[0], o[1], o[2], o[3]);
-                *reinterpret_cast<float4 *>(dst + 4) = make_float4(o[4], o[5], o[6], o[7]);
+                *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.out) + at) = make_float4(o0, o1, o2, o3);
             }
         }
     }
