@@ -8,8 +8,8 @@
 //   S^T = K Q^T     (A = K rows from shared memory, B = the block's queries, held in registers for the whole kernel)
 //   O^T += V^T P^T  (A = V transposed in registers, B = the softmax weights as bf16 hi + lo)
 // so every lane owns one column: running max, sum and rescale never cross lanes except two max exchanges per tile.
-// What differs from decode is reuse: a K/V tile is fetched once per workgroup into shared memory (double buffered,
-// one barrier per tile) and feeds 16 column blocks, and the 8x8 in-lane transpose of V is done once per wave and
+// What differs from decode is reuse: K/V tiles are fetched once per workgroup into shared memory (double buffered,
+// one barrier per 64 tokens) and feed 16 column blocks, and the 8x8 in-lane transpose of V is done once per wave and
 // tile for its two blocks.  That makes the path a dense contraction, not a stream; with the softmax arithmetic on
 // the vector ALUs (no packed fp32 here) about as long as the matrix-core work, both units bound it.
 #pragma once
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     constexpr int D = 128;
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     constexpr int kTileBytes = kTile * kPrefillVRowBytes;        // room for one K or V tile in shared memory
-    __shared__ __align__(16) char smem[2][2][kTileBytes];        // [buffer][K, V]
+    __shared__ __align__(16) char smem[2][2][2][kTileBytes];     // [buffer][tile of the step][K, V]
 
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int G = p.G, head0 = kvh * G;
@@ -99,29 +99,35 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) wave_min_pos = min(wave_min_pos, __shfl_xor(wave_min_pos, off));
 
-    // ---- staging: thread t moves piece t of the 512 16-byte pieces of a K tile and of a V tile
-    // (piece = 16 * token + chunk)
+    // ---- staging: a step is 64 tokens = two 32-token tiles; thread t moves piece t of the 512 16-byte pieces of
+    // each tile's K rows and V rows (piece = 16 * token + chunk)
     const size_t page_stride = (size_t)p.Hkv * PS * D * 2;
     const char *kbase = reinterpret_cast<const char *>(p.k_cache) + (size_t)kvh * PS * D * 2;
     const char *vbase = reinterpret_cast<const char *>(p.v_cache) + (size_t)kvh * PS * D * 2;
     const int32_t *bt = p.block_table + (size_t)b * p.MB;
-    const int st_tok = threadIdx.x >> 4, st_chunk = threadIdx.x & 15;       // token 0..31 of the tile
+    const int st_tok = threadIdx.x >> 4, st_chunk = threadIdx.x & 15;       // token 0..31 of a tile
     const int lds_off = st_tok * kPrefillRowBytes + st_chunk * 16;
     const int lds_off_v = st_tok * kPrefillVRowBytes + st_chunk * 16;
-    uint4 sk, sv_;
-    auto fetch_tile = [&](int tile) __attribute__((always_inline)) {
-        const int t = tile * kTile + st_tok;
-        sk = sv_ = make_uint4(0, 0, 0, 0);                                  // rows beyond the context are zero
-        if (t < L) {
-            const int pg = bt[t >> kLog2Ps];
-            const size_t o = (size_t)pg * page_stride + (size_t)(t & (PS - 1)) * 256 + st_chunk * 16;
-            sk = *reinterpret_cast<const uint4 *>(kbase + o);
-            sv_ = *reinterpret_cast<const uint4 *>(vbase + o);
+    uint4 sk[2], sv_[2];
+    auto fetch_step = [&](int step) __attribute__((always_inline)) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int t = (2 * step + sub) * kTile + st_tok;
+            sk[sub] = sv_[sub] = make_uint4(0, 0, 0, 0);                    // rows beyond the context are zero
+            if (t < L) {
+                const int pg = bt[t >> kLog2Ps];
+                const size_t o = (size_t)pg * page_stride + (size_t)(t & (PS - 1)) * 256 + st_chunk * 16;
+                sk[sub] = *reinterpret_cast<const uint4 *>(kbase + o);
+                sv_[sub] = *reinterpret_cast<const uint4 *>(vbase + o);
+            }
         }
     };
-    auto stage_tile = [&](int buf) __attribute__((always_inline)) {
-        *reinterpret_cast<uint4 *>(&smem[buf][0][lds_off]) = sk;
-        *reinterpret_cast<uint4 *>(&smem[buf][1][lds_off_v]) = sv_;
+    auto stage_step = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            *reinterpret_cast<uint4 *>(&smem[buf][sub][0][lds_off]) = sk[sub];
+            *reinterpret_cast<uint4 *>(&smem[buf][sub][1][lds_off_v]) = sv_[sub];
+        }
     };
 
     // ---- per-column online-softmax state
@@ -138,104 +144,124 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
 #pragma unroll
     for (int cb = 0; cb < kPrefillBlocks; ++cb) raw_limit[cb] = -INFINITY;
     const float inv_scale_log2 = 1.f / p.scale_log2;
-    fetch_tile(0);
-    stage_tile(0);
-    lds_barrier();
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int buf = tile & 1;
-        const bool more = tile + 1 < n_tiles;
-        if (more) fetch_tile(tile + 1);                          // in flight while this tile is computed
-        const int tb = tile * kTile;
-        if (tb <= wave_max_pos) {                                // the tile holds tokens some column of this wave sees
-            const char *ks = smem[buf][0], *vs = smem[buf][1];
-            uint4 K[8];
+    // ---- one 32-token tile, in three pieces, so that the loop below can run the two tiles of a step interleaved:
+    // the score MFMAs of the second tile and the P.V MFMAs of the first are in the matrix-core queue while the vector
+    // ALUs do the softmax of the first and of the second tile.
+    auto read_k = [&](const char *ks, uint4 (&K)[8]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            K[kk] = *reinterpret_cast<const uint4 *>(ks + col * kPrefillRowBytes + (4 * kk + j) * 16);
+            K[4 + kk] = *reinterpret_cast<const uint4 *>(ks + (16 + col) * kPrefillRowBytes + (4 * kk + j) * 16);
+        }
+    };
+    // Raw scores q.k of the column blocks.  The softmax scale is applied inside the exponent (one fused multiply-add
+    // per score): scale > 0, so the order of scores is that of the raw dot products.
+    auto scores = [&](const uint4 (&K)[8], f32x4_t (&s0)[kPrefillBlocks], f32x4_t (&s1)[kPrefillBlocks]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+            s0[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f}; s1[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                K[kk] = *reinterpret_cast<const uint4 *>(ks + col * kPrefillRowBytes + (4 * kk + j) * 16);
-                K[4 + kk] = *reinterpret_cast<const uint4 *>(ks + (16 + col) * kPrefillRowBytes + (4 * kk + j) * 16);
-            }
-            const bool need_mask = tb + kTile - 1 > wave_min_pos;
-            // Raw scores q.k of the column blocks: all their MFMAs are issued before the first result is read, so the
-            // matrix cores work on the later blocks while the vector ALUs do the softmax of the earlier ones.  The
-            // softmax scale is applied inside the exponent (one fused multiply-add per score): scale > 0, so the
-            // order of scores is that of the raw dot products.
-            f32x4_t s0[kPrefillBlocks], s1[kPrefillBlocks];
-#pragma unroll
-            for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-                s0[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f}; s1[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    s0[cb] = mfma_bf16(K[kk], Q[cb][kk], s0[cb]);
-                    s1[cb] = mfma_bf16(K[4 + kk], Q[cb][kk], s1[cb]);
-                }
-            }
-            // The V^T operands of the tile, shared by the column blocks, come transposed out of shared memory: in a
-            // transposing 8-byte read the 16 lanes of a group each name four consecutive 16-bit values (lane 4k + q:
-            // dims 4q .. 4q+3 of token k of the group's four tokens) and lane i receives value i of each token, i.e.
-            // one output dim for four tokens.  Two reads (tokens 4j .. 4j+3 and 16+4j .. 16+4j+3, exactly the tokens
-            // whose weights this lane group holds) make the operand of one 16-dim block of output rows.
-            uint4 A[8];
-            {
-                const char *v_lo = vs + (4 * j + (col >> 2)) * kPrefillVRowBytes + (col & 3) * 8;
-                const char *v_hi = v_lo + 16 * kPrefillVRowBytes;
-#pragma unroll
-                for (int eb = 0; eb < 8; ++eb) {
-                    const uint2 a0 = lds_read_tr16_b64(v_lo + eb * 32);
-                    const uint2 a1 = lds_read_tr16_b64(v_hi + eb * 32);
-                    A[eb] = make_uint4(a0.x, a0.y, a1.x, a1.y);
-                }
-            }
-#pragma unroll
-            for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-                float sv[8];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) { sv[i] = s0[cb][i]; sv[4 + i] = s1[cb][i]; }
-                if (need_mask) {                                 // tokens after the column's position
-#pragma unroll
-                    for (int r = 0; r < 8; ++r)
-                        if (tb + slot_token(j, r) > pos[cb]) sv[r] = -INFINITY;
-                }
-                float lmax = sv[0];
-#pragma unroll
-                for (int r = 1; r < 8; ++r) lmax = fmaxf(lmax, sv[r]);
-                // The reference m of a column (log2 domain) is moved, and its sums rescaled, only when a score exceeds
-                // it by more than the slack: any common reference gives the same softmax, and 2^slack times the
-                // weights is far from overflow.  After a column's first tiles this is rare, so the exchange between
-                // the four lane groups of a column and the rescale of 32 accumulators leave the common path.
-                if (__any(lmax > raw_limit[cb])) {
-                    float tmax = lmax;
-                    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-                    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-                    // a column whose tokens are all masked so far keeps a finite stand-in: exp2 then sees -inf - finite
-                    const float mn = fmaxf(fmaxf(m[cb], tmax * p.scale_log2), -1e30f);
-                    const float alpha = fast_exp2(m[cb] - mn);
-                    l[cb] *= alpha;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[cb][e] *= alpha;
-                    m[cb] = mn;
-                    raw_limit[cb] = (mn + kPrefillSlack) * inv_scale_log2;
-                }
-                float pw[8], psum = 0.f;
-#pragma unroll
-                for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(fmaf(sv[r], p.scale_log2, -m[cb])); psum += pw[r]; }
-                l[cb] += psum;
-                uint32_t hi[4], lo[4];
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    hi[w] = pack_bf16x2(pw[2 * w], pw[2 * w + 1]);
-                    const float r0 = pw[2 * w] - bf16_bits_to_float(hi[w] & 0xffffu);
-                    const float r1 = pw[2 * w + 1] - __uint_as_float(hi[w] & 0xffff0000u);
-                    lo[w] = pack_bf16x2(r0, r1);
-                }
-                const uint4 Ph = make_uint4(hi[0], hi[1], hi[2], hi[3]), Pl = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-                // O^T += V^T P^T for this block; the next block's softmax follows while these MFMAs run
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[cb][e] = mfma_bf16(A[e], Ph, acc[cb][e]);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[cb][e] = mfma_bf16(A[e], Pl, acc[cb][e]);
+                s0[cb] = mfma_bf16(K[kk], Q[cb][kk], s0[cb]);
+                s1[cb] = mfma_bf16(K[4 + kk], Q[cb][kk], s1[cb]);
             }
         }
-        if (more) stage_tile(buf ^ 1);
+    };
+    auto softmax = [&](int tb, const f32x4_t (&s0)[kPrefillBlocks], const f32x4_t (&s1)[kPrefillBlocks],
+                       uint4 (&Ph)[kPrefillBlocks], uint4 (&Pl)[kPrefillBlocks]) __attribute__((always_inline)) {
+        const bool need_mask = tb + kTile - 1 > wave_min_pos;
+#pragma unroll
+        for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+            float sv[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { sv[i] = s0[cb][i]; sv[4 + i] = s1[cb][i]; }
+            if (need_mask) {                                     // tokens after the column's position
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    if (tb + slot_token(j, r) > pos[cb]) sv[r] = -INFINITY;
+            }
+            float lmax = sv[0];
+#pragma unroll
+            for (int r = 1; r < 8; ++r) lmax = fmaxf(lmax, sv[r]);
+            // The reference m of a column (log2 domain) is moved, and its sums rescaled, only when a score exceeds it
+            // by more than the slack: any common reference gives the same softmax, and 2^slack times the weights is
+            // far from overflow.  After a column's first tiles this is rare, so the exchange between the four lane
+            // groups of a column and the rescale of 32 accumulators leave the common path.
+            if (__any(lmax > raw_limit[cb])) {
+                float tmax = lmax;
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+                // a column whose tokens are all masked so far keeps a finite stand-in: exp2 then sees -inf - finite
+                const float mn = fmaxf(fmaxf(m[cb], tmax * p.scale_log2), -1e30f);
+                const float alpha = fast_exp2(m[cb] - mn);
+                l[cb] *= alpha;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[cb][e] *= alpha;
+                m[cb] = mn;
+                raw_limit[cb] = (mn + kPrefillSlack) * inv_scale_log2;
+            }
+            float pw[8], psum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(fmaf(sv[r], p.scale_log2, -m[cb])); psum += pw[r]; }
+            l[cb] += psum;
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                hi[w] = pack_bf16x2(pw[2 * w], pw[2 * w + 1]);
+                const float r0 = pw[2 * w] - bf16_bits_to_float(hi[w] & 0xffffu);
+                const float r1 = pw[2 * w + 1] - __uint_as_float(hi[w] & 0xffff0000u);
+                lo[w] = pack_bf16x2(r0, r1);
+            }
+            Ph[cb] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            Pl[cb] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        }
+    };
+    // O^T += V^T P^T.  The V^T operands, shared by the column blocks, come transposed out of shared memory: in a
+    // transposing 8-byte read the 16 lanes of a group each name four consecutive 16-bit values (lane 4k + q: dims
+    // 4q .. 4q+3 of token k of the group's four tokens) and lane i receives value i of each token, i.e. one output dim
+    // for four tokens.  Two reads (tokens 4j .. 4j+3 and 16+4j .. 16+4j+3, exactly the tokens whose weights this lane
+    // group holds) make the operand of one 16-dim block of output rows.
+    auto pv = [&](const char *vs, const uint4 (&Ph)[kPrefillBlocks], const uint4 (&Pl)[kPrefillBlocks]) __attribute__((always_inline)) {
+        const char *v_lo = vs + (4 * j + (col >> 2)) * kPrefillVRowBytes + (col & 3) * 8;
+        const char *v_hi = v_lo + 16 * kPrefillVRowBytes;
+#pragma unroll
+        for (int eb = 0; eb < 8; ++eb) {
+            const uint2 a0 = lds_read_tr16_b64(v_lo + eb * 32);
+            const uint2 a1 = lds_read_tr16_b64(v_hi + eb * 32);
+            const uint4 A = make_uint4(a0.x, a0.y, a1.x, a1.y);
+#pragma unroll
+            for (int cb = 0; cb < kPrefillBlocks; ++cb) acc[cb][eb] = mfma_bf16(A, Ph[cb], acc[cb][eb]);
+#pragma unroll
+            for (int cb = 0; cb < kPrefillBlocks; ++cb) acc[cb][eb] = mfma_bf16(A, Pl[cb], acc[cb][eb]);
+        }
+    };
+
+    const int n_steps = (n_tiles + 1) >> 1;
+    fetch_step(0);
+    stage_step(0);
+    lds_barrier();
+    for (int step = 0; step < n_steps; ++step) {
+        const int buf = step & 1;
+        const bool more = step + 1 < n_steps;
+        if (more) fetch_step(step + 1);                          // in flight while this step is computed
+        const int tb0 = 2 * step * kTile, tb1 = tb0 + kTile;
+        const bool live1 = tb1 <= wave_max_pos;                  // the tiles hold tokens some column of this wave sees
+        if (tb0 <= wave_max_pos) {
+            uint4 K[8];
+            f32x4_t s0a[kPrefillBlocks], s1a[kPrefillBlocks], s0b[kPrefillBlocks], s1b[kPrefillBlocks];
+            uint4 Ph[kPrefillBlocks], Pl[kPrefillBlocks];
+            read_k(smem[buf][0][0], K);
+            scores(K, s0a, s1a);
+            if (live1) read_k(smem[buf][1][0], K);               // arrives during the first softmax
+            softmax(tb0, s0a, s1a, Ph, Pl);
+            if (live1) scores(K, s0b, s1b);                      // queued ahead of the first product
+            pv(smem[buf][0][1], Ph, Pl);
+            if (live1) {
+                softmax(tb1, s0b, s1b, Ph, Pl);                  // while the matrix cores work on the queue
+                pv(smem[buf][1][1], Ph, Pl);
+            }
+        }
+        if (more) stage_step(buf ^ 1);
         lds_barrier();
     }
 
