@@ -103,3 +103,9 @@ def test_fp8_cache_descriptions():
     with pytest.raises(omni.OmniError) as e:
         omni.Handle(**good(kv_dtype=3))
     assert e.value.status == 3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
