@@ -6,7 +6,9 @@
 // (query token, query head of the group) pairs of that block; a wave owns 32 of them = two 16-column MFMA blocks.
 // The same transposed products as in the decode kernel are used, per 32-token tile and per column block:
 //   S^T = K Q^T     (A = K rows from shared memory, B = the block's queries, held in registers for the whole kernel)
-//   O^T += V^T P^T  (A = V transposed in registers, B = the softmax weights as bf16 hi + lo)
+//   O^T += V^T P^T  (A = V transposed, B = the softmax weights; both as fp16: V * 2^-4 is converted once per
+//                    workgroup on its way into shared memory, exactly for 2^-10 <= |V| < 2^20, and fp16 weights carry
+//                    11 significant bits, so one product does what bf16 weights need a hi + lo pair for)
 // so every lane owns one column: running max, sum and rescale never cross lanes except two max exchanges per tile.
 // What differs from decode is reuse: K/V tiles are fetched once per workgroup into shared memory (double buffered,
 // one barrier per 64 tokens) and feed 16 column blocks, and the 8x8 in-lane transpose of V is done once per wave and
@@ -31,6 +33,36 @@ __device__ __forceinline__ uint2 lds_read_tr16_b64(const char *p) {
     const short4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
         (short4_t __attribute__((address_space(3))) *)(const __attribute__((address_space(3))) char *)p);
     return __builtin_bit_cast(uint2, v);
+}
+
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ f32x4_t mfma_f16(const uint4 &a, const uint4 &b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// Two floats -> packed fp16, round to nearest even.
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
+}
+
+constexpr float kPrefillVScale = 0x1p-4f;             // V is held in shared memory as fp16 of V * 2^-4 (see the kernel)
+constexpr float kPrefillBias = 6.f;                   // the softmax weights are held as 2^6 times exp2(score - reference)
+
+// Eight bf16 values -> eight fp16 values of V * 2^-4.  Exact wherever the scaled value is a normal fp16 number
+// (2^-10 <= |V| < 2^20); below that the spacing is 2^-24, i.e. an absolute error of at most 2^-21 on V; above it the
+// value becomes infinite and shows in the result.
+__device__ __forceinline__ uint4 bf16x8_to_scaled_f16x8(const uint4 &v) {
+    uint4 r;
+    r.x = pack_f16x2(bf16_bits_to_float(v.x & 0xffffu) * kPrefillVScale, __uint_as_float(v.x & 0xffff0000u) * kPrefillVScale);
+    r.y = pack_f16x2(bf16_bits_to_float(v.y & 0xffffu) * kPrefillVScale, __uint_as_float(v.y & 0xffff0000u) * kPrefillVScale);
+    r.z = pack_f16x2(bf16_bits_to_float(v.z & 0xffffu) * kPrefillVScale, __uint_as_float(v.z & 0xffff0000u) * kPrefillVScale);
+    r.w = pack_f16x2(bf16_bits_to_float(v.w & 0xffffu) * kPrefillVScale, __uint_as_float(v.w & 0xffff0000u) * kPrefillVScale);
+    return r;
 }
 
 struct PrefillParams {
@@ -126,7 +158,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             *reinterpret_cast<uint4 *>(&smem[buf][sub][0][lds_off]) = sk[sub];
-            *reinterpret_cast<uint4 *>(&smem[buf][sub][1][lds_off_v]) = sv_[sub];
+            *reinterpret_cast<uint4 *>(&smem[buf][sub][1][lds_off_v]) = bf16x8_to_scaled_f16x8(sv_[sub]);
         }
     };
 
@@ -168,7 +200,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         }
     };
     auto softmax = [&](int tb, const f32x4_t (&s0)[kPrefillBlocks], const f32x4_t (&s1)[kPrefillBlocks],
-                       uint4 (&Ph)[kPrefillBlocks], uint4 (&Pl)[kPrefillBlocks]) __attribute__((always_inline)) {
+                       uint4 (&P)[kPrefillBlocks]) __attribute__((always_inline)) {
         const bool need_mask = tb + kTile - 1 > wave_min_pos;
 #pragma unroll
         for (int cb = 0; cb < kPrefillBlocks; ++cb) {
@@ -184,36 +216,31 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
 #pragma unroll
             for (int r = 1; r < 8; ++r) lmax = fmaxf(lmax, sv[r]);
             // The reference m of a column (log2 domain) is moved, and its sums rescaled, only when a score exceeds it
-            // by more than the slack: any common reference gives the same softmax, and 2^slack times the weights is
-            // far from overflow.  After a column's first tiles this is rare, so the exchange between the four lane
+            // by more than bias + slack: any common reference gives the same softmax.  A move puts m at the running
+            // maximum less the bias, so the largest weight of a column lies in [2^bias, 2^(bias + slack)]: below the
+            // largest fp16 number, and a weight loses precision as an fp16 subnormal only when it is 2^-20 of the
+            // largest or less.  After a column's first tiles moves are rare, so the exchange between the four lane
             // groups of a column and the rescale of 32 accumulators leave the common path.
             if (__any(lmax > raw_limit[cb])) {
                 float tmax = lmax;
                 tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
                 tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
                 // a column whose tokens are all masked so far keeps a finite stand-in: exp2 then sees -inf - finite
-                const float mn = fmaxf(fmaxf(m[cb], tmax * p.scale_log2), -1e30f);
+                const float mn = fmaxf(fmaxf(m[cb], fmaf(tmax, p.scale_log2, -kPrefillBias)), -1e30f);
                 const float alpha = fast_exp2(m[cb] - mn);
                 l[cb] *= alpha;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[cb][e] *= alpha;
                 m[cb] = mn;
-                raw_limit[cb] = (mn + kPrefillSlack) * inv_scale_log2;
+                raw_limit[cb] = (mn + kPrefillBias + kPrefillSlack) * inv_scale_log2;
             }
             float pw[8], psum = 0.f;
 #pragma unroll
             for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(fmaf(sv[r], p.scale_log2, -m[cb])); psum += pw[r]; }
             l[cb] += psum;
-            uint32_t hi[4], lo[4];
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                hi[w] = pack_bf16x2(pw[2 * w], pw[2 * w + 1]);
-                const float r0 = pw[2 * w] - bf16_bits_to_float(hi[w] & 0xffffu);
-                const float r1 = pw[2 * w + 1] - __uint_as_float(hi[w] & 0xffff0000u);
-                lo[w] = pack_bf16x2(r0, r1);
-            }
-            Ph[cb] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-            Pl[cb] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+            // the weights go to the matrix core as fp16 (11 significant bits; the sum above keeps the fp32 values)
+            P[cb] = make_uint4(pack_f16x2(pw[0], pw[1]), pack_f16x2(pw[2], pw[3]), pack_f16x2(pw[4], pw[5]),
+                               pack_f16x2(pw[6], pw[7]));
         }
     };
     // O^T += V^T P^T.  The V^T operands, shared by the column blocks, come transposed out of shared memory: in a
@@ -221,7 +248,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     // 4q .. 4q+3 of token k of the group's four tokens) and lane i receives value i of each token, i.e. one output dim
     // for four tokens.  Two reads (tokens 4j .. 4j+3 and 16+4j .. 16+4j+3, exactly the tokens whose weights this lane
     // group holds) make the operand of one 16-dim block of output rows.
-    auto pv = [&](const char *vs, const uint4 (&Ph)[kPrefillBlocks], const uint4 (&Pl)[kPrefillBlocks]) __attribute__((always_inline)) {
+    auto pv = [&](const char *vs, const uint4 (&P)[kPrefillBlocks]) __attribute__((always_inline)) {
         const char *v_lo = vs + (4 * j + (col >> 2)) * kPrefillVRowBytes + (col & 3) * 8;
         const char *v_hi = v_lo + 16 * kPrefillVRowBytes;
 #pragma unroll
@@ -230,9 +257,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
             const uint2 a1 = lds_read_tr16_b64(v_hi + eb * 32);
             const uint4 A = make_uint4(a0.x, a0.y, a1.x, a1.y);
 #pragma unroll
-            for (int cb = 0; cb < kPrefillBlocks; ++cb) acc[cb][eb] = mfma_bf16(A, Ph[cb], acc[cb][eb]);
-#pragma unroll
-            for (int cb = 0; cb < kPrefillBlocks; ++cb) acc[cb][eb] = mfma_bf16(A, Pl[cb], acc[cb][eb]);
+            for (int cb = 0; cb < kPrefillBlocks; ++cb) acc[cb][eb] = mfma_f16(A, P[cb], acc[cb][eb]);
         }
     };
 
@@ -249,16 +274,16 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         if (tb0 <= wave_max_pos) {
             uint4 K[8];
             f32x4_t s0a[kPrefillBlocks], s1a[kPrefillBlocks], s0b[kPrefillBlocks], s1b[kPrefillBlocks];
-            uint4 Ph[kPrefillBlocks], Pl[kPrefillBlocks];
+            uint4 P[kPrefillBlocks];
             read_k(smem[buf][0][0], K);
             scores(K, s0a, s1a);
             if (live1) read_k(smem[buf][1][0], K);               // arrives during the first softmax
-            softmax(tb0, s0a, s1a, Ph, Pl);
+            softmax(tb0, s0a, s1a, P);
             if (live1) scores(K, s0b, s1b);                      // queued ahead of the first product
-            pv(smem[buf][0][1], Ph, Pl);
+            pv(smem[buf][0][1], P);
             if (live1) {
-                softmax(tb1, s0b, s1b, Ph, Pl);                  // while the matrix cores work on the queue
-                pv(smem[buf][1][1], Ph, Pl);
+                softmax(tb1, s0b, s1b, P);                       // while the matrix cores work on the queue
+                pv(smem[buf][1][1], P);
             }
         }
         if (more) stage_step(buf ^ 1);
@@ -275,7 +300,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         const int c = cb * 16 + col;
         const int tl = c / G, g = c - tl * G;
         const size_t row = ((size_t)(q_row0 + q0 + wave * TW + tl) * p.Hq + head0 + g) * D;
-        const float inv = 1.f / lsum;                            // every live column saw its own position: lsum > 0
+        const float inv = (1.f / kPrefillVScale) / lsum;         // every live column saw its own position: lsum > 0
 #pragma unroll
         for (int eb = 0; eb < 8; ++eb) {                         // acc[cb][eb][i] = O^T[dim 16 eb + 4 j + i][column]
             const float o0 = acc[cb][eb][0] * inv, o1 = acc[cb][eb][1] * inv, o2 = acc[cb][eb][2] * inv, o3 = acc[cb][eb][3] * inv;
