@@ -15,6 +15,8 @@
 // tile for its two blocks.  That makes the path a dense contraction, not a stream; with the softmax arithmetic on
 // the vector ALUs (no packed fp32 here) about as long as the matrix-core work, both units bound it.
 #pragma once
+#include <type_traits>
+
 #include "decode_mfma.hpp"
 
 namespace omni {
@@ -25,7 +27,8 @@ constexpr int kPrefillBlocks = 2;                     // 16-column MFMA blocks p
 constexpr int kPrefillCols = 16 * kPrefillBlocks;     // (token, head) pairs per wave
 constexpr int kPrefillRowBytes = 256 + 16;            // a 256-byte K row plus padding: conflict-free 16-byte LDS reads
 constexpr int kPrefillVRowBytes = 256 + 32;           // V rows: conflict-free 8-byte transposing reads (4 rows x 32 B)
-constexpr float kPrefillSlack = 8.f;                  // log2 units a score may exceed a column's reference maximum
+constexpr float kPrefillBias = 6.f;                   // a moved reference sits this many log2 units below the maximum
+constexpr float kPrefillSumLimit = 32768.f;           // sum of a lane's 8 weights of a tile beyond which the reference moves
 
 // Transposing 64-bit read from shared memory (see its use below for the lane arrangement).
 __device__ __forceinline__ uint2 lds_read_tr16_b64(const char *p) {
@@ -44,6 +47,12 @@ __device__ __forceinline__ f32x4_t mfma_f16(const uint4 &a, const uint4 &b, f32x
 
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
+// c + the two fp16 values packed in w, in fp32.
+__device__ __forceinline__ float sum_f16x2(uint32_t w, float c) {
+    const f16x2_t ones = {(_Float16)1.f, (_Float16)1.f};
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, w), ones, c, false);
+}
+
 // Two floats -> packed fp16, round to nearest even.
 __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
     const f32x2_t v = {lo, hi};
@@ -51,7 +60,6 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
 }
 
 constexpr float kPrefillVScale = 0x1p-4f;             // V is held in shared memory as fp16 of V * 2^-4 (see the kernel)
-constexpr float kPrefillBias = 6.f;                   // the softmax weights are held as 2^6 times exp2(score - reference)
 
 // Eight bf16 values -> eight fp16 values of V * 2^-4.  Exact wherever the scaled value is a normal fp16 number
 // (2^-10 <= |V| < 2^20); below that the spacing is 2^-24, i.e. an absolute error of at most 2^-21 on V; above it the
@@ -74,6 +82,9 @@ struct PrefillParams {
     float scale_log2;
     int Hq, Hkv, G, MB;
     int out_bf16;
+#ifdef PF_TRACE
+    void *trace;
+#endif
 };
 
 // Query tokens per wave and per workgroup for a group of G heads.
@@ -132,7 +143,8 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     for (int off = 32; off > 0; off >>= 1) wave_min_pos = min(wave_min_pos, __shfl_xor(wave_min_pos, off));
 
     // ---- staging: a step is 64 tokens = two 32-token tiles; thread t moves piece t of the 512 16-byte pieces of
-    // each tile's K rows and V rows (piece = 16 * token + chunk)
+    // each tile's K rows and V rows (piece = 16 * token + chunk).  The products below run as a pipeline in which V of a
+    // tile is needed two tiles after its K, so V is fetched and staged one step behind K.
     const size_t page_stride = (size_t)p.Hkv * PS * D * 2;
     const char *kbase = reinterpret_cast<const char *>(p.k_cache) + (size_t)kvh * PS * D * 2;
     const char *vbase = reinterpret_cast<const char *>(p.v_cache) + (size_t)kvh * PS * D * 2;
@@ -140,26 +152,37 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     const int st_tok = threadIdx.x >> 4, st_chunk = threadIdx.x & 15;       // token 0..31 of a tile
     const int lds_off = st_tok * kPrefillRowBytes + st_chunk * 16;
     const int lds_off_v = st_tok * kPrefillVRowBytes + st_chunk * 16;
+    const int n_steps = (n_tiles + 1) >> 1;
     uint4 sk[2], sv_[2];
-    auto fetch_step = [&](int step) __attribute__((always_inline)) {
+    // Page numbers are looked up one step before the rows they address are fetched, so that no fetch waits for its
+    // own table entry: pg_k holds the pages of the step whose K rows are fetched next, pg_v (the same entries one
+    // step later) those of the step whose V rows are fetched next.
+    int pg_k[2], pg_v[2] = {0, 0};
+    auto lookup = [&](int step) __attribute__((always_inline)) {
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int t = (2 * step + sub) * kTile + st_tok;
-            sk[sub] = sv_[sub] = make_uint4(0, 0, 0, 0);                    // rows beyond the context are zero
-            if (t < L) {
-                const int pg = bt[t >> kLog2Ps];
-                const size_t o = (size_t)pg * page_stride + (size_t)(t & (PS - 1)) * 256 + st_chunk * 16;
-                sk[sub] = *reinterpret_cast<const uint4 *>(kbase + o);
-                sv_[sub] = *reinterpret_cast<const uint4 *>(vbase + o);
-            }
+            pg_k[sub] = (step < n_steps && t < L) ? bt[t >> kLog2Ps] : -1;
         }
     };
-    auto stage_step = [&](int buf) __attribute__((always_inline)) {
+    auto fetch_rows = [&](const char *base, int step, const int (&pg)[2], uint4 (&r)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
-            *reinterpret_cast<uint4 *>(&smem[buf][sub][0][lds_off]) = sk[sub];
-            *reinterpret_cast<uint4 *>(&smem[buf][sub][1][lds_off_v]) = bf16x8_to_scaled_f16x8(sv_[sub]);
+            const int t = (2 * step + sub) * kTile + st_tok;
+            r[sub] = make_uint4(0, 0, 0, 0);                                // rows beyond the context are zero
+            if (pg[sub] >= 0)
+                r[sub] = *reinterpret_cast<const uint4 *>(base + (size_t)pg[sub] * page_stride + (size_t)(t & (PS - 1)) * 256 +
+                                                          st_chunk * 16);
         }
+    };
+    auto stage_k = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) *reinterpret_cast<uint4 *>(&smem[buf][sub][0][lds_off]) = sk[sub];
+    };
+    auto stage_v = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+            *reinterpret_cast<uint4 *>(&smem[buf][sub][1][lds_off_v]) = bf16x8_to_scaled_f16x8(sv_[sub]);
     };
 
     // ---- per-column online-softmax state
@@ -171,77 +194,85 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[cb][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
+    // A tile holds tokens that some column of this wave sees.
+    auto tile_active = [&](int t) { return t >= 0 && t * kTile <= wave_max_pos; };
 
-    float raw_limit[kPrefillBlocks];                                 // raw score above which a column's m must move
-#pragma unroll
-    for (int cb = 0; cb < kPrefillBlocks; ++cb) raw_limit[cb] = -INFINITY;
-    const float inv_scale_log2 = 1.f / p.scale_log2;
-    // ---- one 32-token tile, in three pieces, so that the loop below can run the two tiles of a step interleaved:
-    // the score MFMAs of the second tile and the P.V MFMAs of the first are in the matrix-core queue while the vector
-    // ALUs do the softmax of the first and of the second tile.
-    auto read_k = [&](const char *ks, uint4 (&K)[8]) __attribute__((always_inline)) {
+    // ---- the three pieces of a tile's work
+    // Raw scores q.k of the column blocks: S[cb][h] holds tokens 16 h + 4 j .. + 3 of the tile for column `col`.  The
+    // softmax scale is applied inside the exponent (one fused multiply-add per score): scale > 0, so the order of
+    // scores is that of the raw dot products.
+    auto scores = [&](const char *ks, f32x4_t (&S)[kPrefillBlocks][2]) __attribute__((always_inline)) {
+        uint4 K[8];
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             K[kk] = *reinterpret_cast<const uint4 *>(ks + col * kPrefillRowBytes + (4 * kk + j) * 16);
             K[4 + kk] = *reinterpret_cast<const uint4 *>(ks + (16 + col) * kPrefillRowBytes + (4 * kk + j) * 16);
         }
-    };
-    // Raw scores q.k of the column blocks.  The softmax scale is applied inside the exponent (one fused multiply-add
-    // per score): scale > 0, so the order of scores is that of the raw dot products.
-    auto scores = [&](const uint4 (&K)[8], f32x4_t (&s0)[kPrefillBlocks], f32x4_t (&s1)[kPrefillBlocks]) __attribute__((always_inline)) {
 #pragma unroll
         for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-            s0[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f}; s1[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            S[cb][0] = f32x4_t{0.f, 0.f, 0.f, 0.f}; S[cb][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        }
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                s0[cb] = mfma_bf16(K[kk], Q[cb][kk], s0[cb]);
-                s1[cb] = mfma_bf16(K[4 + kk], Q[cb][kk], s1[cb]);
+        for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+            for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+                S[cb][0] = mfma_bf16(K[kk], Q[cb][kk], S[cb][0]);
+                S[cb][1] = mfma_bf16(K[4 + kk], Q[cb][kk], S[cb][1]);
             }
         }
     };
-    auto softmax = [&](int tb, const f32x4_t (&s0)[kPrefillBlocks], const f32x4_t (&s1)[kPrefillBlocks],
-                       uint4 (&P)[kPrefillBlocks]) __attribute__((always_inline)) {
-        const bool need_mask = tb + kTile - 1 > wave_min_pos;
+    // Weights of tile t from its raw scores: P[cb] as one fp16 MFMA operand.  A column's reference m (log2 domain) is
+    // moved only when a weight would leave the fp16 range, which shows in the sum of the tile's weights: any common
+    // reference gives the same softmax.  A move puts m at the running maximum less the bias, so the largest weight of a
+    // column then lies between 2^bias and the limit, and a weight loses precision as an fp16 subnormal only when it is
+    // 2^-20 of the largest or less.  After a column's first tiles moves are rare, so the maximum over the tile, its
+    // exchange between the four lane groups of a column and the rescale of what was summed under the old reference
+    // leave the common path.  The sums are taken over the rounded weights, the ones the matrix cores multiply.
+    auto weights = [&](auto fast, int t, f32x4_t (&S)[kPrefillBlocks][2], uint4 (&P)[kPrefillBlocks]) __attribute__((always_inline)) {
+        const int tb = t * kTile;
+        if constexpr (!decltype(fast)::value) {
+            if (tb + kTile - 1 > wave_min_pos) {                 // tokens after the column's position
+#pragma unroll
+                for (int cb = 0; cb < kPrefillBlocks; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 8; ++r)
+                        if (tb + slot_token(j, r) > pos[cb]) S[cb][r >> 2][r & 3] = -INFINITY;
+            }
+        }
+        float psum[kPrefillBlocks];
+        auto form = [&](int cb) __attribute__((always_inline)) {
+            float pw[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) pw[r] = fast_exp2(fmaf(S[cb][r >> 2][r & 3], p.scale_log2, -m[cb]));
+            P[cb] = make_uint4(pack_f16x2(pw[0], pw[1]), pack_f16x2(pw[2], pw[3]), pack_f16x2(pw[4], pw[5]),
+                               pack_f16x2(pw[6], pw[7]));
+            psum[cb] = sum_f16x2(P[cb].w, sum_f16x2(P[cb].z, sum_f16x2(P[cb].y, sum_f16x2(P[cb].x, 0.f))));
+        };
+        bool over = false;
 #pragma unroll
         for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-            float sv[8];
+            form(cb);
+            over |= !(psum[cb] < kPrefillSumLimit);              // also true for an infinite or undefined sum
+        }
+        if (__any(over)) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { sv[i] = s0[cb][i]; sv[4 + i] = s1[cb][i]; }
-            if (need_mask) {                                     // tokens after the column's position
-#pragma unroll
-                for (int r = 0; r < 8; ++r)
-                    if (tb + slot_token(j, r) > pos[cb]) sv[r] = -INFINITY;
-            }
-            float lmax = sv[0];
-#pragma unroll
-            for (int r = 1; r < 8; ++r) lmax = fmaxf(lmax, sv[r]);
-            // The reference m of a column (log2 domain) is moved, and its sums rescaled, only when a score exceeds it
-            // by more than bias + slack: any common reference gives the same softmax.  A move puts m at the running
-            // maximum less the bias, so the largest weight of a column lies in [2^bias, 2^(bias + slack)]: below the
-            // largest fp16 number, and a weight loses precision as an fp16 subnormal only when it is 2^-20 of the
-            // largest or less.  After a column's first tiles moves are rare, so the exchange between the four lane
-            // groups of a column and the rescale of 32 accumulators leave the common path.
-            if (__any(lmax > raw_limit[cb])) {
-                float tmax = lmax;
+            for (int cb = 0; cb < kPrefillBlocks; ++cb) {
+                float tmax = fmaxf(fmaxf(fmaxf(S[cb][0][0], S[cb][0][1]), fmaxf(S[cb][0][2], S[cb][0][3])),
+                                   fmaxf(fmaxf(S[cb][1][0], S[cb][1][1]), fmaxf(S[cb][1][2], S[cb][1][3])));
                 tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
                 tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
                 // a column whose tokens are all masked so far keeps a finite stand-in: exp2 then sees -inf - finite
                 const float mn = fmaxf(fmaxf(m[cb], fmaf(tmax, p.scale_log2, -kPrefillBias)), -1e30f);
-                const float alpha = fast_exp2(m[cb] - mn);
+                const float alpha = fast_exp2(m[cb] - mn);       // 0 while m is still -inf
                 l[cb] *= alpha;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[cb][e] *= alpha;
                 m[cb] = mn;
-                raw_limit[cb] = (mn + kPrefillBias + kPrefillSlack) * inv_scale_log2;
+                form(cb);
             }
-            float pw[8], psum = 0.f;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) { pw[r] = fast_exp2(fmaf(sv[r], p.scale_log2, -m[cb])); psum += pw[r]; }
-            l[cb] += psum;
-            // the weights go to the matrix core as fp16 (11 significant bits; the sum above keeps the fp32 values)
-            P[cb] = make_uint4(pack_f16x2(pw[0], pw[1]), pack_f16x2(pw[2], pw[3]), pack_f16x2(pw[4], pw[5]),
-                               pack_f16x2(pw[6], pw[7]));
         }
+#pragma unroll
+        for (int cb = 0; cb < kPrefillBlocks; ++cb) l[cb] += psum[cb];
     };
     // O^T += V^T P^T.  The V^T operands, shared by the column blocks, come transposed out of shared memory: in a
     // transposing 8-byte read the 16 lanes of a group each name four consecutive 16-bit values (lane 4k + q: dims
@@ -260,35 +291,70 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
             for (int cb = 0; cb < kPrefillBlocks; ++cb) acc[cb][eb] = mfma_f16(A, P[cb], acc[cb][eb]);
         }
     };
+    // ---- the pipeline.  Phase t multiplies the weights of tile t-1 into the accumulators and forms the scores of
+    // tile t+1 on the matrix cores while the vector ALUs turn the scores of tile t into weights; the three are
+    // independent, so one wave keeps both units busy.  A step is the two phases of an (even, odd) pair of tiles and
+    // ends with one barrier: during step s the workgroup reads K of step s (tiles 2s, 2s+1) and V of step s-1 from
+    // shared memory and stages K of step s+1 and V of step s.  Steps in which every tile touched lies wholly before
+    // all of the wave's positions run without the per-tile conditions (`fast`).
+    f32x4_t Se[kPrefillBlocks][2], So[kPrefillBlocks][2];        // scores of the even / odd tile in flight
+    uint4 Pe[kPrefillBlocks], Po[kPrefillBlocks];                // weights of the even / odd tile in flight
+#pragma unroll
+    for (int cb = 0; cb < kPrefillBlocks; ++cb) Pe[cb] = Po[cb] = make_uint4(0, 0, 0, 0);
+    auto step_body = [&](auto fast, int s) __attribute__((always_inline)) {
+        constexpr bool kFast = decltype(fast)::value;
+        const int buf = s & 1;
+        // phase 2s-1: P.V of tile 2s-2, weights of tile 2s-1, scores of tile 2s
+        if (kFast || tile_active(2 * s - 2)) pv(smem[buf ^ 1][0][1], Pe);
+        if (kFast || tile_active(2 * s)) scores(smem[buf][0][0], Se);
+        if (kFast || tile_active(2 * s - 1)) weights(fast, 2 * s - 1, So, Po);
+        // phase 2s: P.V of tile 2s-1, weights of tile 2s, scores of tile 2s+1
+        if (kFast || tile_active(2 * s - 1)) pv(smem[buf ^ 1][1][1], Po);
+        if (kFast || tile_active(2 * s + 1)) scores(smem[buf][1][0], So);
+        if (kFast || tile_active(2 * s)) weights(fast, 2 * s, Se, Pe);
+    };
+    // last step whose tiles 2s-2 .. 2s+1 are all wholly visible to every live column of the wave
+    const int fast_last = wave_max_pos < 0 ? -1 : ((wave_min_pos - (kTile - 1)) / kTile - 1) / 2;
 
-    const int n_steps = (n_tiles + 1) >> 1;
-    fetch_step(0);
-    stage_step(0);
+    lookup(0);
+    fetch_rows(kbase, 0, pg_k, sk);
+    pg_v[0] = pg_k[0]; pg_v[1] = pg_k[1];
+    lookup(1);
+    stage_k(0);
     lds_barrier();
-    for (int step = 0; step < n_steps; ++step) {
-        const int buf = step & 1;
-        const bool more = step + 1 < n_steps;
-        if (more) fetch_step(step + 1);                          // in flight while this step is computed
-        const int tb0 = 2 * step * kTile, tb1 = tb0 + kTile;
-        const bool live1 = tb1 <= wave_max_pos;                  // the tiles hold tokens some column of this wave sees
-        if (tb0 <= wave_max_pos) {
-            uint4 K[8];
-            f32x4_t s0a[kPrefillBlocks], s1a[kPrefillBlocks], s0b[kPrefillBlocks], s1b[kPrefillBlocks];
-            uint4 P[kPrefillBlocks];
-            read_k(smem[buf][0][0], K);
-            scores(K, s0a, s1a);
-            if (live1) read_k(smem[buf][1][0], K);               // arrives during the first softmax
-            softmax(tb0, s0a, s1a, P);
-            if (live1) scores(K, s0b, s1b);                      // queued ahead of the first product
-            pv(smem[buf][0][1], P);
-            if (live1) {
-                softmax(tb1, s0b, s1b, P);                       // while the matrix cores work on the queue
-                pv(smem[buf][1][1], P);
-            }
+#ifdef PF_TRACE
+    long long tt[5] = {0, 0, 0, 0, 0}; long long t0 = wall_clock64(), t1; int nfast = 0;
+#define PF_T(i) { t1 = wall_clock64(); tt[i] += t1 - t0; t0 = t1; }
+#else
+#define PF_T(i)
+#endif
+    for (int s = 0; s <= n_steps; ++s) {
+        fetch_rows(vbase, s, pg_v, sv_);                         // in flight while this step is computed
+        fetch_rows(kbase, s + 1, pg_k, sk);
+        pg_v[0] = pg_k[0]; pg_v[1] = pg_k[1];
+        lookup(s + 2);
+        PF_T(0)
+        if (s >= 1 && s <= fast_last && s + 1 < n_steps) { step_body(std::true_type{}, s);
+#ifdef PF_TRACE
+            ++nfast;
+#endif
+            PF_T(1) }
+        else { step_body(std::false_type{}, s); PF_T(2) }
+        if (s < n_steps) {
+            stage_k((s + 1) & 1);
+            stage_v(s & 1);
+            PF_T(3)
+            lds_barrier();
+            PF_T(4)
         }
-        if (more) stage_step(buf ^ 1);
-        lds_barrier();
     }
+#ifdef PF_TRACE
+    if (blockIdx.x == gridDim.x - 1 && blockIdx.y == 0 && blockIdx.z == 0 && lane == 0) {
+        long long *o = reinterpret_cast<long long *>(p.trace) + wave * 8;
+        for (int i = 0; i < 5; ++i) o[i] = tt[i];
+        o[5] = n_steps + 1; o[6] = nfast;
+    }
+#endif
 
     // ---- normalise and store: a lane holds, for each of its columns, dims 16 eb + 4j .. + 3 of every 16-dim block eb
 #pragma unroll
