@@ -6,9 +6,9 @@
 // (query token, query head of the group) pairs of that block; a wave owns 32 of them = two 16-column MFMA blocks.
 // The same transposed products as in the decode kernel are used, per 32-token tile and per column block:
 //   S^T = K Q^T     (A = K rows from shared memory, B = the block's queries, held in registers for the whole kernel)
-//   O^T += V^T P^T  (A = V transposed, B = the softmax weights; both as fp16: V * 2^-4 is converted once per
-//                    workgroup on its way into shared memory, exactly for 2^-10 <= |V| < 2^20, and fp16 weights carry
-//                    11 significant bits, so one product does what bf16 weights need a hi + lo pair for)
+//   O^T += V^T P^T  (A = V transposed, B = the softmax weights; both as fp16: V is converted once per workgroup on
+//                    its way into shared memory, exactly for 2^-14 <= |V| <= 65504, and fp16 weights carry 11
+//                    significant bits, so one product does what bf16 weights need a hi + lo pair for)
 // so every lane owns one column: running max, sum and rescale never cross lanes except two max exchanges per tile.
 // What differs from decode is reuse: K/V tiles are fetched once per workgroup into shared memory (double buffered,
 // one barrier per 64 tokens) and feed 16 column blocks, and the 8x8 in-lane transpose of V is done once per wave and
@@ -59,17 +59,15 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
 }
 
-constexpr float kPrefillVScale = 0x1p-4f;             // V is held in shared memory as fp16 of V * 2^-4 (see the kernel)
-
-// Eight bf16 values -> eight fp16 values of V * 2^-4.  Exact wherever the scaled value is a normal fp16 number
-// (2^-10 <= |V| < 2^20); below that the spacing is 2^-24, i.e. an absolute error of at most 2^-21 on V; above it the
-// value becomes infinite and shows in the result.
-__device__ __forceinline__ uint4 bf16x8_to_scaled_f16x8(const uint4 &v) {
+// Eight bf16 values -> eight fp16 values.  Exact wherever the value is a normal fp16 number (2^-14 <= |V| <= 65504);
+// below that the spacing is 2^-24, i.e. an absolute error of at most 2^-25; above it the value becomes infinite and
+// shows in the result.
+__device__ __forceinline__ uint4 bf16x8_to_f16x8(const uint4 &v) {
     uint4 r;
-    r.x = pack_f16x2(bf16_bits_to_float(v.x & 0xffffu) * kPrefillVScale, __uint_as_float(v.x & 0xffff0000u) * kPrefillVScale);
-    r.y = pack_f16x2(bf16_bits_to_float(v.y & 0xffffu) * kPrefillVScale, __uint_as_float(v.y & 0xffff0000u) * kPrefillVScale);
-    r.z = pack_f16x2(bf16_bits_to_float(v.z & 0xffffu) * kPrefillVScale, __uint_as_float(v.z & 0xffff0000u) * kPrefillVScale);
-    r.w = pack_f16x2(bf16_bits_to_float(v.w & 0xffffu) * kPrefillVScale, __uint_as_float(v.w & 0xffff0000u) * kPrefillVScale);
+    r.x = pack_f16x2(bf16_bits_to_float(v.x & 0xffffu), __uint_as_float(v.x & 0xffff0000u));
+    r.y = pack_f16x2(bf16_bits_to_float(v.y & 0xffffu), __uint_as_float(v.y & 0xffff0000u));
+    r.z = pack_f16x2(bf16_bits_to_float(v.z & 0xffffu), __uint_as_float(v.z & 0xffff0000u));
+    r.w = pack_f16x2(bf16_bits_to_float(v.w & 0xffffu), __uint_as_float(v.w & 0xffff0000u));
     return r;
 }
 
@@ -87,9 +85,9 @@ struct PrefillParams {
 #endif
 };
 
-// Query tokens per wave and per workgroup for a group of G heads.
-__host__ __device__ inline int prefill_tokens_per_wave(int G) { return kPrefillCols / G; }
-__host__ __device__ inline int prefill_tokens_per_block(int G) { return kPrefillWaves * prefill_tokens_per_wave(G); }
+// Query tokens per workgroup for a group of G heads: its 256 columns are the (token, head) pairs in token-major order,
+// cut into runs of 32 for the waves wherever that falls.
+__host__ __device__ inline int prefill_tokens_per_block(int G) { return kPrefillWaves * kPrefillCols / G; }
 
 template <int PS>
 __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(PrefillParams p) {
@@ -102,7 +100,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     const int G = p.G, head0 = kvh * G;
     const int L = p.context_lens[b];
     const int n_q = min(p.q_lens[b], L);
-    const int TW = prefill_tokens_per_wave(G), QB = kPrefillWaves * TW;
+    const int QB = prefill_tokens_per_block(G);
     const int q0 = blockIdx.x * QB;                              // first query token of this workgroup
     if (n_q <= 0 || q0 >= n_q) return;
     const int lane = threadIdx.x & 63;
@@ -119,10 +117,10 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     int wave_max_pos = -1;
 #pragma unroll
     for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-        const int c = cb * 16 + col;
+        const int c = wave * kPrefillCols + cb * 16 + col;       // column of the workgroup
         const int tl = c / G, g = c - tl * G;
-        const int qi = q0 + wave * TW + tl;                      // query token inside the chunk
-        const bool live = tl < TW && qi < n_q;
+        const int qi = q0 + tl;                                  // query token inside the chunk
+        const bool live = tl < QB && qi < n_q;
         pos[cb] = live ? pos0 + qi : -1;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) Q[cb][kk] = make_uint4(0, 0, 0, 0);
@@ -160,19 +158,21 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     int pg_k[2], pg_v[2] = {0, 0};
     auto lookup = [&](int step) __attribute__((always_inline)) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const int t = (2 * step + sub) * kTile + st_tok;
-            pg_k[sub] = (step < n_steps && t < L) ? bt[t >> kLog2Ps] : -1;
-        }
+        for (int sub = 0; sub < 2; ++sub)                                   // an entry of the table for every lane
+            pg_k[sub] = bt[min((2 * step + sub) * kTile + st_tok, L - 1) >> kLog2Ps];
     };
-    auto fetch_rows = [&](const char *base, int step, const int (&pg)[2], uint4 (&r)[2]) __attribute__((always_inline)) {
+    auto fetch_rows = [&](auto fast, const char *base, int step, const int (&pg)[2], uint4 (&r)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int t = (2 * step + sub) * kTile + st_tok;
-            r[sub] = make_uint4(0, 0, 0, 0);                                // rows beyond the context are zero
-            if (pg[sub] >= 0)
-                r[sub] = *reinterpret_cast<const uint4 *>(base + (size_t)pg[sub] * page_stride + (size_t)(t & (PS - 1)) * 256 +
-                                                          st_chunk * 16);
+            const uint4 *src = reinterpret_cast<const uint4 *>(base + (size_t)pg[sub] * page_stride +
+                                                               (size_t)(t & (PS - 1)) * 256 + st_chunk * 16);
+            if constexpr (decltype(fast)::value) {
+                r[sub] = *src;
+            } else {
+                r[sub] = make_uint4(0, 0, 0, 0);                            // rows beyond the context are zero
+                if (step < n_steps && t < L) r[sub] = *src;
+            }
         }
     };
     auto stage_k = [&](int buf) __attribute__((always_inline)) {
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     auto stage_v = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
-            *reinterpret_cast<uint4 *>(&smem[buf][sub][1][lds_off_v]) = bf16x8_to_scaled_f16x8(sv_[sub]);
+            *reinterpret_cast<uint4 *>(&smem[buf][sub][1][lds_off_v]) = bf16x8_to_f16x8(sv_[sub]);
     };
 
     // ---- per-column online-softmax state
@@ -304,6 +304,10 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     auto step_body = [&](auto fast, int s) __attribute__((always_inline)) {
         constexpr bool kFast = decltype(fast)::value;
         const int buf = s & 1;
+        fetch_rows(fast, vbase, s, pg_v, sv_);                   // in flight while this step is computed
+        fetch_rows(fast, kbase, s + 1, pg_k, sk);
+        pg_v[0] = pg_k[0]; pg_v[1] = pg_k[1];
+        lookup(s + 2);
         // phase 2s-1: P.V of tile 2s-2, weights of tile 2s-1, scores of tile 2s
         if (kFast || tile_active(2 * s - 2)) pv(smem[buf ^ 1][0][1], Pe);
         if (kFast || tile_active(2 * s)) scores(smem[buf][0][0], Se);
@@ -312,12 +316,18 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         if (kFast || tile_active(2 * s - 1)) pv(smem[buf ^ 1][1][1], Po);
         if (kFast || tile_active(2 * s + 1)) scores(smem[buf][1][0], So);
         if (kFast || tile_active(2 * s)) weights(fast, 2 * s, Se, Pe);
+        if (kFast || s < n_steps) {
+            stage_k(buf ^ 1);
+            stage_v(buf);
+            lds_barrier();
+        }
     };
-    // last step whose tiles 2s-2 .. 2s+1 are all wholly visible to every live column of the wave
-    const int fast_last = wave_max_pos < 0 ? -1 : ((wave_min_pos - (kTile - 1)) / kTile - 1) / 2;
+    // last step whose tiles 2s-2 .. 2s+1 are all wholly visible to every live column of the wave and whose fetches
+    // (V of step s, K of step s+1) lie wholly inside the context
+    const int fast_last = wave_max_pos < 0 ? -1 : min(((wave_min_pos - (kTile - 1)) / kTile - 1) / 2, L / (2 * kTile) - 2);
 
     lookup(0);
-    fetch_rows(kbase, 0, pg_k, sk);
+    fetch_rows(std::false_type{}, kbase, 0, pg_k, sk);
     pg_v[0] = pg_k[0]; pg_v[1] = pg_k[1];
     lookup(1);
     stage_k(0);
@@ -329,24 +339,12 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
 #define PF_T(i)
 #endif
     for (int s = 0; s <= n_steps; ++s) {
-        fetch_rows(vbase, s, pg_v, sv_);                         // in flight while this step is computed
-        fetch_rows(kbase, s + 1, pg_k, sk);
-        pg_v[0] = pg_k[0]; pg_v[1] = pg_k[1];
-        lookup(s + 2);
-        PF_T(0)
-        if (s >= 1 && s <= fast_last && s + 1 < n_steps) { step_body(std::true_type{}, s);
+        if (s >= 1 && s <= fast_last) { step_body(std::true_type{}, s);
 #ifdef PF_TRACE
             ++nfast;
 #endif
             PF_T(1) }
         else { step_body(std::false_type{}, s); PF_T(2) }
-        if (s < n_steps) {
-            stage_k((s + 1) & 1);
-            stage_v(s & 1);
-            PF_T(3)
-            lds_barrier();
-            PF_T(4)
-        }
     }
 #ifdef PF_TRACE
     if (blockIdx.x == gridDim.x - 1 && blockIdx.y == 0 && blockIdx.z == 0 && lane == 0) {
@@ -363,10 +361,10 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         lsum += __shfl_xor(lsum, 16);                            // the four lane groups hold disjoint tokens
         lsum += __shfl_xor(lsum, 32);
         if (pos[cb] < 0) continue;
-        const int c = cb * 16 + col;
+        const int c = wave * kPrefillCols + cb * 16 + col;
         const int tl = c / G, g = c - tl * G;
-        const size_t row = ((size_t)(q_row0 + q0 + wave * TW + tl) * p.Hq + head0 + g) * D;
-        const float inv = (1.f / kPrefillVScale) / lsum;         // every live column saw its own position: lsum > 0
+        const size_t row = ((size_t)(q_row0 + q0 + tl) * p.Hq + head0 + g) * D;
+        const float inv = 1.f / lsum;                            // every live column saw its own position: lsum > 0
 #pragma unroll
         for (int eb = 0; eb < 8; ++eb) {                         // acc[cb][eb][i] = O^T[dim 16 eb + 4 j + i][column]
             const float o0 = acc[cb][eb][0] * inv, o1 = acc[cb][eb][1] * inv, o2 = acc[cb][eb][2] * inv, o3 = acc[cb][eb][3] * inv;
