@@ -198,7 +198,9 @@ omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v
  * [batch] int64 are DEVICE arrays; max_q_len is a HOST upper bound on q_lens (it sizes the grid; longer chunks are
  * cut off).  Rows of out that no request owns are not written; requests with q_lens[b] <= 0 are skipped.
  * bf16 q/K/V with head_dim 128 only (matrix-core kernel; fp32 accumulation): else OMNI_ERR_UNSUPPORTED.
- * scale must be positive.  One launch, no workspace.
+ * V enters the weighted sum as fp16: exact for 2^-14 <= |V| <= 65504; a smaller value carries an absolute error of at
+ * most 2^-25; a larger one (or a non-finite one) makes non-finite outputs for the queries of its request whose tiles
+ * reach it, never wrong finite ones.  scale must be positive.  One launch, no workspace.
  * Errors: NULL, SHAPE (max_q_len <= 0, scale <= 0, alignment), UNSUPPORTED, HIP.
  */
 omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,

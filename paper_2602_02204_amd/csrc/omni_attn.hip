@@ -484,11 +484,6 @@ omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void
     p.scale_log2 = scale * kLog2e;
     p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
     p.out_bf16 = d.out_dtype == OMNI_BF16;
-#ifdef PF_TRACE
-    { static void *tr = nullptr; if (!tr) hipMalloc(&tr, 4096); p.trace = tr;
-      if (getenv("PF_TRACE_DUMP")) { long long hb[64]; hipDeviceSynchronize(); hipMemcpy(hb, tr, 512, hipMemcpyDeviceToHost);
-        for (int w = 0; w < 8; ++w) { printf("wave %d:", w); for (int i = 0; i < 7; ++i) printf(" %lld", hb[w * 8 + i]); printf("\n"); } fflush(stdout); } }
-#endif
     const int qb = prefill_tokens_per_block(h->G);
     const dim3 grid((unsigned)((max_q_len + qb - 1) / qb), (unsigned)d.num_kv_heads, (unsigned)d.batch);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);

@@ -2,18 +2,20 @@
 // head_dim 128, group size <= 16.  Query i of request b's chunk sits at position p = L_b - n_b + i and attends to
 // tokens 0 .. p (causal inside the chunk).
 //
-// A workgroup (8 waves, two per SIMD) owns one (request, KV head, block of query tokens).  Its "columns" are the
-// (query token, query head of the group) pairs of that block; a wave owns 32 of them = two 16-column MFMA blocks.
-// The same transposed products as in the decode kernel are used, per 32-token tile and per column block:
+// A workgroup (8 waves, two per SIMD) owns one (request, KV head, block of query tokens).  Its 256 "columns" are the
+// (query token, query head of the group) pairs of that block in token-major order; a wave owns 32 consecutive ones =
+// two 16-column MFMA blocks.  The same transposed products as in the decode kernel are used, per 32-token tile and
+// per column block:
 //   S^T = K Q^T     (A = K rows from shared memory, B = the block's queries, held in registers for the whole kernel)
 //   O^T += V^T P^T  (A = V transposed, B = the softmax weights; both as fp16: V is converted once per workgroup on
 //                    its way into shared memory, exactly for 2^-14 <= |V| <= 65504, and fp16 weights carry 11
 //                    significant bits, so one product does what bf16 weights need a hi + lo pair for)
-// so every lane owns one column: running max, sum and rescale never cross lanes except two max exchanges per tile.
+// so every lane owns one column: running reference, sum and rescale never cross lanes on the common path.
 // What differs from decode is reuse: K/V tiles are fetched once per workgroup into shared memory (double buffered,
-// one barrier per 64 tokens) and feed 16 column blocks, and the 8x8 in-lane transpose of V is done once per wave and
-// tile for its two blocks.  That makes the path a dense contraction, not a stream; with the softmax arithmetic on
-// the vector ALUs (no packed fp32 here) about as long as the matrix-core work, both units bound it.
+// one barrier per 64 tokens) and feed 16 column blocks, and V^T comes out of shared memory through transposing reads.
+// That makes the path a dense contraction, not a stream.  The three pieces of a tile's work are software-pipelined
+// across tiles, so that a wave has matrix-core and vector-ALU instructions to issue side by side; on this chip both
+// kinds go through one issue port per SIMD, and the sum of the two instruction streams is what bounds the kernel.
 #pragma once
 #include <type_traits>
 
@@ -80,9 +82,6 @@ struct PrefillParams {
     float scale_log2;
     int Hq, Hkv, G, MB;
     int out_bf16;
-#ifdef PF_TRACE
-    void *trace;
-#endif
 };
 
 // Query tokens per workgroup for a group of G heads: its 256 columns are the (token, head) pairs in token-major order,
@@ -332,27 +331,10 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     lookup(1);
     stage_k(0);
     lds_barrier();
-#ifdef PF_TRACE
-    long long tt[5] = {0, 0, 0, 0, 0}; long long t0 = wall_clock64(), t1; int nfast = 0;
-#define PF_T(i) { t1 = wall_clock64(); tt[i] += t1 - t0; t0 = t1; }
-#else
-#define PF_T(i)
-#endif
     for (int s = 0; s <= n_steps; ++s) {
-        if (s >= 1 && s <= fast_last) { step_body(std::true_type{}, s);
-#ifdef PF_TRACE
-            ++nfast;
-#endif
-            PF_T(1) }
-        else { step_body(std::false_type{}, s); PF_T(2) }
+        if (s >= 1 && s <= fast_last) step_body(std::true_type{}, s);
+        else step_body(std::false_type{}, s);
     }
-#ifdef PF_TRACE
-    if (blockIdx.x == gridDim.x - 1 && blockIdx.y == 0 && blockIdx.z == 0 && lane == 0) {
-        long long *o = reinterpret_cast<long long *>(p.trace) + wave * 8;
-        for (int i = 0; i < 5; ++i) o[i] = tt[i];
-        o[5] = n_steps + 1; o[6] = nfast;
-    }
-#endif
 
     // ---- normalise and store: a lane holds, for each of its columns, dims 16 eb + 4j .. + 3 of every 16-dim block eb
 #pragma unroll

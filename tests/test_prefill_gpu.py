@@ -98,6 +98,58 @@ def test_peaked_softmax_and_large_scores_in_a_chunk():
     check_chunk(wl, ch, label="peaked")
 
 
+def _map_pool(cache, fn):
+    """Apply fn to the values of a bf16 pool, keeping the NaN of slots nobody owns."""
+    f = W.bf16_bits_to_f32(cache)
+    g = fn(np.nan_to_num(f)).astype(np.float32)
+    return np.where(np.isnan(f), W.BF16_NAN_BITS, W.f32_to_bf16_bits(g)).astype(np.uint16)
+
+
+def test_scores_that_grow_along_the_context_move_the_reference_many_times():
+    """All-positive q and K whose rows grow with the token position: the running maximum of every column keeps rising
+    (by some 30 log2 units over the context), so the kernel's softmax reference moves again and again, inside the
+    pipelined steps too, with accumulated and pending weights to rescale each time."""
+    lens = [900, 333]
+    wl = W.build("chunk", 920, lens, Hq=14, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    wl.k_cache = _map_pool(wl.k_cache, np.abs)
+    for b, L in enumerate(lens):
+        t = np.arange(L)
+        pages, slots = wl.block_table[b, t // wl.ps], t % wl.ps
+        rows = W.bf16_bits_to_f32(wl.k_cache[pages, :, slots, :]) * (0.2 + 2.8 * t / L)[:, None, None].astype(np.float32)
+        wl.k_cache[pages, :, slots, :] = W.f32_to_bf16_bits(rows)
+    ch = W.add_chunk(wl, [200, 333], 921, in_cache=True)
+    ch.q = W.f32_to_bf16_bits(np.abs(W.bf16_bits_to_f32(ch.q)))
+    check_chunk(wl, ch, label="growing")
+
+
+@pytest.mark.parametrize("log2_factor", [-12, 13])
+def test_v_magnitudes_near_both_ends_of_the_fp16_range(log2_factor):
+    """The kernel multiplies V as fp16: exact for 2^-14 <= |V| <= 65504, an absolute error of at most 2^-25 per value
+    below that.  V scaled by 2^-12 straddles the lower end, by 2^13 comes close to the upper one."""
+    f = np.float32(2.0 ** log2_factor)
+    wl = W.build("chunk", 930, [400, 77], Hq=8, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    wl.v_cache = _map_pool(wl.v_cache, lambda v: v * f)
+    assert np.nanmax(np.abs(W.bf16_bits_to_f32(wl.v_cache))) < 65504
+    ch = W.add_chunk(wl, [150, 77], 931, in_cache=True)
+    dev, got = run_chunk(wl, ch)
+    ref = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                                    ch.q_offsets, wl.scale, wl.dtype)
+    err = np.max(np.abs(got - ref))
+    assert np.all(np.isfinite(got)) and err <= TOL[wl.dtype] * float(f) + 2.0 ** -24, f"max|err| {err:.3e}"
+
+
+def test_a_v_value_beyond_the_fp16_range_shows_as_non_finite_output():
+    """Such a value is outside the documented range of the call; the queries that attend to it must not get a wrong
+    finite number (earlier queries of the same tile may see it too, as 0 * inf; the other dims stay clean)."""
+    wl = W.build("chunk", 940, [96], Hq=4, Hkv=1, D=128, ps=16, dtype=W.BF16)
+    page, slot, dim = wl.block_table[0, 2], 5, 17                            # token 37, seen by queries 37 .. 95
+    wl.v_cache[page, 0, slot, dim] = W.f32_to_bf16_bits(np.array([1e5], dtype=np.float32))[0]
+    ch = W.add_chunk(wl, [96], 941, in_cache=True)
+    dev, got = run_chunk(wl, ch)
+    assert np.all(np.isfinite(np.delete(got, dim, axis=2)))
+    assert not np.any(np.isfinite(got[37:, :, dim]))
+
+
 def test_full_size_prefill_chunk_sampled_rows():
     """Eight thinker-sized requests, each with a 512-token chunk at the end of a 512..4096-token context."""
     wl = W.make("thinker", batch=8, append=False)
