@@ -314,12 +314,12 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         // phase 2s: P.V of tile 2s-1, weights of tile 2s, scores of tile 2s+1
         if (kFast || tile_active(2 * s - 1)) pv(smem[buf ^ 1][1][1], Po);
         if (kFast || tile_active(2 * s + 1)) scores(smem[buf][1][0], So);
-        if (kFast || tile_active(2 * s)) weights(fast, 2 * s, Se, Pe);
-        if (kFast || s < n_steps) {
+        if (kFast || s < n_steps) {                              // ahead of the weights: one block with the MFMAs above
             stage_k(buf ^ 1);
             stage_v(buf);
-            lds_barrier();
         }
+        if (kFast || tile_active(2 * s)) weights(fast, 2 * s, Se, Pe);
+        if (kFast || s < n_steps) lds_barrier();
     };
     // last step whose tiles 2s-2 .. 2s+1 are all wholly visible to every live column of the wave and whose fetches
     // (V of step s, K of step s+1) lie wholly inside the context
