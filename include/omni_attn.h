@@ -197,11 +197,13 @@ omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v
  * The chunk's K/V rows must be in the pools already (omni_kv_append_chunk).  q_lens [batch] int32 and q_offsets
  * [batch] int64 are DEVICE arrays; max_q_len is a HOST upper bound on q_lens (it sizes the grid; longer chunks are
  * cut off).  Rows of out that no request owns are not written; requests with q_lens[b] <= 0 are skipped.
- * bf16 q/K/V with head_dim 128 only (matrix-core kernel; fp32 accumulation): else OMNI_ERR_UNSUPPORTED.
- * V enters the weighted sum as fp16: exact for 2^-14 <= |V| <= 65504; a smaller value carries an absolute error of at
- * most 2^-25; a larger one (or a non-finite one) makes non-finite outputs for the queries of its request whose tiles
- * reach it, never wrong finite ones.  scale must be positive.  One launch, no workspace.
- * Errors: NULL, SHAPE (max_q_len <= 0, scale <= 0, alignment), UNSUPPORTED, HIP.
+ * bf16 q/K/V with head_dim 128 run on the matrix cores (fp32 accumulation).  There V enters the weighted sum as
+ * fp16: exact for 2^-14 <= |V| <= 65504; a smaller value carries an absolute error of at most 2^-25; a larger one (or a
+ * non-finite one) makes non-finite outputs for the queries of its request whose tiles reach it, never wrong finite
+ * ones; and scale must be positive.  Every other fp32 / bf16 configuration (and this one under OMNI_TUNE_KERNEL = 1)
+ * runs a plain vector-ALU kernel in fp32 arithmetic, without those two conditions.  An 8-bit cache:
+ * OMNI_ERR_UNSUPPORTED.  One launch, no workspace.
+ * Errors: NULL, SHAPE (max_q_len <= 0, scale <= 0 on the matrix-core path, alignment), UNSUPPORTED, HIP.
  */
 omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
                                       const int32_t *block_table, const int32_t *context_lens, const int32_t *q_lens,

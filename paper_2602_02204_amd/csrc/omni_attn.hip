@@ -12,6 +12,7 @@
 #include "decode_mfma.hpp"
 #include "decode_valu.hpp"
 #include "prefill_mfma.hpp"
+#include "prefill_valu.hpp"
 
 using namespace omni;
 
@@ -471,8 +472,9 @@ omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void
     if (!h || !q || !k_cache || !v_cache || !block_table || !context_lens || !q_lens || !q_offsets || !out)
         return OMNI_ERR_NULL;
     const omni_attn_desc_t &d = h->d;
-    if (!(d.kv_dtype == OMNI_BF16 && d.head_dim == 128)) return OMNI_ERR_UNSUPPORTED;
-    if (max_q_len <= 0 || !(scale > 0.f)) return OMNI_ERR_SHAPE;
+    if (d.kv_dtype == OMNI_FP8_E4M3) return OMNI_ERR_UNSUPPORTED;
+    const bool mfma = d.kv_dtype == OMNI_BF16 && d.head_dim == 128 && h->tune_kernel != 1;
+    if (max_q_len <= 0 || (mfma && !(scale > 0.f))) return OMNI_ERR_SHAPE;
     if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(out, 16) ||
         misaligned(block_table, 4) || misaligned(context_lens, 4) || misaligned(q_lens, 4) || misaligned(q_offsets, 8))
         return OMNI_ERR_SHAPE;
@@ -484,12 +486,23 @@ omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void
     p.scale_log2 = scale * kLog2e;
     p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
     p.out_bf16 = d.out_dtype == OMNI_BF16;
-    const int qb = prefill_tokens_per_block(h->G);
+    const int qb = mfma ? prefill_tokens_per_block(h->G) : kWaves;       // query tokens per workgroup
     const dim3 grid((unsigned)((max_q_len + qb - 1) / qb), (unsigned)d.num_kv_heads, (unsigned)d.batch);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     (void)hipGetLastError();
-    if (d.page_size == 16) prefill_mfma_kernel<16><<<grid, kPrefillThreads, 0, s>>>(p);
-    else prefill_mfma_kernel<32><<<grid, kPrefillThreads, 0, s>>>(p);
+    if (mfma) {
+        if (d.page_size == 16) prefill_mfma_kernel<16><<<grid, kPrefillThreads, 0, s>>>(p);
+        else prefill_mfma_kernel<32><<<grid, kPrefillThreads, 0, s>>>(p);
+    } else {
+        const int l2 = ilog2(d.page_size);
+        if (d.kv_dtype == OMNI_BF16) {
+            if (d.head_dim == 128) prefill_valu_kernel<uint16_t, 128><<<grid, kThreads, 0, s>>>(p, l2);
+            else prefill_valu_kernel<uint16_t, 64><<<grid, kThreads, 0, s>>>(p, l2);
+        } else {
+            if (d.head_dim == 128) prefill_valu_kernel<float, 128><<<grid, kThreads, 0, s>>>(p, l2);
+            else prefill_valu_kernel<float, 64><<<grid, kThreads, 0, s>>>(p, l2);
+        }
+    }
     if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
     return OMNI_OK;
 }

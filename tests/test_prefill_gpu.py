@@ -25,9 +25,9 @@ class ChunkOnDevice:
         self.out = torch.full((ch.total, wl.Hq, wl.D), float("nan"), dtype=out_dtype, device="cuda")
 
 
-def run_chunk(wl, ch, max_q_len=None, out_dtype=W.F32):
+def run_chunk(wl, ch, max_q_len=None, out_dtype=W.F32, tuning=None):
     """Append the chunk's rows, then attend; returns (DeviceBatch, fp64 output with NaN in rows nobody owns)."""
-    dev = DeviceBatch(wl, out_dtype=out_dtype)
+    dev = DeviceBatch(wl, out_dtype=out_dtype, tuning=tuning)
     c = ChunkOnDevice(dev, ch, torch.float32 if out_dtype == W.F32 else torch.bfloat16)
     mq = max_q_len or max(ch.max_q_len, 1)
     dev.h.omni_kv_append_chunk(c.k_new, c.v_new, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens,
@@ -66,6 +66,28 @@ def test_chunks_of_many_shapes(G, Hkv, ps):
     # rounding residue: 1 to within a few ulp)
     v0 = W.bf16_bits_to_f32(wl.v_cache[wl.block_table[0, 0], :, 0, :]).astype(np.float64)
     assert np.max(np.abs(got[ch.q_offsets[0]] - np.repeat(v0, G, axis=0))) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype,D,G,Hkv,ps", [(W.F32, 64, 2, 2, 16), (W.F32, 64, 7, 1, 32), (W.F32, 128, 4, 2, 16),
+                                              (W.BF16, 64, 5, 2, 16), (W.BF16, 64, 16, 1, 32)])
+def test_chunks_on_every_other_dtype_and_head_size(dtype, D, G, Hkv, ps):
+    """fp32 caches and head_dim 64 go through the vector-ALU kernel (fp32 caches to 1e-5)."""
+    lens = [300, 64, 1, 0, 33, 257, 96, 40]
+    q_lens = [300, 1, 1, 0, 17, 100, 37, 40]
+    wl = W.build("chunk", 800 + G + D, lens, Hq=G * Hkv, Hkv=Hkv, D=D, ps=ps, dtype=dtype, pool_factor=1.5)
+    ch = W.add_chunk(wl, q_lens, 801 + G, in_cache=False, gap=3)
+    check_chunk(wl, ch, label=f"{dtype} D={D} G={G} ps={ps}")
+
+
+def test_vector_alu_kernel_agrees_with_the_matrix_core_kernel_on_bf16():
+    """The same bf16 / head_dim 128 chunks through both kernels (kernel choice 1 = vector ALU): each within the bar of
+    the oracle, and within twice the bar of each other."""
+    wl = W.build("chunk", 950, [700, 129, 64], Hq=14, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    ch = W.add_chunk(wl, [260, 129, 1], 951, in_cache=True)
+    got_mfma, ref = check_chunk(wl, ch, label="mfma")
+    got_valu, _ = check_chunk(wl, ch, label="valu", tuning={omni.OMNI_TUNE_KERNEL: 1})
+    assert np.nanmax(np.abs(got_mfma - got_valu)) <= 2 * TOL[W.BF16]
+    assert np.nanmax(np.abs(got_valu - ref)) <= 1e-5                      # fp32 arithmetic on exact bf16 inputs
 
 
 def test_one_token_chunks_agree_with_the_decode_call():
@@ -170,10 +192,10 @@ def test_full_size_prefill_chunk_sampled_rows():
 
 
 def test_prefill_argument_errors():
-    h = omni.Handle(batch=2, num_q_heads=4, num_kv_heads=2, head_dim=64, page_size=16, num_pages=8,
-                    max_blocks_per_seq=4, kv_dtype=omni.OMNI_F32)
+    h = omni.Handle(batch=2, num_q_heads=4, num_kv_heads=2, head_dim=128, page_size=16, num_pages=8,
+                    max_blocks_per_seq=4, kv_dtype=omni.OMNI_FP8_E4M3, q_dtype=omni.OMNI_BF16)
     L = omni.lib()
-    assert L.omni_paged_prefill_attn(h._h, 256, 256, 256, 256, 256, 256, 256, 8, 1.0, 256, None) == 4     # fp32 / D=64
+    assert L.omni_paged_prefill_attn(h._h, 256, 256, 256, 256, 256, 256, 256, 8, 1.0, 256, None) == 4     # 8-bit cache
     hb = omni.Handle(batch=2, num_q_heads=4, num_kv_heads=2, head_dim=128, page_size=16, num_pages=8,
                      max_blocks_per_seq=4, kv_dtype=omni.OMNI_BF16)
     assert L.omni_paged_prefill_attn(hb._h, 256, 256, 256, 256, 256, 256, 256, 0, 1.0, 256, None) == 2
