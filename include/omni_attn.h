@@ -266,8 +266,9 @@ omni_status_t omni_debug_stream_read(const void *a, size_t a_bytes, const void *
 
 /* Profiling aid for the benchmark.  After omni_debug_profile_begin(h, capacity, stride) every stride-th attention
  * call (omni_paged_decode_attn or omni_decode_step; the first one included) records a HIP event pair around its
- * attention kernel (the kernel that reads the KV cache) on the caller's stream, until `capacity` pairs are used.
- * An event pair costs a few microseconds of stream time, hence the stride.  omni_debug_profile_end synchronises the
+ * attention kernel (the kernel that reads the KV cache) on the caller's stream, until `capacity` pairs are used;
+ * for the matrix-core kernel the pair is attached to the kernel's dispatch, so it spans that kernel alone.  Do not
+ * capture such calls into a graph.  An event pair costs a few microseconds of stream time, hence the stride.  omni_debug_profile_end synchronises the
  * recorded events, writes the elapsed milliseconds of each recorded launch to host_ms[0 .. *count) (host_ms must hold
  * `capacity` floats), destroys the events and switches recording off.  Errors: NULL, SHAPE (capacity or stride <= 0),
  * HIP. */
