@@ -160,6 +160,17 @@ def test_v_magnitudes_near_both_ends_of_the_fp16_range(log2_factor):
     assert np.all(np.isfinite(got)) and err <= TOL[wl.dtype] * float(f) + 2.0 ** -24, f"max|err| {err:.3e}"
 
 
+def test_v_values_that_are_fp16_subnormals_are_not_flushed():
+    """Every V element is 2^-20, an fp16 subnormal: a softmax-weighted mean of equal rows is that value again, so the
+    output is 2^-20 up to fp32 rounding; flushing subnormal operands to zero anywhere on the way would give 0."""
+    wl = W.build("chunk", 960, [300, 45], Hq=14, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    v = np.float32(2.0 ** -20)
+    wl.v_cache = _map_pool(wl.v_cache, lambda x: np.full_like(x, v))
+    ch = W.add_chunk(wl, [120, 45], 961, in_cache=True)
+    dev, got = run_chunk(wl, ch)
+    assert np.max(np.abs(got / float(v) - 1.0)) <= 1e-3
+
+
 def test_a_v_value_beyond_the_fp16_range_shows_as_non_finite_output():
     """Such a value is outside the documented range of the call; the queries that attend to it must not get a wrong
     finite number (earlier queries of the same tile may see it too, as 0 * inf; the other dims stay clean)."""
