@@ -159,6 +159,34 @@ def test_golden_hand_worked_cases():
     assert n == 4
 
 
+def test_golden_hand_worked_causal_chunks():
+    """Hand-worked chunks (tests/golden/causal_chunk_cases.txt): rational softmax weights over tokens 0 .. own position."""
+    n = 0
+    for line in open(os.path.join(os.path.dirname(GOLDEN), "causal_chunk_cases.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, scale, q, K, V, exp = [f.strip() for f in line.split("|")]
+        q = np.array([_parse_vals(r) for r in q.split(";")], dtype=np.float32)[:, None, :]      # [n, Hq = 1, D]
+        K = np.array([_parse_vals(r) for r in K.split(";")], dtype=np.float32)
+        V = np.array([_parse_vals(r) for r in V.split(";")], dtype=np.float32)
+        exp = np.array([_parse_vals(r) for r in exp.split(";")])
+        L, D = K.shape
+        ps = 2
+        npg = (L + ps - 1) // ps
+        kc = np.full((npg + 1, 1, ps, D), np.nan, dtype=np.float32)
+        vc = kc.copy()
+        table = np.arange(npg, 0, -1, dtype=np.int32)[None, :]           # pages npg..1, page 0 unused
+        for t in range(L):
+            kc[table[0, t // ps], 0, t % ps] = K[t]
+            vc[table[0, t // ps], 0, t % ps] = V[t]
+        out = oracle.paged_prefill_attn(q, kc, vc, table, np.array([L], np.int32), np.array([len(q)], np.int32),
+                                        np.array([0], np.int64), float(scale), W.F32)
+        assert np.allclose(out[:, 0], exp, atol=4e-6), name
+        n += 1
+    assert n == 3
+
+
 # --------------------------------------------------------------------------- invariants
 def test_key_shift_invariance_large_shift():
     # Adding u to every key adds the constant scale*q.u to every score of a head: softmax does not move.
