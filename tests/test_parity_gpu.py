@@ -37,6 +37,38 @@ def kernels_for(wl):
     return ks
 
 
+# --------------------------------------------------------------------------- hand-worked cases
+def test_hand_worked_cases_through_the_c_abi():
+    """tests/golden/closed_form_cases.txt (rational softmax weights), zero-padded to head_dim 64 in fp32: both the
+    split-free plan and a forced 32-token partition are held to 1e-5 of the hand-worked result."""
+    import math
+    import os
+
+    def vals(txt):
+        return [math.log(float(tok[2:])) if tok.startswith("ln") else float(tok) for tok in txt.split()]
+
+    n = 0
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "closed_form_cases.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, scale, q, K, V, exp = [f.strip() for f in line.split("|")]
+        q = np.array(vals(q), dtype=np.float32)
+        K = np.array([vals(r) for r in K.split(";")], dtype=np.float32)
+        V = np.array([vals(r) for r in V.split(";")], dtype=np.float32)
+        exp = np.array(vals(exp))
+        L, d = K.shape
+        wl = W.build("golden", 7, [L], Hq=1, Hkv=1, D=64, ps=16, dtype=W.F32, scale=float(scale))
+        pg = wl.block_table[0, 0]
+        wl.k_cache[pg, 0, :L] = 0.0; wl.v_cache[pg, 0, :L] = 0.0; wl.q[0, 0] = 0.0
+        wl.k_cache[pg, 0, :L, :d] = K; wl.v_cache[pg, 0, :L, :d] = V; wl.q[0, 0, :d] = q
+        for tuning in (None, {omni.OMNI_TUNE_FORCE_PARTITION: 32}):
+            got = DeviceBatch(wl, tuning=tuning).attend()
+            assert np.max(np.abs(got[0, 0, :d] - exp)) <= 1e-5 and np.all(got[0, 0, d:] == 0.0), name
+        n += 1
+    assert n == 4
+
+
 # --------------------------------------------------------------------------- the five configurations
 def test_tiny_config_fp32():
     wl = W.make("tiny")
