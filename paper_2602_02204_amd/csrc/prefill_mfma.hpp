@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     const int wg_last = min(n_q, q0 + QB) - 1;                   // last query token of the workgroup
     const int n_tiles = (pos0 + wg_last) / kTile + 1;            // tiles that hold tokens 0 .. position of wg_last
 
-    // ---- this lane's four columns: query token, head, position; and the queries as MFMA B operands
+    // ---- this lane's columns (one per column block): query token, head, position; and the queries as MFMA B operands
     int pos[kPrefillBlocks];                                     // -1: padding column (never stored)
     uint4 Q[kPrefillBlocks][4];
     int wave_max_pos = -1;
