@@ -58,8 +58,8 @@ struct MfmaTileLoader {
         const char *k0 = kbase + o0 + koff, *k1 = kbase + o1 + koff;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            K[kk] = *reinterpret_cast<const uint4 *>(k0 + kk * 64);
-            K[4 + kk] = *reinterpret_cast<const uint4 *>(k1 + kk * 64);
+            K[kk] = nt_load16(k0 + kk * 64);
+            K[4 + kk] = nt_load16(k1 + kk * 64);
         }
     }
     __device__ __forceinline__ void issue_v(int pg0, int pg1, uint4 (&V)[8]) const {
@@ -68,8 +68,8 @@ struct MfmaTileLoader {
         const char *v0 = vbase + o0 + voff, *v1 = vbase + o1 + voff;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            V[r] = *reinterpret_cast<const uint4 *>(v0 + r * 256);
-            V[4 + r] = *reinterpret_cast<const uint4 *>(v1 + r * 256);
+            V[r] = nt_load16(v0 + r * 256);
+            V[4 + r] = nt_load16(v1 + r * 256);
         }
     }
 };

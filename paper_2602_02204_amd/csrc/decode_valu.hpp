@@ -81,8 +81,8 @@ __global__ __launch_bounds__(kThreads) void decode_valu_kernel(AttnParams p) {
         if (valid) {
             const int page = bt[t >> p.log2_ps];
             const size_t off = ((((size_t)page * p.Hkv + kvh) << p.log2_ps) + (t & ps_mask)) * D + c * VEC;
-            kraw = *reinterpret_cast<const uint4 *>(kc + off);
-            vraw = *reinterpret_cast<const uint4 *>(vc + off);
+            kraw = nt_load16(kc + off);
+            vraw = nt_load16(vc + off);
         }
         float kf[VEC], vf[VEC];
         ElemTraits<T>::unpack(kraw, kf);
