@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the attention kernel on the thinker workload (seed 1), from two rocprofv3 counter runs
 # (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000, the factors a plain 1 GiB copy gives); see
 # profiles/decode_mfma_kernel_thinker_hbm_traffic.txt.  Not measured by this script: null for any other workload.
-MEASURED_TRAFFIC_BYTES = {("thinker", 1): 300.4e6}
+MEASURED_TRAFFIC_BYTES = {("thinker", 1): 300.2e6}
 EVENT_STRIDE = 8                # one timed step in eight carries the HIP event pair around the attention kernel
 
 

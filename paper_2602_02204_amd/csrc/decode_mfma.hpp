@@ -62,6 +62,42 @@ struct MfmaTileLoader {
             K[4 + kk] = nt_load16(k1 + kk * 64);
         }
     }
+    // K through shared memory: the loads above fetch 64 bytes of each of 16 rows per instruction, i.e. every cache line
+    // in two halves by two instructions, which keeps non-temporal loads from paying off for K.  Here a wave copies the
+    // tile's rows into its own 8 KB of shared memory with loads that cover four whole rows per instruction (lane l of
+    // instruction r: row 4r + l/16 of the 16-token block, 16-byte chunk (l % 16) ^ row, landing at 16 l behind the
+    // instruction's base: the xor spreads a column of chunks over the banks), and reads its MFMA operands back from
+    // there.  No register holds the tile while it is on its way.
+    int kst_goff[4];                 // per lane: byte offset of the chunk it fetches in instruction r, inside a block
+    int kst_roff[4];                 // per lane: byte offset of the operand of k-step kk inside a staged block
+    __device__ __forceinline__ void init_staging(int lane) {
+        const int sub = lane >> 4, p16 = lane & 15, i = lane & 15, j = lane >> 4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 4 * r + sub;
+            kst_goff[r] = row * 256 + ((p16 ^ row) << 4);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) kst_roff[kk] = i * 256 + (((4 * kk + j) ^ i) << 4);
+    }
+    __device__ __forceinline__ void issue_k_staged(int pg0, int pg1, char *stage) const {
+        const size_t o0 = (size_t)pg0 * page_stride;
+        const size_t o1 = (PS == 16) ? (size_t)pg1 * page_stride : o0 + 16 * 256;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kbase + o0 + kst_goff[r]),
+                                             (__attribute__((address_space(3))) void *)(stage + r * 1024), 16, 0, 2);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kbase + o1 + kst_goff[r]),
+                                             (__attribute__((address_space(3))) void *)(stage + 4096 + r * 1024), 16, 0, 2);
+        }
+    }
+    __device__ __forceinline__ void read_k_staged(const char *stage, uint4 (&K)[8]) const {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            K[kk] = *reinterpret_cast<const uint4 *>(stage + kst_roff[kk]);
+            K[4 + kk] = *reinterpret_cast<const uint4 *>(stage + 4096 + kst_roff[kk]);
+        }
+    }
     __device__ __forceinline__ void issue_v(int pg0, int pg1, uint4 (&V)[8]) const {
         const size_t o0 = (size_t)pg0 * page_stride;
         const size_t o1 = (PS == 16) ? (size_t)pg1 * page_stride : o0 + 16 * 256;
@@ -223,15 +259,17 @@ __device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], M
 }
 
 constexpr int kMaxRing = 4;
+constexpr int kKStageBytes = 8192;                     // one 32-token K tile of a 16-bit cache (D = 128)
 
 // Shared-memory layout for a batch of B requests and G query heads per KV head: as many ring slots (up to four) as
 // fit while two workgroups still share the 160 KB of a compute unit; at least one fits for every supported B and G.
-inline MfmaLds mfma_lds_layout(int B, int G) {
+inline MfmaLds mfma_lds_layout(int B, int G, bool kv8) {
     constexpr int D = 128;
     MfmaLds L;
     L.ring_off = ((2 * B + 1) * 4 + 15) & ~15;
     L.slot_floats = kWaves * G * (D + 4) + 2 * kWaves * kMaxGroup;
-    const int budget = 80 * 1024 - 512 - L.ring_off;            // 512 B for the kernel's static variables
+    // 512 B for the kernel's static variables, and for 16-bit caches the waves' K tiles (static as well)
+    const int budget = 80 * 1024 - 512 - L.ring_off - (kv8 ? 0 : kWaves * kKStageBytes);
     const int depth = budget / (L.slot_floats * 4);
     L.ring_depth = depth > kMaxRing ? kMaxRing : (depth < 1 ? 1 : depth);
     L.total = L.ring_off + L.ring_depth * L.slot_floats * 4;
@@ -295,6 +333,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     __shared__ PlanSmem ps;
     extern __shared__ __align__(16) int E[];                 // E[B + 1] tile offsets, then Lc[B] lengths, then the ring
+    __shared__ __align__(16) char kstage_all[KV8 ? 16 : kWaves * kKStageBytes];    // 16-bit caches: a K tile per wave
     float *ring = reinterpret_cast<float *>(reinterpret_cast<char *>(E) + p.lds.ring_off);
     const int RING = p.lds.ring_depth, slot_floats = p.lds.slot_floats;
 
@@ -321,6 +360,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     ld.vbase = reinterpret_cast<const char *>(p.v_cache) + (size_t)kvh * PS * D * ES;
     ld.koff = col * 256 + j * 16;
     ld.voff = col * 16 + (4 * j) * 256;
+    ld.init_staging(lane);
+    char *kstage = kstage_all + (KV8 ? 0 : wave * kKStageBytes);
     Mfma8TileLoader<PS> ld8;
     ld8.page_stride = ld.page_stride; ld8.kbase = ld.kbase; ld8.vbase = ld.vbase;
     ld8.k_scale = KV8 ? p.k_scale + kvh : nullptr; ld8.v_scale = KV8 ? p.v_scale + kvh : nullptr;
@@ -438,7 +479,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         uint2 Vr[KV8 ? 8 : 1];
         float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
         auto issue_k = [&](int pg0, int pg1) __attribute__((always_inline)) {
-            if constexpr (KV8) ld8.issue_k(pg0, pg1, Kr, ks); else ld.issue_k(pg0, pg1, K);
+            if constexpr (KV8) ld8.issue_k(pg0, pg1, Kr, ks); else ld.issue_k_staged(pg0, pg1, kstage);
         };
         auto issue_v = [&](int pg0, int pg1) __attribute__((always_inline)) {
             if constexpr (KV8) ld8.issue_v(pg0, pg1, Vr, vs); else ld.issue_v(pg0, pg1, V);
@@ -466,14 +507,27 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 const SlotInfo nxt = slot_info(s + 1);
                 const bool more = nxt.req >= 0;
                 float sv[8];
-                if constexpr (KV8) mfma_scores_fp8(Kr, Q, sv, p.scale_log2, ks);
-                else mfma_scores(K, Q, sv, p.scale_log2);
+                if constexpr (KV8) {
+                    mfma_scores_fp8(Kr, Q, sv, p.scale_log2, ks);
+                } else {
+                    // the copy into shared memory is complete when every load of this wave is (vmcnt = 0; the compiler
+                    // does not order shared-memory reads behind such copies by itself)
+                    __builtin_amdgcn_s_waitcnt(0x0f70);
+                    ld.read_k_staged(kstage, K);                 // the staged tile into operand registers ...
+                    __builtin_amdgcn_s_waitcnt(0xc07f);          // ... and once they are there (lgkmcnt = 0) ...
+                    if (more) {                                  // ... the next tile may take its place
+                        if (nxt.append) append_row(nxt);
+                        issue_k(nxt.pg0, nxt.pg1);
+                    }
+                    mfma_scores(K, Q, sv, p.scale_log2);
+                }
                 if (!stamped) { OMNI_STAMP(p, 3); stamped = true; }
                 OMNI_STAMP(p, 16 + (s < 15 ? s : 15));
-                if (more) {
-                    if (nxt.append) append_row(nxt);
-                    issue_k(nxt.pg0, nxt.pg1);
-                    if (nxt.req != seg.b) load_q(nxt.req, Q);
+                if constexpr (KV8) {
+                    if (more) {
+                        issue_k(nxt.pg0, nxt.pg1);
+                        if (nxt.req != seg.b) load_q(nxt.req, Q);
+                    }
                 }
                 if constexpr (KV8) {
                     const float v0 = vs[0], v1 = vs[1];          // of the current tile: the next V request replaces them
@@ -483,7 +537,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                     mfma_softmax_pv<true>(sv, V, st, cur.tile * kTile, seg.L, j, v0, v1);
                 } else {
                     mfma_softmax_pv(sv, V, st, cur.tile * kTile, seg.L, j);
-                    if (more) issue_v(nxt.pg0, nxt.pg1);
+                    // The wait at the top of the loop covers every load of the wave (the compiler would make any wait
+                    // for an older load one for all while a copy into shared memory is in flight), so the query of the
+                    // next request and the next V rows are asked for here, where nothing waits for them until then.
+                    if (more) {
+                        if (nxt.req != seg.b) load_q(nxt.req, Q);
+                        issue_v(nxt.pg0, nxt.pg1);
+                    }
                 }
                 ++s; cur = nxt;
             }

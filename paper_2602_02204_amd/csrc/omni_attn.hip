@@ -68,7 +68,7 @@ struct omni_handle_s {
         kernel = fp8 ? 2 : ((tune_kernel == 2 && mfma_ok) ? 2 : (tune_kernel == 1 ? 1 : (mfma_ok ? 2 : 1)));
         nw = tune_target_wgs / d.num_kv_heads;
         if (nw < 1) nw = 1;
-        lds = mfma_lds_layout(d.batch, G);
+        lds = mfma_lds_layout(d.batch, G, fp8);
         lds_attr_set = false;
         long long ranges = nw;
         if (tune_force_partition > 0) {
