@@ -142,14 +142,49 @@ struct Mfma8TileLoader {
         ks[0] = k_scale[(size_t)pg0 * Hkv];
         ks[1] = k_scale[(size_t)pgb * Hkv];
     }
+    // K through shared memory, as in the 16-bit loader: a 16-token block is 2 KB = two instructions of eight whole rows
+    // (lane l of instruction r: row 8r + l/8, 16-byte chunk (l % 8) ^ (row % 8)); a lane reads its 32 bytes of a row back
+    // as two chunks.
+    int kst_goff[2], kst_roff[2];
+    __device__ __forceinline__ void init_staging(int lane) {
+        const int i = lane & 15, j = lane >> 4;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int row = 8 * r + (lane >> 3);
+            kst_goff[r] = row * 128 + (((lane & 7) ^ (row & 7)) << 4);
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) kst_roff[e] = i * 128 + (((2 * j + e) ^ (i & 7)) << 4);
+    }
+    __device__ __forceinline__ void issue_k_staged(int pg0, int pg1, char *stage, float (&ks)[2]) const {
+        const int pgb = (PS == 16) ? pg1 : pg0;
+        const size_t o0 = (size_t)pg0 * page_stride;
+        const size_t o1 = (PS == 16) ? (size_t)pg1 * page_stride : o0 + 16 * 128;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kbase + o0 + kst_goff[r]),
+                                             (__attribute__((address_space(3))) void *)(stage + r * 1024), 16, 0, 2);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kbase + o1 + kst_goff[r]),
+                                             (__attribute__((address_space(3))) void *)(stage + 2048 + r * 1024), 16, 0, 2);
+        }
+        ks[0] = k_scale[(size_t)pg0 * Hkv];
+        ks[1] = k_scale[(size_t)pgb * Hkv];
+    }
+    __device__ __forceinline__ void read_k_staged(const char *stage, uint4 (&Kr)[4]) const {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            Kr[e] = *reinterpret_cast<const uint4 *>(stage + kst_roff[e]);
+            Kr[2 + e] = *reinterpret_cast<const uint4 *>(stage + 2048 + kst_roff[e]);
+        }
+    }
     __device__ __forceinline__ void issue_v(int pg0, int pg1, uint2 (&Vr)[8], float (&vs)[2]) const {
         const int pgb = (PS == 16) ? pg1 : pg0;
         const char *v0 = vbase + (size_t)pg0 * page_stride + voff;
         const char *v1 = (PS == 16) ? vbase + (size_t)pg1 * page_stride + voff : v0 + 16 * 128;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            Vr[r] = *reinterpret_cast<const uint2 *>(v0 + r * 128);
-            Vr[4 + r] = *reinterpret_cast<const uint2 *>(v1 + r * 128);
+            Vr[r] = nt_load8(v0 + r * 128);
+            Vr[4 + r] = nt_load8(v1 + r * 128);
         }
         vs[0] = v_scale[(size_t)pg0 * Hkv];
         vs[1] = v_scale[(size_t)pgb * Hkv];
@@ -268,8 +303,8 @@ inline MfmaLds mfma_lds_layout(int B, int G, bool kv8) {
     MfmaLds L;
     L.ring_off = ((2 * B + 1) * 4 + 15) & ~15;
     L.slot_floats = kWaves * G * (D + 4) + 2 * kWaves * kMaxGroup;
-    // 512 B for the kernel's static variables, and for 16-bit caches the waves' K tiles (static as well)
-    const int budget = 80 * 1024 - 512 - L.ring_off - (kv8 ? 0 : kWaves * kKStageBytes);
+    // 512 B for the kernel's static variables, and the waves' K tiles (static as well)
+    const int budget = 80 * 1024 - 512 - L.ring_off - kWaves * (kv8 ? kKStageBytes / 2 : kKStageBytes);
     const int depth = budget / (L.slot_floats * 4);
     L.ring_depth = depth > kMaxRing ? kMaxRing : (depth < 1 ? 1 : depth);
     L.total = L.ring_off + L.ring_depth * L.slot_floats * 4;
@@ -333,7 +368,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     __shared__ PlanSmem ps;
     extern __shared__ __align__(16) int E[];                 // E[B + 1] tile offsets, then Lc[B] lengths, then the ring
-    __shared__ __align__(16) char kstage_all[KV8 ? 16 : kWaves * kKStageBytes];    // 16-bit caches: a K tile per wave
+    __shared__ __align__(16) char kstage_all[kWaves * (KV8 ? kKStageBytes / 2 : kKStageBytes)];    // a K tile per wave
     float *ring = reinterpret_cast<float *>(reinterpret_cast<char *>(E) + p.lds.ring_off);
     const int RING = p.lds.ring_depth, slot_floats = p.lds.slot_floats;
 
@@ -361,13 +396,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     ld.koff = col * 256 + j * 16;
     ld.voff = col * 16 + (4 * j) * 256;
     ld.init_staging(lane);
-    char *kstage = kstage_all + (KV8 ? 0 : wave * kKStageBytes);
+    char *kstage = kstage_all + wave * (KV8 ? kKStageBytes / 2 : kKStageBytes);
     Mfma8TileLoader<PS> ld8;
     ld8.page_stride = ld.page_stride; ld8.kbase = ld.kbase; ld8.vbase = ld.vbase;
     ld8.k_scale = KV8 ? p.k_scale + kvh : nullptr; ld8.v_scale = KV8 ? p.v_scale + kvh : nullptr;
     ld8.Hkv = p.Hkv;
     ld8.koff = col * 128 + j * 32;
     ld8.voff = col * 8 + (4 * j) * 128;
+    ld8.init_staging(lane);
 
     auto load_q = [&](int b, uint4 (&Q)[4]) {                    // B operand of K Q^T for request b
 #pragma unroll
@@ -479,7 +515,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         uint2 Vr[KV8 ? 8 : 1];
         float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
         auto issue_k = [&](int pg0, int pg1) __attribute__((always_inline)) {
-            if constexpr (KV8) ld8.issue_k(pg0, pg1, Kr, ks); else ld.issue_k_staged(pg0, pg1, kstage);
+            if constexpr (KV8) ld8.issue_k_staged(pg0, pg1, kstage, ks); else ld.issue_k_staged(pg0, pg1, kstage);
         };
         auto issue_v = [&](int pg0, int pg1) __attribute__((always_inline)) {
             if constexpr (KV8) ld8.issue_v(pg0, pg1, Vr, vs); else ld.issue_v(pg0, pg1, V);
@@ -508,7 +544,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 const bool more = nxt.req >= 0;
                 float sv[8];
                 if constexpr (KV8) {
-                    mfma_scores_fp8(Kr, Q, sv, p.scale_log2, ks);
+                    __builtin_amdgcn_s_waitcnt(0x0f70);          // as below: every load of the wave, the staged tile included
+                    ld8.read_k_staged(kstage, Kr);
+                    const float ks_cur[2] = {ks[0], ks[1]};      // the next request for K replaces the scales
+                    __builtin_amdgcn_s_waitcnt(0xc07f);
+                    if (more) issue_k(nxt.pg0, nxt.pg1);
+                    mfma_scores_fp8(Kr, Q, sv, p.scale_log2, ks_cur);
                 } else {
                     // the copy into shared memory is complete when every load of this wave is (vmcnt = 0; the compiler
                     // does not order shared-memory reads behind such copies by itself)
@@ -523,17 +564,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 }
                 if (!stamped) { OMNI_STAMP(p, 3); stamped = true; }
                 OMNI_STAMP(p, 16 + (s < 15 ? s : 15));
-                if constexpr (KV8) {
-                    if (more) {
-                        issue_k(nxt.pg0, nxt.pg1);
-                        if (nxt.req != seg.b) load_q(nxt.req, Q);
-                    }
-                }
+
                 if constexpr (KV8) {
                     const float v0 = vs[0], v1 = vs[1];          // of the current tile: the next V request replaces them
 #pragma unroll
                     for (int r = 0; r < 8; ++r) V[r] = fp8x8_to_bf16x8(Vr[r].x, Vr[r].y);
-                    if (more) issue_v(nxt.pg0, nxt.pg1);         // the raw V bytes are consumed: request the next ones
+                    if (more) {                                  // the raw V bytes are consumed: request the next ones
+                        if (nxt.req != seg.b) load_q(nxt.req, Q);
+                        issue_v(nxt.pg0, nxt.pg1);
+                    }
                     mfma_softmax_pv<true>(sv, V, st, cur.tile * kTile, seg.L, j, v0, v1);
                 } else {
                     mfma_softmax_pv(sv, V, st, cur.tile * kTile, seg.L, j);
