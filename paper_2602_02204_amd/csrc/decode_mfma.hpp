@@ -298,13 +298,13 @@ constexpr int kKStageBytes = 8192;                     // one 32-token K tile of
 
 // Shared-memory layout for a batch of B requests and G query heads per KV head: as many ring slots (up to four) as
 // fit while two workgroups still share the 160 KB of a compute unit; at least one fits for every supported B and G.
-inline MfmaLds mfma_lds_layout(int B, int G, bool kv8) {
+inline MfmaLds mfma_lds_layout(int B, int G, bool kv8, bool staged) {
     constexpr int D = 128;
     MfmaLds L;
     L.ring_off = ((2 * B + 1) * 4 + 15) & ~15;
     L.slot_floats = kWaves * G * (D + 4) + 2 * kWaves * kMaxGroup;
-    // 512 B for the kernel's static variables, and the waves' K tiles (static as well)
-    const int budget = 80 * 1024 - 512 - L.ring_off - kWaves * (kv8 ? kKStageBytes / 2 : kKStageBytes);
+    // 512 B for the kernel's static variables, and the waves' K tiles (static as well) if K is staged
+    const int budget = 80 * 1024 - 512 - L.ring_off - (staged ? kWaves * (kv8 ? kKStageBytes / 2 : kKStageBytes) : 0);
     const int depth = budget / (L.slot_floats * 4);
     L.ring_depth = depth > kMaxRing ? kMaxRing : (depth < 1 ? 1 : depth);
     L.total = L.ring_off + L.ring_depth * L.slot_floats * 4;
@@ -361,14 +361,16 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
 // combine them: when the ring is full or the range ends.  A range that holds the end of one request and the start of
 // the next is thus processed without a stop in the middle.
 // KV8: the pools hold 8-bit E4M3 bytes with one scale per (page, KV head); queries stay bf16.
-template <int PS, bool KV8 = false>
+// KST: K tiles go through the per-wave staging area in shared memory (the host chooses it where the ring keeps enough
+// slots beside it); otherwise they are loaded straight into the operand registers.
+template <int PS, bool KV8 = false, bool KST = true>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
     constexpr int ES = KV8 ? 1 : 2;                          // bytes per cache element
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     __shared__ PlanSmem ps;
     extern __shared__ __align__(16) int E[];                 // E[B + 1] tile offsets, then Lc[B] lengths, then the ring
-    __shared__ __align__(16) char kstage_all[kWaves * (KV8 ? kKStageBytes / 2 : kKStageBytes)];    // a K tile per wave
+    __shared__ __align__(16) char kstage_all[KST ? kWaves * (KV8 ? kKStageBytes / 2 : kKStageBytes) : 16];  // a K tile per wave
     float *ring = reinterpret_cast<float *>(reinterpret_cast<char *>(E) + p.lds.ring_off);
     const int RING = p.lds.ring_depth, slot_floats = p.lds.slot_floats;
 
@@ -396,7 +398,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     ld.koff = col * 256 + j * 16;
     ld.voff = col * 16 + (4 * j) * 256;
     ld.init_staging(lane);
-    char *kstage = kstage_all + wave * (KV8 ? kKStageBytes / 2 : kKStageBytes);
+    char *kstage = kstage_all + (KST ? wave * (KV8 ? kKStageBytes / 2 : kKStageBytes) : 0);
     Mfma8TileLoader<PS> ld8;
     ld8.page_stride = ld.page_stride; ld8.kbase = ld.kbase; ld8.vbase = ld.vbase;
     ld8.k_scale = KV8 ? p.k_scale + kvh : nullptr; ld8.v_scale = KV8 ? p.v_scale + kvh : nullptr;
@@ -515,7 +517,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         uint2 Vr[KV8 ? 8 : 1];
         float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
         auto issue_k = [&](int pg0, int pg1) __attribute__((always_inline)) {
-            if constexpr (KV8) ld8.issue_k_staged(pg0, pg1, kstage, ks); else ld.issue_k_staged(pg0, pg1, kstage);
+            if constexpr (KST) {
+                if constexpr (KV8) ld8.issue_k_staged(pg0, pg1, kstage, ks); else ld.issue_k_staged(pg0, pg1, kstage);
+            } else {
+                if constexpr (KV8) ld8.issue_k(pg0, pg1, Kr, ks); else ld.issue_k(pg0, pg1, K);
+            }
         };
         auto issue_v = [&](int pg0, int pg1) __attribute__((always_inline)) {
             if constexpr (KV8) ld8.issue_v(pg0, pg1, Vr, vs); else ld.issue_v(pg0, pg1, V);
@@ -543,44 +549,47 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 const SlotInfo nxt = slot_info(s + 1);
                 const bool more = nxt.req >= 0;
                 float sv[8];
-                if constexpr (KV8) {
-                    __builtin_amdgcn_s_waitcnt(0x0f70);          // as below: every load of the wave, the staged tile included
-                    ld8.read_k_staged(kstage, Kr);
-                    const float ks_cur[2] = {ks[0], ks[1]};      // the next request for K replaces the scales
-                    __builtin_amdgcn_s_waitcnt(0xc07f);
-                    if (more) issue_k(nxt.pg0, nxt.pg1);
-                    mfma_scores_fp8(Kr, Q, sv, p.scale_log2, ks_cur);
-                } else {
-                    // the copy into shared memory is complete when every load of this wave is (vmcnt = 0; the compiler
-                    // does not order shared-memory reads behind such copies by itself)
+                float ks_cur[2] = {ks[0], ks[1]};                // scales of this tile's K (8-bit cache)
+                if constexpr (KST) {
+                    // The copy into shared memory is complete when every load of this wave is (vmcnt = 0; the compiler
+                    // does not order shared-memory reads behind such copies by itself).  This one wait also covers the V
+                    // rows and the query asked for at the end of the previous tile, so nothing below waits for memory:
+                    // the compiler would turn any wait for an older load into one for all loads while a copy into
+                    // shared memory is in flight.
                     __builtin_amdgcn_s_waitcnt(0x0f70);
-                    ld.read_k_staged(kstage, K);                 // the staged tile into operand registers ...
-                    __builtin_amdgcn_s_waitcnt(0xc07f);          // ... and once they are there (lgkmcnt = 0) ...
-                    if (more) {                                  // ... the next tile may take its place
+                    ks_cur[0] = ks[0]; ks_cur[1] = ks[1];
+                    if constexpr (KV8) ld8.read_k_staged(kstage, Kr); else ld.read_k_staged(kstage, K);
+                    __builtin_amdgcn_s_waitcnt(0xc07f);          // operands are in registers (lgkmcnt = 0) ...
+                    if (more) {                                  // ... so the next tile may take their place
                         if (nxt.append) append_row(nxt);
                         issue_k(nxt.pg0, nxt.pg1);
                     }
-                    mfma_scores(K, Q, sv, p.scale_log2);
+                    if constexpr (KV8) mfma_scores_fp8(Kr, Q, sv, p.scale_log2, ks_cur);
+                    else mfma_scores(K, Q, sv, p.scale_log2);
+                } else {
+                    if constexpr (KV8) mfma_scores_fp8(Kr, Q, sv, p.scale_log2, ks);
+                    else mfma_scores(K, Q, sv, p.scale_log2);
+                    if (more) {
+                        if (nxt.append) append_row(nxt);
+                        issue_k(nxt.pg0, nxt.pg1);
+                        if (nxt.req != seg.b) load_q(nxt.req, Q);
+                    }
                 }
                 if (!stamped) { OMNI_STAMP(p, 3); stamped = true; }
                 OMNI_STAMP(p, 16 + (s < 15 ? s : 15));
-
                 if constexpr (KV8) {
                     const float v0 = vs[0], v1 = vs[1];          // of the current tile: the next V request replaces them
 #pragma unroll
                     for (int r = 0; r < 8; ++r) V[r] = fp8x8_to_bf16x8(Vr[r].x, Vr[r].y);
                     if (more) {                                  // the raw V bytes are consumed: request the next ones
-                        if (nxt.req != seg.b) load_q(nxt.req, Q);
+                        if (KST && nxt.req != seg.b) load_q(nxt.req, Q);
                         issue_v(nxt.pg0, nxt.pg1);
                     }
                     mfma_softmax_pv<true>(sv, V, st, cur.tile * kTile, seg.L, j, v0, v1);
                 } else {
                     mfma_softmax_pv(sv, V, st, cur.tile * kTile, seg.L, j);
-                    // The wait at the top of the loop covers every load of the wave (the compiler would make any wait
-                    // for an older load one for all while a copy into shared memory is in flight), so the query of the
-                    // next request and the next V rows are asked for here, where nothing waits for them until then.
                     if (more) {
-                        if (nxt.req != seg.b) load_q(nxt.req, Q);
+                        if (KST && nxt.req != seg.b) load_q(nxt.req, Q);
                         issue_v(nxt.pg0, nxt.pg1);
                     }
                 }

@@ -52,6 +52,7 @@ struct omni_handle_s {
     int r_cap = 0;               // bound on partial-result slots (range index + request index)
     size_t off_ml = 0, off_o = 0, ws_bytes = 0;
     MfmaLds lds{};               // shared-memory layout of the matrix-core kernel
+    bool k_staged = true;        // K tiles through shared memory (matrix-core kernel)
     bool lds_attr_set = false;   // the kernel has been told how much dynamic shared memory it may get
     void *ws = nullptr;
     size_t ws_given = 0;
@@ -68,7 +69,10 @@ struct omni_handle_s {
         kernel = fp8 ? 2 : ((tune_kernel == 2 && mfma_ok) ? 2 : (tune_kernel == 1 ? 1 : (mfma_ok ? 2 : 1)));
         nw = tune_target_wgs / d.num_kv_heads;
         if (nw < 1) nw = 1;
-        lds = mfma_lds_layout(d.batch, G, fp8);
+        // K goes through the staging area unless that leaves the ring with fewer than three slots it would otherwise have
+        const MfmaLds plain = mfma_lds_layout(d.batch, G, fp8, false), staged = mfma_lds_layout(d.batch, G, fp8, true);
+        k_staged = staged.ring_depth >= (plain.ring_depth < 3 ? plain.ring_depth : 3);
+        lds = k_staged ? staged : plain;
         lds_attr_set = false;
         long long ranges = nw;
         if (tune_force_partition > 0) {
@@ -251,10 +255,12 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     const bool prof_in_dispatch = prof && h->kernel == 2;
     if (prof && !prof_in_dispatch && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
     if (h->kernel == 2) {
-        const void *fn = fp8 ? (d.page_size == 16 ? reinterpret_cast<const void *>(&decode_mfma_kernel<16, true>)
-                                                  : reinterpret_cast<const void *>(&decode_mfma_kernel<32, true>))
-                             : (d.page_size == 16 ? reinterpret_cast<const void *>(&decode_mfma_kernel<16, false>)
-                                                  : reinterpret_cast<const void *>(&decode_mfma_kernel<32, false>));
+        const bool ps16 = d.page_size == 16, st = h->k_staged;
+        const void *fn;
+        if (fp8) fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true> : (const void *)&decode_mfma_kernel<16, true, false>)
+                           : (st ? (const void *)&decode_mfma_kernel<32, true, true> : (const void *)&decode_mfma_kernel<32, true, false>);
+        else fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true> : (const void *)&decode_mfma_kernel<16, false, false>)
+                       : (st ? (const void *)&decode_mfma_kernel<32, false, true> : (const void *)&decode_mfma_kernel<32, false, false>);
         if (!h->lds_attr_set) {          // more than the default 64 KB of dynamic shared memory
             if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, h->lds.total) != hipSuccess) {
                 (void)hipGetLastError();
@@ -262,19 +268,14 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
             }
             h->lds_attr_set = true;
         }
-        if (prof_in_dispatch) {
-            void *args[] = {&p};
-            if (hipExtLaunchKernel(fn, grid, dim3(kThreads), args, (size_t)h->lds.total, s, h->prof_events[2 * h->prof_used],
-                                   h->prof_events[2 * h->prof_used + 1], 0) != hipSuccess) {
-                (void)hipGetLastError();
-                return OMNI_ERR_HIP;
-            }
-        } else if (fp8) {
-            if (d.page_size == 16) decode_mfma_kernel<16, true><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
-            else decode_mfma_kernel<32, true><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
-        } else {
-            if (d.page_size == 16) decode_mfma_kernel<16, false><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
-            else decode_mfma_kernel<32, false><<<grid, kThreads, (size_t)h->lds.total, s>>>(p);
+        void *args[] = {&p};
+        const hipError_t le = prof_in_dispatch
+            ? hipExtLaunchKernel(fn, grid, dim3(kThreads), args, (size_t)h->lds.total, s, h->prof_events[2 * h->prof_used],
+                                 h->prof_events[2 * h->prof_used + 1], 0)
+            : hipLaunchKernel(fn, grid, dim3(kThreads), args, (size_t)h->lds.total, s);
+        if (le != hipSuccess) {
+            (void)hipGetLastError();
+            return OMNI_ERR_HIP;
         }
     } else if (d.kv_dtype == OMNI_BF16) {
         if (d.head_dim == 128) launch_valu<uint16_t, 128>(p, grid, dyn, s);
