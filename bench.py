@@ -235,14 +235,17 @@ def main():
         pack["plain_copy_GB/s"] = 2 * kv_bytes / us / 1e3
         del kd, vd, kd2, vd2
 
-    # ---- multi-token queries (chunked prefill) on the matrix cores: 32 thinker-shaped requests, each with a chunk of
-    # 512 new tokens at the end of its context; useful flops = 4 * D * Hq per (query, visible token) pair
-    prefill = None
-    if not args.timed_only and wl.dtype == W.BF16 and wl.D == 128:
-        pw = W.make(wl.name, batch=min(32, wl.B), append=False)
-        ch = W.add_chunk(pw, [512] * pw.B, 77, in_cache=True)
+    # ---- multi-token queries (chunked prefill) on the matrix cores; useful flops = 4 * D * Hq per (query, visible
+    # token) pair.  (a) 32 thinker-shaped requests, each with a chunk of 512 new tokens at the end of its context: the
+    # query blocks fill the chip.  (b) ONE long request (about 30k tokens of context) with a 512-token chunk: 60
+    # workgroups unless the context is split, measured both ways.
+    def measure_prefill(pw, chunk, split):
+        ch = W.add_chunk(pw, [chunk] * pw.B, 77, in_cache=True)
         ph = omni.Handle(batch=pw.B, num_q_heads=pw.Hq, num_kv_heads=pw.Hkv, head_dim=pw.D, page_size=pw.ps,
                          num_pages=pw.P, max_blocks_per_seq=pw.MB, kv_dtype=kvd, out_dtype=omni.OMNI_F32)
+        if not split:
+            ph.omni_set_tuning(omni.OMNI_TUNE_PREFILL_SPLITS, 1)
+        pws = ph.alloc_workspace(prefill_max_q_len=ch.max_q_len)
         pq, pk, pv = to_dev(ch.q, pw.dtype), to_dev(pw.k_cache, pw.dtype), to_dev(pw.v_cache, pw.dtype)
         pbt, plens = torch.from_numpy(pw.block_table).cuda(), torch.from_numpy(pw.context_lens).cuda()
         pql, pqo = torch.from_numpy(ch.q_lens).cuda(), torch.from_numpy(ch.q_offsets).cuda()
@@ -271,10 +274,21 @@ def main():
         if not (perr <= 2e-3):
             print(f"bench.py: prefill parity check failed, max|err|={perr:.3e}", file=sys.stderr)
             sys.exit(1)
-        prefill = {"kernel": "prefill_mfma_kernel", "workload": f"{pw.B} {pw.name}-shaped requests, chunk of 512 tokens each",
-                   "query_token_pairs": pairs, "useful_flops": flops, "avg_us": us, "TFLOP/s": flops / us / 1e6,
-                   "peak_TFLOP/s": 2500.0, "frac": flops / us / 1e6 / 2500.0, "parity_max_abs_err_sampled": perr}
-        del pq, pk, pv, pout
+        return {"query_token_pairs": pairs, "useful_flops": flops, "avg_us": us, "TFLOP/s": flops / us / 1e6,
+                "peak_TFLOP/s": 2500.0, "frac": flops / us / 1e6 / 2500.0, "parity_max_abs_err_sampled": perr,
+                "context_split_workspace_MB": ph.omni_prefill_workspace_bytes(ch.max_q_len) / 1e6}
+
+    prefill = None
+    prefill_one = None
+    if not args.timed_only and wl.dtype == W.BF16 and wl.D == 128:
+        pw = W.make(wl.name, batch=min(32, wl.B), append=False)
+        prefill = {"kernel": "prefill_mfma_kernel", "workload": f"{pw.B} {pw.name}-shaped requests, chunk of 512 tokens each"}
+        prefill.update(measure_prefill(pw, 512, True))
+        p1 = W.make("long", batch=1, append=False)
+        prefill_one = {"kernel": "prefill_mfma_kernel + prefill_merge_kernel",
+                       "workload": f"one request of {int(p1.context_lens[0])} tokens, chunk of 512 tokens",
+                       "context_split": measure_prefill(p1, 512, True), "no_split": measure_prefill(p1, 512, False)}
+        del pw, p1
 
     # ---- the same batch over an 8-bit (E4M3) KV cache with per-page scales: half the bytes per token
     fp8 = None
@@ -405,6 +419,7 @@ def main():
                   "kv_gbs_cache_warm": kv_bytes / (ms_warm * 1e-3) / 1e9 if ms_warm else None,
                   "kv_pack_unpack": pack,
                   "prefill_chunk": prefill,
+                  "prefill_chunk_one_long_request": prefill_one,
                   "fp8_kv_cache": fp8,
                   "parity_max_abs_err_sampled": max_err},
     }

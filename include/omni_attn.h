@@ -87,7 +87,11 @@ typedef enum {
     OMNI_TUNE_KERNEL = 0,           /* 0 = auto, 1 = vector-ALU kernel, 2 = matrix-core (MFMA) kernel (bf16, head_dim 128 only) */
     OMNI_TUNE_TARGET_WORKGROUPS = 1,/* workgroups the attention kernel is launched with (> 0; rounded down to a multiple of Hkv) */
     OMNI_TUNE_MIN_PARTITION = 2,    /* smallest range of context, in tokens, one workgroup may be given (multiple of 32) */
-    OMNI_TUNE_FORCE_PARTITION = 3   /* > 0: every workgroup range is exactly this many tokens (multiple of 32); 0 = plan decides */
+    OMNI_TUNE_FORCE_PARTITION = 3,  /* > 0: every workgroup range is exactly this many tokens (multiple of 32); 0 = plan decides */
+    OMNI_TUNE_PREFILL_SPLITS = 4,   /* omni_paged_prefill_attn, matrix-core path: 0 = the library decides from the grid how many
+                                       workgroups may share a query block's context, 1 = never split, 2 .. 16 = this many */
+    OMNI_TUNE_PREFILL_MIN_SPLIT = 5 /* fewest tokens of context one of them takes (multiple of 64; default 256): a query
+                                       block with a shorter context is shared by fewer, decided on the device */
 } omni_tune_key_t;
 
 /* Validate `desc` and create a handle holding host-side plan state only (no device memory).
@@ -104,6 +108,11 @@ omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value);
 
 /* Bytes of device workspace omni_paged_decode_attn needs for this handle (split-context partials and plan words). */
 omni_status_t omni_workspace_bytes(omni_handle_t h, size_t *bytes);
+
+/* Bytes of workspace with which omni_paged_prefill_attn splits the context for chunks of up to max_q_len tokens
+ * (0 where it would not split).  The one registered workspace serves both calls: register the larger of the two
+ * sizes.  Errors: NULL, SHAPE (max_q_len <= 0). */
+omni_status_t omni_prefill_workspace_bytes(omni_handle_t h, int32_t max_q_len, size_t *bytes);
 
 /* Hand the library a caller-owned device buffer of at least omni_workspace_bytes, 256-byte aligned.
  * The library keeps the pointer only; contents need no initialisation.  The buffer must not be shared by calls that
@@ -202,7 +211,14 @@ omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v
  * non-finite one) makes non-finite outputs for the queries of its request whose tiles reach it, never wrong finite
  * ones; and scale must be positive.  Every other fp32 / bf16 configuration (and this one under OMNI_TUNE_KERNEL = 1)
  * runs a plain vector-ALU kernel in fp32 arithmetic, without those two conditions.  An 8-bit cache:
- * OMNI_ERR_UNSUPPORTED.  One launch, no workspace.
+ * OMNI_ERR_UNSUPPORTED.
+ * One launch and no workspace, unless the call would leave most of the chip idle (few requests, short chunks: a
+ * workgroup owns floor(256 / group size) query tokens of one request and KV head) and the registered workspace holds
+ * at least omni_prefill_workspace_bytes(max_q_len): then the matrix-core path lets up to 16 workgroups share a
+ * query block's context in equal runs of 64-token steps (as many as the context gives OMNI_TUNE_PREFILL_MIN_SPLIT
+ * tokens each), and a second launch merges their pieces (log-sum-exp, in order of position: the same exact
+ * re-association as in decode).  How a block is shared depends on the handle, its tuning, max_q_len and the lengths
+ * only, so the result is bit-identical from run to run.
  * Errors: NULL, SHAPE (max_q_len <= 0, scale <= 0 on the matrix-core path, alignment), UNSUPPORTED, HIP.
  */
 omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,

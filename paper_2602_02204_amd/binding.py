@@ -15,10 +15,12 @@ LIB_PATH = os.environ.get("OMNI_ATTN_LIB") or os.path.join(_HERE, "libomni_attn.
 
 OMNI_F32, OMNI_BF16, OMNI_FP8_E4M3 = 0, 1, 2
 OMNI_TUNE_KERNEL, OMNI_TUNE_TARGET_WORKGROUPS, OMNI_TUNE_MIN_PARTITION, OMNI_TUNE_FORCE_PARTITION = 0, 1, 2, 3
+OMNI_TUNE_PREFILL_SPLITS, OMNI_TUNE_PREFILL_MIN_SPLIT = 4, 5
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = (
-    "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_set_workspace",
+    "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_prefill_workspace_bytes",
+    "omni_set_workspace",
     "omni_paged_decode_attn", "omni_paged_decode_attn_fp8", "omni_kv_append", "omni_decode_step", "omni_kv_pack", "omni_kv_unpack", "omni_paged_prefill_attn", "omni_kv_append_chunk", "omni_get_plan",
     "omni_status_string",
     "omni_debug_last_plan", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
@@ -54,6 +56,7 @@ def lib():
         L.omni_destroy.argtypes = [vp]; L.omni_destroy.restype = None
         L.omni_set_tuning.argtypes = [vp, C.c_int32, C.c_int32]
         L.omni_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
+        L.omni_prefill_workspace_bytes.argtypes = [vp, C.c_int32, C.POINTER(C.c_size_t)]
         L.omni_set_workspace.argtypes = [vp, vp, C.c_size_t]
         L.omni_paged_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_paged_decode_attn_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
@@ -176,6 +179,11 @@ class Handle:
         _ck(lib().omni_workspace_bytes(self._h, C.byref(n)), "omni_workspace_bytes")
         return n.value
 
+    def omni_prefill_workspace_bytes(self, max_q_len: int) -> int:
+        n = C.c_size_t()
+        _ck(lib().omni_prefill_workspace_bytes(self._h, int(max_q_len), C.byref(n)), "omni_prefill_workspace_bytes")
+        return n.value
+
     def omni_set_workspace(self, tensor_or_ptr, nbytes: Optional[int] = None) -> None:
         if nbytes is None:
             nbytes = tensor_or_ptr.numel() * tensor_or_ptr.element_size()
@@ -248,10 +256,13 @@ class Handle:
         _ck(lib().omni_debug_profile_end(self._h, buf, C.byref(n)), "omni_debug_profile_end")
         return [buf[i] for i in range(n.value)]
 
-    def alloc_workspace(self, device="cuda"):
-        """Convenience for callers that use torch for memory: allocate and register the workspace."""
+    def alloc_workspace(self, device="cuda", prefill_max_q_len: int = 0):
+        """Convenience for callers that use torch for memory: allocate and register the workspace (large enough for
+        the context split of multi-token queries of up to prefill_max_q_len tokens, if given)."""
         import torch
         n = self.omni_workspace_bytes()
+        if prefill_max_q_len > 0:
+            n = max(n, self.omni_prefill_workspace_bytes(prefill_max_q_len))
         ws = torch.empty(n, dtype=torch.uint8, device=device)
         self.omni_set_workspace(ws)
         return ws

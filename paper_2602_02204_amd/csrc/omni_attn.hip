@@ -44,6 +44,8 @@ struct omni_handle_s {
     int tune_target_wgs = kDefaultTargetWorkgroups;
     int tune_min_partition = kDefaultMinPartition;
     int tune_force_partition = 0;
+    int tune_prefill_splits = 0;
+    int tune_prefill_min_split = kPrefillMinSplitTokens;
     // derived
     int kernel = 1;              // 1 = vector ALU, 2 = MFMA
     int G = 1;
@@ -59,6 +61,28 @@ struct omni_handle_s {
     // profiling aid: event pairs around the partition kernel
     std::vector<hipEvent_t> prof_events;
     int prof_used = 0, prof_stride = 1, prof_calls = 0;
+
+    // Context split of the multi-token-query kernel for chunks of up to max_q_len tokens: where the query blocks fill
+    // at most half of the compute units, as many workgroups per (query block, KV head, request) as it takes to fill
+    // them, at most 16 and no more than the longest context the handle allows can use.  1 = no split.
+    int prefill_splits(int max_q_len) const {
+        if (!(d.kv_dtype == OMNI_BF16 && d.head_dim == 128 && tune_kernel != 1) || tune_prefill_splits == 1) return 1;
+        const int qb = prefill_tokens_per_block(G);
+        const long long wgs = (long long)((max_q_len + qb - 1) / qb) * d.num_kv_heads * d.batch;
+        const int by_ctx = (max_ctx + 2 * kTile - 1) / (2 * kTile) / (tune_prefill_min_split / (2 * kTile));
+        int ns = tune_prefill_splits > 1 ? tune_prefill_splits : (wgs > 128 ? 1 : (int)(256 / wgs));
+        if (ns > 16) ns = 16;
+        if (ns > by_ctx) ns = by_ctx;            // no context the handle allows would use more
+        return ns < 1 ? 1 : ns;
+    }
+    static size_t prefill_ml_bytes(const omni_attn_desc_t &d, int max_q_len, int ns) {
+        return align256((size_t)d.batch * max_q_len * d.num_q_heads * ns * sizeof(float2));
+    }
+    size_t prefill_ws_bytes(int max_q_len) const {
+        const int ns = prefill_splits(max_q_len);
+        if (ns <= 1) return 0;
+        return prefill_ml_bytes(d, max_q_len, ns) + align256((size_t)d.batch * max_q_len * d.num_q_heads * ns * d.head_dim * sizeof(float));
+    }
 
     void derive() {
         G = d.num_q_heads / d.num_kv_heads;
@@ -154,6 +178,12 @@ omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value) {
         case OMNI_TUNE_FORCE_PARTITION:
             if (value < 0 || value % kTile) return OMNI_ERR_SHAPE;
             h->tune_force_partition = value; break;
+        case OMNI_TUNE_PREFILL_SPLITS:
+            if (value < 0 || value > 16) return OMNI_ERR_SHAPE;
+            h->tune_prefill_splits = value; break;
+        case OMNI_TUNE_PREFILL_MIN_SPLIT:
+            if (value < 2 * kTile || value % (2 * kTile)) return OMNI_ERR_SHAPE;
+            h->tune_prefill_min_split = value; break;
         default: return OMNI_ERR_SHAPE;
     }
     h->derive();
@@ -165,6 +195,13 @@ omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value) {
 omni_status_t omni_workspace_bytes(omni_handle_t h, size_t *bytes) {
     if (!h || !bytes) return OMNI_ERR_NULL;
     *bytes = h->ws_bytes;
+    return OMNI_OK;
+}
+
+omni_status_t omni_prefill_workspace_bytes(omni_handle_t h, int32_t max_q_len, size_t *bytes) {
+    if (!h || !bytes) return OMNI_ERR_NULL;
+    if (max_q_len <= 0) return OMNI_ERR_SHAPE;
+    *bytes = h->prefill_ws_bytes(max_q_len);
     return OMNI_OK;
 }
 
@@ -499,12 +536,24 @@ omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void
     p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
     p.out_bf16 = d.out_dtype == OMNI_BF16;
     const int qb = mfma ? prefill_tokens_per_block(h->G) : kWaves;       // query tokens per workgroup
-    const dim3 grid((unsigned)((max_q_len + qb - 1) / qb), (unsigned)d.num_kv_heads, (unsigned)d.batch);
+    // The context is split only if the registered workspace holds the pieces (omni_prefill_workspace_bytes).
+    int ns = mfma ? h->prefill_splits(max_q_len) : 1;
+    if (ns > 1 && (!h->ws || h->ws_given < h->prefill_ws_bytes(max_q_len))) ns = 1;
+    p.num_splits = ns; p.max_q_len = max_q_len;
+    p.min_split_steps = h->tune_prefill_min_split / (2 * kTile);
+    p.part_ml = reinterpret_cast<float2 *>(h->ws);
+    p.part_o = ns > 1 ? reinterpret_cast<float *>(reinterpret_cast<char *>(h->ws) + omni_handle_s::prefill_ml_bytes(d, max_q_len, ns)) : nullptr;
+    const dim3 grid((unsigned)((max_q_len + qb - 1) / qb) * (unsigned)ns, (unsigned)d.num_kv_heads, (unsigned)d.batch);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     (void)hipGetLastError();
     if (mfma) {
         if (d.page_size == 16) prefill_mfma_kernel<16><<<grid, kPrefillThreads, 0, s>>>(p);
         else prefill_mfma_kernel<32><<<grid, kPrefillThreads, 0, s>>>(p);
+        if (ns > 1) {
+            if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+            const long long items = (long long)max_q_len * d.num_q_heads * 32;
+            prefill_merge_kernel<<<dim3((unsigned)((items + kThreads - 1) / kThreads), (unsigned)d.batch), kThreads, 0, s>>>(p);
+        }
     } else {
         const int l2 = ilog2(d.page_size);
         if (d.kv_dtype == OMNI_BF16) {

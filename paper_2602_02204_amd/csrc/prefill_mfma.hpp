@@ -82,7 +82,21 @@ struct PrefillParams {
     float scale_log2;
     int Hq, Hkv, G, MB;
     int out_bf16;
+    // Context split (matrix-core kernel): each workgroup's 64-token steps are dealt to num_splits workgroups, which
+    // leave unnormalised rows and (reference, sum) per (request, query token < max_q_len, head, split) for the merge.
+    int num_splits;                   // 1: no split, results go straight to out
+    int min_split_steps;              // fewest 64-token steps a split's share may have
+    int max_q_len;
+    float *part_o;                    // [B, max_q_len, Hq, num_splits, D]
+    float2 *part_ml;                  // [B, max_q_len, Hq, num_splits]
 };
+
+// A split's share of the context is at least this many 64-token steps: below that the pieces' trip through memory
+// costs more than the extra workgroups bring.  Decided per query block on the device, where the lengths are known.
+constexpr int kPrefillMinSplitTokens = 256;          // default; a tuning value
+__device__ __forceinline__ int prefill_effective_splits(int num_splits, int n_steps, int min_split_steps) {
+    return max(1, min(num_splits, n_steps / min_split_steps));
+}
 
 // Query tokens per workgroup for a group of G heads: its 256 columns are the (token, head) pairs in token-major order,
 // cut into runs of 32 for the waves wherever that falls.
@@ -100,7 +114,9 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     const int L = p.context_lens[b];
     const int n_q = min(p.q_lens[b], L);
     const int QB = prefill_tokens_per_block(G);
-    const int q0 = blockIdx.x * QB;                              // first query token of this workgroup
+    const int NS = p.num_splits;
+    const int split = NS > 1 ? (int)blockIdx.x % NS : 0;
+    const int q0 = (NS > 1 ? (int)blockIdx.x / NS : (int)blockIdx.x) * QB;      // first query token of this workgroup
     if (n_q <= 0 || q0 >= n_q) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -150,6 +166,12 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     const int lds_off = st_tok * kPrefillRowBytes + st_chunk * 16;
     const int lds_off_v = st_tok * kPrefillVRowBytes + st_chunk * 16;
     const int n_steps = (n_tiles + 1) >> 1;
+    // this workgroup's share of the steps: [s_begin, s_end), all of them without a split.  The launch provides NS
+    // workgroups per query block; how many of them share the work depends on the block's context.
+    const int ns_eff = prefill_effective_splits(NS, n_steps, p.min_split_steps);
+    if (split >= ns_eff) return;
+    const int s_begin = (int)((long long)n_steps * split / ns_eff);
+    const int s_end = (int)((long long)n_steps * (split + 1) / ns_eff);
     uint4 sk[2], sv_[2];
     // Page numbers are looked up one step before the rows they address are fetched, so that no fetch waits for its
     // own table entry: pg_k holds the pages of the step whose K rows are fetched next, pg_v (the same entries one
@@ -170,7 +192,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
                 r[sub] = *src;
             } else {
                 r[sub] = make_uint4(0, 0, 0, 0);                            // rows beyond the context are zero
-                if (step < n_steps && t < L) r[sub] = *src;
+                if (step < s_end && t < L) r[sub] = *src;
             }
         }
     };
@@ -193,8 +215,8 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[cb][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
-    // A tile holds tokens that some column of this wave sees.
-    auto tile_active = [&](int t) { return t >= 0 && t * kTile <= wave_max_pos; };
+    // A tile of this workgroup's steps that holds tokens some column of this wave sees.
+    auto tile_active = [&](int t) { return t >= 2 * s_begin && t < 2 * s_end && t * kTile <= wave_max_pos; };
 
     // ---- the three pieces of a tile's work
     // Raw scores q.k of the column blocks: S[cb][h] holds tokens 16 h + 4 j .. + 3 of the tile for column `col`.  The
@@ -314,26 +336,29 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         // phase 2s: P.V of tile 2s-1, weights of tile 2s, scores of tile 2s+1
         if (kFast || tile_active(2 * s - 1)) pv(smem[buf ^ 1][1][1], Po);
         if (kFast || tile_active(2 * s + 1)) scores(smem[buf][1][0], So);
-        if (kFast || s < n_steps) {                              // ahead of the weights: one block with the MFMAs above
+        if (kFast || s < s_end) {                                // ahead of the weights: one block with the MFMAs above
             stage_k(buf ^ 1);
             stage_v(buf);
         }
         if (kFast || tile_active(2 * s)) weights(fast, 2 * s, Se, Pe);
-        if (kFast || s < n_steps) lds_barrier();
+        if (kFast || s < s_end) lds_barrier();
     };
-    // last step whose tiles 2s-2 .. 2s+1 are all wholly visible to every live column of the wave and whose fetches
-    // (V of step s, K of step s+1) lie wholly inside the context
-    const int fast_last = wave_max_pos < 0 ? -1 : min(((wave_min_pos - (kTile - 1)) / kTile - 1) / 2, L / (2 * kTile) - 2);
+    // last step whose tiles 2s-2 .. 2s+1 are all wholly visible to every live column of the wave and all this
+    // workgroup's, and whose fetches (V of step s, K of step s+1) lie wholly inside the context
+    const int fast_last = wave_max_pos < 0 ? -1 : min(min(((wave_min_pos - (kTile - 1)) / kTile - 1) / 2, L / (2 * kTile) - 2),
+                                                      s_end - 1);
 
-    lookup(0);
-    fetch_rows(std::false_type{}, kbase, 0, pg_k, sk);
-    pg_v[0] = pg_k[0]; pg_v[1] = pg_k[1];
-    lookup(1);
-    stage_k(0);
-    lds_barrier();
-    for (int s = 0; s <= n_steps; ++s) {
-        if (s >= 1 && s <= fast_last) step_body(std::true_type{}, s);
-        else step_body(std::false_type{}, s);
+    {
+        lookup(s_begin);
+        fetch_rows(std::false_type{}, kbase, s_begin, pg_k, sk);
+        pg_v[0] = pg_k[0]; pg_v[1] = pg_k[1];
+        lookup(s_begin + 1);
+        stage_k(s_begin & 1);
+        lds_barrier();
+        for (int s = s_begin; s <= s_end; ++s) {
+            if (s > s_begin && s <= fast_last) step_body(std::true_type{}, s);
+            else step_body(std::false_type{}, s);
+        }
     }
 
     // ---- normalise and store: a lane holds, for each of its columns, dims 16 eb + 4j .. + 3 of every 16-dim block eb
@@ -345,6 +370,15 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         if (pos[cb] < 0) continue;
         const int c = wave * kPrefillCols + cb * 16 + col;
         const int tl = c / G, g = c - tl * G;
+        if (ns_eff > 1) {                                        // a piece for the merge: unnormalised, with (m, l)
+            const size_t pi = ((((size_t)b * p.max_q_len + q0 + tl) * p.Hq + head0 + g) * NS + split);
+            float *po = p.part_o + pi * D;
+#pragma unroll
+            for (int eb = 0; eb < 8; ++eb)
+                *reinterpret_cast<float4 *>(po + 16 * eb + 4 * j) = make_float4(acc[cb][eb][0], acc[cb][eb][1], acc[cb][eb][2], acc[cb][eb][3]);
+            if (j == 0) p.part_ml[pi] = make_float2(m[cb], lsum);
+            continue;
+        }
         const size_t row = ((size_t)(q_row0 + q0 + tl) * p.Hq + head0 + g) * D;
         const float inv = 1.f / lsum;                            // every live column saw its own position: lsum > 0
 #pragma unroll
@@ -360,6 +394,55 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
                 *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.out) + at) = make_float4(o0, o1, o2, o3);
             }
         }
+    }
+}
+
+// Merge of a context split: out row = sum_s 2^(m_s - M) o_s / sum_s 2^(m_s - M) l_s over the pieces with l_s > 0, in
+// split order (M = the largest reference among them; any common reference gives the same quotient).  One thread per
+// four output elements of one (query token, head); grid (ceil(max_q_len * Hq * 32 / 256), B).
+__global__ __launch_bounds__(kThreads) void prefill_merge_kernel(PrefillParams p) {
+    constexpr int D = 128;
+    const int b = blockIdx.y;
+    const long long lin = (long long)blockIdx.x * kThreads + threadIdx.x;
+    const int d4 = (int)(lin & 31);
+    const long long rh = lin >> 5;
+    const int head = (int)(rh % p.Hq);
+    const long long qi = rh / p.Hq;
+    const int L = p.context_lens[b];
+    const int n_q = min(p.q_lens[b], L);
+    if (qi >= n_q || qi >= p.max_q_len) return;
+    // the split count of the row's query block, as the attention kernel derived it
+    const int QB = prefill_tokens_per_block(p.G);
+    const int wg_last = min(n_q, ((int)qi / QB + 1) * QB) - 1;
+    const int n_tiles = (L - n_q + wg_last) / kTile + 1;
+    const int ns_eff = prefill_effective_splits(p.num_splits, (n_tiles + 1) >> 1, p.min_split_steps);
+    if (ns_eff == 1) return;                                     // written by the attention kernel itself
+    const int NS = p.num_splits;
+    const size_t pi = (((size_t)b * p.max_q_len + qi) * p.Hq + head) * NS;
+    float M = -INFINITY, den = 0.f;
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < ns_eff; ++s) {
+        const float2 ml = p.part_ml[pi + s];
+        if (ml.y > 0.f) {
+            const float4 o = *reinterpret_cast<const float4 *>(p.part_o + (pi + s) * D + 4 * d4);
+            const float Mn = fmaxf(M, ml.x);
+            const float a = fast_exp2(M - Mn);                   // 0 while M is still -inf
+            const float w = fast_exp2(ml.x - Mn);
+            num.x = num.x * a + w * o.x; num.y = num.y * a + w * o.y;
+            num.z = num.z * a + w * o.z; num.w = num.w * a + w * o.w;
+            den = den * a + w * ml.y;
+            M = Mn;
+        }
+    }
+    const float inv = 1.f / den;                                 // the split that holds the token's own position has l > 0
+    const size_t at = ((size_t)(p.q_offsets[b] + qi) * p.Hq + head) * D + 4 * d4;
+    if (p.out_bf16) {
+        uint2 pk;
+        pk.x = (uint32_t)float_to_bf16_rne(num.x * inv) | ((uint32_t)float_to_bf16_rne(num.y * inv) << 16);
+        pk.y = (uint32_t)float_to_bf16_rne(num.z * inv) | ((uint32_t)float_to_bf16_rne(num.w * inv) << 16);
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(p.out) + at) = pk;
+    } else {
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.out) + at) = make_float4(num.x * inv, num.y * inv, num.z * inv, num.w * inv);
     }
 }
 

@@ -80,6 +80,25 @@ def test_tuning_validation_and_plan():
                      (omni.OMNI_TUNE_MIN_PARTITION, 48), (omni.OMNI_TUNE_FORCE_PARTITION, 40), (99, 1)]:
         with pytest.raises(omni.OmniError):
             h.omni_set_tuning(key, val)
+    # context split of multi-token queries: no workspace where the grid fills the chip or the split is switched off
+    one = omni.Handle(**good(batch=1, max_blocks_per_seq=2048))
+    assert one.omni_prefill_workspace_bytes(512) > 0
+    assert omni.Handle(**good(batch=64, max_blocks_per_seq=2048)).omni_prefill_workspace_bytes(512) == 0
+    assert omni.Handle(**good(batch=1, max_blocks_per_seq=8)).omni_prefill_workspace_bytes(64) == 0    # 128 tokens at most
+    one.omni_set_tuning(omni.OMNI_TUNE_PREFILL_SPLITS, 1)
+    assert one.omni_prefill_workspace_bytes(512) == 0
+    one.omni_set_tuning(omni.OMNI_TUNE_PREFILL_SPLITS, 3)
+    Hq, D = good()["num_q_heads"], good()["head_dim"]
+    assert one.omni_prefill_workspace_bytes(100) >= 100 * Hq * 3 * (D + 2) * 4
+    with pytest.raises(omni.OmniError):
+        one.omni_prefill_workspace_bytes(0)
+    for key, val in [(omni.OMNI_TUNE_PREFILL_SPLITS, 17), (omni.OMNI_TUNE_PREFILL_MIN_SPLIT, 0),
+                     (omni.OMNI_TUNE_PREFILL_MIN_SPLIT, 96)]:
+        with pytest.raises(omni.OmniError):
+            one.omni_set_tuning(key, val)
+    short = omni.Handle(**good(batch=1, max_blocks_per_seq=8))
+    short.omni_set_tuning(omni.OMNI_TUNE_PREFILL_MIN_SPLIT, 64)               # 128 tokens: two shares of 64
+    assert short.omni_prefill_workspace_bytes(64) >= 64 * Hq * 2 * (D + 2) * 4
     big = omni.Handle(**good(max_blocks_per_seq=4096))
     before = big.omni_workspace_bytes()
     big.omni_set_tuning(omni.OMNI_TUNE_FORCE_PARTITION, 32)

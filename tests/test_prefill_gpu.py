@@ -25,11 +25,16 @@ class ChunkOnDevice:
         self.out = torch.full((ch.total, wl.Hq, wl.D), float("nan"), dtype=out_dtype, device="cuda")
 
 
-def run_chunk(wl, ch, max_q_len=None, out_dtype=W.F32, tuning=None):
-    """Append the chunk's rows, then attend; returns (DeviceBatch, fp64 output with NaN in rows nobody owns)."""
+def run_chunk(wl, ch, max_q_len=None, out_dtype=W.F32, tuning=None, split_workspace=False):
+    """Append the chunk's rows, then attend; returns (DeviceBatch, fp64 output with NaN in rows nobody owns).
+    split_workspace: register a workspace large enough for the context split (poisoned with NaN first)."""
     dev = DeviceBatch(wl, out_dtype=out_dtype, tuning=tuning)
     c = ChunkOnDevice(dev, ch, torch.float32 if out_dtype == W.F32 else torch.bfloat16)
     mq = max_q_len or max(ch.max_q_len, 1)
+    if split_workspace:
+        n = max(dev.h.omni_workspace_bytes(), dev.h.omni_prefill_workspace_bytes(mq))
+        dev.ws = torch.full((n // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        dev.h.omni_set_workspace(dev.ws)
     dev.h.omni_kv_append_chunk(c.k_new, c.v_new, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens,
                                c.q_lens, c.q_offsets, mq)
     dev.h.omni_paged_prefill_attn(c.q, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens, c.q_lens,
@@ -253,3 +258,70 @@ def test_prefill_argument_errors():
     assert L.omni_paged_prefill_attn(hb._h, 256, 256, 256, 256, 256, 256, 256, 0, 1.0, 256, None) == 2
     assert L.omni_paged_prefill_attn(hb._h, 256, 256, 256, 256, 256, None, 256, 8, 1.0, 256, None) == 1
     assert L.omni_kv_append_chunk(hb._h, 256, 256, 256, 256, 256, 256, 256, 256 + 4, 8, None) == 2        # int64 array off by 4
+
+
+# --------------------------------------------------------------------------- context split
+SPLIT_CASES = {
+    # name: (context lengths, chunk lengths, G, Hkv, page size)
+    "one-long-request": ([3000], [300], 7, 4, 16),
+    "whole-prompt": ([1500], [1500], 4, 2, 32),
+    "ragged-batch": ([2100, 64, 1, 0, 700, 129, 65], [37, 64, 1, 0, 400, 1, 65], 7, 2, 16),
+    "short-contexts": ([40, 100, 63, 64, 65, 200], [40, 3, 63, 1, 65, 130], 8, 1, 16),     # fewer steps than splits
+    "group-16": ([900, 333], [90, 333], 16, 1, 32),
+}
+
+
+@pytest.mark.parametrize("splits,min_split", [(0, 1024), (0, 64), (2, 64), (3, 128), (7, 64), (16, 64), (16, 256)],
+                         ids=lambda v: str(v))
+@pytest.mark.parametrize("case", list(SPLIT_CASES))
+def test_context_split_against_the_oracle_and_the_unsplit_kernel(case, splits, min_split):
+    """The matrix-core kernel with every workgroup's context dealt to several workgroups and merged afterwards:
+    within the bar of the oracle for every split count (0 = the library's own choice) and smallest share (64 tokens:
+    every split the context has steps for is used; requests with fewer steps are shared by fewer workgroups or by
+    none, whose rows the merge must leave alone), and within a quarter of the
+    bar of the unsplit result (every piece rounds its weights to fp16 against a reference of its own, so the two
+    differ by rounding errors of the weights, not only by the order of summation).  The workspace starts out as NaN."""
+    lens, q_lens, G, Hkv, ps = SPLIT_CASES[case]
+    wl = W.build("split", 1300 + len(lens), lens, Hq=G * Hkv, Hkv=Hkv, D=128, ps=ps, dtype=W.BF16, pool_factor=1.5)
+    ch = W.add_chunk(wl, q_lens, 1301, in_cache=True, gap=2)
+    one, _ = check_chunk(wl, ch, label=f"{case} unsplit", tuning={omni.OMNI_TUNE_PREFILL_SPLITS: 1})
+    got, _ = check_chunk(wl, ch, label=f"{case} splits={splits}", split_workspace=True,
+                         tuning={omni.OMNI_TUNE_PREFILL_SPLITS: splits, omni.OMNI_TUNE_PREFILL_MIN_SPLIT: min_split})
+    assert np.nanmax(np.abs(got - one)) <= TOL[W.BF16] / 4
+
+
+def test_context_split_needs_its_workspace_and_is_repeatable():
+    """Without a workspace of omni_prefill_workspace_bytes the call does not split (bit-identical to splits = 1); with
+    it the result is bit-identical from call to call, also after the workspace was overwritten in between."""
+    wl = W.build("split", 1400, [2500, 900], Hq=28, Hkv=4, D=128, ps=16, dtype=W.BF16)
+    ch = W.add_chunk(wl, [128, 200], 1401, in_cache=True)
+    _, unsplit = run_chunk(wl, ch, tuning={omni.OMNI_TUNE_PREFILL_SPLITS: 1})
+    dev, small_ws = run_chunk(wl, ch)                                     # decode-sized workspace only
+    need = dev.h.omni_prefill_workspace_bytes(ch.max_q_len)
+    assert need > dev.h.omni_workspace_bytes() and dev.h.omni_get_plan()["kernel"] == omni.KERNEL_MFMA
+    assert np.array_equal(small_ws, unsplit, equal_nan=True)
+    dev, a = run_chunk(wl, ch, split_workspace=True)
+    assert not np.array_equal(a, unsplit, equal_nan=True)                 # it did split
+    c = ChunkOnDevice(dev, ch)
+    for poison in (0.0, float("inf")):
+        dev.ws.fill_(poison)
+        dev.h.omni_paged_prefill_attn(c.q, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens, c.q_lens,
+                                      c.q_offsets, ch.max_q_len, float(wl.scale), c.out)
+        torch.cuda.synchronize()
+        assert np.array_equal(c.out.cpu().numpy().astype(np.float64), a, equal_nan=True)
+
+
+def test_context_split_with_bf16_output_and_a_larger_max_q_len():
+    wl = W.build("split", 1500, [1800, 70], Hq=14, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    ch = W.add_chunk(wl, [100, 70], 1501, in_cache=True)
+    got, ref = None, None
+    dev, got = run_chunk(wl, ch, max_q_len=160, out_dtype=W.BF16, split_workspace=True,
+                         tuning={omni.OMNI_TUNE_PREFILL_SPLITS: 4})
+    ref = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                                    ch.q_offsets, wl.scale, wl.dtype)
+    owned = np.zeros(ch.total, dtype=bool)
+    for b in range(wl.B):
+        owned[ch.q_offsets[b]:ch.q_offsets[b] + ch.q_lens[b]] = True
+    err = np.abs(got[owned] - ref[owned])
+    assert np.all(err <= TOL[W.BF16] + np.abs(ref[owned]) * 2.0 ** -8)    # the bar plus a bf16 rounding of the result
+    assert np.all(np.isnan(got[~owned]))
