@@ -320,6 +320,27 @@ def test_max_context_hint_and_wide_table():
         assert np.max(np.abs(got - ref)) <= TOL[wl.dtype]
 
 
+@pytest.mark.parametrize("kernel", [omni.KERNEL_MFMA, omni.KERNEL_VALU], ids=["mfma", "valu"])
+@pytest.mark.parametrize("B", [5, 64, 67, 300])
+def test_lengths_at_any_four_byte_alignment(B, kernel):
+    """context_lens needs 4-byte alignment only: the plan reads it in 16-byte pieces where the address allows and
+    word by word otherwise (and for a batch that is no multiple of four); same bits either way."""
+    rng = np.random.default_rng(40 + B)
+    wl = W.build("align", 41 + B, rng.integers(0, 400, size=B), Hq=8, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    dev = DeviceBatch(wl, tuning={omni.OMNI_TUNE_KERNEL: kernel})
+    ref = oracle_out(wl)
+    outs = []
+    for off in range(4):
+        buf = torch.zeros(B + 4, dtype=torch.int32, device="cuda")
+        buf[off:off + B] = torch.from_numpy(wl.context_lens).cuda()
+        dev.context_lens = buf[off:off + B]
+        assert dev.context_lens.data_ptr() % 16 == 4 * off
+        got = dev.attend()
+        assert np.max(np.abs(got - ref)) <= TOL[wl.dtype], f"offset {off}"
+        outs.append(got)
+    assert all(np.array_equal(outs[0], o) for o in outs[1:])
+
+
 # --------------------------------------------------------------------------- full-size configurations, sampled rows
 FULL = ["thinker", "talker", "long", "mixed"]
 
