@@ -102,6 +102,85 @@ def test_replayed_decode_steps_match_oracle_and_eager(name, kw):
     g.close()
 
 
+def test_replayed_chunk_steps_with_a_split_context_match_oracle_and_eager():
+    """omni_kv_append_chunk + omni_paged_prefill_attn with the context shared between workgroups (attention and merge
+    kernels) recorded once and replayed for three consecutive chunks of the same requests: lengths, chunk lengths,
+    offsets, queries and new rows change in place between the replays."""
+    chunks = [np.array([64, 17, 0], dtype=np.int32), np.array([33, 64, 1], dtype=np.int32),
+              np.array([1, 40, 64], dtype=np.int32)]
+    start = np.array([900, 300, 0], dtype=np.int64)
+    final = start + sum(c.astype(np.int64) for c in chunks)
+    wl = W.build("graph-chunks", 77, final, Hq=14, Hkv=2, D=128, ps=16, dtype=W.BF16, pool_factor=1.5)
+    k_full, v_full = wl.k_cache.copy(), wl.v_cache.copy()
+    blank_rows(wl.k_cache, wl, start, final)
+    blank_rows(wl.v_cache, wl, start, final)
+    MQ, ROWS = 64, 3 * 64 + 8
+    tuning = {omni.OMNI_TUNE_PREFILL_SPLITS: 4, omni.OMNI_TUNE_PREFILL_MIN_SPLIT: 128}
+    sides = [DeviceBatch(wl, tuning=tuning), DeviceBatch(wl, tuning=tuning)]
+    for side in sides:
+        side.ws = side.h.alloc_workspace(prefill_max_q_len=MQ)
+        assert side.h.omni_prefill_workspace_bytes(MQ) > 0
+    graph_side, eager_side = sides
+    stream = torch.cuda.Stream()
+    dt = graph_side.k_cache.dtype
+    q = torch.zeros((ROWS, wl.Hq, wl.D), dtype=dt, device="cuda")
+    k_new = torch.zeros((ROWS, wl.Hkv, wl.D), dtype=dt, device="cuda")
+    v_new = torch.zeros_like(k_new)
+    lens = torch.zeros(wl.B, dtype=torch.int32, device="cuda")
+    q_lens = torch.zeros(wl.B, dtype=torch.int32, device="cuda")
+    q_offs = torch.zeros(wl.B, dtype=torch.int64, device="cuda")
+    outs = [torch.zeros((ROWS, wl.Hq, wl.D), dtype=torch.float32, device="cuda") for _ in sides]
+
+    def call(side, out, s):
+        side.h.omni_kv_append_chunk(k_new, v_new, side.k_cache, side.v_cache, side.block_table, lens, q_lens, q_offs, MQ, s)
+        side.h.omni_paged_prefill_attn(q, side.k_cache, side.v_cache, side.block_table, lens, q_lens, q_offs, MQ,
+                                       float(wl.scale), out, s)
+
+    call(graph_side, outs[0], stream)                        # nothing to do yet (all lengths zero)
+    torch.cuda.synchronize()
+    with omni.Graph(stream) as g:
+        call(graph_side, outs[0], stream)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(8)
+    done = start.copy()
+    for step, n in enumerate(chunks):
+        cur = (done + n).astype(np.int32)
+        offs = np.array([0, 64 + step, 128 + 2 * step], dtype=np.int64)      # rows of the requests inside the row buffers
+        qf = rng.standard_normal((ROWS, wl.Hq, wl.D)).astype(np.float32)
+        q_host = W.f32_to_bf16_bits(qf)
+        kn = np.zeros((ROWS, wl.Hkv, wl.D), dtype=np.uint16); vn = np.zeros_like(kn)
+        for b in range(wl.B):
+            for i in range(int(n[b])):
+                t = int(done[b]) + i
+                kn[offs[b] + i] = k_full[wl.block_table[b, t // wl.ps], :, t % wl.ps, :]
+                vn[offs[b] + i] = v_full[wl.block_table[b, t // wl.ps], :, t % wl.ps, :]
+        q.copy_(to_dev(q_host, wl.dtype)); k_new.copy_(to_dev(kn, wl.dtype)); v_new.copy_(to_dev(vn, wl.dtype))
+        lens.copy_(torch.from_numpy(cur).cuda()); q_lens.copy_(torch.from_numpy(n).cuda()); q_offs.copy_(torch.from_numpy(offs).cuda())
+        for o in outs:
+            o.fill_(float("nan"))
+        _ = float(q.float().abs().sum())
+        torch.cuda.synchronize()
+
+        g.launch()
+        call(eager_side, outs[1], None)
+        torch.cuda.synchronize()
+
+        got = outs[0].cpu().numpy().astype(np.float64)
+        assert np.array_equal(got, outs[1].cpu().numpy().astype(np.float64), equal_nan=True), f"chunk {step}: replay != eager"
+        assert np.array_equal(as_bytes(bits_of(graph_side.k_cache)), as_bytes(bits_of(eager_side.k_cache)))
+        ref = oracle.paged_prefill_attn(q_host, k_full, v_full, wl.block_table, cur, n, offs, wl.scale, wl.dtype)
+        owned = np.zeros(ROWS, dtype=bool)
+        for b in range(wl.B):
+            owned[offs[b]:offs[b] + n[b]] = True
+        assert np.all(np.isnan(got[~owned]))
+        assert np.max(np.abs(got[owned] - ref[owned])) <= TOL[wl.dtype], f"chunk {step}"
+        done = done + n
+    assert np.array_equal(as_bytes(bits_of(graph_side.k_cache)), as_bytes(k_full))
+    assert np.array_equal(as_bytes(bits_of(graph_side.v_cache)), as_bytes(v_full))
+    g.close()
+
+
 def test_graph_rejects_the_null_stream():
     L = omni.lib()
     assert L.omni_graph_begin(None) == 4
