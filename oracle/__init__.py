@@ -45,6 +45,9 @@ def lib():
         L.oracle_paged_decode_attn_fp8.restype = C.c_int
         L.oracle_paged_decode_attn_fp8.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 7 + [C.c_float, C.c_void_p,
                                                                                            C.c_void_p, C.c_int32, C.c_int32]
+        L.oracle_paged_prefill_attn_fp8.restype = C.c_int
+        L.oracle_paged_prefill_attn_fp8.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 9 + [C.c_float, C.c_void_p,
+                                                                                            C.c_void_p, C.c_int64, C.c_int32]
         L.oracle_gather.restype = None
         L.oracle_gather.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 3 + [C.c_int32, C.c_void_p]
         _lib = L
@@ -245,3 +248,36 @@ def paged_decode_attn_fp8(q, k_cache, v_cache, k_scale, v_scale, block_table, co
         lib().oracle_paged_decode_attn_fp8(C.byref(s), _p(q), _p(k_cache), _p(v_cache), _p(ks), _p(vs), _p(bt), _p(lens),
                                            C.c_float(scale), _p(out), None, 0, num_threads)
     return out
+
+
+def paged_prefill_attn_fp8(q, k_cache, v_cache, k_scale, v_scale, block_table, context_lens, q_lens, q_offsets, scale,
+                           rows: Optional[Sequence[Tuple[int, int, int]]] = None, num_threads: int = 0) -> np.ndarray:
+    """Multi-token (chunk) queries over the 8-bit (E4M3) cache with one fp32 scale per (page, KV head); q is bf16 bits
+    [Tq, Hq, D].  fp64 [Tq, Hq, D], or [len(rows), D] for (b, i, h) triples."""
+    _check(q, "bf16", "q")
+    assert k_cache.dtype == np.uint8 and v_cache.dtype == np.uint8 and k_cache.flags.c_contiguous
+    Tq, Hq, D = q.shape
+    P, Hkv, ps, D2 = k_cache.shape
+    assert D == D2 and Hq % Hkv == 0 and k_scale.shape == (P, Hkv) and v_scale.shape == (P, Hkv)
+    s = _Shape(block_table.shape[0], Hq, Hkv, D, ps, block_table.shape[1], _DT["bf16"], 2)
+    bt = np.ascontiguousarray(block_table, dtype=np.int32)
+    lens = np.ascontiguousarray(context_lens, dtype=np.int32)
+    ql = np.ascontiguousarray(q_lens, dtype=np.int32)
+    qo = np.ascontiguousarray(q_offsets, dtype=np.int64)
+    ks = np.ascontiguousarray(k_scale, dtype=np.float32)
+    vs = np.ascontiguousarray(v_scale, dtype=np.float32)
+    for b in range(block_table.shape[0]):                    # the C code trusts these
+        if ql[b] > 0 and (ql[b] > lens[b] or qo[b] < 0 or qo[b] + ql[b] > Tq):
+            raise ValueError(f"request {b}: chunk of {ql[b]} rows at {qo[b]} does not fit (context {lens[b]}, {Tq} rows)")
+    r, n = None, 0
+    if rows is not None:
+        r = np.ascontiguousarray(np.asarray(rows, dtype=np.int32).reshape(-1, 3))
+        for b, i, h in r:
+            if not (0 <= b < block_table.shape[0] and 0 <= i < ql[b] and 0 <= h < Hq):
+                raise ValueError(f"row ({b}, {i}, {h}) is outside the chunks")
+        n = len(r)
+    out = np.zeros((n, D) if rows is not None else (Tq, Hq, D), dtype=np.float64)
+    lib().oracle_paged_prefill_attn_fp8(C.byref(s), _p(q), _p(k_cache), _p(v_cache), _p(ks), _p(vs), _p(bt), _p(lens),
+                                        _p(ql), _p(qo), C.c_float(scale), _p(out), _p(r), n, num_threads)
+    return out
+

@@ -362,3 +362,77 @@ int oracle_paged_decode_attn_fp8(const oracle_shape_t *s, const void *q, const u
     }
     return used;
 }
+
+/*
+ * Multi-token queries over the quantised cache: the chunk definition above (query i of request b at position
+ * p = context_lens[b] - q_lens[b] + i attends to tokens 0 .. p), taken over the de-quantised rows
+ * decode(byte) * scale[page, kv head].  `rows` as above.
+ * Pins: one-token chunks equal oracle_paged_decode_attn_fp8; with power-of-two scales the result equals, bit for
+ * bit, oracle_paged_prefill_attn on the de-quantised fp32 pools; general scales against a dense causal brute force.
+ */
+int oracle_paged_prefill_attn_fp8(const oracle_shape_t *s, const void *q, const uint8_t *k_cache, const uint8_t *v_cache,
+                                  const float *k_scale, const float *v_scale, const int32_t *block_table,
+                                  const int32_t *context_lens, const int32_t *q_lens, const int64_t *q_offsets,
+                                  float scale, double *out, const int32_t *rows, int64_t nrows, int32_t num_threads)
+{
+    int G = s->Hq / s->Hkv;
+    int64_t total = nrows;
+    int64_t *first = NULL;
+    if (!rows) {
+        first = (int64_t *)malloc(sizeof(int64_t) * (size_t)(s->B + 1));
+        first[0] = 0;
+        for (int b = 0; b < s->B; ++b) first[b + 1] = first[b] + (q_lens[b] > 0 ? q_lens[b] : 0);
+        total = first[s->B] * s->Hq;
+    }
+    int used = 1;
+#ifdef _OPENMP
+    if (num_threads > 0) omp_set_num_threads(num_threads);
+    #pragma omp parallel
+    {
+        #pragma omp single
+        used = omp_get_num_threads();
+    }
+    #pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int64_t r = 0; r < total; ++r) {
+        int b, i, h;
+        if (rows) { b = rows[3 * r]; i = rows[3 * r + 1]; h = rows[3 * r + 2]; }
+        else {
+            int64_t row = r / s->Hq;
+            h = (int)(r % s->Hq);
+            b = 0;
+            while (first[b + 1] <= row) ++b;
+            i = (int)(row - first[b]);
+        }
+        int g = h / G;
+        int n = context_lens[b] - q_lens[b] + i + 1;              /* tokens 0 .. p */
+        int64_t qoff = ((q_offsets[b] + i) * s->Hq + h) * s->D;
+        double *o = rows ? out + r * s->D : out + ((q_offsets[b] + i) * s->Hq + h) * s->D;
+        for (int d = 0; d < s->D; ++d) o[d] = 0.0;
+        if (n <= 0) continue;
+        double *sc = (double *)malloc(sizeof(double) * (size_t)n);
+        double m = -INFINITY;
+        for (int t = 0; t < n; ++t) {
+            int64_t page = block_table[(int64_t)b * s->MB + t / s->ps];
+            int64_t koff = row_offset(s, block_table, b, g, t);
+            double ks = (double)k_scale[page * s->Hkv + g], acc = 0.0;
+            for (int d = 0; d < s->D; ++d)
+                acc += widen(q, qoff + d, s->q_dtype) * (oracle_fp8_e4m3_decode(k_cache[koff + d]) * ks);
+            sc[t] = (double)scale * acc;
+            if (sc[t] > m) m = sc[t];
+        }
+        double l = 0.0;
+        for (int t = 0; t < n; ++t) {
+            double p = exp(sc[t] - m);
+            l += p;
+            int64_t page = block_table[(int64_t)b * s->MB + t / s->ps];
+            int64_t voff = row_offset(s, block_table, b, g, t);
+            double vs = (double)v_scale[page * s->Hkv + g];
+            for (int d = 0; d < s->D; ++d) o[d] += p * (oracle_fp8_e4m3_decode(v_cache[voff + d]) * vs);
+        }
+        for (int d = 0; d < s->D; ++d) o[d] /= l;
+        free(sc);
+    }
+    free(first);
+    return used;
+}

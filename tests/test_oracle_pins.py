@@ -561,6 +561,63 @@ def test_fp8_attention_with_general_scales_and_quantisation_error_is_small():
     assert 1e-5 < d < 0.2
 
 
+def _fp8_chunk_case(seed, power_of_two):
+    wl = W.build("f8c", seed, [70, 5, 33, 1, 0, 90], Hq=6, Hkv=2, D=64, ps=16, dtype=W.BF16, pool_factor=1.5)
+    ch = W.add_chunk(wl, [40, 5, 1, 1, 0, 17], seed + 1, in_cache=True, gap=2)
+    return wl, ch, W.quantize_fp8(wl, power_of_two_scales=power_of_two)
+
+
+def test_fp8_chunks_of_one_token_are_the_fp8_decode_oracle():
+    wl = W.build("f8c", 53, [37, 5, 64, 1, 0, 90], Hq=6, Hkv=2, D=64, ps=16, dtype=W.BF16, pool_factor=1.5)
+    f8 = W.quantize_fp8(wl)
+    ones = np.where(wl.context_lens > 0, 1, 0).astype(np.int32)
+    offs = np.arange(wl.B, dtype=np.int64)
+    got = oracle.paged_prefill_attn_fp8(wl.q, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                                        wl.context_lens, ones, offs, wl.scale)
+    ref = oracle.paged_decode_attn_fp8(wl.q, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                                       wl.context_lens, wl.scale)
+    assert np.array_equal(got, ref)
+
+
+def test_fp8_chunks_with_power_of_two_scales_are_the_chunk_oracle_on_dequantised_pools():
+    wl, ch, f8 = _fp8_chunk_case(54, True)
+    got = oracle.paged_prefill_attn_fp8(ch.q, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                                        wl.context_lens, ch.q_lens, ch.q_offsets, wl.scale)
+    kd, vd = _dequantized(wl, f8)
+    ref = oracle.paged_prefill_attn(W.bf16_bits_to_f32(ch.q), kd, vd, wl.block_table, wl.context_lens, ch.q_lens,
+                                    ch.q_offsets, wl.scale, W.F32)
+    assert np.array_equal(got, ref)
+    rows = [(0, 0, 0), (0, 39, 5), (5, 16, 3), (2, 0, 1)]
+    some = oracle.paged_prefill_attn_fp8(ch.q, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                                         wl.context_lens, ch.q_lens, ch.q_offsets, wl.scale, rows=rows)
+    for r, (b, i, h) in enumerate(rows):
+        assert np.array_equal(some[r], got[ch.q_offsets[b] + i, h])
+
+
+def test_fp8_chunks_with_general_scales_against_a_dense_causal_brute_force():
+    import torch
+    wl, ch, f8 = _fp8_chunk_case(55, False)
+    got = oracle.paged_prefill_attn_fp8(ch.q, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                                        wl.context_lens, ch.q_lens, ch.q_offsets, wl.scale)
+    kd = torch.from_numpy(f8.k_cache).view(torch.float8_e4m3fn).to(torch.float64).numpy() * f8.k_scale.astype(np.float64)[:, :, None, None]
+    vd = torch.from_numpy(f8.v_cache).view(torch.float8_e4m3fn).to(torch.float64).numpy() * f8.v_scale.astype(np.float64)[:, :, None, None]
+    qf = W.bf16_bits_to_f32(ch.q).astype(np.float64)
+    for b in range(wl.B):
+        L, n = int(wl.context_lens[b]), int(ch.q_lens[b])
+        if n == 0:
+            continue
+        t = np.arange(L)
+        K = np.repeat(kd[wl.block_table[b, t // wl.ps], :, t % wl.ps, :], wl.G, axis=1)
+        V = np.repeat(vd[wl.block_table[b, t // wl.ps], :, t % wl.ps, :], wl.G, axis=1)
+        Q = qf[ch.q_offsets[b]:ch.q_offsets[b] + n]                                  # [n, Hq, D]
+        S = np.einsum("ihd,thd->iht", Q, K) * float(wl.scale)
+        pos = L - n + np.arange(n)
+        S = np.where(t[None, None, :] <= pos[:, None, None], S, -np.inf)              # causal inside the chunk
+        Pm = np.exp(S - S.max(axis=2, keepdims=True)); Pm /= Pm.sum(axis=2, keepdims=True)
+        ref = np.einsum("iht,thd->ihd", Pm, np.nan_to_num(V))                          # rows beyond a position weigh 0
+        assert np.max(np.abs(got[ch.q_offsets[b]:ch.q_offsets[b] + n] - ref)) < 1e-12
+
+
 def test_chunk_oracle_rejects_rows_outside_the_chunks():
     wl, ch = _chunk_case(seed=61)
     args = (ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens, ch.q_offsets, wl.scale, wl.dtype)
