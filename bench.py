@@ -239,21 +239,32 @@ def main():
     # token) pair.  (a) 32 thinker-shaped requests, each with a chunk of 512 new tokens at the end of its context: the
     # query blocks fill the chip.  (b) ONE long request (about 30k tokens of context) with a 512-token chunk: 60
     # workgroups unless the context is split, measured both ways.
-    def measure_prefill(pw, chunk, split):
+    def measure_prefill(pw, chunk, split, fp8=False):
         ch = W.add_chunk(pw, [chunk] * pw.B, 77, in_cache=True)
         ph = omni.Handle(batch=pw.B, num_q_heads=pw.Hq, num_kv_heads=pw.Hkv, head_dim=pw.D, page_size=pw.ps,
-                         num_pages=pw.P, max_blocks_per_seq=pw.MB, kv_dtype=kvd, out_dtype=omni.OMNI_F32)
+                         num_pages=pw.P, max_blocks_per_seq=pw.MB, kv_dtype=omni.OMNI_FP8_E4M3 if fp8 else kvd,
+                         q_dtype=omni.OMNI_BF16, out_dtype=omni.OMNI_F32)
         if not split:
             ph.omni_set_tuning(omni.OMNI_TUNE_PREFILL_SPLITS, 1)
         pws = ph.alloc_workspace(prefill_max_q_len=ch.max_q_len)
-        pq, pk, pv = to_dev(ch.q, pw.dtype), to_dev(pw.k_cache, pw.dtype), to_dev(pw.v_cache, pw.dtype)
+        pq = to_dev(ch.q, pw.dtype)
+        if fp8:
+            p8 = W.quantize_fp8(pw)
+            pk, pv = torch.from_numpy(p8.k_cache).cuda(), torch.from_numpy(p8.v_cache).cuda()
+            pks, pvs = torch.from_numpy(p8.k_scale).cuda(), torch.from_numpy(p8.v_scale).cuda()
+        else:
+            pk, pv = to_dev(pw.k_cache, pw.dtype), to_dev(pw.v_cache, pw.dtype)
         pbt, plens = torch.from_numpy(pw.block_table).cuda(), torch.from_numpy(pw.context_lens).cuda()
         pql, pqo = torch.from_numpy(ch.q_lens).cuda(), torch.from_numpy(ch.q_offsets).cuda()
         pout = torch.empty((ch.total, pw.Hq, pw.D), dtype=torch.float32, device="cuda")
         Lh, nh = pw.context_lens.astype(np.int64), ch.q_lens.astype(np.int64)
         pairs = int(np.sum(nh * (Lh - nh) + nh * (nh + 1) // 2))
         flops = 4.0 * pw.D * pw.Hq * pairs
-        run = lambda: ph.omni_paged_prefill_attn(pq, pk, pv, pbt, plens, pql, pqo, ch.max_q_len, float(pw.scale), pout, stream)
+        if fp8:
+            run = lambda: ph.omni_paged_prefill_attn_fp8(pq, pk, pv, pks, pvs, pbt, plens, pql, pqo, ch.max_q_len,
+                                                         float(pw.scale), pout, stream)
+        else:
+            run = lambda: ph.omni_paged_prefill_attn(pq, pk, pv, pbt, plens, pql, pqo, ch.max_q_len, float(pw.scale), pout, stream)
         for _ in range(3):
             run()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
@@ -267,8 +278,12 @@ def main():
         rows = [(live[0], 0, 0), (live[-1], int(ch.q_lens[live[-1]]) - 1, pw.Hq - 1),
                 (live[len(live) // 2], int(ch.q_lens[live[len(live) // 2]]) // 2, 3)]
         import oracle as _oracle
-        pref = _oracle.paged_prefill_attn(ch.q, pw.k_cache, pw.v_cache, pw.block_table, pw.context_lens, ch.q_lens,
-                                          ch.q_offsets, pw.scale, pw.dtype, rows=rows)
+        if fp8:
+            pref = _oracle.paged_prefill_attn_fp8(ch.q, p8.k_cache, p8.v_cache, p8.k_scale, p8.v_scale, pw.block_table,
+                                                  pw.context_lens, ch.q_lens, ch.q_offsets, pw.scale, rows=rows)
+        else:
+            pref = _oracle.paged_prefill_attn(ch.q, pw.k_cache, pw.v_cache, pw.block_table, pw.context_lens, ch.q_lens,
+                                              ch.q_offsets, pw.scale, pw.dtype, rows=rows)
         pgot = pout.cpu().numpy().astype(np.float64)
         perr = float(max(np.max(np.abs(pgot[ch.q_offsets[b] + i, hh] - pref[r])) for r, (b, i, hh) in enumerate(rows)))
         if not (perr <= 2e-3):
@@ -284,6 +299,7 @@ def main():
         pw = W.make(wl.name, batch=min(32, wl.B), append=False)
         prefill = {"kernel": "prefill_mfma_kernel", "workload": f"{pw.B} {pw.name}-shaped requests, chunk of 512 tokens each"}
         prefill.update(measure_prefill(pw, 512, True))
+        prefill["over_8bit_kv_cache"] = measure_prefill(pw, 512, True, fp8=True)
         p1 = W.make("long", batch=1, append=False)
         prefill_one = {"kernel": "prefill_mfma_kernel + prefill_merge_kernel",
                        "workload": f"one request of {int(p1.context_lens[0])} tokens, chunk of 512 tokens",

@@ -143,7 +143,8 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h,
  * Bytes are widened exactly to bf16 in registers, products and sums are fp32, the K scale joins the softmax scale and
  * the V scale the softmax weights.  NaN bytes in slots no live token owns never reach the result.
  * omni_kv_append, omni_kv_pack and omni_kv_unpack move the bytes of such a cache like any other (scales are the
- * caller's); omni_paged_decode_attn, omni_decode_step and omni_paged_prefill_attn return OMNI_ERR_UNSUPPORTED for it.
+ * caller's); omni_paged_decode_attn, omni_decode_step and omni_paged_prefill_attn return OMNI_ERR_UNSUPPORTED for it
+ * (multi-token queries over such a cache: omni_paged_prefill_attn_fp8).  Scales must be positive.
  * Errors: NULL, SHAPE (alignment), UNSUPPORTED (handle is not an fp8 one), WORKSPACE, HIP.
  */
 omni_status_t omni_paged_decode_attn_fp8(omni_handle_t h,
@@ -211,7 +212,7 @@ omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v
  * non-finite one) makes non-finite outputs for the queries of its request whose tiles reach it, never wrong finite
  * ones; and scale must be positive.  Every other fp32 / bf16 configuration (and this one under OMNI_TUNE_KERNEL = 1)
  * runs a plain vector-ALU kernel in fp32 arithmetic, without those two conditions.  An 8-bit cache:
- * OMNI_ERR_UNSUPPORTED.
+ * OMNI_ERR_UNSUPPORTED here, see omni_paged_prefill_attn_fp8.
  * One launch and no workspace, unless the call would leave most of the chip idle (few requests, short chunks: a
  * workgroup owns floor(256 / group size) query tokens of one request and KV head) and the registered workspace holds
  * at least omni_prefill_workspace_bytes(max_q_len): then the matrix-core path lets up to 16 workgroups share a
@@ -224,6 +225,16 @@ omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v
 omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
                                       const int32_t *block_table, const int32_t *context_lens, const int32_t *q_lens,
                                       const int64_t *q_offsets, int32_t max_q_len, float scale, void *out, void *stream);
+
+/* omni_paged_prefill_attn over the quantised cache of omni_paged_decode_attn_fp8 (same handle, pools and scales; same
+ * matrix-core kernel, context split and workspace rule).  K bytes are widened exactly to bf16; a V element enters the
+ * weighted sum as decode(byte) * scale rounded once to fp16 (relative error 2^-12; its magnitude must stay within the
+ * fp16 range as above); the K scale of a page joins the softmax scale.  scale must be positive.
+ * Errors: NULL, SHAPE, UNSUPPORTED (handle is not an fp8 one), HIP. */
+omni_status_t omni_paged_prefill_attn_fp8(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
+                                          const float *k_scale, const float *v_scale, const int32_t *block_table,
+                                          const int32_t *context_lens, const int32_t *q_lens, const int64_t *q_offsets,
+                                          int32_t max_q_len, float scale, void *out, void *stream);
 
 /* The multi-token form of omni_kv_append: row q_offsets[b] + i of k_new / v_new [total rows, num_kv_heads, head_dim]
  * is copied, bit for bit, to position context_lens[b] - q_lens[b] + i of request b, for i < q_lens[b].  Any dtype

@@ -66,7 +66,8 @@ struct omni_handle_s {
     // at most half of the compute units, as many workgroups per (query block, KV head, request) as it takes to fill
     // them, at most 16 and no more than the longest context the handle allows can use.  1 = no split.
     int prefill_splits(int max_q_len) const {
-        if (!(d.kv_dtype == OMNI_BF16 && d.head_dim == 128 && tune_kernel != 1) || tune_prefill_splits == 1) return 1;
+        const bool mfma = (d.kv_dtype == OMNI_BF16 && d.head_dim == 128 && tune_kernel != 1) || d.kv_dtype == OMNI_FP8_E4M3;
+        if (!mfma || tune_prefill_splits == 1) return 1;
         const int qb = prefill_tokens_per_block(G);
         const long long wgs = (long long)((max_q_len + qb - 1) / qb) * d.num_kv_heads * d.batch;
         const int by_ctx = (max_ctx + 2 * kTile - 1) / (2 * kTile) / (tune_prefill_min_split / (2 * kTile));
@@ -515,20 +516,25 @@ omni_status_t omni_kv_append_chunk(omni_handle_t h, const void *k_new, const voi
                        max_q_len);
 }
 
-omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
-                                      const int32_t *block_table, const int32_t *context_lens, const int32_t *q_lens,
-                                      const int64_t *q_offsets, int32_t max_q_len, float scale, void *out, void *stream) {
+// The launch shared by omni_paged_prefill_attn (k_scale = v_scale = null) and omni_paged_prefill_attn_fp8.
+static omni_status_t launch_prefill(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
+                                    const float *k_scale, const float *v_scale, const int32_t *block_table,
+                                    const int32_t *context_lens, const int32_t *q_lens, const int64_t *q_offsets,
+                                    int32_t max_q_len, float scale, void *out, void *stream) {
     if (!h || !q || !k_cache || !v_cache || !block_table || !context_lens || !q_lens || !q_offsets || !out)
         return OMNI_ERR_NULL;
     const omni_attn_desc_t &d = h->d;
-    if (d.kv_dtype == OMNI_FP8_E4M3) return OMNI_ERR_UNSUPPORTED;
-    const bool mfma = d.kv_dtype == OMNI_BF16 && d.head_dim == 128 && h->tune_kernel != 1;
+    const bool fp8 = d.kv_dtype == OMNI_FP8_E4M3;
+    if (fp8 != (k_scale != nullptr)) return OMNI_ERR_UNSUPPORTED;
+    if (fp8 && (!v_scale || misaligned(k_scale, 4) || misaligned(v_scale, 4))) return v_scale ? OMNI_ERR_SHAPE : OMNI_ERR_NULL;
+    const bool mfma = fp8 || (d.kv_dtype == OMNI_BF16 && d.head_dim == 128 && h->tune_kernel != 1);
     if (max_q_len <= 0 || (mfma && !(scale > 0.f))) return OMNI_ERR_SHAPE;
     if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(out, 16) ||
         misaligned(block_table, 4) || misaligned(context_lens, 4) || misaligned(q_lens, 4) || misaligned(q_offsets, 8))
         return OMNI_ERR_SHAPE;
     PrefillParams p;
     p.q = q; p.k_cache = k_cache; p.v_cache = v_cache;
+    p.k_scale = k_scale; p.v_scale = v_scale;
     p.block_table = block_table; p.context_lens = context_lens; p.q_lens = q_lens;
     p.q_offsets = reinterpret_cast<const long long *>(q_offsets);
     p.out = out;
@@ -547,8 +553,13 @@ omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     (void)hipGetLastError();
     if (mfma) {
-        if (d.page_size == 16) prefill_mfma_kernel<16><<<grid, kPrefillThreads, 0, s>>>(p);
-        else prefill_mfma_kernel<32><<<grid, kPrefillThreads, 0, s>>>(p);
+        if (fp8) {
+            if (d.page_size == 16) prefill_mfma_kernel<16, true><<<grid, kPrefillThreads, 0, s>>>(p);
+            else prefill_mfma_kernel<32, true><<<grid, kPrefillThreads, 0, s>>>(p);
+        } else {
+            if (d.page_size == 16) prefill_mfma_kernel<16><<<grid, kPrefillThreads, 0, s>>>(p);
+            else prefill_mfma_kernel<32><<<grid, kPrefillThreads, 0, s>>>(p);
+        }
         if (ns > 1) {
             if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
             const long long items = (long long)max_q_len * d.num_q_heads * 32;
@@ -566,6 +577,23 @@ omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void
     }
     if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
     return OMNI_OK;
+}
+
+omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
+                                      const int32_t *block_table, const int32_t *context_lens, const int32_t *q_lens,
+                                      const int64_t *q_offsets, int32_t max_q_len, float scale, void *out, void *stream) {
+    return launch_prefill(h, q, k_cache, v_cache, nullptr, nullptr, block_table, context_lens, q_lens, q_offsets, max_q_len,
+                          scale, out, stream);
+}
+
+omni_status_t omni_paged_prefill_attn_fp8(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
+                                          const float *k_scale, const float *v_scale, const int32_t *block_table,
+                                          const int32_t *context_lens, const int32_t *q_lens, const int64_t *q_offsets,
+                                          int32_t max_q_len, float scale, void *out, void *stream) {
+    if (!h || !k_scale || !v_scale) return OMNI_ERR_NULL;
+    if (h->d.kv_dtype != OMNI_FP8_E4M3) return OMNI_ERR_UNSUPPORTED;
+    return launch_prefill(h, q, k_cache, v_cache, k_scale, v_scale, block_table, context_lens, q_lens, q_offsets, max_q_len,
+                          scale, out, stream);
 }
 
 struct omni_graph_s {

@@ -73,9 +73,21 @@ __device__ __forceinline__ uint4 bf16x8_to_f16x8(const uint4 &v) {
     return r;
 }
 
+// Eight E4M3 bytes times a scale -> eight fp16 values: widened exactly (bf16, then fp32), scaled in fp32, rounded once.
+__device__ __forceinline__ uint4 fp8x8_scaled_to_f16x8(uint32_t lo, uint32_t hi, float sc) {
+    const uint4 v = fp8x8_to_bf16x8(lo, hi);
+    uint4 r;
+    r.x = pack_f16x2(bf16_bits_to_float(v.x & 0xffffu) * sc, __uint_as_float(v.x & 0xffff0000u) * sc);
+    r.y = pack_f16x2(bf16_bits_to_float(v.y & 0xffffu) * sc, __uint_as_float(v.y & 0xffff0000u) * sc);
+    r.z = pack_f16x2(bf16_bits_to_float(v.z & 0xffffu) * sc, __uint_as_float(v.z & 0xffff0000u) * sc);
+    r.w = pack_f16x2(bf16_bits_to_float(v.w & 0xffffu) * sc, __uint_as_float(v.w & 0xffff0000u) * sc);
+    return r;
+}
+
 struct PrefillParams {
     const void *q;                    // [Tq, Hq, D] bf16
     const void *k_cache, *v_cache;
+    const float *k_scale, *v_scale;   // 8-bit cache only (else null): [P, Hkv] scales of the K and V pools
     const int32_t *block_table, *context_lens, *q_lens;
     const long long *q_offsets;
     void *out;                        // [Tq, Hq, D]
@@ -102,12 +114,18 @@ __device__ __forceinline__ int prefill_effective_splits(int num_splits, int n_st
 // cut into runs of 32 for the waves wherever that falls.
 __host__ __device__ inline int prefill_tokens_per_block(int G) { return kPrefillWaves * kPrefillCols / G; }
 
-template <int PS>
+// KV8: the pools hold 8-bit E4M3 bytes with one scale per (page, KV head).  The staging threads widen K to bf16
+// (exact) and V times its page's scale to fp16 (one rounding, 2^-12 relative: the size of the weights' own rounding) on
+// the way into shared memory, so the products are the 16-bit ones; the K scale of each 16-token half of a tile joins
+// the softmax scale in the exponent's multiply-add.
+template <int PS, bool KV8 = false>
 __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(PrefillParams p) {
     constexpr int D = 128;
+    constexpr int ES = KV8 ? 1 : 2;                              // bytes per cache element
     constexpr int kLog2Ps = (PS == 16) ? 4 : 5;
     constexpr int kTileBytes = kTile * kPrefillVRowBytes;        // room for one K or V tile in shared memory
     __shared__ __align__(16) char smem[2][2][2][kTileBytes];     // [buffer][tile of the step][K, V]
+    __shared__ float kscale_lds[2][2][2];                        // 8-bit cache: [buffer][tile][16-token half] K scales
 
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int G = p.G, head0 = kvh * G;
@@ -158,9 +176,9 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     // ---- staging: a step is 64 tokens = two 32-token tiles; thread t moves piece t of the 512 16-byte pieces of
     // each tile's K rows and V rows (piece = 16 * token + chunk).  The products below run as a pipeline in which V of a
     // tile is needed two tiles after its K, so V is fetched and staged one step behind K.
-    const size_t page_stride = (size_t)p.Hkv * PS * D * 2;
-    const char *kbase = reinterpret_cast<const char *>(p.k_cache) + (size_t)kvh * PS * D * 2;
-    const char *vbase = reinterpret_cast<const char *>(p.v_cache) + (size_t)kvh * PS * D * 2;
+    const size_t page_stride = (size_t)p.Hkv * PS * D * ES;
+    const char *kbase = reinterpret_cast<const char *>(p.k_cache) + (size_t)kvh * PS * D * ES;
+    const char *vbase = reinterpret_cast<const char *>(p.v_cache) + (size_t)kvh * PS * D * ES;
     const int32_t *bt = p.block_table + (size_t)b * p.MB;
     const int st_tok = threadIdx.x >> 4, st_chunk = threadIdx.x & 15;       // token 0..31 of a tile
     const int lds_off = st_tok * kPrefillRowBytes + st_chunk * 16;
@@ -172,7 +190,8 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     if (split >= ns_eff) return;
     const int s_begin = (int)((long long)n_steps * split / ns_eff);
     const int s_end = (int)((long long)n_steps * (split + 1) / ns_eff);
-    uint4 sk[2], sv_[2];
+    uint4 sk[2], sv_[2];                                         // 8-bit cache: 8 bytes each, in .x and .y
+    float sks[2] = {1.f, 1.f}, svs[2] = {1.f, 1.f};             // 8-bit cache: the scales of the rows' pages
     // Page numbers are looked up one step before the rows they address are fetched, so that no fetch waits for its
     // own table entry: pg_k holds the pages of the step whose K rows are fetched next, pg_v (the same entries one
     // step later) those of the step whose V rows are fetched next.
@@ -182,28 +201,44 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         for (int sub = 0; sub < 2; ++sub)                                   // an entry of the table for every lane
             pg_k[sub] = bt[min((2 * step + sub) * kTile + st_tok, L - 1) >> kLog2Ps];
     };
-    auto fetch_rows = [&](auto fast, const char *base, int step, const int (&pg)[2], uint4 (&r)[2]) __attribute__((always_inline)) {
+    auto fetch_rows = [&](auto fast, const char *base, const float *scale, int step, const int (&pg)[2], uint4 (&r)[2],
+                          float (&sc)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int t = (2 * step + sub) * kTile + st_tok;
-            const uint4 *src = reinterpret_cast<const uint4 *>(base + (size_t)pg[sub] * page_stride +
-                                                               (size_t)(t & (PS - 1)) * 256 + st_chunk * 16);
-            if constexpr (decltype(fast)::value) {
-                r[sub] = *src;
+            const char *src = base + (size_t)pg[sub] * page_stride + (size_t)(t & (PS - 1)) * (D * ES) + st_chunk * (8 * ES);
+            const bool in = decltype(fast)::value || (step < s_end && t < L);
+            r[sub] = make_uint4(0, 0, 0, 0);                                // rows beyond the context are zero
+            if constexpr (KV8) {
+                if (in) {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(src);
+                    r[sub].x = v.x; r[sub].y = v.y;
+                }
+                sc[sub] = scale[(size_t)pg[sub] * p.Hkv];                   // the page is a valid one also beyond the context
             } else {
-                r[sub] = make_uint4(0, 0, 0, 0);                            // rows beyond the context are zero
-                if (step < s_end && t < L) r[sub] = *src;
+                if (in) r[sub] = *reinterpret_cast<const uint4 *>(src);
             }
         }
     };
     auto stage_k = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) *reinterpret_cast<uint4 *>(&smem[buf][sub][0][lds_off]) = sk[sub];
+        for (int sub = 0; sub < 2; ++sub) {
+            if constexpr (KV8) {
+                *reinterpret_cast<uint4 *>(&smem[buf][sub][0][lds_off]) = fp8x8_to_bf16x8(sk[sub].x, sk[sub].y);
+                if (st_chunk == 0 && (st_tok & 15) == 0) kscale_lds[buf][sub][st_tok >> 4] = sks[sub];
+            } else {
+                *reinterpret_cast<uint4 *>(&smem[buf][sub][0][lds_off]) = sk[sub];
+            }
+        }
     };
     auto stage_v = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-            *reinterpret_cast<uint4 *>(&smem[buf][sub][1][lds_off_v]) = bf16x8_to_f16x8(sv_[sub]);
+        for (int sub = 0; sub < 2; ++sub) {
+            if constexpr (KV8)
+                *reinterpret_cast<uint4 *>(&smem[buf][sub][1][lds_off_v]) = fp8x8_scaled_to_f16x8(sv_[sub].x, sv_[sub].y, svs[sub]);
+            else
+                *reinterpret_cast<uint4 *>(&smem[buf][sub][1][lds_off_v]) = bf16x8_to_f16x8(sv_[sub]);
+        }
     };
 
     // ---- per-column online-softmax state
@@ -222,7 +257,10 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     // Raw scores q.k of the column blocks: S[cb][h] holds tokens 16 h + 4 j .. + 3 of the tile for column `col`.  The
     // softmax scale is applied inside the exponent (one fused multiply-add per score): scale > 0, so the order of
     // scores is that of the raw dot products.
-    auto scores = [&](const char *ks, f32x4_t (&S)[kPrefillBlocks][2]) __attribute__((always_inline)) {
+    auto scores = [&](const char *ks, f32x4_t (&S)[kPrefillBlocks][2], const float *ksc, float (&a)[2]) __attribute__((always_inline)) {
+        if constexpr (KV8) {                                     // read with the rows: both are replaced together
+            a[0] = ksc[0] * p.scale_log2; a[1] = ksc[1] * p.scale_log2;
+        }
         uint4 K[8];
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
@@ -249,7 +287,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     // 2^-20 of the largest or less.  After a column's first tiles moves are rare, so the maximum over the tile, its
     // exchange between the four lane groups of a column and the rescale of what was summed under the old reference
     // leave the common path.  The sums are taken over the rounded weights, the ones the matrix cores multiply.
-    auto weights = [&](auto fast, int t, f32x4_t (&S)[kPrefillBlocks][2], uint4 (&P)[kPrefillBlocks]) __attribute__((always_inline)) {
+    auto weights = [&](auto fast, int t, f32x4_t (&S)[kPrefillBlocks][2], uint4 (&P)[kPrefillBlocks], const float (&a)[2]) __attribute__((always_inline)) {
         const int tb = t * kTile;
         if constexpr (!decltype(fast)::value) {
             if (tb + kTile - 1 > wave_min_pos) {                 // tokens after the column's position
@@ -264,7 +302,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         auto form = [&](int cb) __attribute__((always_inline)) {
             float pw[8];
 #pragma unroll
-            for (int r = 0; r < 8; ++r) pw[r] = fast_exp2(fmaf(S[cb][r >> 2][r & 3], p.scale_log2, -m[cb]));
+            for (int r = 0; r < 8; ++r) pw[r] = fast_exp2(fmaf(S[cb][r >> 2][r & 3], KV8 ? a[r >> 2] : p.scale_log2, -m[cb]));
             P[cb] = make_uint4(pack_f16x2(pw[0], pw[1]), pack_f16x2(pw[2], pw[3]), pack_f16x2(pw[4], pw[5]),
                                pack_f16x2(pw[6], pw[7]));
             psum[cb] = sum_f16x2(P[cb].w, sum_f16x2(P[cb].z, sum_f16x2(P[cb].y, sum_f16x2(P[cb].x, 0.f))));
@@ -278,12 +316,14 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         if (__any(over)) {
 #pragma unroll
             for (int cb = 0; cb < kPrefillBlocks; ++cb) {
-                float tmax = fmaxf(fmaxf(fmaxf(S[cb][0][0], S[cb][0][1]), fmaxf(S[cb][0][2], S[cb][0][3])),
-                                   fmaxf(fmaxf(S[cb][1][0], S[cb][1][1]), fmaxf(S[cb][1][2], S[cb][1][3])));
+                const float t0 = fmaxf(fmaxf(S[cb][0][0], S[cb][0][1]), fmaxf(S[cb][0][2], S[cb][0][3]));
+                const float t1 = fmaxf(fmaxf(S[cb][1][0], S[cb][1][1]), fmaxf(S[cb][1][2], S[cb][1][3]));
+                // the largest scaled score of the tile, in log2 units (scales are positive)
+                float tmax = KV8 ? fmaxf(t0 * a[0], t1 * a[1]) : fmaxf(t0, t1) * p.scale_log2;
                 tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
                 tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
                 // a column whose tokens are all masked so far keeps a finite stand-in: exp2 then sees -inf - finite
-                const float mn = fmaxf(fmaxf(m[cb], fmaf(tmax, p.scale_log2, -kPrefillBias)), -1e30f);
+                const float mn = fmaxf(fmaxf(m[cb], tmax - kPrefillBias), -1e30f);
                 const float alpha = fast_exp2(m[cb] - mn);       // 0 while m is still -inf
                 l[cb] *= alpha;
 #pragma unroll
@@ -320,27 +360,29 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     // all of the wave's positions run without the per-tile conditions (`fast`).
     f32x4_t Se[kPrefillBlocks][2], So[kPrefillBlocks][2];        // scores of the even / odd tile in flight
     uint4 Pe[kPrefillBlocks], Po[kPrefillBlocks];                // weights of the even / odd tile in flight
+    float ae[2] = {0.f, 0.f}, ao[2] = {0.f, 0.f};                // 8-bit cache: their scores' multipliers per 16-token half
+    const float *k_scale = KV8 ? p.k_scale + kvh : nullptr, *v_scale = KV8 ? p.v_scale + kvh : nullptr;
 #pragma unroll
     for (int cb = 0; cb < kPrefillBlocks; ++cb) Pe[cb] = Po[cb] = make_uint4(0, 0, 0, 0);
     auto step_body = [&](auto fast, int s) __attribute__((always_inline)) {
         constexpr bool kFast = decltype(fast)::value;
         const int buf = s & 1;
-        fetch_rows(fast, vbase, s, pg_v, sv_);                   // in flight while this step is computed
-        fetch_rows(fast, kbase, s + 1, pg_k, sk);
+        fetch_rows(fast, vbase, v_scale, s, pg_v, sv_, svs);     // in flight while this step is computed
+        fetch_rows(fast, kbase, k_scale, s + 1, pg_k, sk, sks);
         pg_v[0] = pg_k[0]; pg_v[1] = pg_k[1];
         lookup(s + 2);
         // phase 2s-1: P.V of tile 2s-2, weights of tile 2s-1, scores of tile 2s
         if (kFast || tile_active(2 * s - 2)) pv(smem[buf ^ 1][0][1], Pe);
-        if (kFast || tile_active(2 * s)) scores(smem[buf][0][0], Se);
-        if (kFast || tile_active(2 * s - 1)) weights(fast, 2 * s - 1, So, Po);
+        if (kFast || tile_active(2 * s)) scores(smem[buf][0][0], Se, kscale_lds[buf][0], ae);
+        if (kFast || tile_active(2 * s - 1)) weights(fast, 2 * s - 1, So, Po, ao);
         // phase 2s: P.V of tile 2s-1, weights of tile 2s, scores of tile 2s+1
         if (kFast || tile_active(2 * s - 1)) pv(smem[buf ^ 1][1][1], Po);
-        if (kFast || tile_active(2 * s + 1)) scores(smem[buf][1][0], So);
+        if (kFast || tile_active(2 * s + 1)) scores(smem[buf][1][0], So, kscale_lds[buf][1], ao);
         if (kFast || s < s_end) {                                // ahead of the weights: one block with the MFMAs above
             stage_k(buf ^ 1);
             stage_v(buf);
         }
-        if (kFast || tile_active(2 * s)) weights(fast, 2 * s, Se, Pe);
+        if (kFast || tile_active(2 * s)) weights(fast, 2 * s, Se, Pe, ae);
         if (kFast || s < s_end) lds_barrier();
     };
     // last step whose tiles 2s-2 .. 2s+1 are all wholly visible to every live column of the wave and all this
@@ -350,7 +392,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
 
     {
         lookup(s_begin);
-        fetch_rows(std::false_type{}, kbase, s_begin, pg_k, sk);
+        fetch_rows(std::false_type{}, kbase, k_scale, s_begin, pg_k, sk, sks);
         pg_v[0] = pg_k[0]; pg_v[1] = pg_k[1];
         lookup(s_begin + 1);
         stage_k(s_begin & 1);

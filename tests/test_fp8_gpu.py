@@ -118,3 +118,102 @@ def test_fp8_handle_moves_bytes_and_rejects_16_bit_calls():
     hb = omni.Handle(batch=2, num_q_heads=4, num_kv_heads=2, head_dim=128, page_size=16, num_pages=8,
                      max_blocks_per_seq=4, kv_dtype=omni.OMNI_BF16)
     assert L.omni_paged_decode_attn_fp8(hb._h, 256, 256, 256, 256, 256, 256, 256, 1.0, 256, None) == 4
+
+
+# --------------------------------------------------------------------------- multi-token queries over the 8-bit cache
+def run_chunk_fp8(wl, f8, ch, max_q_len=None, tuning=None, split_workspace=False):
+    fb = Fp8Batch(wl, f8, tuning)
+    mq = max_q_len or max(ch.max_q_len, 1)
+    if split_workspace:
+        n = max(fb.h.omni_workspace_bytes(), fb.h.omni_prefill_workspace_bytes(mq))
+        fb.ws = torch.full((n // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        fb.h.omni_set_workspace(fb.ws)
+    q = to_dev(ch.q, wl.dtype)
+    q_lens, q_offs = torch.from_numpy(ch.q_lens).cuda(), torch.from_numpy(ch.q_offsets).cuda()
+    out = torch.full((ch.total, wl.Hq, wl.D), float("nan"), dtype=torch.float32, device="cuda")
+    fb.h.omni_paged_prefill_attn_fp8(q, fb.k, fb.v, fb.ks, fb.vs, fb.bt, fb.lens, q_lens, q_offs, mq, float(wl.scale), out)
+    torch.cuda.synchronize()
+    return fb, out.cpu().numpy().astype(np.float64)
+
+
+def check_chunk_fp8(wl, f8, ch, label="", **kw):
+    fb, got = run_chunk_fp8(wl, f8, ch, **kw)
+    ref = oracle.paged_prefill_attn_fp8(ch.q, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                                        wl.context_lens, ch.q_lens, ch.q_offsets, wl.scale)
+    owned = np.zeros(ch.total, dtype=bool)
+    for b in range(wl.B):
+        owned[ch.q_offsets[b]:ch.q_offsets[b] + ch.q_lens[b]] = True
+    assert np.all(np.isnan(got[~owned])), f"{label}: rows nobody owns were written"
+    err = np.max(np.abs(got[owned] - ref[owned])) if owned.any() else 0.0
+    assert np.all(np.isfinite(got[owned])) and err <= TOL[W.BF16], f"{label}: max|err| {err:.3e}"
+    return got, ref
+
+
+@pytest.mark.parametrize("G,Hkv,ps", [(7, 4, 16), (8, 2, 16), (4, 8, 32), (16, 1, 16), (1, 2, 16), (3, 2, 32)])
+def test_chunks_of_many_shapes_fp8(G, Hkv, ps):
+    lens = [300, 64, 1, 0, 33, 257, 96, 40]
+    q_lens = [300, 1, 1, 0, 17, 100, 37, 40]                 # whole prompt, one token, nothing, ragged pieces
+    wl = W.build("f8chunk", 720 + G, lens, Hq=G * Hkv, Hkv=Hkv, D=128, ps=ps, dtype=W.BF16, pool_factor=1.5)
+    ch = W.add_chunk(wl, q_lens, 820 + G, in_cache=True, gap=3)
+    f8 = W.quantize_fp8(wl)
+    got, ref = check_chunk_fp8(wl, f8, ch, label=f"G{G} Hkv{Hkv} ps{ps}")
+    # the first query of the whole-prompt request sees token 0 only: its de-quantised V row, rounded once to fp16
+    v0 = torch.from_numpy(f8.v_cache[wl.block_table[0, 0], :, 0, :]).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    v0 = v0 * f8.v_scale[wl.block_table[0, 0]].astype(np.float64)[:, None]
+    assert np.max(np.abs(got[ch.q_offsets[0]] - np.repeat(v0, G, axis=0))) <= 2.0 ** -11 * np.max(np.abs(v0))
+
+
+def test_one_token_chunks_agree_with_the_decode_call_fp8():
+    wl = W.make("talker", batch=24, len_div=2, append=False)
+    f8 = W.quantize_fp8(wl)
+    ch = W.add_chunk(wl, [1] * wl.B, 5, in_cache=True)
+    ch.q[:] = wl.q                                            # the decode batch's own queries, one row per request
+    got, _ = check_chunk_fp8(wl, f8, ch, label="one-token")
+    dec = Fp8Batch(wl, f8).attend()
+    assert np.max(np.abs(got[ch.q_offsets] - dec)) <= 2 * TOL[W.BF16]
+
+
+@pytest.mark.parametrize("splits,min_split", [(0, 256), (3, 64), (16, 128)], ids=lambda v: str(v))
+def test_context_split_fp8(splits, min_split):
+    wl = W.build("f8split", 1600, [2100, 64, 700, 1, 0], Hq=28, Hkv=4, D=128, ps=16, dtype=W.BF16, pool_factor=1.5)
+    ch = W.add_chunk(wl, [37, 64, 400, 1, 0], 1601, in_cache=True, gap=2)
+    f8 = W.quantize_fp8(wl)
+    check_chunk_fp8(wl, f8, ch, label=f"splits={splits}", split_workspace=True,
+                    tuning={omni.OMNI_TUNE_PREFILL_SPLITS: splits, omni.OMNI_TUNE_PREFILL_MIN_SPLIT: min_split})
+
+
+def test_every_byte_value_and_uneven_scales_fp8():
+    """K and V pools that hold every finite E4M3 byte, page scales spread over 2^-6 .. 2^3 (not powers of two):
+    a wrong decode of any byte, or a scale applied to the wrong half of a tile, shows against the oracle."""
+    rng = np.random.default_rng(77)
+    wl = W.build("f8bytes", 1700, [130, 47], Hq=8, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    ch = W.add_chunk(wl, [50, 47], 1701, in_cache=True)
+    f8 = W.quantize_fp8(wl)
+    finite = np.array([b for b in range(256) if (b & 0x7F) != 0x7F], dtype=np.uint8)
+    live = f8.k_cache != W.FP8_NAN_BYTE
+    f8.k_cache[live] = rng.choice(finite, size=int(live.sum()))
+    live = f8.v_cache != W.FP8_NAN_BYTE
+    f8.v_cache[live] = rng.choice(finite, size=int(live.sum()))
+    f8.k_scale[:] = np.exp2(rng.uniform(-9, -5, size=f8.k_scale.shape)).astype(np.float32)     # scores stay moderate
+    f8.v_scale[:] = np.exp2(rng.uniform(-6, 3, size=f8.v_scale.shape)).astype(np.float32)
+    fb, got = run_chunk_fp8(wl, f8, ch)
+    ref = oracle.paged_prefill_attn_fp8(ch.q, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                                        wl.context_lens, ch.q_lens, ch.q_offsets, wl.scale)
+    # V reaches 448 * 8 here: the bar scales with the values (weights and V both carry 2^-12 relative rounding)
+    bound = 2.0 ** -10 * np.max(np.abs(ref))
+    assert np.all(np.isfinite(got)) and np.max(np.abs(got - ref)) <= max(bound, TOL[W.BF16])
+
+
+def test_fp8_prefill_argument_checks():
+    wl = W.build("f8args", 1800, [40], Hq=4, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    f8 = W.quantize_fp8(wl)
+    fb = Fp8Batch(wl, f8)
+    L = omni.lib()
+    assert L.omni_paged_prefill_attn_fp8(fb.h._h, 256, 256, 256, None, 256, 256, 256, 256, 256, 8, 1.0, 256, None) == 1
+    assert L.omni_paged_prefill_attn_fp8(fb.h._h, 256, 256, 256, 256, 256, 256, 256, 256, 256, 0, 1.0, 256, None) == 2
+    assert L.omni_paged_prefill_attn_fp8(fb.h._h, 256, 256, 256, 256, 256, 256, 256, 256, 256, 8, 0.0, 256, None) == 2
+    hb = omni.Handle(batch=2, num_q_heads=4, num_kv_heads=2, head_dim=128, page_size=16, num_pages=8,
+                     max_blocks_per_seq=4, kv_dtype=omni.OMNI_BF16)
+    assert L.omni_paged_prefill_attn_fp8(hb._h, 256, 256, 256, 256, 256, 256, 256, 256, 256, 8, 1.0, 256, None) == 4
+    assert L.omni_paged_prefill_attn(fb.h._h, 256, 256, 256, 256, 256, 256, 256, 8, 1.0, 256, None) == 4
+
