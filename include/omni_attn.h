@@ -144,7 +144,7 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h,
  * the V scale the softmax weights.  NaN bytes in slots no live token owns never reach the result.
  * omni_kv_append, omni_kv_pack and omni_kv_unpack move the bytes of such a cache like any other (scales are the
  * caller's); omni_paged_decode_attn, omni_decode_step and omni_paged_prefill_attn return OMNI_ERR_UNSUPPORTED for it
- * (multi-token queries over such a cache: omni_paged_prefill_attn_fp8).  Scales must be positive.
+ * (their forms for such a cache: omni_decode_step_fp8, omni_paged_prefill_attn_fp8).  Scales must be positive.
  * Errors: NULL, SHAPE (alignment), UNSUPPORTED (handle is not an fp8 one), WORKSPACE, HIP.
  */
 omni_status_t omni_paged_decode_attn_fp8(omni_handle_t h,
@@ -172,6 +172,15 @@ omni_status_t omni_kv_append(omni_handle_t h,
  * the two separate calls.
  * Errors: NULL, WORKSPACE, HIP.
  */
+/* The decode iteration over the quantised cache: k_new / v_new [batch, num_kv_heads, head_dim] hold E4M3 BYTES, already
+ * divided by the scale of the page they go to (position context_lens[b] - 1); exactly omni_kv_append of those bytes
+ * followed by omni_paged_decode_attn_fp8, in one launch of the attention kernel plus the merge.  Quantising the new
+ * rows, and choosing a page's scale before its first row arrives, is the caller's.
+ * Errors: NULL, SHAPE (alignment), UNSUPPORTED (handle is not an fp8 one), WORKSPACE, HIP. */
+omni_status_t omni_decode_step_fp8(omni_handle_t h, const void *q, const void *k_new, const void *v_new, void *k_cache,
+                                   void *v_cache, const float *k_scale, const float *v_scale, const int32_t *block_table,
+                                   const int32_t *context_lens, float scale, void *out, void *stream);
+
 omni_status_t omni_decode_step(omni_handle_t h,
                                const void *q, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
                                const int32_t *block_table, const int32_t *context_lens,

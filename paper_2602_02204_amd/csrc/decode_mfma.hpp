@@ -491,17 +491,19 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             return si;
         };
         // Fused decode step: the tile that holds the request's last token gets the new K/V row written into its page
-        // (a bit copy, lanes 0-15 the K row, lanes 16-31 the V row) before the tile is requested; the wave waits for
+        // (a bit copy, the first lanes the K row, the next ones the V row, 16 bytes each) before the tile is requested; the wave waits for
         // the write to be acknowledged, so the loads that follow see it.
         auto append_row = [&](const SlotInfo &si) {
             const int pos = Lc[si.req] - 1;
             const int pg = (PS == 16 && (pos & 16)) ? si.pg1 : si.pg0;
-            const size_t row = (size_t)pg * ld.page_stride + (size_t)(pos & (PS - 1)) * (D * 2);
-            if (!KV8 && lane < 32) {                             // the fused append exists for 16-bit caches only
-                const bool is_v = lane >= 16;
+            constexpr int kRowPieces = D * ES / 16;              // 16-byte pieces of a row: 16 (16-bit cache) or 8
+            const size_t row = (size_t)pg * ld.page_stride + (size_t)(pos & (PS - 1)) * (D * ES);
+            if (lane < 2 * kRowPieces) {
+                const bool is_v = lane >= kRowPieces;
+                const int piece = lane & (kRowPieces - 1);
                 const char *src = reinterpret_cast<const char *>(is_v ? p.v_new : p.k_new) +
-                                  ((size_t)si.req * p.Hkv + kvh) * (D * 2) + (lane & 15) * 16;
-                char *dst = const_cast<char *>(is_v ? ld.vbase : ld.kbase) + row + (lane & 15) * 16;
+                                  ((size_t)si.req * p.Hkv + kvh) * (D * ES) + piece * 16;
+                char *dst = const_cast<char *>(is_v ? ld.vbase : ld.kbase) + row + piece * 16;
                 *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

@@ -253,7 +253,7 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
                                       const float *k_scale = nullptr, const float *v_scale = nullptr) {
     if (!h || !q || !k_cache || !v_cache || !block_table || !context_lens || !out) return OMNI_ERR_NULL;
     const bool fp8 = h->d.kv_dtype == OMNI_FP8_E4M3;
-    if (fp8 != (k_scale != nullptr) || (fp8 && (k_new || v_new))) return OMNI_ERR_UNSUPPORTED;
+    if (fp8 != (k_scale != nullptr)) return OMNI_ERR_UNSUPPORTED;
     if (fp8 && (!v_scale || misaligned(k_scale, 4) || misaligned(v_scale, 4))) return v_scale ? OMNI_ERR_SHAPE : OMNI_ERR_NULL;
     if (!h->ws || h->ws_given < h->ws_bytes) return OMNI_ERR_WORKSPACE;
     if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(out, 16) ||
@@ -351,6 +351,15 @@ omni_status_t omni_paged_decode_attn_fp8(omni_handle_t h, const void *q, const v
     if (h->d.kv_dtype != OMNI_FP8_E4M3) return OMNI_ERR_UNSUPPORTED;
     return launch_attention(h, q, nullptr, nullptr, k_cache, v_cache, block_table, context_lens, scale, out, stream,
                             k_scale, v_scale);
+}
+
+omni_status_t omni_decode_step_fp8(omni_handle_t h, const void *q, const void *k_new, const void *v_new, void *k_cache,
+                                   void *v_cache, const float *k_scale, const float *v_scale, const int32_t *block_table,
+                                   const int32_t *context_lens, float scale, void *out, void *stream) {
+    if (!h || !k_new || !v_new || !k_scale || !v_scale) return OMNI_ERR_NULL;
+    if (h->d.kv_dtype != OMNI_FP8_E4M3) return OMNI_ERR_UNSUPPORTED;
+    return launch_attention(h, q, k_new, v_new, k_cache, v_cache, block_table, context_lens, scale, out, stream, k_scale,
+                            v_scale);
 }
 
 omni_status_t omni_decode_step(omni_handle_t h, const void *q, const void *k_new, const void *v_new, void *k_cache,

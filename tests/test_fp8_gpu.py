@@ -217,3 +217,42 @@ def test_fp8_prefill_argument_checks():
     assert L.omni_paged_prefill_attn_fp8(hb._h, 256, 256, 256, 256, 256, 256, 256, 256, 256, 8, 1.0, 256, None) == 4
     assert L.omni_paged_prefill_attn(fb.h._h, 256, 256, 256, 256, 256, 256, 256, 8, 1.0, 256, None) == 4
 
+
+@pytest.mark.parametrize("name,kw,force_pl", [("thinker", dict(batch=12), 0), ("talker", dict(batch=48), 0),
+                                              ("mixed", dict(batch=30, len_div=4), 128), ("long", dict(batch=2, len_div=4), 0)])
+def test_decode_step_fp8_equals_append_then_attention(name, kw, force_pl):
+    """omni_decode_step_fp8 = omni_kv_append of the new byte rows at context_lens - 1, then omni_paged_decode_attn_fp8:
+    same pools and same output bit for bit, and the output within the bar of the oracle over the appended pools."""
+    wl = W.make(name, append=False, **kw)
+    f8 = W.quantize_fp8(wl)
+    rng = np.random.default_rng(3)
+    finite = np.array([b for b in range(256) if (b & 0x7F) != 0x7F], dtype=np.uint8)
+    k_new = rng.choice(finite[(finite & 0x7F) < 0x60], size=(wl.B, wl.Hkv, wl.D)).astype(np.uint8)   # moderate magnitudes
+    v_new = rng.choice(finite, size=(wl.B, wl.Hkv, wl.D)).astype(np.uint8)
+    pos = (wl.context_lens - 1).astype(np.int32)
+    # the last token's rows are not in the pools yet
+    for b in range(wl.B):
+        if pos[b] >= 0:
+            f8.k_cache[wl.block_table[b, pos[b] // wl.ps], :, pos[b] % wl.ps, :] = W.FP8_NAN_BYTE
+            f8.v_cache[wl.block_table[b, pos[b] // wl.ps], :, pos[b] % wl.ps, :] = W.FP8_NAN_BYTE
+    tuning = {omni.OMNI_TUNE_FORCE_PARTITION: force_pl} if force_pl else {}
+    two, one = Fp8Batch(wl, f8, tuning), Fp8Batch(wl, f8, tuning)
+    kn, vn = torch.from_numpy(k_new).cuda(), torch.from_numpy(v_new).cuda()
+    two.h.omni_kv_append(kn, vn, two.k, two.v, two.bt, torch.from_numpy(pos).cuda())
+    ref_two = two.attend()
+    one.out.fill_(float("nan"))
+    one.h.omni_decode_step_fp8(one.q, kn, vn, one.k, one.v, one.ks, one.vs, one.bt, one.lens, float(wl.scale), one.out)
+    torch.cuda.synchronize()
+    got = one.out.cpu().numpy().astype(np.float64)
+    assert np.array_equal(one.k.cpu().numpy(), two.k.cpu().numpy()) and np.array_equal(one.v.cpu().numpy(), two.v.cpu().numpy())
+    assert np.array_equal(got, ref_two)
+    want_k, want_v = f8.k_cache.copy(), f8.v_cache.copy()
+    for b in range(wl.B):
+        if pos[b] >= 0:
+            want_k[wl.block_table[b, pos[b] // wl.ps], :, pos[b] % wl.ps, :] = k_new[b]
+            want_v[wl.block_table[b, pos[b] // wl.ps], :, pos[b] % wl.ps, :] = v_new[b]
+    assert np.array_equal(one.k.cpu().numpy(), want_k) and np.array_equal(one.v.cpu().numpy(), want_v)
+    ref = oracle.paged_decode_attn_fp8(wl.q, want_k, want_v, f8.k_scale, f8.v_scale, wl.block_table, wl.context_lens, wl.scale)
+    bar = max(TOL[W.BF16], 2.0 ** -9 * np.max(np.abs(ref)))           # V bytes reach 448 times the page scale here
+    assert np.all(np.isfinite(got)) and np.max(np.abs(got - ref)) <= bar
+
