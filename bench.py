@@ -183,6 +183,40 @@ def main():
         host_us_eager = (time.perf_counter() - a) * 1e6 / 64
         torch.cuda.synchronize()
 
+    # ---- several query tokens per request (speculative decoding / multi-token prediction): the same batch with T
+    # tokens per request through the same kernel, T * (Hq / Hkv) <= 16 columns; attention + merge over rotating replicas
+    multi = None
+    if not args.timed_only and h.omni_get_plan()["kernel"] == omni.KERNEL_MFMA and 2 * (wl.Hq // wl.Hkv) <= 16:
+        T = 16 // (wl.Hq // wl.Hkv)
+        hT = omni.Handle(batch=wl.B, num_q_heads=wl.Hq, num_kv_heads=wl.Hkv, head_dim=wl.D, page_size=wl.ps,
+                         num_pages=wl.P, max_blocks_per_seq=wl.MB, kv_dtype=kvd, out_dtype=omni.OMNI_F32)
+        hT.omni_set_tuning(omni.OMNI_TUNE_QUERY_TOKENS, T)
+        wsT = hT.alloc_workspace()
+        qT_host = W.f32_to_bf16_bits(np.random.default_rng(5).standard_normal((wl.B * T, wl.Hq, wl.D)).astype(np.float32))
+        qT = to_dev(qT_host, wl.dtype)
+        outT = torch.empty((wl.B, T, wl.Hq, wl.D), dtype=torch.float32, device="cuda")
+        stepT = lambda i: hT.omni_paged_decode_attn(qT, kc[i % R], vc[i % R], bt, lens, scale, outT, stream)
+        for i in range(8):
+            stepT(i)
+        msT = timed(stepT)
+        # parity on sampled rows: the chunk definition with q_lens = T (the appended token is in every replica)
+        import oracle as _oracle
+        kfull, vfull = wl.k_cache.copy(), wl.v_cache.copy()
+        _oracle.kv_append(wl.k_new, wl.v_new, kfull, vfull, wl.block_table, wl.positions, wl.dtype)
+        nT = np.full(wl.B, T, dtype=np.int32)
+        oT = np.arange(wl.B, dtype=np.int64) * T
+        rowsT = [(0, 0, 0), (wl.B - 1, T - 1, wl.Hq - 1), (wl.B // 2, T // 2, 3)]
+        refT = _oracle.paged_prefill_attn(qT_host, kfull, vfull, wl.block_table, wl.context_lens, nT, oT, wl.scale, wl.dtype,
+                                          rows=rowsT)
+        gotT = outT.cpu().numpy().astype(np.float64)
+        errT = float(max(np.max(np.abs(gotT[b, i, hh] - refT[r])) for r, (b, i, hh) in enumerate(rowsT)))
+        if not (errT <= 2e-3):
+            print(f"bench.py: multi-token parity check failed, max|err|={errT:.3e}", file=sys.stderr)
+            sys.exit(1)
+        multi = {"query_tokens_per_request": T, "ms_per_step": msT, "query_tokens_per_s": wl.B * T / (msT * 1e-3),
+                 "parity_max_abs_err_sampled": errT, "note": "omni_paged_decode_attn with OMNI_TUNE_QUERY_TOKENS: attention + merge, no append"}
+        del qT, outT, wsT
+
     # ---- the memory system's ceiling for a kernel of this size: a plain streaming read of one replica's K and V pools
     # (pool bytes >= the algorithmic bytes: it also reads the unused tail slots), timed with event pairs like the
     # attention kernel, over rotating replicas
@@ -439,6 +473,7 @@ def main():
                   "host_us_to_issue_a_step_eager": host_us_eager, "host_us_to_issue_a_step_in_graph": host_us_graph,
                   "kv_gbs_cache_warm": kv_bytes / (ms_warm * 1e-3) / 1e9 if ms_warm else None,
                   "kv_pack_unpack": pack,
+                  "multi_token_decode": multi,
                   "prefill_chunk": prefill,
                   "prefill_chunk_one_long_request": prefill_one,
                   "fp8_kv_cache": fp8,

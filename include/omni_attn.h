@@ -90,8 +90,11 @@ typedef enum {
     OMNI_TUNE_FORCE_PARTITION = 3,  /* > 0: every workgroup range is exactly this many tokens (multiple of 32); 0 = plan decides */
     OMNI_TUNE_PREFILL_SPLITS = 4,   /* omni_paged_prefill_attn, matrix-core path: 0 = the library decides from the grid how many
                                        workgroups may share a query block's context, 1 = never split, 2 .. 16 = this many */
-    OMNI_TUNE_PREFILL_MIN_SPLIT = 5 /* fewest tokens of context one of them takes (multiple of 64; default 256): a query
+    OMNI_TUNE_PREFILL_MIN_SPLIT = 5,/* fewest tokens of context one of them takes (multiple of 64; default 256): a query
                                        block with a shorter context is shared by fewer, decided on the device */
+    OMNI_TUNE_QUERY_TOKENS = 6      /* T >= 1 (default 1): omni_paged_decode_attn and omni_paged_decode_attn_fp8 take T query
+                                       tokens per request, see there.  Matrix-core kernel only, T * (Hq / Hkv) <= 16,
+                                       else UNSUPPORTED */
 } omni_tune_key_t;
 
 /* Validate `desc` and create a handle holding host-side plan state only (no device memory).
@@ -127,6 +130,13 @@ omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes);
  * by a range boundary is put together again by a log-sum-exp merge.  Both are exact re-associations of the definition
  * above.  Two kernel launches (attention, merge).  Writes `out` and the workspace, nothing else.
  * For a fixed handle and tuning the result is bit-identical from run to run and under any physical page permutation.
+ * Several query tokens per request (speculative decoding, multi-token prediction; OMNI_TUNE_QUERY_TOKENS = T > 1): q
+ * and out are [batch, T, num_q_heads, head_dim]; the T tokens are the LAST T of the context_lens[b] tokens (their K/V
+ * rows are in the pools: omni_kv_append_chunk), query i sees tokens 0 .. context_lens[b] - T + i.  The kernel treats
+ * the T * (Hq / Hkv) (token, head) pairs of a KV head as the columns of its matrix-core tiles, so the cache is still
+ * read once: the call costs about what the one-token call costs.  Every request has exactly T tokens (or length 0);
+ * a query that would see no token at all (context_lens[b] < T) gets zeros.  omni_decode_step needs T = 1.
+ * Ragged numbers of new tokens: omni_paged_prefill_attn.
  * Errors: NULL, WORKSPACE, HIP.
  */
 omni_status_t omni_paged_decode_attn(omni_handle_t h,

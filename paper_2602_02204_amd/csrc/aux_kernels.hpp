@@ -13,10 +13,9 @@ namespace omni {
 // issued before any is used, so a round costs one trip to memory and no load depends on a loaded value.
 template <int D, int kRound>
 __device__ __forceinline__ void merge_request(const AttnParams &p, int b, int kvh, int slot_first, int n) {
-    const int G = p.G, head0 = kvh * G;
-    const size_t out0 = ((size_t)b * p.Hq + head0) * D;
-    for (int idx = 4 * threadIdx.x; idx < G * D; idx += 4 * kThreads) {       // one pass up to 1024 elements
-        const int g = idx / D;
+    for (int idx = 4 * threadIdx.x; idx < p.Gq * D; idx += 4 * kThreads) {    // one pass up to 1024 elements
+        const int g = idx / D;                                                // column: (query token, head)
+        const size_t out0 = column_row(p, b, kvh, g) * D + (idx - g * D);
         float M = -INFINITY, den = 0.f;
         float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int j0 = 0; j0 < n; j0 += kRound) {
@@ -26,9 +25,9 @@ __device__ __forceinline__ void merge_request(const AttnParams &p, int b, int kv
             for (int u = 0; u < kRound; ++u) {
                 ml[u] = make_float2(0.f, 0.f); oj[u] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (j0 + u < n) {
-                    const size_t pi = (size_t)(slot_first + j0 + u) * p.Hq + head0;
-                    ml[u] = p.ws.part_ml[pi + g];
-                    oj[u] = *reinterpret_cast<const float4 *>(p.ws.part_o + pi * D + idx);
+                    const size_t pi = column_row(p, slot_first + j0 + u, kvh, g);
+                    ml[u] = p.ws.part_ml[pi];
+                    oj[u] = *reinterpret_cast<const float4 *>(p.ws.part_o + pi * D + (idx - g * D));
                 }
             }
 #pragma unroll
@@ -45,10 +44,10 @@ __device__ __forceinline__ void merge_request(const AttnParams &p, int b, int kv
             }
         }
         const bool live = den > 0.f;
-        store_out(p, out0 + idx + 0, live ? num.x / den : 0.f);
-        store_out(p, out0 + idx + 1, live ? num.y / den : 0.f);
-        store_out(p, out0 + idx + 2, live ? num.z / den : 0.f);
-        store_out(p, out0 + idx + 3, live ? num.w / den : 0.f);
+        store_out(p, out0 + 0, live ? num.x / den : 0.f);
+        store_out(p, out0 + 1, live ? num.y / den : 0.f);
+        store_out(p, out0 + 2, live ? num.z / den : 0.f);
+        store_out(p, out0 + 3, live ? num.w / den : 0.f);
     }
 }
 

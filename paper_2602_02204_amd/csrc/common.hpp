@@ -46,6 +46,8 @@ struct AttnParams {
     PlanParams plan;
     float scale_log2;                   // scale * log2(e): scores are kept in the log2 domain and exp2 is used
     int Hq, Hkv, G, MB;
+    int T;                              // query tokens per request (1 = plain decode); q and out are [B, T, Hq, D]
+    int Gq;                             // T * G: the (query token, head) columns of one KV head
     int log2_ps;
     int out_bf16;
     MfmaLds lds;                        // matrix-core kernel only
@@ -53,6 +55,14 @@ struct AttnParams {
     long long *trace;                   // development builds only: per-wave phase timestamps
 #endif
 };
+
+// Row of `out` (X = request) or of the partial results (X = slot) that column c of KV head kvh stands for: query token
+// c / G, head kvh * G + c % G; both arrays are [X][T][Hq] rows.
+__device__ __forceinline__ size_t column_row(const AttnParams &p, size_t X, int kvh, int c) {
+    if (p.T == 1) return X * p.Hq + kvh * p.G + c;               // plain decode: no division
+    const int qi = c / p.G, g = c - qi * p.G;
+    return (X * p.T + qi) * p.Hq + kvh * p.G + g;
+}
 
 // Phase timestamps for development builds (compiled out otherwise): slot `id` of this wave's record.
 #ifdef OMNI_TRACE
@@ -185,8 +195,10 @@ __device__ __forceinline__ Plan attn_prologue(const AttnParams &p, PlanSmem *ps,
                                               int first_len = 0, bool have_first = false) {
     const Plan pl = plan_build(p.context_lens, p.plan, ps, E, E + p.plan.B + 1, [&](int b) {
         if (w == 0) {
-            const size_t o0 = ((size_t)b * p.Hq + kvh * p.G) * D;
-            for (int i = 0; i < p.G * D; ++i) store_out(p, o0 + i, 0.f);
+            for (int c = 0; c < p.Gq; ++c) {
+                const size_t o0 = column_row(p, b, kvh, c) * D;
+                for (int i = 0; i < D; ++i) store_out(p, o0 + i, 0.f);
+            }
         }
     }, first_len, have_first);
     if (blockIdx.x == 0 && threadIdx.x == 0) {

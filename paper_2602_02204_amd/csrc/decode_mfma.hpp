@@ -233,14 +233,20 @@ __device__ __forceinline__ void mfma_scores(const uint4 (&K)[8], const uint4 (&Q
 // Second half: online softmax over the tile's scores and the weighted V accumulation O^T += V^T P^T.
 // `vs0` / `vs1` scale the weights of the tile's first / second 16 tokens on their way into the product (the V scales of
 // an 8-bit cache; 1 otherwise): the sum of weights stays unscaled.
-template <bool kScaled = false>
-__device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], MfmaState &st, int tb, int t1, int j,
-                                                float vs0 = 1.f, float vs1 = 1.f) {
+// t1: the request's length; t1col: tokens this lane's column may see (t1 less the query tokens after its own; = t1 in
+// plain decode); t1min: the smallest t1col of the wave's columns.
+// kMulti (several query tokens per request): the three differ; otherwise all are t1.
+template <bool kScaled = false, bool kMulti = false>
+__device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], MfmaState &st, int tb, int t1, int t1col,
+                                                int t1min, int j, float vs0 = 1.f, float vs1 = 1.f) {
 #pragma clang fp contract(off)
-    if (tb + 32 > t1) {                                  // ragged last tile (uniform branch)
+    if (tb + 32 > (kMulti ? t1min : t1)) {               // last tiles of the request (uniform branch)
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            if (tb + slot_token(j, r) >= t1) {           // unowned slot: its K/V bits are arbitrary, possibly NaN
+            if (kMulti) {
+                if (tb + slot_token(j, r) >= t1col) sv[r] = -INFINITY;      // not visible to this column
+                if (tb + slot_token(j, r) >= t1) V[r] = make_uint4(0, 0, 0, 0);
+            } else if (tb + slot_token(j, r) >= t1) {    // unowned slot: its K/V bits are arbitrary, possibly NaN
                 sv[r] = -INFINITY;
                 V[r] = make_uint4(0, 0, 0, 0);
             }
@@ -251,7 +257,9 @@ __device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], M
     for (int r = 1; r < 8; ++r) tmax = fmaxf(tmax, sv[r]);
     tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    const float mn = fmaxf(st.m, tmax);                  // finite: every tile holds at least one live token
+    // finite: in plain decode every tile holds a live token; with several query tokens a column may see none of a
+    // tile's, and then keeps a finite stand-in (exp2 below sees -inf - finite, never -inf - -inf)
+    const float mn = kMulti ? fmaxf(fmaxf(st.m, tmax), -1e30f) : fmaxf(st.m, tmax);
     const float alpha = fast_exp2(st.m - mn);
     float pw[8], psum = 0.f;
 #pragma unroll
@@ -317,7 +325,7 @@ inline MfmaLds mfma_lds_layout(int B, int G, bool kv8, bool staged) {
 // elements.  All threads call it between barriers.
 template <int D>
 __device__ __forceinline__ void mfma_combine_segment(const float *slot, const AttnParams &p, const Segment &seg, int kvh) {
-    const int G = p.G, head0 = kvh * G;
+    const int G = p.Gq;                                  // columns: (query token, head) pairs of the KV head
     const float *sm_m = slot + kWaves * G * (D + 4), *sm_l = sm_m + kWaves * kMaxGroup;
     for (int idx = 4 * threadIdx.x; idx < G * D; idx += 4 * kThreads) {
         const int g = idx / D, d = idx - g * D;
@@ -337,7 +345,7 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
             }
         }
         if (seg.nparts == 1) {
-            const size_t o0 = ((size_t)seg.b * p.Hq + head0) * D + idx;
+            const size_t o0 = column_row(p, seg.b, kvh, g) * D + d;
             const bool live = den > 0.f;
             const float4 r = make_float4(live ? num.x / den : 0.f, live ? num.y / den : 0.f, live ? num.z / den : 0.f,
                                          live ? num.w / den : 0.f);
@@ -350,9 +358,9 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
                 *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.out) + o0) = r;
             }
         } else {
-            const size_t pi = (size_t)seg.slot * p.Hq + head0;
-            *reinterpret_cast<float4 *>(p.ws.part_o + pi * D + idx) = num;
-            if (d == 0) p.ws.part_ml[pi + g] = make_float2(M, den);
+            const size_t pi = column_row(p, seg.slot, kvh, g);
+            *reinterpret_cast<float4 *>(p.ws.part_o + pi * D + d) = num;
+            if (d == 0) p.ws.part_ml[pi] = make_float2(M, den);
         }
     }
 }
@@ -363,7 +371,9 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
 // KV8: the pools hold 8-bit E4M3 bytes with one scale per (page, KV head); queries stay bf16.
 // KST: K tiles go through the per-wave staging area in shared memory (the host chooses it where the ring keeps enough
 // slots beside it); otherwise they are loaded straight into the operand registers.
-template <int PS, bool KV8 = false, bool KST = true>
+// MT: several query tokens per request (the columns are (query token, head) pairs with a causal limit each); the
+// one-token kernel is compiled without any of it.
+template <int PS, bool KV8 = false, bool KST = true, bool MT = false>
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
     constexpr int ES = KV8 ? 1 : 2;                          // bytes per cache element
@@ -388,8 +398,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 15, j = lane >> 4;
-    const int G = p.G;
+    const int G = p.G, Gq = MT ? p.Gq : G;                       // heads per KV head; columns = query tokens x heads
     const int head0 = kvh * G;
+    const int col_qi = (MT && col < Gq) ? col / G : 0;           // this lane's column: query token, head, and how many
+    const int col_g = col - col_qi * G;                          // of the request's newest tokens it must not see
+    const int col_back = (MT && col < Gq) ? p.T - 1 - col_qi : 0;
+    const int tokens = MT ? p.T : 1;
 
     MfmaTileLoader<PS> ld;
     ld.page_stride = (size_t)p.Hkv * PS * D * ES;
@@ -410,8 +424,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     auto load_q = [&](int b, uint4 (&Q)[4]) {                    // B operand of K Q^T for request b
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) Q[kk] = make_uint4(0, 0, 0, 0);
-        if (col < G) {
-            const char *qrow = reinterpret_cast<const char *>(p.q) + ((size_t)b * p.Hq + head0 + col) * (D * 2);
+        if (col < Gq) {
+            const char *qrow = reinterpret_cast<const char *>(p.q) + (((size_t)b * tokens + col_qi) * p.Hq + head0 + col_g) * (D * 2);
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)                      // dims of step kk: (4kk + j) * 8 .., or 32j + 8kk .. (KV8)
                 Q[kk] = *reinterpret_cast<const uint4 *>(qrow + (KV8 ? 4 * j + kk : 4 * kk + j) * 16);
@@ -427,8 +441,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         unsigned long long T = 0;
         const bool first = blockIdx.x == 0 && wave == 0;
         pl = plan_build_wave(p.context_lens, p.plan, E, E + p.plan.B + 1, &wp, w == 0 && wave == 0, [&](int b) {
-            const size_t o0 = ((size_t)b * p.Hq + head0) * D;
-            for (int i = 0; i < G * D; ++i) store_out(p, o0 + i, 0.f);
+            for (int c = 0; c < Gq; ++c) {
+                const size_t o0 = column_row(p, b, kvh, c) * D;
+                for (int i = 0; i < D; ++i) store_out(p, o0 + i, 0.f);
+            }
         }, T);
         if (first && lane == 0) {
             p.ws.plan_words[0] = pl.S * kTile; p.ws.plan_words[1] = pl.nranges;
@@ -587,9 +603,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                         if (KST && nxt.req != seg.b) load_q(nxt.req, Q);
                         issue_v(nxt.pg0, nxt.pg1);
                     }
-                    mfma_softmax_pv<true>(sv, V, st, cur.tile * kTile, seg.L, j, v0, v1);
+                    mfma_softmax_pv<true, MT>(sv, V, st, cur.tile * kTile, seg.L, seg.L - col_back, seg.L - (tokens - 1), j, v0, v1);
                 } else {
-                    mfma_softmax_pv(sv, V, st, cur.tile * kTile, seg.L, j);
+                    mfma_softmax_pv<false, MT>(sv, V, st, cur.tile * kTile, seg.L, seg.L - col_back, seg.L - (tokens - 1), j);
                     if (more) {
                         if (KST && nxt.req != seg.b) load_q(nxt.req, Q);
                         issue_v(nxt.pg0, nxt.pg1);
@@ -603,8 +619,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             st.l += __shfl_xor(st.l, 16);                        // per-lane sums of the four lane groups; m is common
             st.l += __shfl_xor(st.l, 32);
             float *slot = ring + (size_t)npend * slot_floats;
-            if (col < G) {
-                float *orow = slot + (wave * G + col) * (D + 4);
+            if (col < Gq) {
+                float *orow = slot + (wave * Gq + col) * (D + 4);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float4 lo4 = make_float4(st.acc[0][i], st.acc[1][i], st.acc[2][i], st.acc[3][i]);
@@ -613,7 +629,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                     *reinterpret_cast<float4 *>(orow + 32 * j + 8 * i + 4) = hi4;
                 }
                 if (j == 0) {
-                    float *sm_m = slot + kWaves * G * (D + 4);
+                    float *sm_m = slot + kWaves * Gq * (D + 4);
                     sm_m[wave * kMaxGroup + col] = st.m; sm_m[kWaves * kMaxGroup + wave * kMaxGroup + col] = st.l;
                 }
             }

@@ -46,6 +46,7 @@ struct omni_handle_s {
     int tune_force_partition = 0;
     int tune_prefill_splits = 0;
     int tune_prefill_min_split = kPrefillMinSplitTokens;
+    int tune_query_tokens = 1;
     // derived
     int kernel = 1;              // 1 = vector ALU, 2 = MFMA
     int G = 1;
@@ -95,7 +96,8 @@ struct omni_handle_s {
         nw = tune_target_wgs / d.num_kv_heads;
         if (nw < 1) nw = 1;
         // K goes through the staging area unless that leaves the ring with fewer than three slots it would otherwise have
-        const MfmaLds plain = mfma_lds_layout(d.batch, G, fp8, false), staged = mfma_lds_layout(d.batch, G, fp8, true);
+        const int Gq = G * tune_query_tokens;    // columns of a KV head: (query token, head) pairs
+        const MfmaLds plain = mfma_lds_layout(d.batch, Gq, fp8, false), staged = mfma_lds_layout(d.batch, Gq, fp8, true);
         k_staged = staged.ring_depth >= (plain.ring_depth < 3 ? plain.ring_depth : 3);
         lds = k_staged ? staged : plain;
         lds_attr_set = false;
@@ -108,9 +110,10 @@ struct omni_handle_s {
         long long cap = ranges + d.batch;
         if (cap > 0x3fffffff) cap = 0x3fffffff;
         r_cap = (int)cap;
+        const size_t rows = (size_t)r_cap * d.num_q_heads * tune_query_tokens;       // partial-result rows
         off_ml = 256;
-        off_o = align256(off_ml + (size_t)r_cap * d.num_q_heads * sizeof(float2));
-        ws_bytes = align256(off_o + (size_t)r_cap * d.num_q_heads * d.head_dim * sizeof(float));
+        off_o = align256(off_ml + rows * sizeof(float2));
+        ws_bytes = align256(off_o + rows * d.head_dim * sizeof(float));
     }
 };
 
@@ -168,7 +171,7 @@ omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value) {
             if (value < 0 || value > 2) return OMNI_ERR_SHAPE;
             if (value == 2 && !(h->d.kv_dtype == OMNI_BF16 && h->d.head_dim == 128) && h->d.kv_dtype != OMNI_FP8_E4M3)
                 return OMNI_ERR_UNSUPPORTED;
-            if (value == 1 && h->d.kv_dtype == OMNI_FP8_E4M3) return OMNI_ERR_UNSUPPORTED;
+            if (value == 1 && (h->d.kv_dtype == OMNI_FP8_E4M3 || h->tune_query_tokens > 1)) return OMNI_ERR_UNSUPPORTED;
             h->tune_kernel = value; break;
         case OMNI_TUNE_TARGET_WORKGROUPS:
             if (value <= 0) return OMNI_ERR_SHAPE;
@@ -182,6 +185,10 @@ omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value) {
         case OMNI_TUNE_PREFILL_SPLITS:
             if (value < 0 || value > 16) return OMNI_ERR_SHAPE;
             h->tune_prefill_splits = value; break;
+        case OMNI_TUNE_QUERY_TOKENS:
+            if (value < 1) return OMNI_ERR_SHAPE;
+            if (value > 1 && (h->kernel != 2 || value * h->G > kMaxGroup)) return OMNI_ERR_UNSUPPORTED;
+            h->tune_query_tokens = value; break;
         case OMNI_TUNE_PREFILL_MIN_SPLIT:
             if (value < 2 * kTile || value % (2 * kTile)) return OMNI_ERR_SHAPE;
             h->tune_prefill_min_split = value; break;
@@ -277,6 +284,8 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.plan.s_force = h->tune_force_partition / kTile;
     p.scale_log2 = scale * kLog2e;
     p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
+    p.T = h->tune_query_tokens; p.Gq = h->G * h->tune_query_tokens;
+    if (p.T > 1 && (k_new || v_new)) return OMNI_ERR_UNSUPPORTED;       // the fused append writes one row per request
     p.log2_ps = ilog2(d.page_size);
     p.out_bf16 = d.out_dtype == OMNI_BF16;
     p.lds = h->lds;
@@ -295,7 +304,12 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     if (h->kernel == 2) {
         const bool ps16 = d.page_size == 16, st = h->k_staged;
         const void *fn;
-        if (fp8) fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true> : (const void *)&decode_mfma_kernel<16, true, false>)
+        if (p.T > 1) {
+            if (fp8) fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true, true> : (const void *)&decode_mfma_kernel<16, true, false, true>)
+                               : (st ? (const void *)&decode_mfma_kernel<32, true, true, true> : (const void *)&decode_mfma_kernel<32, true, false, true>);
+            else fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true, true> : (const void *)&decode_mfma_kernel<16, false, false, true>)
+                           : (st ? (const void *)&decode_mfma_kernel<32, false, true, true> : (const void *)&decode_mfma_kernel<32, false, false, true>);
+        } else if (fp8) fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true> : (const void *)&decode_mfma_kernel<16, true, false>)
                            : (st ? (const void *)&decode_mfma_kernel<32, true, true> : (const void *)&decode_mfma_kernel<32, true, false>);
         else fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true> : (const void *)&decode_mfma_kernel<16, false, false>)
                        : (st ? (const void *)&decode_mfma_kernel<32, false, true> : (const void *)&decode_mfma_kernel<32, false, false>);
