@@ -135,7 +135,9 @@ omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes);
  * rows are in the pools: omni_kv_append_chunk), query i sees tokens 0 .. context_lens[b] - T + i.  The kernel treats
  * the T * (Hq / Hkv) (token, head) pairs of a KV head as the columns of its matrix-core tiles, so the cache is still
  * read once: the call costs about what the one-token call costs.  Every request has exactly T tokens (or length 0);
- * a query that would see no token at all (context_lens[b] < T) gets zeros.  omni_decode_step needs T = 1.
+ * a query that would see no token at all (context_lens[b] < T) gets zeros.  omni_decode_step and omni_decode_step_fp8
+ * then take k_new / v_new [batch, T, num_kv_heads, head_dim] and write row i of request b to position
+ * context_lens[b] - T + i (rows whose position would be negative are skipped) before the attention reads it.
  * Ragged numbers of new tokens: omni_paged_prefill_attn.
  * Errors: NULL, WORKSPACE, HIP.
  */

@@ -323,9 +323,9 @@ inline MfmaLds mfma_lds_layout(int B, int G, bool kv8, bool staged) {
 // normalised output if the request lies inside one range, else the unnormalised values (plus, once per head, the
 // running max and sum) into the segment's partial-result slot.  Every thread owns four consecutive output
 // elements.  All threads call it between barriers.
-template <int D>
+template <int D, bool MT>
 __device__ __forceinline__ void mfma_combine_segment(const float *slot, const AttnParams &p, const Segment &seg, int kvh) {
-    const int G = p.Gq;                                  // columns: (query token, head) pairs of the KV head
+    const int G = MT ? p.Gq : p.G;                       // columns: (query token, head) pairs of the KV head
     const float *sm_m = slot + kWaves * G * (D + 4), *sm_l = sm_m + kWaves * kMaxGroup;
     for (int idx = 4 * threadIdx.x; idx < G * D; idx += 4 * kThreads) {
         const int g = idx / D, d = idx - g * D;
@@ -345,7 +345,7 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
             }
         }
         if (seg.nparts == 1) {
-            const size_t o0 = column_row(p, seg.b, kvh, g) * D + d;
+            const size_t o0 = (MT ? column_row(p, seg.b, kvh, g) : (size_t)seg.b * p.Hq + kvh * G + g) * D + d;
             const bool live = den > 0.f;
             const float4 r = make_float4(live ? num.x / den : 0.f, live ? num.y / den : 0.f, live ? num.z / den : 0.f,
                                          live ? num.w / den : 0.f);
@@ -358,7 +358,7 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
                 *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.out) + o0) = r;
             }
         } else {
-            const size_t pi = column_row(p, seg.slot, kvh, g);
+            const size_t pi = MT ? column_row(p, seg.slot, kvh, g) : (size_t)seg.slot * p.Hq + kvh * G + g;
             *reinterpret_cast<float4 *>(p.ws.part_o + pi * D + d) = num;
             if (d == 0) p.ws.part_ml[pi] = make_float2(M, den);
         }
@@ -441,9 +441,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         unsigned long long T = 0;
         const bool first = blockIdx.x == 0 && wave == 0;
         pl = plan_build_wave(p.context_lens, p.plan, E, E + p.plan.B + 1, &wp, w == 0 && wave == 0, [&](int b) {
-            for (int c = 0; c < Gq; ++c) {
-                const size_t o0 = column_row(p, b, kvh, c) * D;
-                for (int i = 0; i < D; ++i) store_out(p, o0 + i, 0.f);
+            if (!MT) {
+                const size_t o0 = ((size_t)b * p.Hq + head0) * D;
+                for (int i = 0; i < G * D; ++i) store_out(p, o0 + i, 0.f);
+            } else {
+                for (int c = 0; c < Gq; ++c) {
+                    const size_t o0 = column_row(p, b, kvh, c) * D;
+                    for (int i = 0; i < D; ++i) store_out(p, o0 + i, 0.f);
+                }
             }
         }, T);
         if (first && lane == 0) {
@@ -484,7 +489,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 const int32_t *bt = p.block_table + (size_t)lo * p.MB;
                 const int page = (t * kTile) >> kLog2Ps;
                 meta.x = lo;
-                meta.y = t | ((p.k_new != nullptr && t == ((Lc[lo] - 1) >> kLog2Tile)) ? kAppendFlag : 0);
+                // fused step: the tiles that hold the request's newest token(s) get their rows written first
+                bool newest = t == ((Lc[lo] - 1) >> kLog2Tile);
+                if (MT) newest = newest || (t < ((Lc[lo] - 1) >> kLog2Tile) && t >= (max(Lc[lo] - p.T, 0) >> kLog2Tile));
+                meta.y = t | ((p.k_new != nullptr && newest) ? kAppendFlag : 0);
                 if (PS == 16 && page < last_page) {              // both pages exist: one 8-byte read (page is even)
                     struct alignas(4) PagePair { int first, second; };   // rows of odd length keep 4-byte alignment
                     const PagePair pp2 = *reinterpret_cast<const PagePair *>(bt + page);
@@ -509,18 +517,25 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         // Fused decode step: the tile that holds the request's last token gets the new K/V row written into its page
         // (a bit copy, the first lanes the K row, the next ones the V row, 16 bytes each) before the tile is requested; the wave waits for
         // the write to be acknowledged, so the loads that follow see it.
+        // With several query tokens per request the new rows are [B, T, Hkv, D] and each tile takes those of the
+        // request's last T positions that fall into it.
         auto append_row = [&](const SlotInfo &si) {
-            const int pos = Lc[si.req] - 1;
-            const int pg = (PS == 16 && (pos & 16)) ? si.pg1 : si.pg0;
             constexpr int kRowPieces = D * ES / 16;              // 16-byte pieces of a row: 16 (16-bit cache) or 8
-            const size_t row = (size_t)pg * ld.page_stride + (size_t)(pos & (PS - 1)) * (D * ES);
-            if (lane < 2 * kRowPieces) {
-                const bool is_v = lane >= kRowPieces;
-                const int piece = lane & (kRowPieces - 1);
-                const char *src = reinterpret_cast<const char *>(is_v ? p.v_new : p.k_new) +
-                                  ((size_t)si.req * p.Hkv + kvh) * (D * ES) + piece * 16;
-                char *dst = const_cast<char *>(is_v ? ld.vbase : ld.kbase) + row + piece * 16;
-                *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+            const int L = Lc[si.req];
+#pragma unroll 1
+            for (int qi = 0; qi < tokens; ++qi) {
+                const int pos = L - tokens + qi;
+                if (MT && (pos < 0 || (pos >> kLog2Tile) != si.tile)) continue;      // uniform
+                const int pg = (PS == 16 && (pos & 16)) ? si.pg1 : si.pg0;
+                const size_t row = (size_t)pg * ld.page_stride + (size_t)(pos & (PS - 1)) * (D * ES);
+                if (lane < 2 * kRowPieces) {
+                    const bool is_v = lane >= kRowPieces;
+                    const int piece = lane & (kRowPieces - 1);
+                    const char *src = reinterpret_cast<const char *>(is_v ? p.v_new : p.k_new) +
+                                      (((size_t)si.req * tokens + qi) * p.Hkv + kvh) * (D * ES) + piece * 16;
+                    char *dst = const_cast<char *>(is_v ? ld.vbase : ld.kbase) + row + piece * 16;
+                    *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+                }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_s_waitcnt(0);           // all counters: the row is in memory before the tile is read
@@ -644,7 +659,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                     if (r < npend) {
                         const int rb = r == 0 ? pend0 : (r == 1 ? pend1 : (r == 2 ? pend2 : pend3));
                         const Segment sg = plan_segment(E, Lc, pl, rb, range, start, end);
-                        mfma_combine_segment<D>(ring + (size_t)r * slot_floats, p, sg, kvh);   // nobody waits for its stores
+                        mfma_combine_segment<D, MT>(ring + (size_t)r * slot_floats, p, sg, kvh);   // nobody waits for its stores
                     }
                 }
                 lds_barrier();

@@ -285,7 +285,6 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.scale_log2 = scale * kLog2e;
     p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
     p.T = h->tune_query_tokens; p.Gq = h->G * h->tune_query_tokens;
-    if (p.T > 1 && (k_new || v_new)) return OMNI_ERR_UNSUPPORTED;       // the fused append writes one row per request
     p.log2_ps = ilog2(d.page_size);
     p.out_bf16 = d.out_dtype == OMNI_BF16;
     p.lds = h->lds;

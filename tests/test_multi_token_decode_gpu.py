@@ -139,11 +139,78 @@ def test_what_the_setting_rejects():
             h.omni_set_tuning(omni.OMNI_TUNE_QUERY_TOKENS, bad)
     with pytest.raises(omni.OmniError):
         h.omni_set_tuning(omni.OMNI_TUNE_KERNEL, omni.KERNEL_VALU)       # the vector-ALU kernel takes one token
-    ws = h.alloc_workspace()
-    L = omni.lib()
-    import ctypes as C
-    assert L.omni_decode_step(h._h, 256, 256, 256, 256, 256, 256, 256, C.c_float(1.0), 256, None) == 4
     f32 = omni.Handle(batch=4, num_q_heads=4, num_kv_heads=2, head_dim=64, page_size=16, num_pages=64,
                       max_blocks_per_seq=8, kv_dtype=omni.OMNI_F32)
     with pytest.raises(omni.OmniError):
         f32.omni_set_tuning(omni.OMNI_TUNE_QUERY_TOKENS, 2)
+
+
+@pytest.mark.parametrize("G,Hkv,T,ps,fp8", [(7, 4, 2, 16, False), (4, 2, 4, 32, False), (1, 2, 16, 16, False),
+                                            (8, 2, 2, 16, True), (3, 1, 5, 32, True)])
+@pytest.mark.parametrize("force_pl", [0, 32])
+def test_fused_step_equals_chunk_append_then_attention(G, Hkv, T, ps, fp8, force_pl):
+    """omni_decode_step (and its 8-bit form) with T tokens per request: the T new rows land at positions L - T .. L - 1
+    (wherever tile and page boundaries fall between them; rows of negative positions are skipped) before the attention
+    reads them: same pools and output, bit for bit, as writing the rows first and attending afterwards."""
+    lens = [2, 5, 16, 17, 31, 32, 33, 34, 35, 47, 48, 49, 64, 65, 66, 250, 0, 96, 97, 1, 3]
+    wl = W.build("mtstep", 2800 + G + T, lens, Hq=G * Hkv, Hkv=Hkv, D=128, ps=ps, dtype=W.BF16, pool_factor=1.5)
+    q = queries(wl, T, 2900)
+    tuning = {omni.OMNI_TUNE_QUERY_TOKENS: T}
+    if force_pl:
+        tuning[omni.OMNI_TUNE_FORCE_PARTITION] = force_pl
+    rng = np.random.default_rng(2950)
+    if fp8:
+        f8 = W.quantize_fp8(wl)
+        pools_k, pools_v = f8.k_cache, f8.v_cache
+        finite = np.array([b for b in range(256) if (b & 0x7F) < 0x60], dtype=np.uint8)
+        k_new = rng.choice(finite, size=(wl.B, T, wl.Hkv, wl.D)).astype(np.uint8)
+        v_new = rng.choice(finite, size=(wl.B, T, wl.Hkv, wl.D)).astype(np.uint8)
+        poison = W.FP8_NAN_BYTE
+    else:
+        pools_k, pools_v = wl.k_cache, wl.v_cache
+        k_new = W.f32_to_bf16_bits(rng.standard_normal((wl.B, T, wl.Hkv, wl.D)).astype(np.float32))
+        v_new = W.f32_to_bf16_bits(rng.standard_normal((wl.B, T, wl.Hkv, wl.D)).astype(np.float32))
+        poison = np.uint16(0x7fc1)
+    want_k, want_v = pools_k.copy(), pools_v.copy()
+    for b in range(wl.B):                                    # the newest rows are not in the pools yet
+        for i in range(T):
+            t = int(wl.context_lens[b]) - T + i
+            if t >= 0:
+                pg, sl = wl.block_table[b, t // wl.ps], t % wl.ps
+                pools_k[pg, :, sl, :] = poison; pools_v[pg, :, sl, :] = poison
+                want_k[pg, :, sl, :] = k_new[b, i]; want_v[pg, :, sl, :] = v_new[b, i]
+    out = torch.full((wl.B, T, wl.Hq, wl.D), float("nan"), dtype=torch.float32, device="cuda")
+    dq = to_dev(q, wl.dtype)
+    if fp8:
+        fb = Fp8Batch(wl, f8, tuning)
+        kn, vn = torch.from_numpy(k_new).cuda(), torch.from_numpy(v_new).cuda()
+        fb.h.omni_decode_step_fp8(dq, kn, vn, fb.k, fb.v, fb.ks, fb.vs, fb.bt, fb.lens, float(wl.scale), out)
+        torch.cuda.synchronize()
+        got_k, got_v = fb.k.cpu().numpy(), fb.v.cpu().numpy()
+        n, offs = chunk_args(wl, T)
+        ref = oracle.paged_prefill_attn_fp8(q, want_k, want_v, f8.k_scale, f8.v_scale, wl.block_table, wl.context_lens,
+                                            n, offs, wl.scale).reshape(wl.B, T, wl.Hq, wl.D)
+        # attention alone over pools that already hold the rows
+        f8.k_cache[:] = want_k; f8.v_cache[:] = want_v
+        fb2 = Fp8Batch(wl, f8, tuning)
+        out2 = torch.full_like(out, float("nan"))
+        fb2.h.omni_paged_decode_attn_fp8(dq, fb2.k, fb2.v, fb2.ks, fb2.vs, fb2.bt, fb2.lens, float(wl.scale), out2)
+    else:
+        dev = DeviceBatch(wl, tuning=tuning)
+        kn, vn = to_dev(k_new, wl.dtype), to_dev(v_new, wl.dtype)
+        dev.h.omni_decode_step(dq, kn, vn, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens, float(wl.scale), out)
+        torch.cuda.synchronize()
+        from gpu_util import bits_of
+        got_k, got_v = bits_of(dev.k_cache), bits_of(dev.v_cache)
+        wl.k_cache[:] = want_k; wl.v_cache[:] = want_v
+        ref = expected(wl, q, T)
+        dev2 = DeviceBatch(wl, tuning=tuning)
+        out2 = torch.full_like(out, float("nan"))
+        dev2.h.omni_paged_decode_attn(dq, dev2.k_cache, dev2.v_cache, dev2.block_table, dev2.context_lens, float(wl.scale), out2)
+    torch.cuda.synchronize()
+    assert np.array_equal(got_k.view(np.uint8), want_k.view(np.uint8)) and np.array_equal(got_v.view(np.uint8), want_v.view(np.uint8))
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, out2.cpu().numpy().astype(np.float64))
+    bar = TOL[W.BF16] if not fp8 else max(TOL[W.BF16], 2.0 ** -9 * np.max(np.abs(ref)))
+    assert np.all(np.isfinite(got)) and np.max(np.abs(got - ref)) <= bar
+
