@@ -95,10 +95,12 @@ struct omni_handle_s {
         kernel = fp8 ? 2 : ((tune_kernel == 2 && mfma_ok) ? 2 : (tune_kernel == 1 ? 1 : (mfma_ok ? 2 : 1)));
         nw = tune_target_wgs / d.num_kv_heads;
         if (nw < 1) nw = 1;
-        // K goes through the staging area unless that leaves the ring with fewer than three slots it would otherwise have
+        // K goes through the staging area unless that leaves the ring with fewer than three slots where it would have
+        // three or four without (measured: four slots beat staging with two at 8 columns; staging with one slot beats
+        // two slots without at 14 and 16 columns)
         const int Gq = G * tune_query_tokens;    // columns of a KV head: (query token, head) pairs
         const MfmaLds plain = mfma_lds_layout(d.batch, Gq, fp8, false), staged = mfma_lds_layout(d.batch, Gq, fp8, true);
-        k_staged = staged.ring_depth >= (plain.ring_depth < 3 ? plain.ring_depth : 3);
+        k_staged = staged.ring_depth >= 3 || plain.ring_depth <= 2;
         lds = k_staged ? staged : plain;
         lds_attr_set = false;
         long long ranges = nw;
