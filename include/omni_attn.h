@@ -27,6 +27,8 @@
  * Layouts (row-major, contiguous)
  *   q, out              [batch, num_q_heads, head_dim]
  *   k_new, v_new        [batch, num_kv_heads, head_dim]
+ *                       (with OMNI_TUNE_QUERY_TOKENS = T > 1: q, out [batch, T, num_q_heads, head_dim] and
+ *                       k_new, v_new [batch, T, num_kv_heads, head_dim], see omni_paged_decode_attn)
  *   k_cache, v_cache    [num_pages, num_kv_heads, page_size, head_dim]   (two separate pools)
  *   block_table         [batch, max_blocks_per_seq] int32; entry j of row b is the physical page of
  *                       tokens [j*page_size, (j+1)*page_size) of request b; entries at or beyond

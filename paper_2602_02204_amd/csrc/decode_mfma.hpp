@@ -15,6 +15,9 @@
 //     the S^T accumulators of that lane group hold, so P needs no data movement; V is loaded row-wise (a 256-byte
 //     row per 16 lanes) and an 8x8 in-lane transpose (v_perm_b32) turns 8 rows x 8 dims into 8 operands.
 // The weights go to the matrix core as bf16 hi + bf16 lo (two MFMAs), which keeps them to ~2^-16 relative.
+// With T query tokens per request (kernel variant MT, T * G <= 16) a column is a (query token, head) pair instead of
+// a head: it has its own query row, its own causal limit (tokens 0 .. L - T + i) and its own output row; everything
+// that is said of a head above holds per column.  An 8-bit cache (variant KV8) is widened to bf16 in registers.
 #pragma once
 #include "common.hpp"
 
