@@ -95,8 +95,7 @@ typedef enum {
     OMNI_TUNE_PREFILL_MIN_SPLIT = 5,/* fewest tokens of context one of them takes (multiple of 64; default 256): a query
                                        block with a shorter context is shared by fewer, decided on the device */
     OMNI_TUNE_QUERY_TOKENS = 6      /* T >= 1 (default 1): omni_paged_decode_attn and omni_paged_decode_attn_fp8 take T query
-                                       tokens per request, see there.  Matrix-core kernel only, T * (Hq / Hkv) <= 16,
-                                       else UNSUPPORTED */
+                                       tokens per request, see there.  Matrix-core kernel only, else UNSUPPORTED */
 } omni_tune_key_t;
 
 /* Validate `desc` and create a handle holding host-side plan state only (no device memory).
@@ -135,8 +134,9 @@ omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes);
  * Several query tokens per request (speculative decoding, multi-token prediction; OMNI_TUNE_QUERY_TOKENS = T > 1): q
  * and out are [batch, T, num_q_heads, head_dim]; the T tokens are the LAST T of the context_lens[b] tokens (their K/V
  * rows are in the pools: omni_kv_append_chunk), query i sees tokens 0 .. context_lens[b] - T + i.  The kernel treats
- * the T * (Hq / Hkv) (token, head) pairs of a KV head as the columns of its matrix-core tiles, so the cache is still
- * read once: the call costs about what the one-token call costs.  Every request has exactly T tokens (or length 0);
+ * the (token, head) pairs of a KV head as the columns of its matrix-core tiles, 16 per pass: with T * (Hq / Hkv) <= 16
+ * the cache is still read once and the call costs about what the one-token call costs; a larger T takes
+ * ceil(T / floor(16 / (Hq / Hkv))) passes (launch pairs) over the cache.  Every request has exactly T tokens (or length 0);
  * a query that would see no token at all (context_lens[b] < T) gets zeros.  omni_decode_step and omni_decode_step_fp8
  * then take k_new / v_new [batch, T, num_kv_heads, head_dim] and write row i of request b to position
  * context_lens[b] - T + i (rows whose position would be negative are skipped) before the attention reads it.

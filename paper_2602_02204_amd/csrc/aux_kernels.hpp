@@ -15,7 +15,7 @@ template <int D, int kRound>
 __device__ __forceinline__ void merge_request(const AttnParams &p, int b, int kvh, int slot_first, int n) {
     for (int idx = 4 * threadIdx.x; idx < p.Gq * D; idx += 4 * kThreads) {    // one pass up to 1024 elements
         const int g = idx / D;                                                // column: (query token, head)
-        const size_t out0 = column_row(p, b, kvh, g) * D + (idx - g * D);
+        const size_t out0 = out_row(p, b, kvh, g) * D + (idx - g * D);
         float M = -INFINITY, den = 0.f;
         float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int j0 = 0; j0 < n; j0 += kRound) {
@@ -25,7 +25,7 @@ __device__ __forceinline__ void merge_request(const AttnParams &p, int b, int kv
             for (int u = 0; u < kRound; ++u) {
                 ml[u] = make_float2(0.f, 0.f); oj[u] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (j0 + u < n) {
-                    const size_t pi = column_row(p, slot_first + j0 + u, kvh, g);
+                    const size_t pi = partial_row(p, slot_first + j0 + u, kvh, g);
                     ml[u] = p.ws.part_ml[pi];
                     oj[u] = *reinterpret_cast<const float4 *>(p.ws.part_o + pi * D + (idx - g * D));
                 }

@@ -46,8 +46,9 @@ struct AttnParams {
     PlanParams plan;
     float scale_log2;                   // scale * log2(e): scores are kept in the log2 domain and exp2 is used
     int Hq, Hkv, G, MB;
-    int T;                              // query tokens per request (1 = plain decode); q and out are [B, T, Hq, D]
-    int Gq;                             // T * G: the (query token, head) columns of one KV head
+    int Tq;                             // query tokens per request (1 = plain decode); q and out are [B, Tq, Hq, D]
+    int T, t_off;                       // this launch covers query tokens t_off .. t_off + T - 1 of every request
+    int Gq;                             // T * G: the (query token, head) columns of one KV head in this launch
     int log2_ps;
     int out_bf16;
     MfmaLds lds;                        // matrix-core kernel only
@@ -56,12 +57,17 @@ struct AttnParams {
 #endif
 };
 
-// Row of `out` (X = request) or of the partial results (X = slot) that column c of KV head kvh stands for: query token
-// c / G, head kvh * G + c % G; both arrays are [X][T][Hq] rows.
-__device__ __forceinline__ size_t column_row(const AttnParams &p, size_t X, int kvh, int c) {
-    if (p.T == 1) return X * p.Hq + kvh * p.G + c;               // plain decode: no division
+// Column c of KV head kvh stands for query token t_off + c / G of its request and head kvh * G + c % G.  Its row of
+// `out` [B][Tq][Hq] for request b, and its row of the partial results [slot][T][Hq] (this launch's tokens only):
+__device__ __forceinline__ size_t out_row(const AttnParams &p, size_t b, int kvh, int c) {
+    if (p.Tq == 1) return b * p.Hq + kvh * p.G + c;              // plain decode: no division
     const int qi = c / p.G, g = c - qi * p.G;
-    return (X * p.T + qi) * p.Hq + kvh * p.G + g;
+    return (b * p.Tq + p.t_off + qi) * p.Hq + kvh * p.G + g;
+}
+__device__ __forceinline__ size_t partial_row(const AttnParams &p, size_t slot, int kvh, int c) {
+    if (p.T == 1) return slot * p.Hq + kvh * p.G + c;
+    const int qi = c / p.G, g = c - qi * p.G;
+    return (slot * p.T + qi) * p.Hq + kvh * p.G + g;
 }
 
 // Phase timestamps for development builds (compiled out otherwise): slot `id` of this wave's record.
@@ -196,7 +202,7 @@ __device__ __forceinline__ Plan attn_prologue(const AttnParams &p, PlanSmem *ps,
     const Plan pl = plan_build(p.context_lens, p.plan, ps, E, E + p.plan.B + 1, [&](int b) {
         if (w == 0) {
             for (int c = 0; c < p.Gq; ++c) {
-                const size_t o0 = column_row(p, b, kvh, c) * D;
+                const size_t o0 = out_row(p, b, kvh, c) * D;
                 for (int i = 0; i < D; ++i) store_out(p, o0 + i, 0.f);
             }
         }

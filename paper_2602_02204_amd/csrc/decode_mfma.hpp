@@ -348,7 +348,7 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
             }
         }
         if (seg.nparts == 1) {
-            const size_t o0 = (MT ? column_row(p, seg.b, kvh, g) : (size_t)seg.b * p.Hq + kvh * G + g) * D + d;
+            const size_t o0 = (MT ? out_row(p, seg.b, kvh, g) : (size_t)seg.b * p.Hq + kvh * G + g) * D + d;
             const bool live = den > 0.f;
             const float4 r = make_float4(live ? num.x / den : 0.f, live ? num.y / den : 0.f, live ? num.z / den : 0.f,
                                          live ? num.w / den : 0.f);
@@ -361,7 +361,7 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
                 *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.out) + o0) = r;
             }
         } else {
-            const size_t pi = MT ? column_row(p, seg.slot, kvh, g) : (size_t)seg.slot * p.Hq + kvh * G + g;
+            const size_t pi = MT ? partial_row(p, seg.slot, kvh, g) : (size_t)seg.slot * p.Hq + kvh * G + g;
             *reinterpret_cast<float4 *>(p.ws.part_o + pi * D + d) = num;
             if (d == 0) p.ws.part_ml[pi] = make_float2(M, den);
         }
@@ -405,8 +405,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     const int head0 = kvh * G;
     const int col_qi = (MT && col < Gq) ? col / G : 0;           // this lane's column: query token, head, and how many
     const int col_g = col - col_qi * G;                          // of the request's newest tokens it must not see
-    const int col_back = (MT && col < Gq) ? p.T - 1 - col_qi : 0;
-    const int tokens = MT ? p.T : 1;
+    const int tokens = MT ? p.Tq : 1;                            // query tokens per request, t_off .. in this launch
+    const int t_off = MT ? p.t_off : 0;
+    const int col_back = (MT && col < Gq) ? tokens - 1 - (t_off + col_qi) : 0;
 
     MfmaTileLoader<PS> ld;
     ld.page_stride = (size_t)p.Hkv * PS * D * ES;
@@ -428,7 +429,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) Q[kk] = make_uint4(0, 0, 0, 0);
         if (col < Gq) {
-            const char *qrow = reinterpret_cast<const char *>(p.q) + (((size_t)b * tokens + col_qi) * p.Hq + head0 + col_g) * (D * 2);
+            const char *qrow = reinterpret_cast<const char *>(p.q) + (((size_t)b * tokens + t_off + col_qi) * p.Hq + head0 + col_g) * (D * 2);
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)                      // dims of step kk: (4kk + j) * 8 .., or 32j + 8kk .. (KV8)
                 Q[kk] = *reinterpret_cast<const uint4 *>(qrow + (KV8 ? 4 * j + kk : 4 * kk + j) * 16);
@@ -449,7 +450,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 for (int i = 0; i < G * D; ++i) store_out(p, o0 + i, 0.f);
             } else {
                 for (int c = 0; c < Gq; ++c) {
-                    const size_t o0 = column_row(p, b, kvh, c) * D;
+                    const size_t o0 = out_row(p, b, kvh, c) * D;
                     for (int i = 0; i < D; ++i) store_out(p, o0 + i, 0.f);
                 }
             }
@@ -494,7 +495,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 meta.x = lo;
                 // fused step: the tiles that hold the request's newest token(s) get their rows written first
                 bool newest = t == ((Lc[lo] - 1) >> kLog2Tile);
-                if (MT) newest = newest || (t < ((Lc[lo] - 1) >> kLog2Tile) && t >= (max(Lc[lo] - p.T, 0) >> kLog2Tile));
+                if (MT) newest = newest || (t < ((Lc[lo] - 1) >> kLog2Tile) && t >= (max(Lc[lo] - p.Tq, 0) >> kLog2Tile));
                 meta.y = t | ((p.k_new != nullptr && newest) ? kAppendFlag : 0);
                 if (PS == 16 && page < last_page) {              // both pages exist: one 8-byte read (page is even)
                     struct alignas(4) PagePair { int first, second; };   // rows of odd length keep 4-byte alignment
@@ -621,9 +622,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                         if (KST && nxt.req != seg.b) load_q(nxt.req, Q);
                         issue_v(nxt.pg0, nxt.pg1);
                     }
-                    mfma_softmax_pv<true, MT>(sv, V, st, cur.tile * kTile, seg.L, seg.L - col_back, seg.L - (tokens - 1), j, v0, v1);
+                    mfma_softmax_pv<true, MT>(sv, V, st, cur.tile * kTile, seg.L, seg.L - col_back, seg.L - (tokens - 1 - t_off), j, v0, v1);
                 } else {
-                    mfma_softmax_pv<false, MT>(sv, V, st, cur.tile * kTile, seg.L, seg.L - col_back, seg.L - (tokens - 1), j);
+                    mfma_softmax_pv<false, MT>(sv, V, st, cur.tile * kTile, seg.L, seg.L - col_back, seg.L - (tokens - 1 - t_off), j);
                     if (more) {
                         if (KST && nxt.req != seg.b) load_q(nxt.req, Q);
                         issue_v(nxt.pg0, nxt.pg1);

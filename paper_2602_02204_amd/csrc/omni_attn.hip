@@ -50,6 +50,7 @@ struct omni_handle_s {
     // derived
     int kernel = 1;              // 1 = vector ALU, 2 = MFMA
     int G = 1;
+    int pass_tokens = 1;         // query tokens per request one launch of the attention kernel covers
     int max_ctx = 0;
     int nw = 1;                  // workgroups per KV head
     int r_cap = 0;               // bound on partial-result slots (range index + request index)
@@ -98,7 +99,10 @@ struct omni_handle_s {
         // K goes through the staging area unless that leaves the ring with fewer than three slots where it would have
         // three or four without (measured: four slots beat staging with two at 8 columns; staging with one slot beats
         // two slots without at 14 and 16 columns)
-        const int Gq = G * tune_query_tokens;    // columns of a KV head: (query token, head) pairs
+        // query tokens one launch takes: as many as fit the 16 columns of a KV head's tiles; more go in several passes
+        pass_tokens = tune_query_tokens;
+        if (pass_tokens * G > kMaxGroup) pass_tokens = kMaxGroup / G;
+        const int Gq = G * pass_tokens;          // columns of a KV head: (query token, head) pairs
         const MfmaLds plain = mfma_lds_layout(d.batch, Gq, fp8, false), staged = mfma_lds_layout(d.batch, Gq, fp8, true);
         k_staged = staged.ring_depth >= 3 || plain.ring_depth <= 2;
         lds = k_staged ? staged : plain;
@@ -112,7 +116,7 @@ struct omni_handle_s {
         long long cap = ranges + d.batch;
         if (cap > 0x3fffffff) cap = 0x3fffffff;
         r_cap = (int)cap;
-        const size_t rows = (size_t)r_cap * d.num_q_heads * tune_query_tokens;       // partial-result rows
+        const size_t rows = (size_t)r_cap * d.num_q_heads * pass_tokens;             // partial-result rows
         off_ml = 256;
         off_o = align256(off_ml + rows * sizeof(float2));
         ws_bytes = align256(off_o + rows * d.head_dim * sizeof(float));
@@ -189,7 +193,7 @@ omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value) {
             h->tune_prefill_splits = value; break;
         case OMNI_TUNE_QUERY_TOKENS:
             if (value < 1) return OMNI_ERR_SHAPE;
-            if (value > 1 && (h->kernel != 2 || value * h->G > kMaxGroup)) return OMNI_ERR_UNSUPPORTED;
+            if (value > 1 && h->kernel != 2) return OMNI_ERR_UNSUPPORTED;
             h->tune_query_tokens = value; break;
         case OMNI_TUNE_PREFILL_MIN_SPLIT:
             if (value < 2 * kTile || value % (2 * kTile)) return OMNI_ERR_SHAPE;
@@ -286,7 +290,7 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.plan.s_force = h->tune_force_partition / kTile;
     p.scale_log2 = scale * kLog2e;
     p.Hq = d.num_q_heads; p.Hkv = d.num_kv_heads; p.G = h->G; p.MB = d.max_blocks_per_seq;
-    p.T = h->tune_query_tokens; p.Gq = h->G * h->tune_query_tokens;
+    p.Tq = h->tune_query_tokens;
     p.log2_ps = ilog2(d.page_size);
     p.out_bf16 = d.out_dtype == OMNI_BF16;
     p.lds = h->lds;
@@ -294,61 +298,69 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.trace = g_omni_trace;
 #endif
 
-    const dim3 grid((unsigned)(h->nw * d.num_kv_heads));
-    const size_t dyn = (size_t)(2 * d.batch + 1) * sizeof(int);     // tile offsets and lengths of the plan
-    (void)hipGetLastError();
-    const bool prof = (size_t)(2 * h->prof_used + 1) < h->prof_events.size() && (h->prof_calls++ % h->prof_stride) == 0;
-    // Profiled launches of the matrix-core kernel carry their event pair in the dispatch itself (the events then hold
-    // the kernel's own start and stop times); around the other kernels the pair is recorded on the stream.
-    const bool prof_in_dispatch = prof && h->kernel == 2;
-    if (prof && !prof_in_dispatch && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
-    if (h->kernel == 2) {
-        const bool ps16 = d.page_size == 16, st = h->k_staged;
-        const void *fn;
-        if (p.T > 1) {
-            if (fp8) fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true, true> : (const void *)&decode_mfma_kernel<16, true, false, true>)
-                               : (st ? (const void *)&decode_mfma_kernel<32, true, true, true> : (const void *)&decode_mfma_kernel<32, true, false, true>);
-            else fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true, true> : (const void *)&decode_mfma_kernel<16, false, false, true>)
-                           : (st ? (const void *)&decode_mfma_kernel<32, false, true, true> : (const void *)&decode_mfma_kernel<32, false, false, true>);
-        } else if (fp8) fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true> : (const void *)&decode_mfma_kernel<16, true, false>)
-                           : (st ? (const void *)&decode_mfma_kernel<32, true, true> : (const void *)&decode_mfma_kernel<32, true, false>);
-        else fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true> : (const void *)&decode_mfma_kernel<16, false, false>)
-                       : (st ? (const void *)&decode_mfma_kernel<32, false, true> : (const void *)&decode_mfma_kernel<32, false, false>);
-        if (!h->lds_attr_set) {          // more than the default 64 KB of dynamic shared memory
-            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, h->lds.total) != hipSuccess) {
+    // Several query tokens per request: one pass (attention + merge) per pass_tokens of them; the new rows of a fused
+    // step are all written by the first pass.
+    for (int t_off = 0; t_off < p.Tq; t_off += h->pass_tokens) {
+        p.t_off = t_off;
+        p.T = p.Tq - t_off < h->pass_tokens ? p.Tq - t_off : h->pass_tokens;
+        p.Gq = p.T * h->G;
+        if (t_off > 0) { p.k_new = nullptr; p.v_new = nullptr; }
+        const dim3 grid((unsigned)(h->nw * d.num_kv_heads));
+        const size_t dyn = (size_t)(2 * d.batch + 1) * sizeof(int);     // tile offsets and lengths of the plan
+        (void)hipGetLastError();
+        const bool prof = (size_t)(2 * h->prof_used + 1) < h->prof_events.size() && (h->prof_calls++ % h->prof_stride) == 0;
+        // Profiled launches of the matrix-core kernel carry their event pair in the dispatch itself (the events then hold
+        // the kernel's own start and stop times); around the other kernels the pair is recorded on the stream.
+        const bool prof_in_dispatch = prof && h->kernel == 2;
+        if (prof && !prof_in_dispatch && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
+        if (h->kernel == 2) {
+            const bool ps16 = d.page_size == 16, st = h->k_staged;
+            const void *fn;
+            if (p.Tq > 1) {
+                if (fp8) fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true, true> : (const void *)&decode_mfma_kernel<16, true, false, true>)
+                                   : (st ? (const void *)&decode_mfma_kernel<32, true, true, true> : (const void *)&decode_mfma_kernel<32, true, false, true>);
+                else fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true, true> : (const void *)&decode_mfma_kernel<16, false, false, true>)
+                               : (st ? (const void *)&decode_mfma_kernel<32, false, true, true> : (const void *)&decode_mfma_kernel<32, false, false, true>);
+            } else if (fp8) fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true> : (const void *)&decode_mfma_kernel<16, true, false>)
+                               : (st ? (const void *)&decode_mfma_kernel<32, true, true> : (const void *)&decode_mfma_kernel<32, true, false>);
+            else fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true> : (const void *)&decode_mfma_kernel<16, false, false>)
+                           : (st ? (const void *)&decode_mfma_kernel<32, false, true> : (const void *)&decode_mfma_kernel<32, false, false>);
+            if (!h->lds_attr_set) {          // more than the default 64 KB of dynamic shared memory
+                if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, h->lds.total) != hipSuccess) {
+                    (void)hipGetLastError();
+                    return OMNI_ERR_HIP;
+                }
+                h->lds_attr_set = true;
+            }
+            void *args[] = {&p};
+            const hipError_t le = prof_in_dispatch
+                ? hipExtLaunchKernel(fn, grid, dim3(kThreads), args, (size_t)h->lds.total, s, h->prof_events[2 * h->prof_used],
+                                     h->prof_events[2 * h->prof_used + 1], 0)
+                : hipLaunchKernel(fn, grid, dim3(kThreads), args, (size_t)h->lds.total, s);
+            if (le != hipSuccess) {
                 (void)hipGetLastError();
                 return OMNI_ERR_HIP;
             }
-            h->lds_attr_set = true;
+        } else if (d.kv_dtype == OMNI_BF16) {
+            if (d.head_dim == 128) launch_valu<uint16_t, 128>(p, grid, dyn, s);
+            else launch_valu<uint16_t, 64>(p, grid, dyn, s);
+        } else {
+            if (d.head_dim == 128) launch_valu<float, 128>(p, grid, dyn, s);
+            else launch_valu<float, 64>(p, grid, dyn, s);
         }
-        void *args[] = {&p};
-        const hipError_t le = prof_in_dispatch
-            ? hipExtLaunchKernel(fn, grid, dim3(kThreads), args, (size_t)h->lds.total, s, h->prof_events[2 * h->prof_used],
-                                 h->prof_events[2 * h->prof_used + 1], 0)
-            : hipLaunchKernel(fn, grid, dim3(kThreads), args, (size_t)h->lds.total, s);
-        if (le != hipSuccess) {
-            (void)hipGetLastError();
-            return OMNI_ERR_HIP;
+        if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+        if (prof) {
+            if (!prof_in_dispatch && hipEventRecord(h->prof_events[2 * h->prof_used + 1], s) != hipSuccess) return OMNI_ERR_HIP;
+            ++h->prof_used;
         }
-    } else if (d.kv_dtype == OMNI_BF16) {
-        if (d.head_dim == 128) launch_valu<uint16_t, 128>(p, grid, dyn, s);
-        else launch_valu<uint16_t, 64>(p, grid, dyn, s);
-    } else {
-        if (d.head_dim == 128) launch_valu<float, 128>(p, grid, dyn, s);
-        else launch_valu<float, 64>(p, grid, dyn, s);
-    }
-    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
-    if (prof) {
-        if (!prof_in_dispatch && hipEventRecord(h->prof_events[2 * h->prof_used + 1], s) != hipSuccess) return OMNI_ERR_HIP;
-        ++h->prof_used;
-    }
 
-    // Whether any request was cut by a range boundary is known only on the device: the merge kernel always runs, and
-    // its workgroups return at once for requests that the attention kernel finished.
-    const dim3 mgrid((unsigned)(d.batch * d.num_kv_heads));
-    if (d.head_dim == 128) merge_kernel<128><<<mgrid, kThreads, dyn, s>>>(p);
-    else merge_kernel<64><<<mgrid, kThreads, dyn, s>>>(p);
-    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+        // Whether any request was cut by a range boundary is known only on the device: the merge kernel always runs, and
+        // its workgroups return at once for requests that the attention kernel finished.
+        const dim3 mgrid((unsigned)(d.batch * d.num_kv_heads));
+        if (d.head_dim == 128) merge_kernel<128><<<mgrid, kThreads, dyn, s>>>(p);
+        else merge_kernel<64><<<mgrid, kThreads, dyn, s>>>(p);
+        if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+    }
 
     return OMNI_OK;
 }

@@ -50,7 +50,9 @@ LENS = [2, 5, 16, 17, 31, 32, 33, 34, 64, 65, 66, 250, 0, 96, 97, 1, 3]
 
 
 @pytest.mark.parametrize("G,Hkv,T,ps", [(7, 4, 2, 16), (8, 2, 2, 16), (4, 2, 4, 32), (1, 3, 16, 16), (3, 2, 5, 16),
-                                        (5, 1, 3, 32), (16, 1, 1, 16), (2, 2, 7, 16)])
+                                        (5, 1, 3, 32), (16, 1, 1, 16), (2, 2, 7, 16),
+                                        # more columns than a pass holds: several passes, the last one ragged
+                                        (7, 4, 5, 16), (8, 2, 4, 16), (16, 1, 3, 32), (4, 2, 9, 16), (1, 2, 33, 16)])
 @pytest.mark.parametrize("tuning", [{}, {omni.OMNI_TUNE_FORCE_PARTITION: 32}, {omni.OMNI_TUNE_FORCE_PARTITION: 128},
                                     {omni.OMNI_TUNE_TARGET_WORKGROUPS: 64, omni.OMNI_TUNE_MIN_PARTITION: 32}],
                          ids=["default", "force32", "force128", "wg64"])
@@ -134,9 +136,9 @@ def test_what_the_setting_rejects():
     before = h.omni_workspace_bytes()
     h.omni_set_tuning(omni.OMNI_TUNE_QUERY_TOKENS, 2)
     assert h.omni_workspace_bytes() > before                 # twice the partial rows
-    for bad in (0, 3):                                       # 3 x 7 heads do not fit 16 columns
-        with pytest.raises(omni.OmniError):
-            h.omni_set_tuning(omni.OMNI_TUNE_QUERY_TOKENS, bad)
+    h.omni_set_tuning(omni.OMNI_TUNE_QUERY_TOKENS, 5)        # 5 x 7 heads: three passes of up to two tokens
+    with pytest.raises(omni.OmniError):
+        h.omni_set_tuning(omni.OMNI_TUNE_QUERY_TOKENS, 0)
     with pytest.raises(omni.OmniError):
         h.omni_set_tuning(omni.OMNI_TUNE_KERNEL, omni.KERNEL_VALU)       # the vector-ALU kernel takes one token
     f32 = omni.Handle(batch=4, num_q_heads=4, num_kv_heads=2, head_dim=64, page_size=16, num_pages=64,
@@ -146,7 +148,8 @@ def test_what_the_setting_rejects():
 
 
 @pytest.mark.parametrize("G,Hkv,T,ps,fp8", [(7, 4, 2, 16, False), (4, 2, 4, 32, False), (1, 2, 16, 16, False),
-                                            (8, 2, 2, 16, True), (3, 1, 5, 32, True)])
+                                            (8, 2, 2, 16, True), (3, 1, 5, 32, True), (7, 4, 5, 16, False),
+                                            (8, 2, 3, 32, True)])
 @pytest.mark.parametrize("force_pl", [0, 32])
 def test_fused_step_equals_chunk_append_then_attention(G, Hkv, T, ps, fp8, force_pl):
     """omni_decode_step (and its 8-bit form) with T tokens per request: the T new rows land at positions L - T .. L - 1
