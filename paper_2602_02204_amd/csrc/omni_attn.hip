@@ -325,8 +325,10 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
                                : (st ? (const void *)&decode_mfma_kernel<32, true, true> : (const void *)&decode_mfma_kernel<32, true, false>);
             else fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true> : (const void *)&decode_mfma_kernel<16, false, false>)
                            : (st ? (const void *)&decode_mfma_kernel<32, false, true> : (const void *)&decode_mfma_kernel<32, false, false>);
-            if (!h->lds_attr_set) {          // more than the default 64 KB of dynamic shared memory
-                if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, h->lds.total) != hipSuccess) {
+            if (!h->lds_attr_set) {          // more than the default 64 KB of dynamic shared memory: the setting belongs to
+                                             // the kernel, not to the handle, so every handle asks for the same bound (what
+                                             // any layout may use) and none lowers what another one needs
+                if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024 - 512) != hipSuccess) {
                     (void)hipGetLastError();
                     return OMNI_ERR_HIP;
                 }

@@ -341,6 +341,19 @@ def test_lengths_at_any_four_byte_alignment(B, kernel):
     assert all(np.array_equal(outs[0], o) for o in outs[1:])
 
 
+def test_handles_with_different_shared_memory_needs_take_turns():
+    """Two live handles on the same kernel variant whose ring layouts differ in size (the larger one above the 64 KB a
+    kernel gets without asking): launches alternate, neither may lower what the other was granted."""
+    rng = np.random.default_rng(600)
+    big = W.build("lds-big", 601, rng.integers(1, 300, size=300), Hq=16, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    small = W.build("lds-small", 602, rng.integers(1, 300, size=16), Hq=16, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    a, b = DeviceBatch(big), DeviceBatch(small)
+    ra, rb = oracle_out(big), oracle_out(small)
+    for _ in range(3):
+        assert np.max(np.abs(a.attend() - ra)) <= TOL[W.BF16]
+        assert np.max(np.abs(b.attend() - rb)) <= TOL[W.BF16]
+
+
 # --------------------------------------------------------------------------- full-size configurations, sampled rows
 FULL = ["thinker", "talker", "long", "mixed"]
 
