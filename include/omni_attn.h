@@ -118,6 +118,14 @@ omni_status_t omni_workspace_bytes(omni_handle_t h, size_t *bytes);
  * sizes.  Errors: NULL, SHAPE (max_q_len <= 0). */
 omni_status_t omni_prefill_workspace_bytes(omni_handle_t h, int32_t max_q_len, size_t *bytes);
 
+/* With OMNI_TUNE_QUERY_TOKENS = T > 1: a DEVICE array [batch] int32 that says how many query tokens each request
+ * brings in the calls that follow, 0 .. T (values outside are clamped): request b's are the last dev_q_lens[b] tokens of
+ * its context, in rows 0 .. dev_q_lens[b] - 1 of its T rows of q / out / k_new / v_new; its other rows of out are
+ * written as zeros and its other new rows are not appended.  The library keeps the pointer and reads the array on the
+ * device at every launch (so a recorded graph follows its contents).  NULL (the default): every request brings T.
+ * Errors: NULL (handle), SHAPE (alignment). */
+omni_status_t omni_set_query_lens(omni_handle_t h, const int32_t *dev_q_lens);
+
 /* Hand the library a caller-owned device buffer of at least omni_workspace_bytes, 256-byte aligned.
  * The library keeps the pointer only; contents need no initialisation.  The buffer must not be shared by calls that
  * run concurrently.  Errors: NULL, WORKSPACE. */
@@ -136,7 +144,8 @@ omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes);
  * rows are in the pools: omni_kv_append_chunk), query i sees tokens 0 .. context_lens[b] - T + i.  The kernel treats
  * the (token, head) pairs of a KV head as the columns of its matrix-core tiles, 16 per pass: with T * (Hq / Hkv) <= 16
  * the cache is still read once and the call costs about what the one-token call costs; a larger T takes
- * ceil(T / floor(16 / (Hq / Hkv))) passes (launch pairs) over the cache.  Every request has exactly T tokens (or length 0);
+ * ceil(T / floor(16 / (Hq / Hkv))) passes (launch pairs) over the cache.  Every request has T tokens unless
+ * omni_set_query_lens says otherwise;
  * a query that would see no token at all (context_lens[b] < T) gets zeros.  omni_decode_step and omni_decode_step_fp8
  * then take k_new / v_new [batch, T, num_kv_heads, head_dim] and write row i of request b to position
  * context_lens[b] - T + i (rows whose position would be negative are skipped) before the attention reads it.

@@ -20,7 +20,7 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = (
     "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_prefill_workspace_bytes",
-    "omni_set_workspace",
+    "omni_set_workspace", "omni_set_query_lens",
     "omni_paged_decode_attn", "omni_paged_decode_attn_fp8", "omni_kv_append", "omni_decode_step", "omni_decode_step_fp8", "omni_kv_pack", "omni_kv_unpack", "omni_paged_prefill_attn", "omni_paged_prefill_attn_fp8", "omni_kv_append_chunk", "omni_get_plan",
     "omni_status_string",
     "omni_debug_last_plan", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
@@ -58,6 +58,7 @@ def lib():
         L.omni_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
         L.omni_prefill_workspace_bytes.argtypes = [vp, C.c_int32, C.POINTER(C.c_size_t)]
         L.omni_set_workspace.argtypes = [vp, vp, C.c_size_t]
+        L.omni_set_query_lens.argtypes = [vp, vp]
         L.omni_paged_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_paged_decode_attn_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_kv_append.argtypes = [vp] * 8
@@ -191,6 +192,11 @@ class Handle:
             nbytes = tensor_or_ptr.numel() * tensor_or_ptr.element_size()
         self._ws = tensor_or_ptr                     # keep the caller's tensor alive
         _ck(lib().omni_set_workspace(self._h, _ptr(tensor_or_ptr), nbytes), "omni_set_workspace")
+
+    def omni_set_query_lens(self, tensor_or_none) -> None:
+        self._q_lens = tensor_or_none                # keep the caller's tensor alive
+        _ck(lib().omni_set_query_lens(self._h, _ptr(tensor_or_none) if tensor_or_none is not None else None),
+            "omni_set_query_lens")
 
     def omni_paged_decode_attn(self, q, k_cache, v_cache, block_table, context_lens, scale, out, stream=None) -> None:
         _ck(lib().omni_paged_decode_attn(self._h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),

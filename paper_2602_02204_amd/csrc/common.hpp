@@ -41,6 +41,8 @@ struct AttnParams {
     const void *v_new;
     const int32_t *block_table;
     const int32_t *context_lens;
+    const int32_t *q_lens;              // several query tokens per request only, may be null: how many of the Tq request b
+                                        // brings (its last q_lens[b] tokens, rows 0 .. q_lens[b] - 1 of its Tq); null = Tq
     void *out;
     Workspace ws;
     PlanParams plan;

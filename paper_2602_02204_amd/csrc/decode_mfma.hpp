@@ -309,10 +309,10 @@ constexpr int kKStageBytes = 8192;                     // one 32-token K tile of
 
 // Shared-memory layout for a batch of B requests and G query heads per KV head: as many ring slots (up to four) as
 // fit while two workgroups still share the 160 KB of a compute unit; at least one fits for every supported B and G.
-inline MfmaLds mfma_lds_layout(int B, int G, bool kv8, bool staged) {
+inline MfmaLds mfma_lds_layout(int B, int G, bool kv8, bool staged, bool query_counts = false) {
     constexpr int D = 128;
     MfmaLds L;
-    L.ring_off = ((2 * B + 1) * 4 + 15) & ~15;
+    L.ring_off = (((query_counts ? 3 : 2) * B + 1) * 4 + 15) & ~15;      // E[B + 1], Lc[B] and, if asked for, Nc[B]
     L.slot_floats = kWaves * G * (D + 4) + 2 * kWaves * kMaxGroup;
     // 512 B for the kernel's static variables, and the waves' K tiles (static as well) if K is staged
     const int budget = 80 * 1024 - 512 - L.ring_off - (staged ? kWaves * (kv8 ? kKStageBytes / 2 : kKStageBytes) : 0);
@@ -327,7 +327,8 @@ inline MfmaLds mfma_lds_layout(int B, int G, bool kv8, bool staged) {
 // running max and sum) into the segment's partial-result slot.  Every thread owns four consecutive output
 // elements.  All threads call it between barriers.
 template <int D, bool MT>
-__device__ __forceinline__ void mfma_combine_segment(const float *slot, const AttnParams &p, const Segment &seg, int kvh) {
+__device__ __forceinline__ void mfma_combine_segment(const float *slot, const AttnParams &p, const Segment &seg, int kvh,
+                                                     int n_tokens = 1) {
     const int G = MT ? p.Gq : p.G;                       // columns: (query token, head) pairs of the KV head
     const float *sm_m = slot + kWaves * G * (D + 4), *sm_l = sm_m + kWaves * kMaxGroup;
     for (int idx = 4 * threadIdx.x; idx < G * D; idx += 4 * kThreads) {
@@ -346,6 +347,10 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
                 num.x += a * o.x; num.y += a * o.y; num.z += a * o.z; num.w += a * o.w;
                 den += a * sm_l[w * kMaxGroup + g];
             }
+        }
+        if (MT && p.t_off + g / p.G >= n_tokens) {           // no query token behind this column: zeros, weight 0
+            num = make_float4(0.f, 0.f, 0.f, 0.f);
+            den = 0.f;
         }
         if (seg.nparts == 1) {
             const size_t o0 = (MT ? out_row(p, seg.b, kvh, g) : (size_t)seg.b * p.Hq + kvh * G + g) * D + d;
@@ -407,7 +412,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     const int col_g = col - col_qi * G;                          // of the request's newest tokens it must not see
     const int tokens = MT ? p.Tq : 1;                            // query tokens per request, t_off .. in this launch
     const int t_off = MT ? p.t_off : 0;
-    const int col_back = (MT && col < Gq) ? tokens - 1 - (t_off + col_qi) : 0;
+    const int col_tok = t_off + col_qi;                          // which of the request's query tokens
 
     MfmaTileLoader<PS> ld;
     ld.page_stride = (size_t)p.Hkv * PS * D * ES;
@@ -425,10 +430,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     ld8.voff = col * 8 + (4 * j) * 128;
     ld8.init_staging(lane);
 
+    // Several query tokens per request: Nc[b] = how many request b brings (behind E[] and Lc[] in shared memory).
+    int *Nc = E + 2 * p.plan.B + 1;
     auto load_q = [&](int b, uint4 (&Q)[4]) {                    // B operand of K Q^T for request b
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) Q[kk] = make_uint4(0, 0, 0, 0);
-        if (col < Gq) {
+        if (col < Gq && (!MT || t_off + col_qi < Nc[b])) {       // a column no query token stands behind keeps zeros
             const char *qrow = reinterpret_cast<const char *>(p.q) + (((size_t)b * tokens + t_off + col_qi) * p.Hq + head0 + col_g) * (D * 2);
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)                      // dims of step kk: (4kk + j) * 8 .., or 32j + 8kk .. (KV8)
@@ -461,6 +468,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         }
     } else {
         pl = attn_prologue<D>(p, &ps, E, w, kvh);
+    }
+    if constexpr (MT) {                                          // every wave writes the same values: no barrier needed
+        for (int b = lane; b < p.plan.B; b += 64) {
+            const int n = p.q_lens ? p.q_lens[b] : tokens;
+            Nc[b] = min(max(n, 0), tokens);
+        }
     }
     OMNI_STAMP(p, 1);
     bool stamped = false;
@@ -495,7 +508,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 meta.x = lo;
                 // fused step: the tiles that hold the request's newest token(s) get their rows written first
                 bool newest = t == ((Lc[lo] - 1) >> kLog2Tile);
-                if (MT) newest = newest || (t < ((Lc[lo] - 1) >> kLog2Tile) && t >= (max(Lc[lo] - p.Tq, 0) >> kLog2Tile));
+                if (MT) newest = Nc[lo] > 0 && t <= ((Lc[lo] - 1) >> kLog2Tile) && t >= (max(Lc[lo] - Nc[lo], 0) >> kLog2Tile);
                 meta.y = t | ((p.k_new != nullptr && newest) ? kAppendFlag : 0);
                 if (PS == 16 && page < last_page) {              // both pages exist: one 8-byte read (page is even)
                     struct alignas(4) PagePair { int first, second; };   // rows of odd length keep 4-byte alignment
@@ -526,9 +539,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         auto append_row = [&](const SlotInfo &si) {
             constexpr int kRowPieces = D * ES / 16;              // 16-byte pieces of a row: 16 (16-bit cache) or 8
             const int L = Lc[si.req];
+            const int n_new = MT ? Nc[si.req] : 1;               // rows 0 .. n_new - 1 of the request's new rows
 #pragma unroll 1
-            for (int qi = 0; qi < tokens; ++qi) {
-                const int pos = L - tokens + qi;
+            for (int qi = 0; qi < n_new; ++qi) {
+                const int pos = L - n_new + qi;
                 if (MT && (pos < 0 || (pos >> kLog2Tile) != si.tile)) continue;      // uniform
                 const int pg = (PS == 16 && (pos & 16)) ? si.pg1 : si.pg0;
                 const size_t row = (size_t)pg * ld.page_stride + (size_t)(pos & (PS - 1)) * (D * ES);
@@ -578,6 +592,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         int pend0 = 0, pend1 = 0, pend2 = 0, pend3 = 0;          // their requests
         while (true) {
             const Segment seg = plan_segment(E, Lc, pl, b, range, start, end);
+            // several query tokens: query i of the request's n sits at position L - n + i; a column with no query behind
+            // it runs unmasked on zero queries and is dropped when the segment is combined
+            const int seg_n = MT ? __builtin_amdgcn_readfirstlane(Nc[b]) : 1;
+            const int col_back = (MT && col < Gq && col_tok < seg_n) ? seg_n - 1 - col_tok : 0;
+            const int t1min = MT ? seg.L - max(seg_n - 1 - t_off, 0) : seg.L;
             MfmaState st;
             st.m = -INFINITY; st.l = 0.f;
 #pragma unroll
@@ -622,9 +641,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                         if (KST && nxt.req != seg.b) load_q(nxt.req, Q);
                         issue_v(nxt.pg0, nxt.pg1);
                     }
-                    mfma_softmax_pv<true, MT>(sv, V, st, cur.tile * kTile, seg.L, seg.L - col_back, seg.L - (tokens - 1 - t_off), j, v0, v1);
+                    mfma_softmax_pv<true, MT>(sv, V, st, cur.tile * kTile, seg.L, seg.L - col_back, t1min, j, v0, v1);
                 } else {
-                    mfma_softmax_pv<false, MT>(sv, V, st, cur.tile * kTile, seg.L, seg.L - col_back, seg.L - (tokens - 1 - t_off), j);
+                    mfma_softmax_pv<false, MT>(sv, V, st, cur.tile * kTile, seg.L, seg.L - col_back, t1min, j);
                     if (more) {
                         if (KST && nxt.req != seg.b) load_q(nxt.req, Q);
                         issue_v(nxt.pg0, nxt.pg1);
@@ -663,7 +682,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                     if (r < npend) {
                         const int rb = r == 0 ? pend0 : (r == 1 ? pend1 : (r == 2 ? pend2 : pend3));
                         const Segment sg = plan_segment(E, Lc, pl, rb, range, start, end);
-                        mfma_combine_segment<D, MT>(ring + (size_t)r * slot_floats, p, sg, kvh);   // nobody waits for its stores
+                        mfma_combine_segment<D, MT>(ring + (size_t)r * slot_floats, p, sg, kvh, MT ? Nc[rb] : 1);   // nobody waits for its stores
                     }
                 }
                 lds_barrier();

@@ -60,6 +60,7 @@ struct omni_handle_s {
     bool lds_attr_set = false;   // the kernel has been told how much dynamic shared memory it may get
     void *ws = nullptr;
     size_t ws_given = 0;
+    const int32_t *q_lens = nullptr;     // several query tokens per request: how many each request brings (null: all)
     // profiling aid: event pairs around the partition kernel
     std::vector<hipEvent_t> prof_events;
     int prof_used = 0, prof_stride = 1, prof_calls = 0;
@@ -103,7 +104,8 @@ struct omni_handle_s {
         pass_tokens = tune_query_tokens;
         if (pass_tokens * G > kMaxGroup) pass_tokens = kMaxGroup / G;
         const int Gq = G * pass_tokens;          // columns of a KV head: (query token, head) pairs
-        const MfmaLds plain = mfma_lds_layout(d.batch, Gq, fp8, false), staged = mfma_lds_layout(d.batch, Gq, fp8, true);
+        const bool mt = tune_query_tokens > 1;
+        const MfmaLds plain = mfma_lds_layout(d.batch, Gq, fp8, false, mt), staged = mfma_lds_layout(d.batch, Gq, fp8, true, mt);
         k_staged = staged.ring_depth >= 3 || plain.ring_depth <= 2;
         lds = k_staged ? staged : plain;
         lds_attr_set = false;
@@ -227,6 +229,13 @@ omni_status_t omni_set_workspace(omni_handle_t h, void *dev_ptr, size_t bytes) {
     return OMNI_OK;
 }
 
+omni_status_t omni_set_query_lens(omni_handle_t h, const int32_t *dev_q_lens) {
+    if (!h) return OMNI_ERR_NULL;
+    if (misaligned(dev_q_lens, 4)) return OMNI_ERR_SHAPE;
+    h->q_lens = dev_q_lens;
+    return OMNI_OK;
+}
+
 omni_status_t omni_get_plan(omni_handle_t h, int32_t *kernel, int32_t *partition_grid, int32_t *merge_grid,
                             int32_t *max_request_parts, int32_t *threads_per_workgroup) {
     if (!h) return OMNI_ERR_NULL;
@@ -280,6 +289,7 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.k_new = k_new; p.v_new = v_new;
     p.k_scale = k_scale; p.v_scale = v_scale;
     p.block_table = block_table; p.context_lens = context_lens; p.out = out;
+    p.q_lens = h->tune_query_tokens > 1 ? h->q_lens : nullptr;
     char *ws = reinterpret_cast<char *>(h->ws);
     p.ws.plan_words = reinterpret_cast<int32_t *>(ws);
     p.ws.part_ml = reinterpret_cast<float2 *>(ws + h->off_ml);

@@ -217,3 +217,94 @@ def test_fused_step_equals_chunk_append_then_attention(G, Hkv, T, ps, fp8, force
     bar = TOL[W.BF16] if not fp8 else max(TOL[W.BF16], 2.0 ** -9 * np.max(np.abs(ref)))
     assert np.all(np.isfinite(got)) and np.max(np.abs(got - ref)) <= bar
 
+
+# --------------------------------------------------------------------------- a different number of tokens per request
+def ragged_expected(wl, q, T, n):
+    """Request b brings n[b] <= T tokens in rows 0 .. n[b] - 1 of its T; a query at a negative position and the rows
+    behind n[b] give zeros."""
+    n_eff = np.minimum(n, wl.context_lens).astype(np.int32)
+    offs = (np.arange(wl.B, dtype=np.int64) * T + (n - n_eff)).astype(np.int64)
+    ref = oracle.paged_prefill_attn(q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, n_eff, offs, wl.scale, wl.dtype)
+    return ref.reshape(wl.B, T, wl.Hq, wl.D)
+
+
+@pytest.mark.parametrize("G,Hkv,T,ps", [(7, 4, 2, 16), (4, 2, 4, 32), (1, 2, 16, 16), (8, 2, 4, 16), (3, 1, 7, 16)])
+@pytest.mark.parametrize("tuning", [{}, {omni.OMNI_TUNE_FORCE_PARTITION: 32}], ids=["default", "force32"])
+def test_ragged_numbers_of_query_tokens(G, Hkv, T, ps, tuning):
+    rng = np.random.default_rng(3000 + G + T)
+    lens = np.array(LENS + [700, 33, 64, 129], dtype=np.int64)
+    wl = W.build("mtr", 3100 + G, lens, Hq=G * Hkv, Hkv=Hkv, D=128, ps=ps, dtype=W.BF16, pool_factor=1.5)
+    n = rng.integers(0, T + 1, size=wl.B).astype(np.int32)
+    n[:4] = [T, 0, 1, T]                                     # all, none, one, all
+    q = queries(wl, T, 3200 + G)
+    q4 = q.reshape(wl.B, T, wl.Hq, wl.D)
+    for b in range(wl.B):                                    # rows nobody brings hold NaN: they must not matter
+        q4[b, n[b]:] = np.uint16(0x7fc0)
+    tn = {omni.OMNI_TUNE_QUERY_TOKENS: T}
+    tn.update(tuning)
+    dev = DeviceBatch(wl, tuning=tn)
+    dn = torch.from_numpy(n).cuda()
+    dev.h.omni_set_query_lens(dn)
+    out = torch.full((wl.B, T, wl.Hq, wl.D), float("nan"), device="cuda", dtype=torch.float32)
+    dev.h.omni_paged_decode_attn(to_dev(q, wl.dtype), dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens,
+                                 float(wl.scale), out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    qz = q.copy().reshape(wl.B, T, wl.Hq, wl.D)
+    for b in range(wl.B):
+        qz[b, n[b]:] = 0
+    ref = ragged_expected(wl, qz.reshape(q.shape), T, n)
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got - ref)) <= TOL[wl.dtype]
+    for b in range(wl.B):
+        assert np.all(got[b, n[b]:] == 0), f"request {b}: rows behind its {n[b]} tokens"
+    # the array is read at every launch: new contents, same handle; then back to "every request brings T"
+    n2 = np.minimum(n + 1, T).astype(np.int32)
+    dn.copy_(torch.from_numpy(n2).cuda())
+    q2 = queries(wl, T, 3300 + G)
+    dq2 = to_dev(q2, wl.dtype)
+    dev.h.omni_paged_decode_attn(dq2, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens, float(wl.scale), out)
+    torch.cuda.synchronize()
+    qz2 = q2.copy().reshape(wl.B, T, wl.Hq, wl.D)
+    for b in range(wl.B):
+        qz2[b, n2[b]:] = 0
+    assert np.max(np.abs(out.cpu().numpy().astype(np.float64) - ragged_expected(wl, qz2.reshape(q2.shape), T, n2))) <= TOL[wl.dtype]
+    dev.h.omni_set_query_lens(None)
+    dev.h.omni_paged_decode_attn(dq2, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens, float(wl.scale), out)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(out.cpu().numpy().astype(np.float64) - expected(wl, q2, T))) <= TOL[wl.dtype]
+
+
+@pytest.mark.parametrize("G,Hkv,T,ps", [(7, 4, 2, 16), (4, 2, 4, 32), (2, 2, 9, 16)])
+def test_ragged_fused_step_appends_only_the_rows_a_request_brings(G, Hkv, T, ps):
+    rng = np.random.default_rng(3400 + G)
+    lens = [2, 5, 16, 17, 31, 32, 33, 34, 35, 47, 48, 49, 64, 65, 66, 250, 0, 96, 97, 1, 3]
+    wl = W.build("mtrs", 3500 + G, lens, Hq=G * Hkv, Hkv=Hkv, D=128, ps=ps, dtype=W.BF16, pool_factor=1.5)
+    n = np.minimum(rng.integers(0, T + 1, size=wl.B), wl.context_lens).astype(np.int32)
+    q = queries(wl, T, 3600)
+    k_new = W.f32_to_bf16_bits(rng.standard_normal((wl.B, T, wl.Hkv, wl.D)).astype(np.float32))
+    v_new = W.f32_to_bf16_bits(rng.standard_normal((wl.B, T, wl.Hkv, wl.D)).astype(np.float32))
+    want_k, want_v = wl.k_cache.copy(), wl.v_cache.copy()
+    for b in range(wl.B):
+        for i in range(int(n[b])):
+            t = int(wl.context_lens[b]) - int(n[b]) + i
+            pg, sl = wl.block_table[b, t // wl.ps], t % wl.ps
+            wl.k_cache[pg, :, sl, :] = np.uint16(0x7fc1); wl.v_cache[pg, :, sl, :] = np.uint16(0x7fc1)
+            want_k[pg, :, sl, :] = k_new[b, i]; want_v[pg, :, sl, :] = v_new[b, i]
+    dev = DeviceBatch(wl, tuning={omni.OMNI_TUNE_QUERY_TOKENS: T})
+    dn = torch.from_numpy(n).cuda()
+    dev.h.omni_set_query_lens(dn)
+    out = torch.full((wl.B, T, wl.Hq, wl.D), float("nan"), device="cuda", dtype=torch.float32)
+    dev.h.omni_decode_step(to_dev(q, wl.dtype), to_dev(k_new, wl.dtype), to_dev(v_new, wl.dtype), dev.k_cache, dev.v_cache,
+                           dev.block_table, dev.context_lens, float(wl.scale), out)
+    torch.cuda.synchronize()
+    from gpu_util import bits_of
+    assert np.array_equal(bits_of(dev.k_cache).view(np.uint8), want_k.view(np.uint8))
+    assert np.array_equal(bits_of(dev.v_cache).view(np.uint8), want_v.view(np.uint8))
+    wl.k_cache[:] = want_k; wl.v_cache[:] = want_v
+    qz = q.copy().reshape(wl.B, T, wl.Hq, wl.D)
+    for b in range(wl.B):
+        qz[b, n[b]:] = 0
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got)) and np.max(np.abs(got - ragged_expected(wl, qz.reshape(q.shape), T, n))) <= TOL[wl.dtype]
+
