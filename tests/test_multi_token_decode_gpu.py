@@ -308,3 +308,41 @@ def test_ragged_fused_step_appends_only_the_rows_a_request_brings(G, Hkv, T, ps)
     got = out.cpu().numpy().astype(np.float64)
     assert np.all(np.isfinite(got)) and np.max(np.abs(got - ragged_expected(wl, qz.reshape(q.shape), T, n))) <= TOL[wl.dtype]
 
+
+def test_ragged_counts_over_the_8bit_cache_and_in_a_replayed_graph():
+    """Per-request counts with the 8-bit cache, the call recorded once as a graph: every replay reads the counts (and
+    the lengths and queries) of the moment."""
+    wl = W.make("talker", batch=40, len_div=2, append=False)
+    f8 = W.quantize_fp8(wl)
+    T = 2
+    fb = Fp8Batch(wl, f8, {omni.OMNI_TUNE_QUERY_TOKENS: T})
+    rng = np.random.default_rng(3700)
+    dn = torch.zeros(wl.B, dtype=torch.int32, device="cuda")
+    fb.h.omni_set_query_lens(dn)
+    dq = torch.zeros((wl.B * T, wl.Hq, wl.D), dtype=torch.bfloat16, device="cuda")
+    out = torch.full((wl.B, T, wl.Hq, wl.D), float("nan"), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.Stream()
+    call = lambda: fb.h.omni_paged_decode_attn_fp8(dq, fb.k, fb.v, fb.ks, fb.vs, fb.bt, fb.lens, float(wl.scale), out, stream)
+    call()
+    torch.cuda.synchronize()
+    with omni.Graph(stream) as g:
+        call()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        n = rng.integers(0, T + 1, size=wl.B).astype(np.int32)
+        q = queries(wl, T, 3800 + rep)
+        qz = q.copy().reshape(wl.B, T, wl.Hq, wl.D)
+        for b in range(wl.B):
+            qz[b, n[b]:] = 0
+        dn.copy_(torch.from_numpy(n).cuda()); dq.copy_(to_dev(q, wl.dtype)); out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.launch()
+        torch.cuda.synchronize()
+        n_eff = np.minimum(n, wl.context_lens).astype(np.int32)
+        offs = (np.arange(wl.B, dtype=np.int64) * T + (n - n_eff)).astype(np.int64)
+        ref = oracle.paged_prefill_attn_fp8(qz.reshape(q.shape), f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                                            wl.context_lens, n_eff, offs, wl.scale).reshape(wl.B, T, wl.Hq, wl.D)
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got)) and np.max(np.abs(got - ref)) <= TOL[W.BF16], f"replay {rep}"
+    g.close()
+
