@@ -94,8 +94,11 @@ typedef enum {
                                        workgroups may share a query block's context, 1 = never split, 2 .. 16 = this many */
     OMNI_TUNE_PREFILL_MIN_SPLIT = 5,/* fewest tokens of context one of them takes (multiple of 64; default 256): a query
                                        block with a shorter context is shared by fewer, decided on the device */
-    OMNI_TUNE_QUERY_TOKENS = 6      /* T >= 1 (default 1): omni_paged_decode_attn and omni_paged_decode_attn_fp8 take T query
+    OMNI_TUNE_QUERY_TOKENS = 6,     /* T >= 1 (default 1): omni_paged_decode_attn and omni_paged_decode_attn_fp8 take T query
                                        tokens per request, see there.  Matrix-core kernel only, else UNSUPPORTED */
+    OMNI_TUNE_PREFILL_SORT = 7      /* omni_paged_prefill_attn, matrix-core path with a registered workspace and more than 256
+                                       workgroups: 1 (default) = requests are taken longest context first (one more tiny
+                                       launch ranks them), 0 = in batch order */
 } omni_tune_key_t;
 
 /* Validate `desc` and create a handle holding host-side plan state only (no device memory).
@@ -251,7 +254,9 @@ omni_status_t omni_kv_unpack(omni_handle_t h, const void *k_dense, const void *v
  * query block's context in equal runs of 64-token steps (as many as the context gives OMNI_TUNE_PREFILL_MIN_SPLIT
  * tokens each), and a second launch merges their pieces (log-sum-exp, in order of position: the same exact
  * re-association as in decode).  How a block is shared depends on the handle, its tuning, max_q_len and the lengths
- * only, so the result is bit-identical from run to run.
+ * only, so the result is bit-identical from run to run.  With a registered workspace and more than 256 workgroups a
+ * one-workgroup launch first ranks the requests by context length, and the kernel takes them longest first (the order
+ * changes when a workgroup runs, not what it computes).
  * Errors: NULL, SHAPE (max_q_len <= 0, scale <= 0 on the matrix-core path, alignment), UNSUPPORTED, HIP.
  */
 omni_status_t omni_paged_prefill_attn(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,

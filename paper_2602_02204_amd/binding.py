@@ -16,6 +16,7 @@ LIB_PATH = os.environ.get("OMNI_ATTN_LIB") or os.path.join(_HERE, "libomni_attn.
 OMNI_F32, OMNI_BF16, OMNI_FP8_E4M3 = 0, 1, 2
 OMNI_TUNE_KERNEL, OMNI_TUNE_TARGET_WORKGROUPS, OMNI_TUNE_MIN_PARTITION, OMNI_TUNE_FORCE_PARTITION = 0, 1, 2, 3
 OMNI_TUNE_PREFILL_SPLITS, OMNI_TUNE_PREFILL_MIN_SPLIT, OMNI_TUNE_QUERY_TOKENS = 4, 5, 6
+OMNI_TUNE_PREFILL_SORT = 7
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = (

@@ -47,6 +47,7 @@ struct omni_handle_s {
     int tune_prefill_splits = 0;
     int tune_prefill_min_split = kPrefillMinSplitTokens;
     int tune_query_tokens = 1;
+    int tune_prefill_sort = 1;
     // derived
     int kernel = 1;              // 1 = vector ALU, 2 = MFMA
     int G = 1;
@@ -193,6 +194,9 @@ omni_status_t omni_set_tuning(omni_handle_t h, int32_t key, int32_t value) {
         case OMNI_TUNE_PREFILL_SPLITS:
             if (value < 0 || value > 16) return OMNI_ERR_SHAPE;
             h->tune_prefill_splits = value; break;
+        case OMNI_TUNE_PREFILL_SORT:
+            if (value < 0 || value > 1) return OMNI_ERR_SHAPE;
+            h->tune_prefill_sort = value; break;
         case OMNI_TUNE_QUERY_TOKENS:
             if (value < 1) return OMNI_ERR_SHAPE;
             if (value > 1 && h->kernel != 2) return OMNI_ERR_UNSUPPORTED;
@@ -593,13 +597,25 @@ static omni_status_t launch_prefill(omni_handle_t h, const void *q, const void *
     // The context is split only if the registered workspace holds the pieces (omni_prefill_workspace_bytes).
     int ns = mfma ? h->prefill_splits(max_q_len) : 1;
     if (ns > 1 && (!h->ws || h->ws_given < h->prefill_ws_bytes(max_q_len))) ns = 1;
+    // With a registered workspace and more than one round of workgroups, the requests are taken longest first: a
+    // one-workgroup kernel ranks them into the first words of the workspace (the pieces of a split follow).
+    const long long wgs_all = (long long)((max_q_len + qb - 1) / qb) * d.num_kv_heads * d.batch;
+    const bool sorted = mfma && h->ws && d.batch > 1 && d.batch <= kPrefillOrderMax && wgs_all > 256 && h->tune_prefill_sort != 0;
+    const size_t order_bytes = sorted ? align256((size_t)d.batch * sizeof(int32_t)) : 0;
+    if (ns > 1 && h->ws_given < order_bytes + h->prefill_ws_bytes(max_q_len)) ns = 1;
+    p.order = sorted ? reinterpret_cast<const int32_t *>(h->ws) : nullptr;
+    p.B = d.batch;
     p.num_splits = ns; p.max_q_len = max_q_len;
     p.min_split_steps = h->tune_prefill_min_split / (2 * kTile);
-    p.part_ml = reinterpret_cast<float2 *>(h->ws);
-    p.part_o = ns > 1 ? reinterpret_cast<float *>(reinterpret_cast<char *>(h->ws) + omni_handle_s::prefill_ml_bytes(d, max_q_len, ns)) : nullptr;
+    p.part_ml = reinterpret_cast<float2 *>(reinterpret_cast<char *>(h->ws) + order_bytes);
+    p.part_o = ns > 1 ? reinterpret_cast<float *>(reinterpret_cast<char *>(h->ws) + order_bytes + omni_handle_s::prefill_ml_bytes(d, max_q_len, ns)) : nullptr;
     const dim3 grid((unsigned)((max_q_len + qb - 1) / qb) * (unsigned)ns, (unsigned)d.num_kv_heads, (unsigned)d.batch);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     (void)hipGetLastError();
+    if (sorted) {
+        prefill_order_kernel<<<1, kPrefillOrderMax, 0, s>>>(context_lens, d.batch, reinterpret_cast<int32_t *>(h->ws));
+        if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+    }
     if (mfma) {
         if (fp8) {
             if (d.page_size == 16) prefill_mfma_kernel<16, true><<<grid, kPrefillThreads, 0, s>>>(p);

@@ -101,6 +101,8 @@ struct PrefillParams {
     int max_q_len;
     float *part_o;                    // [B, max_q_len, Hq, num_splits, D]
     float2 *part_ml;                  // [B, max_q_len, Hq, num_splits]
+    const int32_t *order;             // null, or [B]: the requests by descending context length (blockIdx.z -> request)
+    int B;
 };
 
 // A split's share of the context is at least this many 64-token steps: below that the pieces' trip through memory
@@ -127,7 +129,9 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     __shared__ __align__(16) char smem[2][2][2][kTileBytes];     // [buffer][tile of the step][K, V]
     __shared__ float kscale_lds[2][2][2];                        // 8-bit cache: [buffer][tile][16-token half] K scales
 
-    const int b = blockIdx.z, kvh = blockIdx.y;
+    // Workgroups are dispatched in blockIdx order, z slowest: with the requests taken longest first the long-running
+    // workgroups start first and the short ones fill the end of the launch.
+    const int b = p.order ? p.order[blockIdx.z] : (int)blockIdx.z, kvh = blockIdx.y;
     const int G = p.G, head0 = kvh * G;
     const int L = p.context_lens[b];
     const int n_q = min(p.q_lens[b], L);
@@ -437,6 +441,21 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
             }
         }
     }
+}
+
+// order[r] = the request with the r-th longest context (ties by index): one workgroup, thread t ranks request t.
+constexpr int kPrefillOrderMax = 1024;
+__global__ __launch_bounds__(kPrefillOrderMax) void prefill_order_kernel(const int32_t *__restrict__ context_lens, int B,
+                                                                         int32_t *__restrict__ order) {
+    __shared__ int lens[kPrefillOrderMax];
+    const int t = threadIdx.x;
+    if (t < B) lens[t] = context_lens[t];
+    __syncthreads();
+    if (t >= B) return;
+    const int mine = lens[t];
+    int rank = 0;
+    for (int j = 0; j < B; ++j) rank += (lens[j] > mine) || (lens[j] == mine && j < t);
+    order[rank] = t;
 }
 
 // Merge of a context split: out row = sum_s 2^(m_s - M) o_s / sum_s 2^(m_s - M) l_s over the pieces with l_s > 0, in

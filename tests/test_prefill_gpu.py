@@ -325,3 +325,19 @@ def test_context_split_with_bf16_output_and_a_larger_max_q_len():
     err = np.abs(got[owned] - ref[owned])
     assert np.all(err <= TOL[W.BF16] + np.abs(ref[owned]) * 2.0 ** -8)    # the bar plus a bf16 rounding of the result
     assert np.all(np.isnan(got[~owned]))
+
+
+def test_longest_first_order_changes_nothing_but_the_schedule():
+    """More than 256 workgroups and a workspace: the requests are ranked by context length on the device (ties, empty
+    requests and one-token chunks included) and taken longest first; every output bit is as in batch order."""
+    rng = np.random.default_rng(1900)
+    lens = np.concatenate([rng.integers(1, 900, size=40), [0, 0, 300, 300, 300, 1, 64]]).astype(np.int64)
+    q_lens = np.minimum(lens, rng.integers(0, 200, size=lens.size)).astype(np.int64)
+    q_lens[-5:-2] = [300, 17, 300]
+    wl = W.build("order", 1901, lens, Hq=14, Hkv=2, D=128, ps=16, dtype=W.BF16, pool_factor=1.5)
+    ch = W.add_chunk(wl, q_lens, 1902, in_cache=True, gap=1)
+    assert ((ch.max_q_len + 35) // 36) * wl.Hkv * wl.B > 256
+    got_sorted, _ = check_chunk(wl, ch, label="sorted")
+    _, in_order = run_chunk(wl, ch, tuning={omni.OMNI_TUNE_PREFILL_SORT: 0})
+    assert np.array_equal(got_sorted, in_order, equal_nan=True)
+
