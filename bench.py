@@ -74,8 +74,7 @@ def main():
     log(f"workload {wl.name}: B={wl.B} Hq={wl.Hq} Hkv={wl.Hkv} D={wl.D} ps={wl.ps} T={wl.total_tokens} "
         f"KV bytes/call={kv_bytes / 1e6:.1f} MB pool pages={wl.P}")
 
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import to_dev
+    from paper_2602_02204_amd.devmem import to_dev
 
     kvd = omni.OMNI_BF16 if wl.dtype == W.BF16 else omni.OMNI_F32
     h = omni.Handle(batch=wl.B, num_q_heads=wl.Hq, num_kv_heads=wl.Hkv, head_dim=wl.D, page_size=wl.ps,

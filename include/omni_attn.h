@@ -1,12 +1,11 @@
 /*
  * omni_attn.h - C ABI of the MI355X (gfx950) batched decode-attention library.
  *
- * The operation is the attention inside the "one batched forward step for each
- * iteration" that the paper's model runner executes for an autoregressive stage
- * (Section 3.1 "Overview"; Section 3.3 "AR stage support": each engine has its
- * own scheduler, KV manager and model runner), over the paged KV cache the
- * engine inherits (Section 5, "LLM serving systems": paged attention, KV cache
- * management).  It is the same call for a Thinker-like text stage and a
+ * The operation is the attention inside the forward step that the paper's
+ * model runner executes once per decode iteration over the whole batch of an
+ * autoregressive stage (Section 3.1, overview; Section 3.3, AR stage support:
+ * every engine brings its own scheduler, KV manager and model runner), over
+ * the paged KV cache the engine inherits (Section 5, LLM serving systems).  It is the same call for a Thinker-like text stage and a
  * Talker-like speech-token stage (Section 2.1).  One call = one attention
  * layer's decode step for the whole batch: every request contributes exactly
  * one query token, which attends to all context_lens[b] tokens of its request.
@@ -57,7 +56,8 @@ typedef enum {
     OMNI_ERR_DTYPE = 3,         /* unknown dtype code or unsupported q/kv/out combination */
     OMNI_ERR_UNSUPPORTED = 4,   /* head_dim, page_size, group size or batch outside what the kernels cover */
     OMNI_ERR_WORKSPACE = 5,     /* workspace missing, misaligned or smaller than omni_workspace_bytes */
-    OMNI_ERR_HIP = 6            /* the HIP runtime reported an error at launch */
+    OMNI_ERR_HIP = 6,           /* the HIP runtime reported an error at launch */
+    OMNI_ERR_NOMEM = 7          /* host memory for a handle or a graph object could not be allocated */
 } omni_status_t;
 
 typedef enum {
@@ -190,14 +190,20 @@ omni_status_t omni_kv_append(omni_handle_t h,
                              const int32_t *block_table, const int32_t *positions, void *stream);
 
 /*
- * One decode iteration of an autoregressive stage for the whole batch (Section 3.1: "one batched forward step for
- * each iteration"; Section 2.2: the AR decoding loop adds one token per request): exactly omni_kv_append with
+ * One decode iteration of an autoregressive stage for the whole batch (Section 3.1: the model runner takes one
+ * forward step over the whole batch per iteration; Section 2.2: the AR decoding loop adds one token per request):
+ * exactly omni_kv_append with
  * positions[b] = context_lens[b] - 1 (requests of length 0 are skipped) followed by omni_paged_decode_attn, but with
  * the append fused into the attention kernel where the hardware path allows it (bf16, head_dim 128): the workgroup
  * that will read a request's last tile first writes the new K/V row into that page.  Same results, bit for bit, as
  * the two separate calls.
  * Errors: NULL, WORKSPACE, HIP.
  */
+omni_status_t omni_decode_step(omni_handle_t h,
+                               const void *q, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                               const int32_t *block_table, const int32_t *context_lens,
+                               float scale, void *out, void *stream);
+
 /* The decode iteration over the quantised cache: k_new / v_new [batch, num_kv_heads, head_dim] hold E4M3 BYTES, already
  * divided by the scale of the page they go to (position context_lens[b] - 1); exactly omni_kv_append of those bytes
  * followed by omni_paged_decode_attn_fp8, in one launch of the attention kernel plus the merge.  Quantising the new
@@ -207,14 +213,9 @@ omni_status_t omni_decode_step_fp8(omni_handle_t h, const void *q, const void *k
                                    void *v_cache, const float *k_scale, const float *v_scale, const int32_t *block_table,
                                    const int32_t *context_lens, float scale, void *out, void *stream);
 
-omni_status_t omni_decode_step(omni_handle_t h,
-                               const void *q, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
-                               const int32_t *block_table, const int32_t *context_lens,
-                               float scale, void *out, void *stream);
-
 /*
  * Dense copies of whole requests, the payload a connector ships when the KV cache of a request moves between a
- * prefill and a decode engine (Section 3.4, "Disaggregated Data Transfer": the connector also carries KV cache between
+ * prefill and a decode engine (Section 3.4, disaggregated data transfer: the connector also carries KV cache between
  * prefill and decode).  For every request b with token_offsets[b] >= 0 and every t < context_lens[b]:
  *   pack:    k_dense[token_offsets[b] + t, g, :] = k_cache[block_table[b][t / page_size], g, t % page_size, :]
  *   unpack:  the same assignment in the other direction
@@ -327,6 +328,19 @@ omni_status_t omni_debug_gather(omni_handle_t h, const void *cache, const int32_
  * Errors: OMNI_ERR_NULL, OMNI_ERR_SHAPE (alignment), OMNI_ERR_HIP. */
 omni_status_t omni_debug_stream_read(const void *a, size_t a_bytes, const void *b, size_t b_bytes, void *sink,
                                      void *stream);
+
+/* Host-only: the shared-memory layout the matrix-core kernel of this handle is launched with.  host_out[0] = bytes of
+ * dynamic shared memory, [1] = bytes of the kernel variant's static K staging area, [2] = ring slots, [3] = 1 if K
+ * tiles are staged through shared memory, [4] = 1 if two workgroups fit one compute unit's 160 KB, [5] = the most
+ * dynamic shared memory any launch may ask for.  Errors: NULL, UNSUPPORTED (the handle runs the vector-ALU kernel). */
+omni_status_t omni_debug_lds_layout(omni_handle_t h, int32_t host_out[6]);
+
+/* What the loaded code object says about a kernel of this handle (hipFuncGetAttributes; needs a device): which = 0 the
+ * attention kernel variant the handle launches (matrix-core kernel only), 1 the merge kernel.  host_out[0] = registers
+ * per lane, [1] = static shared memory in bytes, [2] = dynamic shared memory at launch, [3] = the kernel's thread
+ * limit per workgroup, [4] = scratch (spill) bytes per lane, [5] = threads per workgroup the library launches.
+ * Errors: NULL, SHAPE (which), UNSUPPORTED, HIP. */
+omni_status_t omni_debug_kernel_resources(omni_handle_t h, int32_t which, int32_t host_out[6]);
 
 /* Profiling aid for the benchmark.  After omni_debug_profile_begin(h, capacity, stride) every stride-th attention
  * call (omni_paged_decode_attn or omni_decode_step; the first one included) records a HIP event pair around its

@@ -7,6 +7,7 @@ come in as host numpy arrays (fp32, or uint16 bf16 bit patterns).
 from __future__ import annotations
 
 import ctypes as C
+import os
 from typing import Optional, Sequence, Tuple
 
 import numpy as np
@@ -26,7 +27,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # ORACLE_SANITIZED=1: the address / undefined-behaviour instrumented build (the process must preload its runtime)
+        path = _build.build(force=False, sanitize=os.environ.get("ORACLE_SANITIZED") == "1")
         L = C.CDLL(path)
         L.oracle_paged_decode_attn.restype = C.c_int
         L.oracle_paged_decode_attn.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 5 + [C.c_float, C.c_void_p,

@@ -24,7 +24,7 @@ EXPORTS = (
     "omni_set_workspace", "omni_set_query_lens",
     "omni_paged_decode_attn", "omni_paged_decode_attn_fp8", "omni_kv_append", "omni_decode_step", "omni_decode_step_fp8", "omni_kv_pack", "omni_kv_unpack", "omni_paged_prefill_attn", "omni_paged_prefill_attn_fp8", "omni_kv_append_chunk", "omni_get_plan",
     "omni_status_string",
-    "omni_debug_last_plan", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
+    "omni_debug_last_plan", "omni_debug_lds_layout", "omni_debug_kernel_resources", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
     "omni_debug_profile_end", "omni_graph_begin", "omni_graph_end", "omni_graph_launch", "omni_graph_destroy",
 )
 
@@ -73,6 +73,8 @@ def lib():
         L.omni_get_plan.argtypes = [vp] + [i32p] * 5
         L.omni_status_string.argtypes = [C.c_int]; L.omni_status_string.restype = C.c_char_p
         L.omni_debug_last_plan.argtypes = [vp, i32p, vp]
+        L.omni_debug_lds_layout.argtypes = [vp, i32p]
+        L.omni_debug_kernel_resources.argtypes = [vp, C.c_int32, i32p]
         L.omni_debug_gather.argtypes = [vp, vp, vp, vp, C.c_int32, vp, vp]
         L.omni_debug_stream_read.argtypes = [vp, C.c_size_t, vp, C.c_size_t, vp, vp]
         L.omni_debug_profile_begin.argtypes = [vp, C.c_int32, C.c_int32]
@@ -263,6 +265,18 @@ class Handle:
         arr = (C.c_int32 * 4)()
         _ck(lib().omni_debug_last_plan(self._h, arr, _stream(stream)), "omni_debug_last_plan")
         return {"partition_len": arr[0], "request_parts": arr[1], "total_tokens": arr[2]}
+
+    def omni_debug_lds_layout(self) -> dict:
+        arr = (C.c_int32 * 6)()
+        _ck(lib().omni_debug_lds_layout(self._h, arr), "omni_debug_lds_layout")
+        return {"dynamic_bytes": arr[0], "static_bytes": arr[1], "ring_slots": arr[2], "k_staged": bool(arr[3]),
+                "two_workgroups_per_cu": bool(arr[4]), "max_dynamic_bytes": arr[5]}
+
+    def omni_debug_kernel_resources(self, which: int = 0) -> dict:
+        arr = (C.c_int32 * 6)()
+        _ck(lib().omni_debug_kernel_resources(self._h, int(which), arr), "omni_debug_kernel_resources")
+        return {"registers_per_lane": arr[0], "static_lds_bytes": arr[1], "dynamic_lds_bytes": arr[2],
+                "max_threads_per_workgroup": arr[3], "scratch_bytes_per_lane": arr[4], "threads_launched": arr[5]}
 
     def omni_debug_gather(self, cache, block_table, context_lens, request: int, dense_out, stream=None) -> None:
         _ck(lib().omni_debug_gather(self._h, _ptr(cache), _ptr(block_table), _ptr(context_lens), int(request),

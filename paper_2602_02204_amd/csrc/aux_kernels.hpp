@@ -131,6 +131,7 @@ struct PackParams {
     const long long *token_offsets;  // first dense row of each request; < 0: skip the request
     const int32_t *q_lens;           // null: whole requests; else only the last q_lens[b] tokens of each request move,
                                      // and dense row token_offsets[b] holds the first of them
+    int max_tokens;                  // with q_lens: at most this many tokens of a request move (the grid's bound)
     int Hkv, MB, log2_ps, row_vecs;
 };
 
@@ -148,13 +149,15 @@ __global__ __launch_bounds__(kThreads) void kv_pack_kernel(PackParams p) {
     constexpr int kU = 2;                                    // pieces of K and of V a thread keeps in flight
     const int b = blockIdx.y;
     const int L = p.context_lens[b];
-    const int first = p.q_lens ? L - max(0, min(p.q_lens[b], L)) : 0;      // first token that moves
+    const int n_move = p.q_lens ? max(0, min(p.q_lens[b], L)) : L;
+    const int first = L - n_move;                                          // first token that moves
+    const int end = p.q_lens ? first + min(n_move, p.max_tokens) : L;      // one past the last (a longer chunk is cut off)
     const int t0 = first + blockIdx.x * kPackTokens;
     const long long off = p.token_offsets[b] - first;                      // dense row of token 0 (may be virtual)
-    if (p.token_offsets[b] < 0 || t0 >= L) return;
+    if (p.token_offsets[b] < 0 || t0 >= end) return;
     const int log2_rv = 31 - __clz(p.row_vecs);              // row_vecs is 8, 16 or 32
     const int vecs_per_token = p.Hkv << log2_rv;
-    const int total = min(kPackTokens, L - t0) * vecs_per_token;
+    const int total = min(kPackTokens, end - t0) * vecs_per_token;
     const int32_t *bt = p.block_table + (size_t)b * p.MB;
     const uint4 *ks = reinterpret_cast<const uint4 *>(p.k_src), *vs = reinterpret_cast<const uint4 *>(p.v_src);
     uint4 *kd = reinterpret_cast<uint4 *>(p.k_dst), *vd = reinterpret_cast<uint4 *>(p.v_dst);

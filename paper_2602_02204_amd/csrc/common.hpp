@@ -29,6 +29,8 @@ struct MfmaLds {
     int slot_floats;
     int ring_depth;                     // 1 .. 4
     int total;                          // bytes of dynamic shared memory
+    int static_bytes;                   // bytes of the kernel variant's static K staging area (0 if K is not staged)
+    bool two_per_cu;                    // total + static_bytes leave room for a second workgroup on the compute unit
 };
 
 struct AttnParams {
@@ -54,9 +56,6 @@ struct AttnParams {
     int log2_ps;
     int out_bf16;
     MfmaLds lds;                        // matrix-core kernel only
-#ifdef OMNI_TRACE
-    long long *trace;                   // development builds only: per-wave phase timestamps
-#endif
 };
 
 // Column c of KV head kvh stands for query token t_off + c / G of its request and head kvh * G + c % G.  Its row of
@@ -71,17 +70,6 @@ __device__ __forceinline__ size_t partial_row(const AttnParams &p, size_t slot, 
     const int qi = c / p.G, g = c - qi * p.G;
     return (slot * p.T + qi) * p.Hq + kvh * p.G + g;
 }
-
-// Phase timestamps for development builds (compiled out otherwise): slot `id` of this wave's record.
-#ifdef OMNI_TRACE
-#define OMNI_STAMP(p, id)                                                                              \
-    do {                                                                                               \
-        if ((p).trace && (threadIdx.x & 63) == 0)                                                      \
-            (p).trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 32 + (id)] = wall_clock64(); \
-    } while (0)
-#else
-#define OMNI_STAMP(p, id) do { } while (0)
-#endif
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
@@ -180,6 +168,18 @@ __device__ __forceinline__ void wg_combine_and_store(CombineSmem<D> &sm, const A
     lds_barrier();
 }
 
+// The all-zero output rows of an empty request for the columns of one KV head, written by the 64 lanes of a wave
+// together, four elements per lane and store.
+template <int D>
+__device__ __forceinline__ void wave_zero_rows(const AttnParams &p, int b, int kvh) {
+    for (int idx = 4 * (int)(threadIdx.x & 63); idx < p.Gq * D; idx += 4 * 64) {
+        const int c = idx / D, d = idx - c * D;
+        const size_t at = out_row(p, b, kvh, c) * D + d;
+        if (p.out_bf16) *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(p.out) + at) = make_uint2(0u, 0u);
+        else *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.out) + at) = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
 // blockIdx -> (workgroup index w within its KV head, KV head).  Workgroups are dealt to the eight compute dies
 // round-robin by blockIdx; this mapping gives every die a share of every KV head (a KV head is a fixed 4 KB or 8 KB
 // slice of each page, i.e. a fixed set of address bits) instead of binding each die to one head.
@@ -202,12 +202,7 @@ template <int D>
 __device__ __forceinline__ Plan attn_prologue(const AttnParams &p, PlanSmem *ps, int *E, int w, int kvh,
                                               int first_len = 0, bool have_first = false) {
     const Plan pl = plan_build(p.context_lens, p.plan, ps, E, E + p.plan.B + 1, [&](int b) {
-        if (w == 0) {
-            for (int c = 0; c < p.Gq; ++c) {
-                const size_t o0 = out_row(p, b, kvh, c) * D;
-                for (int i = 0; i < D; ++i) store_out(p, o0 + i, 0.f);
-            }
-        }
+        if (w == 0) wave_zero_rows<D>(p, b, kvh);
     }, first_len, have_first);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         const unsigned long long T = ps->total_tokens;

@@ -308,15 +308,19 @@ constexpr int kMaxRing = 4;
 constexpr int kKStageBytes = 8192;                     // one 32-token K tile of a 16-bit cache (D = 128)
 
 // Shared-memory layout for a batch of B requests and G query heads per KV head: as many ring slots (up to four) as
-// fit while two workgroups still share the 160 KB of a compute unit; at least one fits for every supported B and G.
+// fit while two workgroups still share the 160 KB of a compute unit.  Where not even one slot fits beside the plan's
+// arrays (thousands of requests with 16 columns), the layout keeps one slot and `two_per_cu` is false: the launch is
+// still valid, with one workgroup per compute unit.
+constexpr int kLdsPerWorkgroup = 80 * 1024 - 512;      // half a compute unit's shared memory less the kernel's own variables
 inline MfmaLds mfma_lds_layout(int B, int G, bool kv8, bool staged, bool query_counts = false) {
     constexpr int D = 128;
     MfmaLds L;
     L.ring_off = (((query_counts ? 3 : 2) * B + 1) * 4 + 15) & ~15;      // E[B + 1], Lc[B] and, if asked for, Nc[B]
     L.slot_floats = kWaves * G * (D + 4) + 2 * kWaves * kMaxGroup;
-    // 512 B for the kernel's static variables, and the waves' K tiles (static as well) if K is staged
-    const int budget = 80 * 1024 - 512 - L.ring_off - (staged ? kWaves * (kv8 ? kKStageBytes / 2 : kKStageBytes) : 0);
+    L.static_bytes = staged ? kWaves * (kv8 ? kKStageBytes / 2 : kKStageBytes) : 0;   // the waves' K tiles
+    const int budget = kLdsPerWorkgroup - L.ring_off - L.static_bytes;
     const int depth = budget / (L.slot_floats * 4);
+    L.two_per_cu = depth >= 1;
     L.ring_depth = depth > kMaxRing ? kMaxRing : (depth < 1 ? 1 : depth);
     L.total = L.ring_off + L.ring_depth * L.slot_floats * 4;
     return L;
@@ -394,15 +398,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
 
     int w, kvh;
     wg_coords(p, &w, &kvh);
-    OMNI_STAMP(p, 0);
-#ifdef OMNI_TRACE
-    if (p.trace && (threadIdx.x & 63) == 0) {
-        unsigned xcc, hwid;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
-        p.trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 32 + 8] = ((long long)xcc << 32) | hwid;
-    }
-#endif
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 15, j = lane >> 4;
@@ -451,17 +446,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     if (wave_plan) {
         unsigned long long T = 0;
         const bool first = blockIdx.x == 0 && wave == 0;
-        pl = plan_build_wave(p.context_lens, p.plan, E, E + p.plan.B + 1, &wp, w == 0 && wave == 0, [&](int b) {
-            if (!MT) {
-                const size_t o0 = ((size_t)b * p.Hq + head0) * D;
-                for (int i = 0; i < G * D; ++i) store_out(p, o0 + i, 0.f);
-            } else {
-                for (int c = 0; c < Gq; ++c) {
-                    const size_t o0 = out_row(p, b, kvh, c) * D;
-                    for (int i = 0; i < D; ++i) store_out(p, o0 + i, 0.f);
-                }
-            }
-        }, T);
+        pl = plan_build_wave(p.context_lens, p.plan, E, E + p.plan.B + 1, &wp, w == 0 && wave == 0,
+                             [&](int b) { wave_zero_rows<D>(p, b, kvh); }, T);
         if (first && lane == 0) {
             p.ws.plan_words[0] = pl.S * kTile; p.ws.plan_words[1] = pl.nranges;
             p.ws.plan_words[2] = (int)(T & 0xffffffffULL); p.ws.plan_words[3] = (int)(T >> 32);
@@ -475,14 +461,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             Nc[b] = min(max(n, 0), tokens);
         }
     }
-    OMNI_STAMP(p, 1);
-    bool stamped = false;
 
     for (int range = w; range < pl.nranges; range += p.plan.nw) {
         const int start = range * pl.S, end = min(pl.C, start + pl.S);
         const int len = end - start;
         const int first_b = wave_plan ? wave_first_request(wp, start) : plan_first_request(p.plan, &ps, E, start);
-        OMNI_STAMP(p, 9);
 
         // ---- this wave's tiles: tile g = wave + 4*slot of the range, slot = 0 .. nk-1.  Lane s of the wave looks up
         // everything about slot s (of the current group of 64 slots) once: the request, the tile's index inside the
@@ -501,7 +484,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                     if (E[mid] <= pos) lo = mid; else hi = mid;
                 }
                 const int t = pos - E[lo];
-                OMNI_STAMP(p, 10);
                 const int last_page = (Lc[lo] - 1) >> kLog2Ps;
                 const int32_t *bt = p.block_table + (size_t)lo * p.MB;
                 const int page = (t * kTile) >> kLog2Ps;
@@ -585,7 +567,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             load_q(cur.req, Q);
             issue_v(cur.pg0, cur.pg1);
         }
-        OMNI_STAMP(p, 2);
 
         int b = first_b;
         int npend = 0;                   // finished segments waiting in ring slots 0 .. npend-1
@@ -631,8 +612,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                         if (nxt.req != seg.b) load_q(nxt.req, Q);
                     }
                 }
-                if (!stamped) { OMNI_STAMP(p, 3); stamped = true; }
-                OMNI_STAMP(p, 16 + (s < 15 ? s : 15));
                 if constexpr (KV8) {
                     const float v0 = vs[0], v1 = vs[1];          // of the current tile: the next V request replaces them
 #pragma unroll
@@ -671,7 +650,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                     sm_m[wave * kMaxGroup + col] = st.m; sm_m[kWaves * kMaxGroup + wave * kMaxGroup + col] = st.l;
                 }
             }
-            if (cur.req < 0) OMNI_STAMP(p, 7);                   // this wave's last tile is done
             if (npend == 0) pend0 = b; else if (npend == 1) pend1 = b; else if (npend == 2) pend2 = b; else pend3 = b;
             ++npend;
             const bool last = __builtin_amdgcn_readfirstlane(E[b]) + seg.hi >= end;
@@ -691,7 +669,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             if (last) break;
             do { ++b; } while (b < p.plan.B - 1 && E[b + 1] == E[b]);    // skip requests that own no tile
         }
-        OMNI_STAMP(p, 4);
     }
 }
 

@@ -22,6 +22,9 @@ namespace {
 constexpr int kDefaultTargetWorkgroups = 512;     // two 4-wave workgroups per compute unit
 constexpr int kDefaultMinPartition = 128;
 constexpr int kMaxBatch = 4096;                      // the plan keeps 2 * batch + 1 words in shared memory
+// Dynamic shared memory any layout of the matrix-core kernel may ask for: normally half a compute unit's 160 KB, and up
+// to a whole one (less the static staging area and the kernel's own variables) for the largest batches with 16 columns.
+constexpr int kMaxDynamicLds = 160 * 1024 - kWaves * kKStageBytes - 1024;
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -32,11 +35,6 @@ bool misaligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t
 int elem_bytes(int dtype) { return dtype == OMNI_F32 ? 4 : (dtype == OMNI_BF16 ? 2 : 1); }
 
 }  // namespace
-
-#ifdef OMNI_TRACE
-static long long *g_omni_trace = nullptr;
-extern "C" void omni_dev_set_trace(long long *dev_buf) { g_omni_trace = dev_buf; }
-#endif
 
 struct omni_handle_s {
     omni_attn_desc_t d;
@@ -107,7 +105,7 @@ struct omni_handle_s {
         const int Gq = G * pass_tokens;          // columns of a KV head: (query token, head) pairs
         const bool mt = tune_query_tokens > 1;
         const MfmaLds plain = mfma_lds_layout(d.batch, Gq, fp8, false, mt), staged = mfma_lds_layout(d.batch, Gq, fp8, true, mt);
-        k_staged = staged.ring_depth >= 3 || plain.ring_depth <= 2;
+        k_staged = staged.two_per_cu && (staged.ring_depth >= 3 || plain.ring_depth <= 2);
         lds = k_staged ? staged : plain;
         lds_attr_set = false;
         long long ranges = nw;
@@ -137,6 +135,7 @@ const char *omni_status_string(omni_status_t s) {
         case OMNI_ERR_UNSUPPORTED: return "unsupported configuration";
         case OMNI_ERR_WORKSPACE: return "workspace missing or too small";
         case OMNI_ERR_HIP: return "HIP error";
+        case OMNI_ERR_NOMEM: return "out of host memory";
     }
     return "unknown status";
 }
@@ -160,7 +159,7 @@ omni_status_t omni_create(const omni_attn_desc_t *desc, omni_handle_t *out_handl
     if (desc->num_q_heads / desc->num_kv_heads > kMaxGroup) return OMNI_ERR_UNSUPPORTED;
     if (desc->batch > kMaxBatch) return OMNI_ERR_UNSUPPORTED;
     omni_handle_s *h = new (std::nothrow) omni_handle_s();
-    if (!h) return OMNI_ERR_HIP;
+    if (!h) return OMNI_ERR_NOMEM;
     h->d = *desc;
     h->derive();
     *out_handle = h;
@@ -272,6 +271,21 @@ static omni_status_t launch_append(omni_handle_t h, const void *k_new, const voi
                                    const int32_t *block_table, const int32_t *positions, int positions_are_lengths,
                                    void *stream);
 
+// The variant of the matrix-core kernel a handle launches: page size, cache width, K staging, query tokens per request.
+static const void *mfma_variant(const omni_handle_s *h) {
+    const bool ps16 = h->d.page_size == 16, st = h->k_staged, fp8 = h->d.kv_dtype == OMNI_FP8_E4M3;
+    if (h->tune_query_tokens > 1) {
+        if (fp8) return ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true, true> : (const void *)&decode_mfma_kernel<16, true, false, true>)
+                             : (st ? (const void *)&decode_mfma_kernel<32, true, true, true> : (const void *)&decode_mfma_kernel<32, true, false, true>);
+        return ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true, true> : (const void *)&decode_mfma_kernel<16, false, false, true>)
+                    : (st ? (const void *)&decode_mfma_kernel<32, false, true, true> : (const void *)&decode_mfma_kernel<32, false, false, true>);
+    }
+    if (fp8) return ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true> : (const void *)&decode_mfma_kernel<16, true, false>)
+                         : (st ? (const void *)&decode_mfma_kernel<32, true, true> : (const void *)&decode_mfma_kernel<32, true, false>);
+    return ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true> : (const void *)&decode_mfma_kernel<16, false, false>)
+                : (st ? (const void *)&decode_mfma_kernel<32, false, true> : (const void *)&decode_mfma_kernel<32, false, false>);
+}
+
 // The attention launch shared by omni_paged_decode_attn (k_new = v_new = null) and omni_decode_step.
 static omni_status_t launch_attention(omni_handle_t h, const void *q, const void *k_new, const void *v_new,
                                       const void *k_cache, const void *v_cache, const int32_t *block_table,
@@ -308,9 +322,6 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.log2_ps = ilog2(d.page_size);
     p.out_bf16 = d.out_dtype == OMNI_BF16;
     p.lds = h->lds;
-#ifdef OMNI_TRACE
-    p.trace = g_omni_trace;
-#endif
 
     // Several query tokens per request: one pass (attention + merge) per pass_tokens of them; the new rows of a fused
     // step are all written by the first pass.
@@ -328,21 +339,11 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
         const bool prof_in_dispatch = prof && h->kernel == 2;
         if (prof && !prof_in_dispatch && hipEventRecord(h->prof_events[2 * h->prof_used], s) != hipSuccess) return OMNI_ERR_HIP;
         if (h->kernel == 2) {
-            const bool ps16 = d.page_size == 16, st = h->k_staged;
-            const void *fn;
-            if (p.Tq > 1) {
-                if (fp8) fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true, true> : (const void *)&decode_mfma_kernel<16, true, false, true>)
-                                   : (st ? (const void *)&decode_mfma_kernel<32, true, true, true> : (const void *)&decode_mfma_kernel<32, true, false, true>);
-                else fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true, true> : (const void *)&decode_mfma_kernel<16, false, false, true>)
-                               : (st ? (const void *)&decode_mfma_kernel<32, false, true, true> : (const void *)&decode_mfma_kernel<32, false, false, true>);
-            } else if (fp8) fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, true, true> : (const void *)&decode_mfma_kernel<16, true, false>)
-                               : (st ? (const void *)&decode_mfma_kernel<32, true, true> : (const void *)&decode_mfma_kernel<32, true, false>);
-            else fn = ps16 ? (st ? (const void *)&decode_mfma_kernel<16, false, true> : (const void *)&decode_mfma_kernel<16, false, false>)
-                           : (st ? (const void *)&decode_mfma_kernel<32, false, true> : (const void *)&decode_mfma_kernel<32, false, false>);
+            const void *fn = mfma_variant(h);
             if (!h->lds_attr_set) {          // more than the default 64 KB of dynamic shared memory: the setting belongs to
                                              // the kernel, not to the handle, so every handle asks for the same bound (what
                                              // any layout may use) and none lowers what another one needs
-                if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024 - 512) != hipSuccess) {
+                if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds) != hipSuccess) {
                     (void)hipGetLastError();
                     return OMNI_ERR_HIP;
                 }
@@ -456,6 +457,38 @@ omni_status_t omni_debug_last_plan(omni_handle_t h, int32_t host_out[4], void *s
     return OMNI_OK;
 }
 
+omni_status_t omni_debug_lds_layout(omni_handle_t h, int32_t host_out[6]) {
+    if (!h || !host_out) return OMNI_ERR_NULL;
+    if (h->kernel != 2) return OMNI_ERR_UNSUPPORTED;
+    host_out[0] = h->lds.total; host_out[1] = h->lds.static_bytes; host_out[2] = h->lds.ring_depth;
+    host_out[3] = h->k_staged ? 1 : 0; host_out[4] = h->lds.two_per_cu ? 1 : 0; host_out[5] = kMaxDynamicLds;
+    return OMNI_OK;
+}
+
+omni_status_t omni_debug_kernel_resources(omni_handle_t h, int32_t which, int32_t host_out[6]) {
+    if (!h || !host_out) return OMNI_ERR_NULL;
+    const void *fn = nullptr;
+    int dyn = 0;
+    if (which == 0) {
+        if (h->kernel != 2) return OMNI_ERR_UNSUPPORTED;
+        fn = mfma_variant(h);
+        dyn = h->lds.total;
+    } else if (which == 1) {
+        fn = h->d.head_dim == 128 ? (const void *)&merge_kernel<128> : (const void *)&merge_kernel<64>;
+        dyn = (int)((2 * h->d.batch + 1) * sizeof(int));
+    } else {
+        return OMNI_ERR_SHAPE;
+    }
+    hipFuncAttributes a;
+    if (hipFuncGetAttributes(&a, fn) != hipSuccess) {
+        (void)hipGetLastError();
+        return OMNI_ERR_HIP;
+    }
+    host_out[0] = a.numRegs; host_out[1] = (int32_t)a.sharedSizeBytes; host_out[2] = dyn;
+    host_out[3] = a.maxThreadsPerBlock; host_out[4] = (int32_t)a.localSizeBytes; host_out[5] = kThreads;
+    return OMNI_OK;
+}
+
 omni_status_t omni_debug_profile_begin(omni_handle_t h, int32_t capacity, int32_t stride) {
     if (!h) return OMNI_ERR_NULL;
     if (capacity <= 0 || stride <= 0) return OMNI_ERR_SHAPE;
@@ -534,6 +567,7 @@ static omni_status_t launch_pack(omni_handle_t h, bool unpack, const void *k_src
     p.block_table = block_table; p.context_lens = context_lens;
     p.token_offsets = reinterpret_cast<const long long *>(token_offsets);
     p.q_lens = q_lens;
+    p.max_tokens = max_tokens;
     p.Hkv = d.num_kv_heads; p.MB = d.max_blocks_per_seq; p.log2_ps = ilog2(d.page_size);
     p.row_vecs = d.head_dim * elem_bytes(d.kv_dtype) / 16;
     const int span = q_lens ? max_tokens : h->max_ctx;                     // tokens per request the grid must cover
@@ -692,8 +726,9 @@ omni_status_t omni_graph_end(void *stream, omni_graph_t *out_graph) {
     if (!g || hipGraphInstantiate(&g->exec, graph, nullptr, nullptr, 0) != hipSuccess) {
         (void)hipGetLastError();
         (void)hipGraphDestroy(graph);
+        const omni_status_t st = g ? OMNI_ERR_HIP : OMNI_ERR_NOMEM;
         delete g;
-        return OMNI_ERR_HIP;
+        return st;
     }
     (void)hipGraphDestroy(graph);
     *out_graph = g;

@@ -85,7 +85,8 @@ __device__ __forceinline__ int block_inclusive_scan(int v, PlanSmem *ps, int *to
 }
 
 // Build E[] and Lc[] in shared memory and choose S.  All 256 threads call this.  Requests of length <= 0 own no
-// tile; `zero_row(b)` is invoked for each of them by one thread so that the caller can write their all-zero output.
+// tile; `zero_row(b)` is invoked for each of them by all lanes of one wave together (a wave-uniform call), so that the
+// caller can write their all-zero output with whole-wave stores.
 // `first_len` is context_lens[threadIdx.x] if the caller has already loaded it (have_first), so that the load can be
 // issued ahead of other traffic.  Only shared memory is synchronised: global loads in flight are not waited for.
 template <typename ZeroRow>
@@ -97,11 +98,14 @@ __device__ __forceinline__ Plan plan_build(const int32_t *__restrict__ lens, con
     for (int base = 0; base < pp.B; base += kThreads) {
         const int b = base + threadIdx.x;
         int c = 0, L = 0;
+        bool empty = false;
         if (b < pp.B) {
             L = (have_first && base == 0) ? first_len : lens[b];
             if (L > 0) { c = (L + kTile - 1) >> kLog2Tile; tokens += (unsigned long long)L; }
-            else zero_row(b);
+            else empty = true;
         }
+        for (unsigned long long em = __ballot(empty); em; em &= em - 1)       // each wave takes its own empty requests
+            zero_row(base + (int)(threadIdx.x & ~63u) + (int)__builtin_ctzll(em));
         int tot;
         const int incl = block_inclusive_scan(c, ps, &tot) + carry;
         if (b < pp.B) { E[b] = incl - c; Lc[b] = c ? L : 0; }
@@ -130,8 +134,8 @@ struct WavePlan {
     int i0, i1, i2, i3;  // tiles up to and including request 4*lane + i (requests beyond the batch own no tile)
 };
 
-// `zero_row(b)` is called for each request of length <= 0 if `zero_rows`; `total_tokens` receives the sum of the
-// lengths (in every lane).
+// `zero_row(b)` is called, by all lanes of the wave together, for each request of length <= 0 if `zero_rows`;
+// `total_tokens` receives the sum of the lengths (in every lane).
 template <typename ZeroRow>
 __device__ __forceinline__ Plan plan_build_wave(const int32_t *__restrict__ lens, const PlanParams &pp, int *E, int *Lc,
                                                 WavePlan *wp, bool zero_rows, ZeroRow zero_row,
@@ -154,7 +158,10 @@ __device__ __forceinline__ Plan plan_build_wave(const int32_t *__restrict__ lens
     for (int i = 0; i < 4; ++i) {
         const int b = 4 * lane + i;
         if (L[i] > 0) { c[i] = (L[i] + kTile - 1) >> kLog2Tile; tokens += (unsigned long long)L[i]; }
-        else { c[i] = 0; L[i] = 0; if (zero_rows && b < pp.B) zero_row(b); }
+        else { c[i] = 0; L[i] = 0; }
+        if (zero_rows)
+            for (unsigned long long em = __ballot(c[i] == 0 && b < pp.B); em; em &= em - 1)
+                zero_row(4 * (int)__builtin_ctzll(em) + i);
         run += c[i];
         incl[i] = run;
     }

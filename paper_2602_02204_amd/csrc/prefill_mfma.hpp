@@ -135,17 +135,18 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
     const int G = p.G, head0 = kvh * G;
     const int L = p.context_lens[b];
     const int n_q = min(p.q_lens[b], L);
+    const int n_live = min(n_q, p.max_q_len);                    // a chunk longer than the grid's bound is cut off there
     const int QB = prefill_tokens_per_block(G);
     const int NS = p.num_splits;
     const int split = NS > 1 ? (int)blockIdx.x % NS : 0;
     const int q0 = (NS > 1 ? (int)blockIdx.x / NS : (int)blockIdx.x) * QB;      // first query token of this workgroup
-    if (n_q <= 0 || q0 >= n_q) return;
+    if (n_live <= 0 || q0 >= n_live) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 15, j = lane >> 4;
     const long long q_row0 = p.q_offsets[b];
     const int pos0 = L - n_q;                                    // position of the chunk's first token
-    const int wg_last = min(n_q, q0 + QB) - 1;                   // last query token of the workgroup
+    const int wg_last = min(n_live, q0 + QB) - 1;                // last query token of the workgroup
     const int n_tiles = (pos0 + wg_last) / kTile + 1;            // tiles that hold tokens 0 .. position of wg_last
 
     // ---- this lane's columns (one per column block): query token, head, position; and the queries as MFMA B operands
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_mfma_kernel(Prefil
         const int c = wave * kPrefillCols + cb * 16 + col;       // column of the workgroup
         const int tl = c / G, g = c - tl * G;
         const int qi = q0 + tl;                                  // query token inside the chunk
-        const bool live = tl < QB && qi < n_q;
+        const bool live = tl < QB && qi < n_live;
         pos[cb] = live ? pos0 + qi : -1;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) Q[cb][kk] = make_uint4(0, 0, 0, 0);
@@ -471,10 +472,11 @@ __global__ __launch_bounds__(kThreads) void prefill_merge_kernel(PrefillParams p
     const long long qi = rh / p.Hq;
     const int L = p.context_lens[b];
     const int n_q = min(p.q_lens[b], L);
-    if (qi >= n_q || qi >= p.max_q_len) return;
+    const int n_live = min(n_q, p.max_q_len);
+    if (qi >= n_live) return;
     // the split count of the row's query block, as the attention kernel derived it
     const int QB = prefill_tokens_per_block(p.G);
-    const int wg_last = min(n_q, ((int)qi / QB + 1) * QB) - 1;
+    const int wg_last = min(n_live, ((int)qi / QB + 1) * QB) - 1;
     const int n_tiles = (L - n_q + wg_last) / kTile + 1;
     const int ns_eff = prefill_effective_splits(p.num_splits, (n_tiles + 1) >> 1, p.min_split_steps);
     if (ns_eff == 1) return;                                     // written by the attention kernel itself

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kThreads) void prefill_valu_kernel(PrefillParams p,
     const int L = p.context_lens[b];
     const int n_q = min(p.q_lens[b], L);
     const int qi = blockIdx.x * kWaves + wave;                   // query token inside the chunk
-    if (qi >= n_q) return;
+    if (qi >= min(n_q, p.max_q_len)) return;                     // a chunk longer than the grid's bound is cut off there
     const int pos = L - n_q + qi;                                // attends to tokens 0 .. pos
     const size_t q_row = (size_t)(p.q_offsets[b] + qi);
     const int ps = 1 << log2_ps;

@@ -6,20 +6,7 @@ import torch
 
 from paper_2602_02204_amd import binding as omni
 from paper_2602_02204_amd import workloads as W
-
-
-def to_dev(a: np.ndarray, dtype: str):
-    """Host array -> device tensor; bf16 bit patterns are reinterpreted, not converted."""
-    if a.dtype == np.uint16:
-        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
-    return torch.from_numpy(a).cuda()
-
-
-def bits_of(t: torch.Tensor) -> np.ndarray:
-    """Device tensor -> host numpy with the stored bits (bf16 comes back as uint16)."""
-    if t.dtype == torch.bfloat16:
-        return t.view(torch.int16).cpu().numpy().view(np.uint16)
-    return t.cpu().numpy()
+from paper_2602_02204_amd.devmem import bits_of, to_dev  # noqa: F401  (re-exported for the tests)
 
 
 class DeviceBatch:

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     assert omni.status_string(0) == "ok"
-    assert len({omni.status_string(i) for i in range(7)}) == 7
+    assert len({omni.status_string(i) for i in range(8)}) == 8
 
 
 @pytest.mark.parametrize("over,status", [
@@ -107,6 +107,32 @@ def test_tuning_validation_and_plan():
     assert f32.omni_get_plan()["kernel"] == omni.KERNEL_VALU
     with pytest.raises(omni.OmniError):
         f32.omni_set_tuning(omni.OMNI_TUNE_KERNEL, omni.KERNEL_MFMA)
+
+
+@pytest.mark.parametrize("kv", [omni.OMNI_BF16, omni.OMNI_FP8_E4M3], ids=["bf16", "fp8"])
+def test_shared_memory_layout_fits_for_every_batch_and_group(kv):
+    """Over the whole (batch, columns) range the library accepts: the dynamic and static shared memory of the
+    matrix-core kernel fit two workgroups per compute unit (half of 160 KB each) wherever the layout says so, never
+    exceed what the launch may ask for, and K is staged only where its staging area leaves room for a ring slot."""
+    for B in (1, 64, 256, 257, 1024, 2048, 3000, 4096):
+        for G in (1, 4, 7, 8, 16):
+            for T in (1, 2, 16 // G if G < 16 else 1):
+                h = omni.Handle(**good(batch=B, num_q_heads=2 * G, kv_dtype=kv,
+                                       q_dtype=omni.OMNI_BF16 if kv == omni.OMNI_FP8_E4M3 else None))
+                if T > 1:
+                    h.omni_set_tuning(omni.OMNI_TUNE_QUERY_TOKENS, T)
+                lay = h.omni_debug_lds_layout()
+                used = lay["dynamic_bytes"] + lay["static_bytes"] + 512
+                assert 1 <= lay["ring_slots"] <= 4, (B, G, T, lay)
+                assert lay["dynamic_bytes"] <= lay["max_dynamic_bytes"] and used <= 160 * 1024, (B, G, T, lay)
+                if lay["two_workgroups_per_cu"]:
+                    assert used <= 80 * 1024, (B, G, T, lay)
+                assert (lay["static_bytes"] > 0) == lay["k_staged"]
+                if lay["k_staged"]:
+                    assert lay["two_workgroups_per_cu"], (B, G, T, lay)
+    # the benchmark shapes keep two workgroups per compute unit
+    for B, Hq, Hkv in ((64, 28, 4), (256, 16, 2), (8, 28, 4), (128, 32, 8)):
+        assert omni.Handle(**good(batch=B, num_q_heads=Hq, num_kv_heads=Hkv)).omni_debug_lds_layout()["two_workgroups_per_cu"]
 
 
 def test_fp8_cache_descriptions():

@@ -341,3 +341,56 @@ def test_longest_first_order_changes_nothing_but_the_schedule():
     _, in_order = run_chunk(wl, ch, tuning={omni.OMNI_TUNE_PREFILL_SORT: 0})
     assert np.array_equal(got_sorted, in_order, equal_nan=True)
 
+
+
+@pytest.mark.parametrize("split", [False, True], ids=["one-launch", "context-split"])
+@pytest.mark.parametrize("kernel", [omni.KERNEL_AUTO, omni.KERNEL_VALU], ids=["mfma", "valu"])
+def test_chunks_longer_than_max_q_len_are_cut_off_there(split, kernel):
+    """q_lens above the host's bound: query tokens 0 .. max_q_len - 1 of every chunk are computed (each still at its
+    position in the full chunk), the others are not touched.  Group size 7 makes a query block 36 tokens, so a bound of
+    40 ends inside the second block; with the context split the pieces of tokens beyond the bound would land in the
+    next request's rows, and those of the last request behind the workspace: a guard area there must stay as it was."""
+    if split and kernel == omni.KERNEL_VALU:
+        pytest.skip("the vector-ALU kernel never splits the context")
+    wl = W.build("cut", 1600, [1500, 900, 700], Hq=14, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    ch = W.add_chunk(wl, [100, 90, 50], 1601, in_cache=True)
+    mq = 40
+    dev = DeviceBatch(wl, tuning={omni.OMNI_TUNE_KERNEL: kernel} if kernel else None)
+    c = ChunkOnDevice(dev, ch)
+    guard = 1 << 20
+    need = max(dev.h.omni_workspace_bytes(), dev.h.omni_prefill_workspace_bytes(mq) if split else 0)
+    if split:
+        assert dev.h.omni_prefill_workspace_bytes(mq) > 0
+    buf = torch.full(((need + guard) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    buf[need // 4:] = 12345.0
+    dev.ws = buf
+    dev.h.omni_set_workspace(buf, need)
+    dev.h.omni_paged_prefill_attn(c.q, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens, c.q_lens,
+                                  c.q_offsets, mq, float(wl.scale), c.out)
+    torch.cuda.synchronize()
+    assert bool(torch.all(buf[need // 4:] == 12345.0)), "wrote behind the registered workspace"
+    got = c.out.cpu().numpy().astype(np.float64)
+    ref = oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, ch.q_lens,
+                                    ch.q_offsets, wl.scale, wl.dtype)
+    for b in range(wl.B):
+        o, n = int(ch.q_offsets[b]), int(ch.q_lens[b])
+        assert np.max(np.abs(got[o:o + mq] - ref[o:o + mq])) <= TOL[wl.dtype], f"request {b}"
+        assert np.all(np.isnan(got[o + mq:o + n])), f"request {b}: tokens beyond the bound were written"
+
+
+def test_chunk_append_is_cut_off_at_max_q_len_too():
+    wl = W.build("cut", 1610, [300, 120], Hq=8, Hkv=2, D=128, ps=16, dtype=W.BF16)
+    ch = W.add_chunk(wl, [70, 50], 1611, in_cache=False)
+    mq = 40
+    dev = DeviceBatch(wl)
+    c = ChunkOnDevice(dev, ch)
+    dev.h.omni_kv_append_chunk(c.k_new, c.v_new, dev.k_cache, dev.v_cache, dev.block_table, dev.context_lens,
+                               c.q_lens, c.q_offsets, mq)
+    torch.cuda.synchronize()
+    # the first mq rows of each chunk, at their positions in the full chunk: the same as a chunk of mq tokens that ends
+    # q_lens - mq tokens before the context does
+    cut = np.minimum(ch.q_lens, mq).astype(np.int32)
+    oracle.kv_append_chunk(ch.k_new, ch.v_new, wl.k_cache, wl.v_cache, wl.block_table,
+                           (wl.context_lens - (ch.q_lens - cut)).astype(np.int32), cut, ch.q_offsets)
+    assert np.array_equal(as_bytes(bits_of(dev.k_cache)), as_bytes(wl.k_cache))
+    assert np.array_equal(as_bytes(bits_of(dev.v_cache)), as_bytes(wl.v_cache))
