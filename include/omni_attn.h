@@ -161,6 +161,23 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h,
                                      float scale, void *out, void *stream);
 
 /*
+ * omni_paged_decode_attn for callers that cannot allocate device memory and so have no workspace to register: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same
+ * results bit for bit; the plan words and partial rows go to an 8 MiB array that lives in the library's device image
+ * (each GPU the library runs on holds its copy until the process ends) instead of the handle's workspace, which need
+ * not be set.  The call makes no hipMalloc / hipFree and calls no allocating routine; its first call on a device looks
+ * up the array's address.  All handles and streams of a process share a GPU's array: calls that overlap in time on
+ * one GPU (different streams or threads) race on it, so issue them on one stream or order them yourself.  Nothing in
+ * the array needs clearing between calls.  16-bit and fp32 caches only.
+ * Errors: NULL, UNSUPPORTED (fp8 handle), WORKSPACE (omni_workspace_bytes of the handle exceeds 8 MiB: register a
+ * workspace and use omni_paged_decode_attn), SHAPE (alignment), HIP.
+ */
+omni_status_t omni_paged_decode_attn_static(omni_handle_t h,
+                                            const void *q, const void *k_cache, const void *v_cache,
+                                            const int32_t *block_table, const int32_t *context_lens,
+                                            float scale, void *out, void *stream);
+
+/*
  * The same attention over a quantised KV cache (the paper lists quantised attention only among its diffusion engine's
  * options, Section 3.3; here it halves the bytes the decode path streams).  The handle is created with
  * kv_dtype = OMNI_FP8_E4M3, q_dtype = OMNI_BF16, head_dim 128.  k_cache / v_cache hold one E4M3 byte per element in

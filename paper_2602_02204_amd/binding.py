@@ -22,7 +22,7 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 EXPORTS = (
     "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_prefill_workspace_bytes",
     "omni_set_workspace", "omni_set_query_lens",
-    "omni_paged_decode_attn", "omni_paged_decode_attn_fp8", "omni_kv_append", "omni_decode_step", "omni_decode_step_fp8", "omni_kv_pack", "omni_kv_unpack", "omni_paged_prefill_attn", "omni_paged_prefill_attn_fp8", "omni_kv_append_chunk", "omni_get_plan",
+    "omni_paged_decode_attn", "omni_paged_decode_attn_static", "omni_paged_decode_attn_fp8", "omni_kv_append", "omni_decode_step", "omni_decode_step_fp8", "omni_kv_pack", "omni_kv_unpack", "omni_paged_prefill_attn", "omni_paged_prefill_attn_fp8", "omni_kv_append_chunk", "omni_get_plan",
     "omni_status_string",
     "omni_debug_last_plan", "omni_debug_lds_layout", "omni_debug_kernel_resources", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
     "omni_debug_profile_end", "omni_graph_begin", "omni_graph_end", "omni_graph_launch", "omni_graph_destroy",
@@ -62,6 +62,7 @@ def lib():
         L.omni_set_query_lens.argtypes = [vp, vp]
         L.omni_paged_decode_attn.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_paged_decode_attn_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
+        L.omni_paged_decode_attn_static.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_kv_append.argtypes = [vp] * 8
         L.omni_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_decode_step_fp8.argtypes = [vp] * 10 + [C.c_float, vp, vp]
@@ -205,6 +206,11 @@ class Handle:
         _ck(lib().omni_paged_decode_attn(self._h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
                                          _ptr(context_lens), C.c_float(float(scale)), _ptr(out), _stream(stream)),
             "omni_paged_decode_attn")
+
+    def omni_paged_decode_attn_static(self, q, k_cache, v_cache, block_table, context_lens, scale, out, stream=None) -> None:
+        _ck(lib().omni_paged_decode_attn_static(self._h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                                _ptr(context_lens), C.c_float(float(scale)), _ptr(out), _stream(stream)),
+            "omni_paged_decode_attn_static")
 
     def omni_paged_decode_attn_fp8(self, q, k_cache, v_cache, k_scale, v_scale, block_table, context_lens, scale, out,
                                    stream=None) -> None:

@@ -287,15 +287,17 @@ static const void *mfma_variant(const omni_handle_s *h) {
 }
 
 // The attention launch shared by omni_paged_decode_attn (k_new = v_new = null) and omni_decode_step.
+// `ws_base` = null: the workspace the caller registered with the handle; else a buffer of at least h->ws_bytes.
 static omni_status_t launch_attention(omni_handle_t h, const void *q, const void *k_new, const void *v_new,
                                       const void *k_cache, const void *v_cache, const int32_t *block_table,
                                       const int32_t *context_lens, float scale, void *out, void *stream,
-                                      const float *k_scale = nullptr, const float *v_scale = nullptr) {
+                                      const float *k_scale = nullptr, const float *v_scale = nullptr,
+                                      void *ws_base = nullptr) {
     if (!h || !q || !k_cache || !v_cache || !block_table || !context_lens || !out) return OMNI_ERR_NULL;
     const bool fp8 = h->d.kv_dtype == OMNI_FP8_E4M3;
     if (fp8 != (k_scale != nullptr)) return OMNI_ERR_UNSUPPORTED;
     if (fp8 && (!v_scale || misaligned(k_scale, 4) || misaligned(v_scale, 4))) return v_scale ? OMNI_ERR_SHAPE : OMNI_ERR_NULL;
-    if (!h->ws || h->ws_given < h->ws_bytes) return OMNI_ERR_WORKSPACE;
+    if (!ws_base && (!h->ws || h->ws_given < h->ws_bytes)) return OMNI_ERR_WORKSPACE;
     if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(out, 16) ||
         misaligned(k_new, 16) || misaligned(v_new, 16) || misaligned(block_table, 4) || misaligned(context_lens, 4))
         return OMNI_ERR_SHAPE;
@@ -308,7 +310,7 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.k_scale = k_scale; p.v_scale = v_scale;
     p.block_table = block_table; p.context_lens = context_lens; p.out = out;
     p.q_lens = h->tune_query_tokens > 1 ? h->q_lens : nullptr;
-    char *ws = reinterpret_cast<char *>(h->ws);
+    char *ws = reinterpret_cast<char *>(ws_base ? ws_base : h->ws);
     p.ws.plan_words = reinterpret_cast<int32_t *>(ws);
     p.ws.part_ml = reinterpret_cast<float2 *>(ws + h->off_ml);
     p.ws.part_o = reinterpret_cast<float *>(ws + h->off_o);
@@ -386,6 +388,37 @@ omni_status_t omni_paged_decode_attn(omni_handle_t h, const void *q, const void 
                                      const int32_t *block_table, const int32_t *context_lens, float scale, void *out,
                                      void *stream) {
     return launch_attention(h, q, nullptr, nullptr, k_cache, v_cache, block_table, context_lens, scale, out, stream);
+}
+
+// ---- omni_paged_decode_attn without a workspace from the caller: the partial rows and plan words go to a static device
+// array.  `scratch` is a host-side stand-in for the array, not a device address: host code uses only the address that
+// hipGetSymbolAddress returns for the current device (every device holds its own copy of the array).
+constexpr size_t kScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices] = {};
+
+omni_status_t omni_paged_decode_attn_static(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
+                                            const int32_t *block_table, const int32_t *context_lens, float scale,
+                                            void *out, void *stream) {
+    if (!h) return OMNI_ERR_NULL;
+    if (h->d.kv_dtype == OMNI_FP8_E4M3) return OMNI_ERR_UNSUPPORTED;
+    if (h->ws_bytes > kScratchBytes) return OMNI_ERR_WORKSPACE;      // larger problems need omni_set_workspace
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return OMNI_ERR_HIP;
+    }
+    if (!g_scratch_ptr[dev]) {                                       // first call on this device: look the array up
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return OMNI_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return launch_attention(h, q, nullptr, nullptr, k_cache, v_cache, block_table, context_lens, scale, out, stream,
+                            nullptr, nullptr, g_scratch_ptr[dev]);
 }
 
 omni_status_t omni_paged_decode_attn_fp8(omni_handle_t h, const void *q, const void *k_cache, const void *v_cache,
