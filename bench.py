@@ -8,9 +8,11 @@ omni_kv_append + omni_paged_decode_attn instead (three launches).
 Inputs are resident in HBM before the timed region.  The KV pools are replicated and the steps rotate over the
 replicas so that the 256 MB memory-side cache cannot serve the reads of the next step.
 
-Prints ONE JSON line: metric/value (tokens/s = requests decoded per second, one token each), ms_per_step, the roofline
-of the dominant kernel (algorithmic KV bytes per launch / its average duration from HIP events recorded by the
-library around that kernel) and the fp64 CPU oracle timed on this machine's host cores.
+Prints ONE JSON line: metric/value (tokens/s = requests decoded per second, one token each) and ms_per_step from
+exactly --steps timed steps with nothing else in the stream; the roofline of the dominant kernel (algorithmic KV bytes
+per launch / its average duration over at least 32 launches, each with a HIP event pair in its own dispatch, in an
+untimed loop after the timed region) with the whole-step fraction beside it; the same figures for the other three
+stage-shaped batches (extra.other_workloads); and the fp64 CPU oracle timed on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -24,11 +26,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the attention kernel on the thinker workload (seed 1), from two rocprofv3 counter runs
-# (FETCH_SIZE scaled by 2.000, WRITE_SIZE by 1.000, the factors a plain 1 GiB copy gives); see
-# profiles/decode_mfma_kernel_thinker_hbm_traffic.txt.  Not measured by this script: null for any other workload.
-MEASURED_TRAFFIC_BYTES = {("thinker", 1): 300.2e6}
-EVENT_STRIDE = 8                # one timed step in eight carries the HIP event pair around the attention kernel
+# HBM bytes per launch of the attention kernel, from two rocprofv3 counter runs per workload (FETCH_SIZE scaled by
+# 2.000, WRITE_SIZE by 1.000, the factors a plain 1 GiB copy gives); see profiles/decode_mfma_kernel_*_hbm_traffic.txt.
+# Not measured by this script; valid only for the launch plan of the counter run, so the key holds that plan:
+# (workload, seed, range length in tokens, ranges, workgroups) -> bytes.  Anything else reports null.
+MEASURED_TRAFFIC_BYTES = {("thinker", 1, 1152, 126, 512): 300.2e6}
+KERNEL_EVENT_LAUNCHES = 48      # launches of the attention kernel that carry an event pair (untimed loop)
+STEADY_STEPS = 300              # steps of the steady-state loop reported beside the --steps figure
+OTHER_STEPS = 200               # timed steps for each of the other workloads
 
 
 def parse():
@@ -45,12 +50,154 @@ def parse():
     ap.add_argument("--min-partition", type=int, default=0)
     ap.add_argument("--force-partition", type=int, default=0)
     ap.add_argument("--unfused", action="store_true", help="time omni_kv_append + omni_paged_decode_attn instead")
+    ap.add_argument("--no-other-workloads", action="store_true", help="skip the talker / long / mixed figures")
     ap.add_argument("--timed-only", action="store_true",
                     help="skip the extra record-keeping loops, so that a profiler sees only warm-up and timed steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, so that a counter run has a kernel of known traffic in it")
     ap.add_argument("--verbose", action="store_true")
     return ap.parse_args()
+
+
+class DecodeSetup:
+    """One workload resident on the device: handle, workspace, replicated KV pools, and the step functions."""
+
+    def __init__(self, wl, args, torch, np, omni, W, tuned=True):
+        from paper_2602_02204_amd.devmem import to_dev
+        self.wl, self.torch, self.np, self.omni = wl, torch, np, omni
+        self.kvd = omni.OMNI_BF16 if wl.dtype == W.BF16 else omni.OMNI_F32
+        h = omni.Handle(batch=wl.B, num_q_heads=wl.Hq, num_kv_heads=wl.Hkv, head_dim=wl.D, page_size=wl.ps,
+                        num_pages=wl.P, max_blocks_per_seq=wl.MB, kv_dtype=self.kvd, out_dtype=omni.OMNI_F32)
+        if tuned:
+            for key, val in ((omni.OMNI_TUNE_KERNEL, args.kernel), (omni.OMNI_TUNE_TARGET_WORKGROUPS, args.target_wgs),
+                             (omni.OMNI_TUNE_MIN_PARTITION, args.min_partition),
+                             (omni.OMNI_TUNE_FORCE_PARTITION, args.force_partition)):
+                if val:
+                    h.omni_set_tuning(key, val)
+        self.h = h
+        self.ws = h.alloc_workspace()
+        self.kv_bytes = wl.kv_bytes
+        self.pool_bytes = 2 * wl.k_cache.nbytes
+        R = args.replicas or max(2, int(np.ceil((1 << 30) / max(self.kv_bytes, 1))))
+        self.R = R = min(R, max(1, int(150e9 // self.pool_bytes)))
+        self.q = to_dev(wl.q)
+        k0, v0 = to_dev(wl.k_cache), to_dev(wl.v_cache)
+        self.kc = [k0] + [k0.clone() for _ in range(R - 1)]
+        self.vc = [v0] + [v0.clone() for _ in range(R - 1)]
+        self.bt = torch.from_numpy(wl.block_table).cuda()
+        self.lens = torch.from_numpy(wl.context_lens).cuda()
+        self.k_new, self.v_new = to_dev(wl.k_new), to_dev(wl.v_new)
+        self.pos = torch.from_numpy(wl.positions).cuda()
+        self.out = torch.empty((wl.B, wl.Hq, wl.D), dtype=torch.float32, device="cuda")
+        self.scale = float(wl.scale)
+        self.stream = torch.cuda.current_stream()
+        for r in range(R):                   # every replica holds the appended token before anything is timed
+            h.omni_kv_append(self.k_new, self.v_new, self.kc[r], self.vc[r], self.bt, self.pos, self.stream)
+
+    def step_two_launches(self, i):
+        r = i % self.R
+        self.h.omni_kv_append(self.k_new, self.v_new, self.kc[r], self.vc[r], self.bt, self.pos, self.stream)
+        self.h.omni_paged_decode_attn(self.q, self.kc[r], self.vc[r], self.bt, self.lens, self.scale, self.out, self.stream)
+
+    def step_fused(self, i):
+        r = i % self.R
+        self.h.omni_decode_step(self.q, self.k_new, self.v_new, self.kc[r], self.vc[r], self.bt, self.lens, self.scale,
+                                self.out, self.stream)
+
+    def timed(self, fn, K, fixed_replica=False):
+        """Milliseconds per step over exactly K steps, synchronised on both sides, nothing else in the stream."""
+        self.torch.cuda.synchronize()
+        a = time.perf_counter()
+        for i in range(K):
+            fn(0 if fixed_replica else i)
+        self.torch.cuda.synchronize()
+        return (time.perf_counter() - a) * 1e3 / K
+
+    def kernel_times_ms(self, fn, n=KERNEL_EVENT_LAUNCHES):
+        """Durations of the attention kernel alone over n launches: the library attaches a HIP event pair to the kernel's
+        own dispatch (on the stream the kernel runs on), in an untimed loop of n steps over the rotating replicas."""
+        self.h.omni_debug_profile_begin(n, 1)
+        for i in range(n):
+            fn(i)
+        self.torch.cuda.synchronize()
+        return self.h.omni_debug_profile_end()
+
+    def stream_read_ceiling(self, k_avg_us, n=32):
+        """The memory system's ceiling for a kernel of this size: a plain streaming read of one replica's K and V pools
+        (pool bytes >= the algorithmic bytes: it also reads the unused tail slots and, where the pool is larger than
+        the batch, the pages nobody owns), timed with event pairs over the rotating replicas."""
+        torch, np, omni = self.torch, self.np, self.omni
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for i in range(8):
+            omni.omni_debug_stream_read(self.kc[i % self.R], self.vc[i % self.R], sink, self.stream)
+        for i, (a, b) in enumerate(evs):
+            a.record(self.stream)
+            omni.omni_debug_stream_read(self.kc[i % self.R], self.vc[i % self.R], sink, self.stream)
+            b.record(self.stream)
+        torch.cuda.synchronize()
+        us = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e3
+        return {"kernel": "stream_read_kernel", "bytes": self.pool_bytes, "avg_us": us, "GB/s": self.pool_bytes / us / 1e3,
+                "attention_vs_stream_read": (self.kv_bytes / k_avg_us) / (self.pool_bytes / us)}
+
+    def plan(self):
+        plan = self.h.omni_debug_last_plan()
+        plan.update(self.h.omni_get_plan())
+        return plan
+
+    def resources(self):
+        res = {"merge_kernel": self.h.omni_debug_kernel_resources(1)}
+        if self.h.omni_get_plan()["kernel"] == self.omni.KERNEL_MFMA:
+            res["decode_mfma_kernel"] = self.h.omni_debug_kernel_resources(0)
+            res["decode_mfma_kernel"]["shared_memory_layout"] = self.h.omni_debug_lds_layout()
+        return res
+
+    def check_parity(self, oracle, W, n_pairs=4):
+        """Sampled rows of the last step against the oracle (on a host copy of the pools with the token appended)."""
+        wl, np = self.wl, self.np
+        kf, vf = wl.k_cache.copy(), wl.v_cache.copy()
+        oracle.kv_append(wl.k_new, wl.v_new, kf, vf, wl.block_table, wl.positions, wl.dtype)
+        rng = np.random.default_rng(0)
+        pairs = [(int(b), int(hh)) for b, hh in zip(rng.integers(0, wl.B, n_pairs), rng.integers(0, wl.Hq, n_pairs))]
+        ref = oracle.paged_decode_attn(wl.q, kf, vf, wl.block_table, wl.context_lens, wl.scale, wl.dtype, pairs=pairs)
+        got = self.out.cpu().numpy().astype(np.float64)
+        err = float(max(np.max(np.abs(got[b, hh] - ref[i])) for i, (b, hh) in enumerate(pairs)))
+        tol = 2e-3 if wl.dtype == W.BF16 else 1e-5
+        if not (err <= tol):
+            print(f"bench.py: parity check failed on {wl.name}, max|err|={err:.3e} > {tol}", file=sys.stderr)
+            sys.exit(1)
+        return err
+
+
+def traffic_for(wl, plan):
+    if plan["kernel"] != 2:
+        return None
+    return MEASURED_TRAFFIC_BYTES.get((wl.name, wl.seed, plan["partition_len"], plan["request_parts"], plan["partition_grid"]))
+
+
+def measure_other(name, args, torch, np, omni, W, oracle):
+    """One of the other stage-shaped batches through the same step, default tuning: step time over OTHER_STEPS timed
+    steps, the attention kernel over KERNEL_EVENT_LAUNCHES event-carrying launches, the stream-read ceiling."""
+    wl = W.make(name, append=True)
+    d = DecodeSetup(wl, args, torch, np, omni, W, tuned=False)
+    for i in range(10):
+        d.step_fused(i)
+    ms = d.timed(d.step_fused, OTHER_STEPS)
+    km = d.kernel_times_ms(d.step_fused)
+    k_avg_us, k_med_us = float(np.mean(km)) * 1e3, float(np.median(km)) * 1e3
+    plan = d.plan()
+    res = {"config": f"{wl.name}: B={wl.B}, Hq={wl.Hq}, Hkv={wl.Hkv}, D={wl.D}, page={wl.ps}, seed {wl.seed}, "
+                     f"pool {wl.P} pages ({d.pool_bytes / 1e6:.0f} MB of K+V)",
+           "total_context_tokens": wl.total_tokens, "kv_bytes_per_step": d.kv_bytes, "pool_replicas": d.R,
+           "steps": OTHER_STEPS, "ms_per_step": ms, "tokens_per_s": wl.B / (ms * 1e-3),
+           "kv_gbs_per_step": d.kv_bytes / (ms * 1e-3) / 1e9, "step_frac": d.kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "kernel": "decode_mfma_kernel" if plan["kernel"] == 2 else "decode_valu_kernel",
+           "kernel_avg_us": k_avg_us, "kernel_median_us": k_med_us, "kernel_launches_timed": len(km),
+           "kernel_GB/s": d.kv_bytes / k_avg_us / 1e3, "frac": d.kv_bytes / k_avg_us / 1e3 / HBM_PEAK_GBS,
+           "traffic": traffic_for(wl, plan), "stream_read_ceiling": d.stream_read_ceiling(k_avg_us, n=24),
+           "plan": plan, "kernel_resources": d.resources(),
+           "parity_max_abs_err_sampled": d.check_parity(oracle, W)}
+    return res
 
 
 def main():
@@ -64,6 +211,7 @@ def main():
 
     from paper_2602_02204_amd import binding as omni
     from paper_2602_02204_amd import workloads as W
+    from paper_2602_02204_amd.devmem import to_dev
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -74,84 +222,36 @@ def main():
     log(f"workload {wl.name}: B={wl.B} Hq={wl.Hq} Hkv={wl.Hkv} D={wl.D} ps={wl.ps} T={wl.total_tokens} "
         f"KV bytes/call={kv_bytes / 1e6:.1f} MB pool pages={wl.P}")
 
-    from paper_2602_02204_amd.devmem import to_dev
-
-    kvd = omni.OMNI_BF16 if wl.dtype == W.BF16 else omni.OMNI_F32
-    h = omni.Handle(batch=wl.B, num_q_heads=wl.Hq, num_kv_heads=wl.Hkv, head_dim=wl.D, page_size=wl.ps,
-                    num_pages=wl.P, max_blocks_per_seq=wl.MB, kv_dtype=kvd, out_dtype=omni.OMNI_F32)
-    if args.kernel:
-        h.omni_set_tuning(omni.OMNI_TUNE_KERNEL, args.kernel)
-    if args.target_wgs:
-        h.omni_set_tuning(omni.OMNI_TUNE_TARGET_WORKGROUPS, args.target_wgs)
-    if args.min_partition:
-        h.omni_set_tuning(omni.OMNI_TUNE_MIN_PARTITION, args.min_partition)
-    if args.force_partition:
-        h.omni_set_tuning(omni.OMNI_TUNE_FORCE_PARTITION, args.force_partition)
-    ws = h.alloc_workspace()
-
-    pool_bytes = 2 * wl.k_cache.nbytes
-    R = args.replicas or max(2, int(np.ceil((1 << 30) / max(kv_bytes, 1))))
-    R = min(R, max(1, int(150e9 // pool_bytes)))
-    q = to_dev(wl.q, wl.dtype)
-    k0, v0 = to_dev(wl.k_cache, wl.dtype), to_dev(wl.v_cache, wl.dtype)
-    kc = [k0] + [k0.clone() for _ in range(R - 1)]
-    vc = [v0] + [v0.clone() for _ in range(R - 1)]
-    bt = torch.from_numpy(wl.block_table).cuda()
-    lens = torch.from_numpy(wl.context_lens).cuda()
-    k_new, v_new = to_dev(wl.k_new, wl.dtype), to_dev(wl.v_new, wl.dtype)
-    pos = torch.from_numpy(wl.positions).cuda()
-    out = torch.empty((wl.B, wl.Hq, wl.D), dtype=torch.float32, device="cuda")
-    scale = float(wl.scale)
-    stream = torch.cuda.current_stream()
-
-    def step_two_launches(i):
-        r = i % R
-        h.omni_kv_append(k_new, v_new, kc[r], vc[r], bt, pos, stream)
-        h.omni_paged_decode_attn(q, kc[r], vc[r], bt, lens, scale, out, stream)
-
-    def step_fused(i):
-        r = i % R
-        h.omni_decode_step(q, k_new, v_new, kc[r], vc[r], bt, lens, scale, out, stream)
-
+    dec = DecodeSetup(wl, args, torch, np, omni, W)
+    h, kvd, R, pool_bytes = dec.h, dec.kvd, dec.R, dec.pool_bytes
+    q, kc, vc, bt, lens, k_new, v_new, out = dec.q, dec.kc, dec.vc, dec.bt, dec.lens, dec.k_new, dec.v_new, dec.out
+    scale, stream = dec.scale, dec.stream
+    step_fused, step_two_launches = dec.step_fused, dec.step_two_launches
     step = step_two_launches if args.unfused else step_fused
 
-    for r in range(R):                       # every replica holds the appended token before anything is timed
-        h.omni_kv_append(k_new, v_new, kc[r], vc[r], bt, pos, stream)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    plan = h.omni_debug_last_plan()
-    plan.update(h.omni_get_plan())
+    plan = dec.plan()
 
-    # ---- timed region: exactly K steps; the library records an event pair around the attention kernel of every
-    # EVENT_STRIDE-th step (a pair costs a few microseconds of stream time, so not around every step)
+    # ---- timed region: exactly K steps between two synchronisations, nothing else in the stream
     K = args.steps
-    h.omni_debug_profile_begin((K + EVENT_STRIDE - 1) // EVENT_STRIDE, EVENT_STRIDE)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(K):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    kernel_ms = h.omni_debug_profile_end()
-    ms_per_step = (t1 - t0) * 1e3 / K
+    ms_per_step = dec.timed(step, K)
     tokens_per_s = wl.B / (ms_per_step * 1e-3)
+
+    # ---- the attention kernel alone (untimed loop, an event pair in every launch's own dispatch)
+    kernel_ms = dec.kernel_times_ms(step)
     k_avg_ms = float(np.mean(kernel_ms))
     k_med_ms = float(np.median(kernel_ms))
     achieved = kv_bytes / (k_avg_ms * 1e-3) / 1e9
 
-    # ---- for the record: the same K steps without the event pairs, as two launches, and on a single replica
-    def timed(fn, fixed_replica=False):
-        torch.cuda.synchronize()
-        a = time.perf_counter()
-        for i in range(K):
-            fn(0 if fixed_replica else i)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - a) * 1e3 / K
+    def timed(fn, fixed_replica=False, steps=None):
+        return dec.timed(fn, steps or K, fixed_replica)
 
-    ms_noevents = ms_other = ms_warm = ms_graph = host_us_graph = host_us_eager = None
+    # ---- for the record: a longer steady-state loop, the same K steps as two launches, and on a single replica
+    ms_steady = ms_other = ms_warm = ms_graph = host_us_graph = host_us_eager = None
     if not args.timed_only:
-        ms_noevents = timed(step)
+        ms_steady = timed(step, steps=max(K, STEADY_STEPS))
         ms_other = timed(step_fused if args.unfused else step_two_launches)
         ms_warm = timed(step, fixed_replica=True)
         # the same steps recorded once as a HIP graph (one step per pool replica) and replayed: what is left of the
@@ -216,29 +316,14 @@ def main():
                  "parity_max_abs_err_sampled": errT, "note": "omni_paged_decode_attn with OMNI_TUNE_QUERY_TOKENS: attention + merge, no append"}
         del qT, outT, wsT
 
-    # ---- the memory system's ceiling for a kernel of this size: a plain streaming read of one replica's K and V pools
-    # (pool bytes >= the algorithmic bytes: it also reads the unused tail slots), timed with event pairs like the
-    # attention kernel, over rotating replicas
-    ceiling = None
-    if not args.timed_only:
-        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(40)]
-        for i in range(8):
-            omni.omni_debug_stream_read(kc[i % R], vc[i % R], sink, stream)
-        for i, (a, b) in enumerate(evs):
-            a.record(stream)
-            omni.omni_debug_stream_read(kc[i % R], vc[i % R], sink, stream)
-            b.record(stream)
-        torch.cuda.synchronize()
-        us = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e3
-        ceiling = {"kernel": "stream_read_kernel", "bytes": pool_bytes, "avg_us": us, "GB/s": pool_bytes / us / 1e3,
-                   "attention_vs_stream_read": (kv_bytes / (k_avg_ms * 1e3)) / (pool_bytes / us)}
+    # ---- the memory system's ceiling for a kernel of this size (plain streaming read of one replica's pools)
+    ceiling = None if args.timed_only else dec.stream_read_ceiling(k_avg_ms * 1e3, n=40)
 
     # ---- the dense copies a connector ships (whole batch packed out of the pools, and unpacked back in)
     pack = None
     if not args.timed_only:
         offs = torch.from_numpy(np.concatenate([[0], np.cumsum(wl.context_lens[:-1])]).astype(np.int64)).cuda()
-        kd = torch.empty((wl.total_tokens, wl.Hkv, wl.D), dtype=k0.dtype, device="cuda")
+        kd = torch.empty((wl.total_tokens, wl.Hkv, wl.D), dtype=kc[0].dtype, device="cuda")
         vd = torch.empty_like(kd)
         pack = {"bytes_read_plus_written": 2 * kv_bytes}
         for nm, fn in (("pack", lambda r: h.omni_kv_pack(kc[r], vc[r], bt, lens, offs, kd, vd, stream)),
@@ -363,13 +448,11 @@ def main():
         step8 = lambda i: h8.omni_decode_step_fp8(q, kn8, vn8, k8[i % R8], v8[i % R8], ks8, vs8, bt, lens, scale, out8, stream)
         for i in range(args.warmup):
             step8(i)
-        h8.omni_debug_profile_begin((K + EVENT_STRIDE - 1) // EVENT_STRIDE, EVENT_STRIDE)
-        torch.cuda.synchronize()
-        a = time.perf_counter()
-        for i in range(K):
+        ms8 = timed(step8, steps=max(K, STEADY_STEPS))
+        h8.omni_debug_profile_begin(KERNEL_EVENT_LAUNCHES, 1)
+        for i in range(KERNEL_EVENT_LAUNCHES):
             step8(i)
         torch.cuda.synchronize()
-        ms8 = (time.perf_counter() - a) * 1e3 / K
         kern8 = float(np.mean(h8.omni_debug_profile_end())) * 1e3
         import oracle as _oracle
         pr8 = [(0, 0), (wl.B - 1, wl.Hq - 1), (wl.B // 2, 3)]
@@ -381,7 +464,7 @@ def main():
             print(f"bench.py: fp8 parity check failed, max|err|={err8:.3e}", file=sys.stderr)
             sys.exit(1)
         fp8 = {"kv_bytes_per_step": kv_bytes // 2, "ms_per_step": ms8, "tokens_per_s": wl.B / (ms8 * 1e-3),
-               "kernel_avg_us": kern8, "kernel_GB/s": kv_bytes / 2 / kern8 / 1e3,
+               "kernel_avg_us": kern8, "kernel_launches_timed": KERNEL_EVENT_LAUNCHES, "kernel_GB/s": kv_bytes / 2 / kern8 / 1e3,
                "kernel_frac_of_hbm_peak": kv_bytes / 2 / kern8 / 1e3 / HBM_PEAK_GBS, "pool_replicas": R8,
                "parity_max_abs_err_sampled": err8, "note": "omni_decode_step_fp8: append fused into the attention kernel, then the merge"}
         del k8, v8
@@ -396,17 +479,22 @@ def main():
 
     # ---- validity: sampled rows of the last step against the oracle (the appended token is in the pools now)
     import oracle
+    for i in range(2):
+        step(i)
+    torch.cuda.synchronize()
+    max_err = dec.check_parity(oracle, W)
     oracle.kv_append(wl.k_new, wl.v_new, wl.k_cache, wl.v_cache, wl.block_table, wl.positions, wl.dtype)
-    rng = np.random.default_rng(0)
-    pairs = [(int(b), int(hh)) for b, hh in zip(rng.integers(0, wl.B, 4), rng.integers(0, wl.Hq, 4))]
-    ref = oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, wl.scale, wl.dtype,
-                                   pairs=pairs)
-    got = out.cpu().numpy().astype(np.float64)
-    max_err = float(max(np.max(np.abs(got[b, hh] - ref[i])) for i, (b, hh) in enumerate(pairs)))
-    tol = 2e-3 if wl.dtype == W.BF16 else 1e-5
-    if not (max_err <= tol):
-        print(f"bench.py: parity check failed, max|err|={max_err:.3e} > {tol}", file=sys.stderr)
-        sys.exit(1)
+
+    # ---- the other stage-shaped batches through the same step (default tuning)
+    resources = dec.resources()
+    others = None
+    if not args.timed_only and not args.no_other_workloads:
+        others = {}
+        for name in ("thinker", "talker", "long", "mixed"):
+            if name != wl.name:
+                log(f"other workload: {name}")
+                others[name] = measure_other(name, args, torch, np, omni, W, oracle)
+                torch.cuda.empty_cache()
 
     # ---- CPU baseline: the oracle as it stands, all host threads, whole batch, one warm-up slice then timed passes
     cpu = None
@@ -458,14 +546,23 @@ def main():
         "kv_gbs_per_step": kv_bytes / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, wl.seed)) if plan["kernel"] == 2 else None,
+                     "traffic": traffic_for(wl, plan),
                      "kernel": "decode_mfma_kernel" if plan["kernel"] == 2 else "decode_valu_kernel",
                      "kernel_avg_us": k_avg_ms * 1e3, "kernel_median_us": k_med_ms * 1e3,
                      "kernel_launches_timed": len(kernel_ms),
                      "algorithmic_bytes_per_launch": kv_bytes,
+                     "step_frac": kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "step_frac_steady": kv_bytes / (ms_steady * 1e-3) / 1e9 / HBM_PEAK_GBS if ms_steady else None,
+                     "steady_steps": max(K, STEADY_STEPS) if ms_steady else None,
+                     "note": "frac = the attention kernel alone (event pairs in its dispatch); step_frac = the same bytes "
+                             "over the whole step of the timed region (attention + merge + launch gaps + the two "
+                             "synchronisations, which weigh 1/steps); step_frac_steady = the same over steady_steps steps. "
+                             "The 0.70 target of this workload is defined on the call, merge included: read step_frac_steady.",
                      "stream_read_ceiling": ceiling},
         "cpu_baseline": cpu,
-        "extra": {"ms_per_step_without_event_pairs": ms_noevents,
+        "extra": {"ms_per_step_steady": ms_steady,
+                  "kernel_resources": resources,
+                  "other_workloads": others,
                   ("ms_per_step_fused" if args.unfused else "ms_per_step_separate_append"): ms_other,
                   "ms_per_step_single_replica_cache_warm": ms_warm,
                   "ms_per_step_replayed_as_hip_graph": ms_graph,
