@@ -50,6 +50,10 @@ def lib():
         L.oracle_paged_prefill_attn_fp8.restype = C.c_int
         L.oracle_paged_prefill_attn_fp8.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 9 + [C.c_float, C.c_void_p,
                                                                                             C.c_void_p, C.c_int64, C.c_int32]
+        L.oracle_fp8_e4m3_encode.restype = C.c_uint8
+        L.oracle_fp8_e4m3_encode.argtypes = [C.c_float]
+        L.oracle_kv_append_quant_fp8.restype = None
+        L.oracle_kv_append_quant_fp8.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 8 + [C.c_float]
         L.oracle_gather.restype = None
         L.oracle_gather.argtypes = [C.POINTER(_Shape)] + [C.c_void_p] * 3 + [C.c_int32, C.c_void_p]
         _lib = L
@@ -222,6 +226,31 @@ def kv_append_chunk(k_new, v_new, k_cache, v_cache, block_table, context_lens, q
 def fp8_e4m3_decode(byte: int) -> float:
     """Value of one OCP E4M3 byte (NaN for 0x7f / 0xff)."""
     return float(lib().oracle_fp8_e4m3_decode(int(byte) & 0xff))
+
+
+def fp8_e4m3_encode(x: float) -> int:
+    """E4M3 code nearest to x (fp32), ties to the even code, magnitudes above 448 saturate, NaN gives 0x7f."""
+    return int(lib().oracle_fp8_e4m3_encode(C.c_float(float(np.float32(x)))))
+
+
+def kv_append_quant_fp8(k_new, v_new, k_cache, v_cache, k_scale, v_scale, block_table, positions, headroom: float) -> None:
+    """In place: quantise the bf16 rows k_new / v_new [B, Hkv, D] into the E4M3 pools at `positions` (< 0 skips).  A row
+    at slot 0 of its page sets that (page, KV head) scale to max(amax * headroom, 2^-100) / 448; other rows use the
+    page's scale.  k_cache / v_cache uint8 [P, Hkv, ps, D]; k_scale / v_scale float32 [P, Hkv]."""
+    _check(k_new, "bf16", "k_new"); _check(v_new, "bf16", "v_new")
+    for a, what in ((k_cache, "k_cache"), (v_cache, "v_cache")):
+        if a.dtype != np.uint8 or not a.flags.c_contiguous:
+            raise TypeError(f"{what}: need C-contiguous uint8")
+    for a, what in ((k_scale, "k_scale"), (v_scale, "v_scale")):
+        if a.dtype != np.float32 or not a.flags.c_contiguous:
+            raise TypeError(f"{what}: need C-contiguous float32")
+    P, Hkv, ps, D = k_cache.shape
+    bt = np.ascontiguousarray(block_table, dtype=np.int32)
+    pos = np.ascontiguousarray(positions, dtype=np.int32)
+    sh = _Shape(bt.shape[0], Hkv, Hkv, D, ps, bt.shape[1], _DT["bf16"], _DT["bf16"])
+    lib().oracle_kv_append_quant_fp8(C.byref(sh), k_new.ctypes.data, v_new.ctypes.data, k_cache.ctypes.data,
+                                     v_cache.ctypes.data, k_scale.ctypes.data, v_scale.ctypes.data, bt.ctypes.data,
+                                     pos.ctypes.data, C.c_float(float(headroom)))
 
 
 def paged_decode_attn_fp8(q, k_cache, v_cache, k_scale, v_scale, block_table, context_lens, scale,

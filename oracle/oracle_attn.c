@@ -436,3 +436,74 @@ int oracle_paged_prefill_attn_fp8(const oracle_shape_t *s, const void *q, const 
     free(first);
     return used;
 }
+
+
+/*
+ * Writing new rows into the quantised cache (the 8-bit form of oracle_kv_append; Section 2.2: the AR decoding loop adds
+ * one token per request per iteration).  The paper names no quantisation rule; the one defined here:
+ *   - the row that OPENS a page (slot 0) fixes the page's scale for that KV head:
+ *         scale = max(amax * headroom, 2^-100) / 448        amax = largest |x| of the row, all in fp32
+ *     (headroom >= 1 leaves room for later rows of the page; 448 is the largest finite E4M3 value);
+ *   - every other row uses the scale its page already has;
+ *   - byte = E4M3 code nearest to clamp(x / scale, -448, 448), ties to the even code; NaN gives the NaN byte 0x7f.
+ * The quotient decides an integer code, so it is taken in the precision the GPU kernel uses: x (bf16, widened exactly)
+ * and scale are fp32, the products and quotients above are single IEEE fp32 operations.
+ * Pins: the encoder against the framework's own E4M3 cast on every representable value, every midpoint and random
+ * values; hand-worked rounding cases (tests/golden/e4m3_rounding_cases.txt); decode(encode(v)) = v for all finite
+ * codes; the append against a numpy brute force built on the framework's cast, with a whole-pool comparison.
+ */
+uint8_t oracle_fp8_e4m3_encode(float x)
+{
+    if (x != x) return 0x7f;
+    uint8_t sign = signbit(x) ? 0x80 : 0x00;
+    double a = fabs((double)x);
+    if (a > 448.0) a = 448.0;
+    int best = 0;
+    double best_err = a;                                   /* code 0 stands for 0 */
+    for (int code = 1; code <= 0x7e; ++code) {             /* the finite non-negative codes, ascending in value */
+        double err = fabs(oracle_fp8_e4m3_decode((uint8_t)code) - a);
+        if (err < best_err || (err == best_err && (code & 1) == 0)) { best = code; best_err = err; }
+    }
+    return (uint8_t)(sign | best);
+}
+
+void oracle_kv_append_quant_fp8(const oracle_shape_t *s, const uint16_t *k_new, const uint16_t *v_new, uint8_t *k_cache,
+                                uint8_t *v_cache, float *k_scale, float *v_scale, const int32_t *block_table,
+                                const int32_t *positions, float headroom)
+{
+    for (int which = 0; which < 2; ++which) {
+        const uint16_t *src = which ? v_new : k_new;
+        uint8_t *cache = which ? v_cache : k_cache;
+        float *scales = which ? v_scale : k_scale;
+        for (int b = 0; b < s->B; ++b) {
+            int pos = positions[b];
+            if (pos < 0) continue;
+            int64_t page = block_table[(int64_t)b * s->MB + pos / s->ps];
+            int slot = pos % s->ps;
+            for (int g = 0; g < s->Hkv; ++g) {
+                const uint16_t *row = src + ((int64_t)b * s->Hkv + g) * s->D;
+                float sc;
+                if (slot == 0) {
+                    float amax = 0.0f;
+                    for (int d = 0; d < s->D; ++d) {
+                        float v = fabsf((float)widen(row, d, ORACLE_BF16));
+                        if (v > amax) amax = v;                /* a NaN element never raises amax */
+                    }
+                    float top = amax * headroom;
+                    if (!(top > 0x1p-100f)) top = 0x1p-100f;
+                    sc = top / 448.0f;
+                    scales[page * s->Hkv + g] = sc;
+                } else {
+                    sc = scales[page * s->Hkv + g];
+                }
+                uint8_t *dst = cache + (((page * s->Hkv + g) * s->ps) + slot) * (int64_t)s->D;
+                for (int d = 0; d < s->D; ++d) {
+                    float qv = (float)widen(row, d, ORACLE_BF16) / sc;
+                    if (qv > 448.0f) qv = 448.0f;
+                    if (qv < -448.0f) qv = -448.0f;
+                    dst[d] = oracle_fp8_e4m3_encode(qv);
+                }
+            }
+        }
+    }
+}

@@ -626,3 +626,116 @@ def test_chunk_oracle_rejects_rows_outside_the_chunks():
     with pytest.raises(ValueError):
         oracle.paged_prefill_attn(ch.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens,
                                   ch.q_lens + 100, ch.q_offsets, wl.scale, wl.dtype)
+
+
+# --------------------------------------------------------------------------- quantising append (E4M3 encoder)
+def _e4m3_golden():
+    path = os.path.join(os.path.dirname(__file__), "golden", "e4m3_rounding_cases.txt")
+    for line in open(path):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            value, byte = line.split()[:2]
+            yield float(value), int(byte, 16)
+
+
+def test_e4m3_encoder_on_hand_worked_cases():
+    n = 0
+    for value, byte in _e4m3_golden():
+        assert oracle.fp8_e4m3_encode(value) == byte, (value, hex(byte), hex(oracle.fp8_e4m3_encode(value)))
+        n += 1
+    assert n >= 16
+    assert oracle.fp8_e4m3_encode(float("nan")) == 0x7F
+
+
+def test_e4m3_encoder_round_trips_every_finite_code_and_is_monotonic():
+    vals = []
+    for code in range(256):
+        v = oracle.fp8_e4m3_decode(code)
+        if np.isnan(v):
+            continue
+        assert oracle.fp8_e4m3_encode(v) == code or (v == 0 and oracle.fp8_e4m3_encode(v) in (0x00, 0x80))
+        vals.append(v)
+    xs = np.linspace(-460.0, 460.0, 20001).astype(np.float32)
+    dec = np.array([oracle.fp8_e4m3_decode(oracle.fp8_e4m3_encode(float(x))) for x in xs])
+    assert np.all(np.diff(dec) >= 0)                                   # rounding never reorders
+    grid = np.array(sorted(vals))
+    nearest = np.abs(grid[None, :] - np.clip(xs, -448, 448).astype(np.float64)[:, None]).min(axis=1)
+    assert np.array_equal(np.abs(dec - np.clip(xs, -448, 448).astype(np.float64)), nearest)   # and picks a nearest value
+
+
+def test_e4m3_encoder_agrees_with_the_frameworks_cast():
+    """torch's float8_e4m3fn cast (round to nearest even) on every representable value, every midpoint between
+    neighbours, values a hair to either side of the midpoints, and random values inside the finite range."""
+    import torch
+    grid = np.array(sorted({oracle.fp8_e4m3_decode(c) for c in range(0x7F)}), dtype=np.float64)
+    mids = (grid[:-1] + grid[1:]) / 2
+    xs = np.concatenate([grid, mids, np.nextafter(mids.astype(np.float32), np.float32(0)),
+                         np.nextafter(mids.astype(np.float32), np.float32(1e9)),
+                         np.random.default_rng(77).uniform(0, 448, 4000), np.random.default_rng(78).normal(0, 1, 4000)])
+    xs = np.concatenate([xs, -xs]).astype(np.float32)
+    want = torch.from_numpy(xs).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = np.array([oracle.fp8_e4m3_encode(float(x)) for x in xs], dtype=np.uint8)
+    assert np.array_equal(got, want)
+
+
+def _quant_case(seed, ps=16, Hkv=2, D=128):
+    rng = np.random.default_rng(seed)
+    lens = np.array([ps + 1, 2 * ps, 5, 3 * ps + 1, 0, 1, ps], dtype=np.int64)       # positions at slot 0 and elsewhere
+    wl = W.build("quant", seed, lens, Hq=2 * Hkv, Hkv=Hkv, D=D, ps=ps, dtype=W.BF16, append=True, pool_factor=1.5)
+    f8 = W.quantize_fp8(wl)
+    # make the new rows span several binades, with a few values beyond what an old page's scale can hold
+    kf = (rng.standard_normal(wl.k_new.shape) * np.exp2(rng.integers(-6, 4, size=wl.k_new.shape[:2] + (1,)))).astype(np.float32)
+    vf = (rng.standard_normal(wl.v_new.shape) * 3.0).astype(np.float32)
+    wl.k_new, wl.v_new = W.f32_to_bf16_bits(kf), W.f32_to_bf16_bits(vf)
+    return wl, f8
+
+
+@pytest.mark.parametrize("headroom", [1.0, 2.0, 1.37])
+@pytest.mark.parametrize("ps", [16, 32])
+def test_quantising_append_against_a_brute_force_on_the_frameworks_cast(headroom, ps):
+    import torch
+    wl, f8 = _quant_case(90 + ps, ps=ps)
+    k8, v8, ks, vs = f8.k_cache.copy(), f8.v_cache.copy(), f8.k_scale.copy(), f8.v_scale.copy()
+    oracle.kv_append_quant_fp8(wl.k_new, wl.v_new, k8, v8, ks, vs, wl.block_table, wl.positions, headroom)
+    # brute force, written separately: fp32 arithmetic in numpy, bytes by the framework's cast
+    ek, ev, eks, evs = f8.k_cache.copy(), f8.v_cache.copy(), f8.k_scale.copy(), f8.v_scale.copy()
+    for cache, scales, new in ((ek, eks, wl.k_new), (ev, evs, wl.v_new)):
+        x = W.bf16_bits_to_f32(new)
+        for b in range(wl.B):
+            pos = int(wl.positions[b])
+            if pos < 0:
+                continue
+            page, slot = int(wl.block_table[b, pos // ps]), pos % ps
+            for g in range(wl.Hkv):
+                if slot == 0:
+                    top = np.float32(np.abs(x[b, g]).max()) * np.float32(headroom)
+                    scales[page, g] = np.maximum(top, np.float32(2.0 ** -100)) / np.float32(448.0)
+                q = np.clip(x[b, g] / scales[page, g], np.float32(-448.0), np.float32(448.0)).astype(np.float32)
+                cache[page, g, slot] = torch.from_numpy(q).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(ks, eks) and np.array_equal(vs, evs)
+    assert np.array_equal(k8, ek) and np.array_equal(v8, ev)                   # whole pools: nothing else changed
+    touched_scales = int((ks != f8.k_scale).sum())
+    assert touched_scales == sum(1 for b in range(wl.B) if wl.positions[b] >= 0 and wl.positions[b] % ps == 0) * wl.Hkv
+
+
+def test_quantising_append_reconstruction_error_and_saturation():
+    wl, f8 = _quant_case(95)
+    k8, v8, ks, vs = f8.k_cache.copy(), f8.v_cache.copy(), f8.k_scale.copy(), f8.v_scale.copy()
+    oracle.kv_append_quant_fp8(wl.k_new, wl.v_new, k8, v8, ks, vs, wl.block_table, wl.positions, 1.0)
+    x = W.bf16_bits_to_f32(wl.k_new).astype(np.float64)
+    dec = np.vectorize(oracle.fp8_e4m3_decode)
+    for b in range(wl.B):
+        pos = int(wl.positions[b])
+        if pos < 0:
+            continue
+        page, slot = int(wl.block_table[b, pos // wl.ps]), pos % wl.ps
+        for g in range(wl.Hkv):
+            s = float(ks[page, g])
+            back = dec(k8[page, g, slot]).astype(np.float64) * s
+            inside = np.abs(x[b, g]) <= 448.0 * s
+            # inside the page's range: half a unit of the last place of a 4-bit significand (2^-4 relative), or half a
+            # subnormal step (2^-10 * scale); outside: the largest value the scale can hold, with the right sign
+            assert np.all(np.abs(back - x[b, g])[inside] <= np.maximum(np.abs(x[b, g])[inside] * 2.0 ** -4, s * 2.0 ** -10) + 1e-30)
+            assert np.all(back[~inside] == np.sign(x[b, g][~inside]) * 448.0 * s)
+            if slot == 0:                                    # headroom 1: the row's largest element lands on +-448 exactly
+                assert np.max(np.abs(dec(k8[page, g, slot]))) == 448.0
