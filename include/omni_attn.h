@@ -231,6 +231,23 @@ omni_status_t omni_decode_step_fp8(omni_handle_t h, const void *q, const void *k
                                    const int32_t *context_lens, float scale, void *out, void *stream);
 
 /*
+ * The append that quantises (Section 2.2: the AR decoding loop adds one token per request per iteration; here into the
+ * quantised cache of omni_paged_decode_attn_fp8).  k_new / v_new [batch, num_kv_heads, head_dim] are bf16 rows; row
+ * (b, g) goes to slot positions[b] % page_size of page block_table[b][positions[b] / page_size], KV head g, as
+ *     byte = E4M3(clamp(x / scale, -448, 448)),  round to nearest even,  NaN -> 0x7f,
+ * with the scale of that (page, KV head).  A row that lands in slot 0 opens its page and fixes that scale first:
+ *     scale = max(amax * headroom, 2^-100) / 448,   amax = the row's largest magnitude
+ * (written to k_scale / v_scale [num_pages, num_kv_heads]); every other row uses the scale its page already has, and
+ * values beyond 448 * scale saturate.  headroom >= 1 leaves room for the page's later rows (1 = the opening row's
+ * largest element maps to 448 exactly).  All arithmetic is fp32; K and V are treated alike.  Requests with
+ * positions[b] < 0 are skipped; two requests must not write into the same page in one call.  One launch.
+ * Errors: NULL, UNSUPPORTED (handle is not an fp8 one), SHAPE (headroom outside [1, 65536], alignment), HIP.
+ */
+omni_status_t omni_kv_append_quant_fp8(omni_handle_t h, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                                       float *k_scale, float *v_scale, const int32_t *block_table,
+                                       const int32_t *positions, float headroom, void *stream);
+
+/*
  * Dense copies of whole requests, the payload a connector ships when the KV cache of a request moves between a
  * prefill and a decode engine (Section 3.4, disaggregated data transfer: the connector also carries KV cache between
  * prefill and decode).  For every request b with token_offsets[b] >= 0 and every t < context_lens[b]:

@@ -22,7 +22,7 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 EXPORTS = (
     "omni_create", "omni_destroy", "omni_set_tuning", "omni_workspace_bytes", "omni_prefill_workspace_bytes",
     "omni_set_workspace", "omni_set_query_lens",
-    "omni_paged_decode_attn", "omni_paged_decode_attn_static", "omni_paged_decode_attn_fp8", "omni_kv_append", "omni_decode_step", "omni_decode_step_fp8", "omni_kv_pack", "omni_kv_unpack", "omni_paged_prefill_attn", "omni_paged_prefill_attn_fp8", "omni_kv_append_chunk", "omni_get_plan",
+    "omni_paged_decode_attn", "omni_paged_decode_attn_static", "omni_paged_decode_attn_fp8", "omni_kv_append", "omni_decode_step", "omni_decode_step_fp8", "omni_kv_append_quant_fp8", "omni_kv_pack", "omni_kv_unpack", "omni_paged_prefill_attn", "omni_paged_prefill_attn_fp8", "omni_kv_append_chunk", "omni_get_plan",
     "omni_status_string",
     "omni_debug_last_plan", "omni_debug_lds_layout", "omni_debug_kernel_resources", "omni_debug_gather", "omni_debug_stream_read", "omni_debug_profile_begin",
     "omni_debug_profile_end", "omni_graph_begin", "omni_graph_end", "omni_graph_launch", "omni_graph_destroy",
@@ -66,6 +66,7 @@ def lib():
         L.omni_kv_append.argtypes = [vp] * 8
         L.omni_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float, vp, vp]
         L.omni_decode_step_fp8.argtypes = [vp] * 10 + [C.c_float, vp, vp]
+        L.omni_kv_append_quant_fp8.argtypes = [vp] * 9 + [C.c_float, vp]
         L.omni_kv_pack.argtypes = [vp] * 9
         L.omni_kv_unpack.argtypes = [vp] * 9
         L.omni_paged_prefill_attn.argtypes = [vp] * 8 + [C.c_int32, C.c_float, vp, vp]
@@ -253,6 +254,12 @@ class Handle:
         _ck(lib().omni_decode_step_fp8(self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
                                        _ptr(k_scale), _ptr(v_scale), _ptr(block_table), _ptr(context_lens),
                                        C.c_float(float(scale)), _ptr(out), _stream(stream)), "omni_decode_step_fp8")
+
+    def omni_kv_append_quant_fp8(self, k_new, v_new, k_cache, v_cache, k_scale, v_scale, block_table, positions,
+                                 headroom: float, stream=None) -> None:
+        _ck(lib().omni_kv_append_quant_fp8(self._h, _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(k_scale),
+                                           _ptr(v_scale), _ptr(block_table), _ptr(positions), C.c_float(float(headroom)),
+                                           _stream(stream)), "omni_kv_append_quant_fp8")
 
     def omni_paged_prefill_attn_fp8(self, q, k_cache, v_cache, k_scale, v_scale, block_table, context_lens, q_lens,
                                     q_offsets, max_q_len: int, scale, out, stream=None) -> None:

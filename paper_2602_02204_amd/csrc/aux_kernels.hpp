@@ -102,6 +102,73 @@ __global__ __launch_bounds__(kThreads) void kv_append_kernel(AppendParams p) {
     reinterpret_cast<uint4 *>(p.v_cache)[dst] = reinterpret_cast<const uint4 *>(p.v_new)[src];
 }
 
+struct AppendQuantParams {
+    const void *k_new, *v_new;       // bf16 [B, Hkv, 128]
+    void *k_cache, *v_cache;         // E4M3 bytes [P, Hkv, ps, 128]
+    float *k_scale, *v_scale;        // [P, Hkv]
+    const int32_t *block_table, *positions;
+    float headroom;
+    int B, Hkv, MB, log2_ps;
+};
+
+// Quantising append into an 8-bit cache: 16 lanes per row of 128 bf16 values (8 each), the K rows first, then the V
+// rows.  A row at slot 0 opens its page and fixes the page's scale for its KV head, max(amax * headroom, 2^-100) / 448
+// (amax over the row by cross-lane maxima); any other row takes the scale its page has.  Bytes: x / scale (one
+// correctly rounded fp32 division), clamped to +-448, converted by the hardware's round-to-nearest-even E4M3 conversion;
+// NaN becomes the byte 0x7f.
+__global__ __launch_bounds__(kThreads) void kv_append_quant_kernel(AppendQuantParams p) {
+    constexpr int D = 128;
+    const long long t = (long long)blockIdx.x * kThreads + threadIdx.x;
+    const long long rows = (long long)p.B * p.Hkv;
+    const long long row2 = t >> 4;
+    const int c = (int)(t & 15);
+    const bool in_grid = row2 < 2 * rows;
+    const bool is_v = row2 >= rows;
+    const long long row = in_grid ? row2 - (is_v ? rows : 0) : 0;
+    const int g = (int)(row % p.Hkv), b = (int)(row / p.Hkv);
+    const int pos = in_grid ? p.positions[b] : -1;
+    const bool live = pos >= 0;
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = 0.f;
+    if (live) {
+        const uint4 raw = *(reinterpret_cast<const uint4 *>(is_v ? p.v_new : p.k_new) + row * (D / 8) + c);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { x[2 * i] = bf16_bits_to_float(w[i] & 0xffffu); x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
+    }
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(x[i]));             // a NaN element never raises the maximum
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    if (!live) return;
+    const int page = p.block_table[(size_t)b * p.MB + (pos >> p.log2_ps)];
+    const int slot = pos & ((1 << p.log2_ps) - 1);
+    float *scales = is_v ? p.v_scale : p.k_scale;
+    const size_t si = (size_t)page * p.Hkv + g;
+    float sc;
+    if (slot == 0) {
+        float top = amax * p.headroom;
+        if (!(top > 0x1p-100f)) top = 0x1p-100f;
+        sc = top / 448.0f;
+        if (c == 0) scales[si] = sc;
+    } else {
+        sc = scales[si];
+    }
+    uint32_t out[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float a = fminf(fmaxf(x[2 * i] / sc, -448.0f), 448.0f), bq = fminf(fmaxf(x[2 * i + 1] / sc, -448.0f), 448.0f);
+        uint32_t pk = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, bq, 0, false) & 0xffffu;
+        if (x[2 * i] != x[2 * i]) pk = (pk & 0xff00u) | 0x7fu;
+        if (x[2 * i + 1] != x[2 * i + 1]) pk = (pk & 0x00ffu) | 0x7f00u;
+        if (i & 1) out[i >> 1] |= pk << 16; else out[i >> 1] = pk;
+    }
+    char *dst = reinterpret_cast<char *>(is_v ? p.v_cache : p.k_cache) + ((((size_t)page * p.Hkv + g) << p.log2_ps) + slot) * D + c * 8;
+    *reinterpret_cast<uint2 *>(dst) = make_uint2(out[0], out[1]);
+}
+
 struct GatherParams {
     const void *cache;
     const int32_t *block_table, *context_lens;

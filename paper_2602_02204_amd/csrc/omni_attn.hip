@@ -479,6 +479,31 @@ static omni_status_t launch_append(omni_handle_t h, const void *k_new, const voi
     return OMNI_OK;
 }
 
+omni_status_t omni_kv_append_quant_fp8(omni_handle_t h, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                                       float *k_scale, float *v_scale, const int32_t *block_table,
+                                       const int32_t *positions, float headroom, void *stream) {
+    if (!h || !k_new || !v_new || !k_cache || !v_cache || !k_scale || !v_scale || !block_table || !positions)
+        return OMNI_ERR_NULL;
+    if (h->d.kv_dtype != OMNI_FP8_E4M3) return OMNI_ERR_UNSUPPORTED;
+    if (!(headroom >= 1.0f) || !(headroom <= 65536.0f)) return OMNI_ERR_SHAPE;
+    if (misaligned(k_new, 16) || misaligned(v_new, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) ||
+        misaligned(k_scale, 4) || misaligned(v_scale, 4) || misaligned(block_table, 4) || misaligned(positions, 4))
+        return OMNI_ERR_SHAPE;
+    const omni_attn_desc_t &d = h->d;
+    AppendQuantParams p;
+    p.k_new = k_new; p.v_new = v_new; p.k_cache = k_cache; p.v_cache = v_cache;
+    p.k_scale = k_scale; p.v_scale = v_scale;
+    p.block_table = block_table; p.positions = positions;
+    p.headroom = headroom;
+    p.B = d.batch; p.Hkv = d.num_kv_heads; p.MB = d.max_blocks_per_seq; p.log2_ps = ilog2(d.page_size);
+    const long long threads = 2LL * p.B * p.Hkv * 16;                      // 16 lanes per K row and per V row
+    const dim3 grid((unsigned)((threads + kThreads - 1) / kThreads));
+    (void)hipGetLastError();
+    kv_append_quant_kernel<<<grid, kThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(p);
+    if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
+    return OMNI_OK;
+}
+
 omni_status_t omni_debug_last_plan(omni_handle_t h, int32_t host_out[4], void *stream) {
     if (!h || !host_out) return OMNI_ERR_NULL;
     if (!h->ws) return OMNI_ERR_WORKSPACE;

@@ -256,3 +256,94 @@ def test_decode_step_fp8_equals_append_then_attention(name, kw, force_pl):
     bar = max(TOL[W.BF16], 2.0 ** -9 * np.max(np.abs(ref)))           # V bytes reach 448 times the page scale here
     assert np.all(np.isfinite(got)) and np.max(np.abs(got - ref)) <= bar
 
+
+
+# --------------------------------------------------------------------------- the append that quantises
+def _append_quant_on_gpu(wl, f8, headroom):
+    dev = Fp8Batch(wl, f8)
+    k_new, v_new = to_dev(wl.k_new, wl.dtype), to_dev(wl.v_new, wl.dtype)
+    pos = torch.from_numpy(wl.positions).cuda()
+    dev.h.omni_kv_append_quant_fp8(k_new, v_new, dev.k, dev.v, dev.ks, dev.vs, dev.bt, pos, headroom)
+    torch.cuda.synchronize()
+    return dev
+
+
+def test_hardware_e4m3_conversion_equals_the_oracles_encoder_on_every_boundary():
+    """Rows made of every representable E4M3 magnitude, every midpoint between neighbours and the bf16 values next to
+    each midpoint, both signs, plus values beyond the range and NaN, written at a slot other than 0 into pages whose
+    scale is 1: the bytes are the encoder's, bit for bit (round to nearest even, saturation, NaN byte)."""
+    grid = np.array(sorted({oracle.fp8_e4m3_decode(c) for c in range(0x7F)}), dtype=np.float64)
+    mids = ((grid[:-1] + grid[1:]) / 2).astype(np.float32)
+    up = W.bf16_bits_to_f32((W.f32_to_bf16_bits(mids).astype(np.uint32) + 1).astype(np.uint16))      # next bf16 above
+    dn = W.bf16_bits_to_f32((W.f32_to_bf16_bits(mids).astype(np.uint32) - 1).astype(np.uint16))      # next bf16 below
+    vals = np.concatenate([grid.astype(np.float32), mids, up, dn[1:], [450.0, 464.0, 2.0 ** 20, 2.0 ** 127, np.nan]]).astype(np.float32)
+    vals = np.concatenate([vals, -vals])
+    assert np.array_equal(W.bf16_bits_to_f32(W.f32_to_bf16_bits(vals[~np.isnan(vals)])), vals[~np.isnan(vals)])  # all are bf16 values
+    D, Hkv = 128, 2
+    B = -(-vals.size // (D * Hkv))
+    flat = np.zeros(B * Hkv * D, dtype=np.float32)
+    flat[:vals.size] = vals
+    lens = np.full(B, 5, dtype=np.int64)                              # position 4: never slot 0
+    wl = W.build("cvt", 300, lens, Hq=2 * Hkv, Hkv=Hkv, D=D, ps=16, dtype=W.BF16, append=True)
+    f8 = W.quantize_fp8(wl)
+    f8.k_scale[:] = 1.0
+    f8.v_scale[:] = 0.5                                               # V: the same values through a scale of one half
+    wl.k_new = W.f32_to_bf16_bits(flat.reshape(B, Hkv, D))
+    wl.v_new = W.f32_to_bf16_bits((flat * np.float32(0.5)).reshape(B, Hkv, D))
+    dev = _append_quant_on_gpu(wl, f8, 1.0)
+    k8, v8, ks, vs = f8.k_cache.copy(), f8.v_cache.copy(), f8.k_scale.copy(), f8.v_scale.copy()
+    oracle.kv_append_quant_fp8(wl.k_new, wl.v_new, k8, v8, ks, vs, wl.block_table, wl.positions, 1.0)
+    assert np.array_equal(dev.k.cpu().numpy(), k8) and np.array_equal(dev.v.cpu().numpy(), v8)
+    assert np.array_equal(dev.ks.cpu().numpy(), ks) and np.array_equal(dev.vs.cpu().numpy(), vs)
+    page, slot = wl.block_table[0, 0], 4
+    want = np.array([oracle.fp8_e4m3_encode(float(x)) for x in flat[:D]], dtype=np.uint8)
+    assert np.array_equal(dev.k.cpu().numpy()[page, 0, slot], want)
+
+
+@pytest.mark.parametrize("headroom", [1.0, 2.0, 1.37])
+@pytest.mark.parametrize("ps,Hkv", [(16, 2), (32, 4), (16, 1)])
+def test_quantising_append_whole_pools_and_scales(headroom, ps, Hkv):
+    """Rows spanning several binades, positions at slot 0 (the page's scale is set from the row) and elsewhere (the
+    page's scale is used, values beyond it saturate), empty requests skipped: pools and scales byte for byte."""
+    rng = np.random.default_rng(400 + ps + Hkv)
+    lens = np.concatenate([[ps + 1, 2 * ps, 5, 3 * ps + 1, 0, 1, ps], rng.integers(1, 200, size=40)]).astype(np.int64)
+    wl = W.build("quant", 401 + ps, lens, Hq=4 * Hkv, Hkv=Hkv, D=128, ps=ps, dtype=W.BF16, append=True, pool_factor=1.5)
+    f8 = W.quantize_fp8(wl)
+    kf = (rng.standard_normal(wl.k_new.shape) * np.exp2(rng.integers(-6, 4, size=wl.k_new.shape[:2] + (1,)))).astype(np.float32)
+    vf = (rng.standard_normal(wl.v_new.shape) * 3.0).astype(np.float32)
+    kf[3, 0, 7] = np.nan                                              # a NaN element: NaN byte, and it never sets a scale
+    wl.k_new, wl.v_new = W.f32_to_bf16_bits(kf), W.f32_to_bf16_bits(vf)
+    wl.k_new[3, 0, 7] = W.BF16_NAN_BITS
+    dev = _append_quant_on_gpu(wl, f8, headroom)
+    k8, v8, ks, vs = f8.k_cache.copy(), f8.v_cache.copy(), f8.k_scale.copy(), f8.v_scale.copy()
+    oracle.kv_append_quant_fp8(wl.k_new, wl.v_new, k8, v8, ks, vs, wl.block_table, wl.positions, headroom)
+    assert np.array_equal(dev.ks.cpu().numpy(), ks) and np.array_equal(dev.vs.cpu().numpy(), vs)
+    assert np.array_equal(dev.k.cpu().numpy(), k8) and np.array_equal(dev.v.cpu().numpy(), v8)
+
+
+def test_decode_over_rows_the_library_quantised_itself():
+    """A talker-shaped batch whose newest token is quantised by omni_kv_append_quant_fp8, then attended to: equal to
+    the oracle's append followed by the oracle's attention over the 8-bit cache."""
+    wl = W.make("talker", batch=40, append=True)
+    f8 = W.quantize_fp8(wl)
+    dev = _append_quant_on_gpu(wl, f8, 1.5)
+    got = dev.attend()
+    oracle.kv_append_quant_fp8(wl.k_new, wl.v_new, f8.k_cache, f8.v_cache, f8.k_scale, f8.v_scale, wl.block_table,
+                               wl.positions, 1.5)
+    err = np.max(np.abs(got - ref_of(wl, f8)))
+    assert np.all(np.isfinite(got)) and err <= TOL[W.BF16], f"{err:.3e}"
+
+
+def test_quantising_append_argument_checks():
+    wl = W.make("talker", batch=4, append=True)
+    f8 = W.quantize_fp8(wl)
+    dev = Fp8Batch(wl, f8)
+    for bad in (0.5, float("nan"), 1e9):
+        with pytest.raises(omni.OmniError) as e:
+            dev.h.omni_kv_append_quant_fp8(dev.q, dev.q, dev.k, dev.v, dev.ks, dev.vs, dev.bt, dev.lens, bad)
+        assert e.value.status == 2
+    bf = omni.Handle(batch=4, num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16, num_pages=64,
+                     max_blocks_per_seq=8, kv_dtype=omni.OMNI_BF16)
+    with pytest.raises(omni.OmniError) as e:
+        bf.omni_kv_append_quant_fp8(dev.q, dev.q, dev.k, dev.v, dev.ks, dev.vs, dev.bt, dev.lens, 1.0)
+    assert e.value.status == 4
