@@ -466,6 +466,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         const int start = range * pl.S, end = min(pl.C, start + pl.S);
         const int len = end - start;
         const int first_b = wave_plan ? wave_first_request(wp, start) : plan_first_request(p.plan, &ps, E, start);
+        // the request that holds the range's last tile bounds every lane's search below: a range rarely spans more than
+        // two or three requests, so the search takes one or two steps instead of log2(B)
+        const int search_hi = wave_plan ? wave_first_request(wp, end - 1) + 1 : p.plan.B;
 
         // ---- this wave's tiles: tile g = wave + 4*slot of the range, slot = 0 .. nk-1.  Lane s of the wave looks up
         // everything about slot s (of the current group of 64 slots) once: the request, the tile's index inside the
@@ -478,7 +481,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             meta = make_int4(-1, 0, 0, 0);
             if (slot < nk) {
                 const int pos = start + wave + kWaves * slot;
-                int lo = first_b, hi = p.plan.B;                 // E[lo] <= pos < E[hi]
+                int lo = first_b, hi = search_hi;                // E[lo] <= pos < E[hi]
                 while (hi - lo > 1) {
                     const int mid = (lo + hi) >> 1;
                     if (E[mid] <= pos) lo = mid; else hi = mid;
