@@ -364,7 +364,8 @@ omni_status_t omni_debug_stream_read(const void *a, size_t a_bytes, const void *
                                      void *stream);
 
 /* Host-only: the shared-memory layout the matrix-core kernel of this handle is launched with.  host_out[0] = bytes of
- * dynamic shared memory, [1] = bytes of the kernel variant's static K staging area, [2] = ring slots, [3] = 1 if K
+ * dynamic shared memory, [1] = bytes of the kernel variant's static K staging area, [2] = online-softmax states the
+ * ring holds (4 .. 16), [3] = 1 if K
  * tiles are staged through shared memory, [4] = 1 if two workgroups fit one compute unit's 160 KB, [5] = the most
  * dynamic shared memory any launch may ask for.  Errors: NULL, UNSUPPORTED (the handle runs the vector-ALU kernel). */
 omni_status_t omni_debug_lds_layout(omni_handle_t h, int32_t host_out[6]);

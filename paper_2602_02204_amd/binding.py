@@ -282,7 +282,7 @@ class Handle:
     def omni_debug_lds_layout(self) -> dict:
         arr = (C.c_int32 * 6)()
         _ck(lib().omni_debug_lds_layout(self._h, arr), "omni_debug_lds_layout")
-        return {"dynamic_bytes": arr[0], "static_bytes": arr[1], "ring_slots": arr[2], "k_staged": bool(arr[3]),
+        return {"dynamic_bytes": arr[0], "static_bytes": arr[1], "ring_states": arr[2], "k_staged": bool(arr[3]),
                 "two_workgroups_per_cu": bool(arr[4]), "max_dynamic_bytes": arr[5]}
 
     def omni_debug_kernel_resources(self, which: int = 0) -> dict:

@@ -22,12 +22,12 @@ struct Workspace {
     float *part_o;
 };
 
-// Shared memory of the matrix-core kernel behind the plan's arrays: `ring_depth` slots, each holding the four waves'
-// online-softmax states of one finished segment as o[wave][G][D + 4] floats followed by m[wave][16] and l[wave][16].
+// Shared memory of the matrix-core kernel behind the plan's arrays: room for `ring_states` online-softmax states, each
+// one wave's share of one request as o[G][D + 4] floats followed by m[16] and l[16].
 struct MfmaLds {
     int ring_off;                       // bytes from the start of dynamic shared memory
-    int slot_floats;
-    int ring_depth;                     // 1 .. 4
+    int state_floats;
+    int ring_states;                    // 4 .. kMaxStates
     int total;                          // bytes of dynamic shared memory
     int static_bytes;                   // bytes of the kernel variant's static K staging area (0 if K is not staged)
     bool two_per_cu;                    // total + static_bytes leave room for a second workgroup on the compute unit

@@ -1,7 +1,8 @@
 // Matrix-core split-context decode kernel for bf16 q/K/V with head_dim 128 and group size <= 16.
 //
-// A workgroup walks the segments of its ranges (see plan.hpp) for one KV head; within a segment its four waves take
-// 32-token tiles round-robin and each keeps its own online-softmax state; the states meet in LDS at the segment's end.
+// A workgroup takes the ranges the plan gives it (see plan.hpp) for one KV head; the 32-token tiles of a range are dealt
+// to its four waves in contiguous runs, a wave keeps one online-softmax state per request its run touches, and the
+// states meet in LDS when the range is done.
 //
 // Per 32-token tile a wave computes, with v_mfma_f32_16x16x32_bf16 (A: 16 rows x 32 k, B: 32 k x 16 columns;
 // a lane holds row/column lane%16 and the 8 consecutive k of group lane/16):
@@ -304,52 +305,72 @@ __device__ __forceinline__ void mfma_softmax_pv(float (&sv)[8], uint4 (&V)[8], M
     }
 }
 
-constexpr int kMaxRing = 4;
+constexpr int kMaxStates = 16;                         // states the ring holds at most
 constexpr int kKStageBytes = 8192;                     // one 32-token K tile of a 16-bit cache (D = 128)
 
-// Shared-memory layout for a batch of B requests and G query heads per KV head: as many ring slots (up to four) as
-// fit while two workgroups still share the 160 KB of a compute unit.  Where not even one slot fits beside the plan's
-// arrays (thousands of requests with 16 columns), the layout keeps one slot and `two_per_cu` is false: the launch is
-// still valid, with one workgroup per compute unit.
+// Shared-memory layout for a batch of B requests and G columns per KV head: as many states (up to sixteen) as fit
+// while two workgroups still share the 160 KB of a compute unit.  Four is the least the kernel works with (one state
+// per wave: one request at a time); where not even four fit beside the plan's arrays (thousands of requests with 16
+// columns), the layout keeps four and `two_per_cu` is false: the launch is still valid, with one workgroup per
+// compute unit.
 constexpr int kLdsPerWorkgroup = 80 * 1024 - 512;      // half a compute unit's shared memory less the kernel's own variables
 inline MfmaLds mfma_lds_layout(int B, int G, bool kv8, bool staged, bool query_counts = false) {
     constexpr int D = 128;
     MfmaLds L;
     L.ring_off = (((query_counts ? 3 : 2) * B + 1) * 4 + 15) & ~15;      // E[B + 1], Lc[B] and, if asked for, Nc[B]
-    L.slot_floats = kWaves * G * (D + 4) + 2 * kWaves * kMaxGroup;
+    L.state_floats = G * (D + 4) + 2 * kMaxGroup;
     L.static_bytes = staged ? kWaves * (kv8 ? kKStageBytes / 2 : kKStageBytes) : 0;   // the waves' K tiles
     const int budget = kLdsPerWorkgroup - L.ring_off - L.static_bytes;
-    const int depth = budget / (L.slot_floats * 4);
-    L.two_per_cu = depth >= 1;
-    L.ring_depth = depth > kMaxRing ? kMaxRing : (depth < 1 ? 1 : depth);
-    L.total = L.ring_off + L.ring_depth * L.slot_floats * 4;
+    const int cap = budget / (L.state_floats * 4);
+    L.two_per_cu = cap >= kWaves;
+    L.ring_states = cap > kMaxStates ? kMaxStates : (cap < kWaves ? kWaves : cap);
+    L.total = L.ring_off + L.ring_states * L.state_floats * 4;
     return L;
 }
 
-// Combine the four waves' (m, l, o) of one finished segment held in a ring slot and store the result: the
-// normalised output if the request lies inside one range, else the unnormalised values (plus, once per head, the
-// running max and sum) into the segment's partial-result slot.  Every thread owns four consecutive output
+// A range (or a chunk of it) of `clen` tiles is dealt to the four waves in contiguous runs: wave w takes tiles
+// run_start(w) .. run_start(w + 1) - 1 of the chunk.  With fewer than four tiles, waves 0 .. clen - 1 take one each.
+__device__ __forceinline__ int run_start(int clen, int w) { return clen >= kWaves ? (clen * w) >> 2 : min(w, clen); }
+// The wave whose run holds tile x of the chunk (0 <= x < clen).
+__device__ __forceinline__ int wave_of_tile(int clen, int x) {
+    return (x >= run_start(clen, 1)) + (x >= run_start(clen, 2)) + (x >= run_start(clen, 3));
+}
+
+// Combine the `cnt` consecutive states (m, l, o) that the waves left for one request's piece of a chunk and store the
+// result: the normalised output if the request lies inside one range, else the unnormalised values (plus, once per
+// head, the running max and sum) into the piece's partial-result slot.  Every thread owns four consecutive output
 // elements.  All threads call it between barriers.
 template <int D, bool MT>
-__device__ __forceinline__ void mfma_combine_segment(const float *slot, const AttnParams &p, const Segment &seg, int kvh,
-                                                     int n_tokens = 1) {
+__device__ __forceinline__ void mfma_combine_states(const float *first, int cnt, int state_floats, const AttnParams &p,
+                                                    const Segment &seg, int kvh, int n_tokens = 1) {
     const int G = MT ? p.Gq : p.G;                       // columns: (query token, head) pairs of the KV head
-    const float *sm_m = slot + kWaves * G * (D + 4), *sm_l = sm_m + kWaves * kMaxGroup;
     for (int idx = 4 * threadIdx.x; idx < G * D; idx += 4 * kThreads) {
         const int g = idx / D, d = idx - g * D;
+        // a request's piece lies in at most four runs: all four reads are issued before any is used (a state that is
+        // not part of the piece is read from the first one and dropped)
+        float mu[kWaves], lu[kWaves];
+        float4 ou[kWaves];
+#pragma unroll
+        for (int u = 0; u < kWaves; ++u) {
+            const float *st = first + (u < cnt ? u : 0) * state_floats;
+            mu[u] = st[G * (D + 4) + g];
+            lu[u] = st[G * (D + 4) + kMaxGroup + g];
+            ou[u] = *reinterpret_cast<const float4 *>(st + g * (D + 4) + d);
+        }
         float M = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm_m[w * kMaxGroup + g]);
+        for (int u = 0; u < kWaves; ++u) {
+            if (u >= cnt) mu[u] = -INFINITY;
+            M = fmaxf(M, mu[u]);
+        }
         float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
         float den = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float mw = sm_m[w * kMaxGroup + g];
-            if (mw > -INFINITY) {
-                const float a = fast_exp2(mw - M);
-                const float4 o = *reinterpret_cast<const float4 *>(slot + (w * G + g) * (D + 4) + d);
-                num.x += a * o.x; num.y += a * o.y; num.z += a * o.z; num.w += a * o.w;
-                den += a * sm_l[w * kMaxGroup + g];
+        for (int u = 0; u < kWaves; ++u) {
+            if (mu[u] > -INFINITY) {
+                const float a = fast_exp2(mu[u] - M);
+                num.x += a * ou[u].x; num.y += a * ou[u].y; num.z += a * ou[u].z; num.w += a * ou[u].w;
+                den += a * lu[u];
             }
         }
         if (MT && p.t_off + g / p.G >= n_tokens) {           // no query token behind this column: zeros, weight 0
@@ -377,12 +398,16 @@ __device__ __forceinline__ void mfma_combine_segment(const float *slot, const At
     }
 }
 
-// Finished segments wait in a ring of shared-memory slots (their per-wave states) until the workgroup meets to
-// combine them: when the ring is full or the range ends.  A range that holds the end of one request and the start of
-// the next is thus processed without a stop in the middle.
+// The tiles of a range are dealt to the four waves in contiguous runs, so a wave holds one online-softmax state per
+// request its run touches: four states plus one per request boundary that falls inside a run, whatever the number
+// of requests (dealt round-robin, every request would leave four).  A wave leaves each finished state in shared memory
+// and goes on; the workgroup meets once, when the range is done: one barrier, then every thread combines, request by
+// request, the one to four consecutive states that belong to it.  A range that holds more requests than the states'
+// area has room for (all but three of its states) is taken in chunks of that many requests, with the same meeting
+// after each chunk.
 // KV8: the pools hold 8-bit E4M3 bytes with one scale per (page, KV head); queries stay bf16.
-// KST: K tiles go through the per-wave staging area in shared memory (the host chooses it where the ring keeps enough
-// slots beside it); otherwise they are loaded straight into the operand registers.
+// KST: K tiles go through the per-wave staging area in shared memory (the host chooses it where room for enough
+// states is left beside it); otherwise they are loaded straight into the operand registers.
 // MT: several query tokens per request (the columns are (query token, head) pairs with a causal limit each); the
 // one-token kernel is compiled without any of it.
 template <int PS, bool KV8 = false, bool KST = true, bool MT = false>
@@ -394,7 +419,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
     extern __shared__ __align__(16) int E[];                 // E[B + 1] tile offsets, then Lc[B] lengths, then the ring
     __shared__ __align__(16) char kstage_all[KST ? kWaves * (KV8 ? kKStageBytes / 2 : kKStageBytes) : 16];  // a K tile per wave
     float *ring = reinterpret_cast<float *>(reinterpret_cast<char *>(E) + p.lds.ring_off);
-    const int RING = p.lds.ring_depth, slot_floats = p.lds.slot_floats;
+    const int state_floats = p.lds.state_floats;
+    const int max_seg = p.lds.ring_states - (kWaves - 1);    // requests a chunk may hold: the states then fit
 
     int w, kvh;
     wg_coords(p, &w, &kvh);
@@ -464,23 +490,39 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
 
     for (int range = w; range < pl.nranges; range += p.plan.nw) {
         const int start = range * pl.S, end = min(pl.C, start + pl.S);
-        const int len = end - start;
-        const int first_b = wave_plan ? wave_first_request(wp, start) : plan_first_request(p.plan, &ps, E, start);
-        // the request that holds the range's last tile bounds every lane's search below: a range rarely spans more than
+        int cs = start;                  // first tile of the chunk
+        int cb = wave_plan ? wave_first_request(wp, start) : plan_first_request(p.plan, &ps, E, start);   // its request
+      while (cs < end) {                 // chunks of the range: normally one
+        // ---- the chunk: up to max_seg requests from tile cs on; nb = the request the next chunk starts with
+        int ce = end, nb = cb;
+        // (with the plan in registers the common case needs no walk: the requests up to the one that holds the range's
+        // last tile, empty ones included, are no more than a chunk may hold)
+        if (!(wave_plan && wave_first_request(wp, end - 1) - cb < max_seg)) {
+            int bb = cb;
+            for (int nseg = 1;; ++nseg) {
+                const int e1 = __builtin_amdgcn_readfirstlane(E[bb + 1]);
+                if (e1 >= end) break;                            // the request reaches the end of the range
+                do { ++bb; } while (__builtin_amdgcn_readfirstlane(E[bb + 1]) == __builtin_amdgcn_readfirstlane(E[bb]));   // next request that owns tiles (one exists: e1 < C)
+                if (nseg == max_seg) { ce = e1; nb = bb; break; }
+            }
+        }
+        const int clen = ce - cs;
+        const int r0 = run_start(clen, wave), nk = run_start(clen, wave + 1) - r0;     // this wave's run of the chunk's tiles
+        const int first_b = cb;
+        // the request that holds the chunk's last tile bounds every lane's search below: a chunk rarely spans more than
         // two or three requests, so the search takes one or two steps instead of log2(B)
-        const int search_hi = wave_plan ? wave_first_request(wp, end - 1) + 1 : p.plan.B;
+        const int search_hi = wave_plan ? wave_first_request(wp, ce - 1) + 1 : p.plan.B;
 
-        // ---- this wave's tiles: tile g = wave + 4*slot of the range, slot = 0 .. nk-1.  Lane s of the wave looks up
+        // ---- this wave's tiles: tile r0 + slot of the chunk, slot = 0 .. nk-1.  Lane s of the wave looks up
         // everything about slot s (of the current group of 64 slots) once: the request, the tile's index inside the
         // request and its physical pages.  The tile loop then only picks values out with v_readlane, so neither the
         // block table nor the plan sits between two tiles, also across request boundaries.
-        const int nk = len > wave ? (len - wave + kWaves - 1) / kWaves : 0;
         int4 meta = make_int4(-1, 0, 0, 0);                      // request, tile in request, page of tokens 0-15, 16-31
         auto fetch_meta = [&](int first_slot) {
             const int slot = first_slot + lane;
             meta = make_int4(-1, 0, 0, 0);
             if (slot < nk) {
-                const int pos = start + wave + kWaves * slot;
+                const int pos = cs + r0 + slot;
                 int lo = first_b, hi = search_hi;                // E[lo] <= pos < E[hi]
                 while (hi - lo > 1) {
                     const int mid = (lo + hi) >> 1;
@@ -570,11 +612,30 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             load_q(cur.req, Q);
             issue_v(cur.pg0, cur.pg1);
         }
+        __builtin_amdgcn_sched_barrier(0);       // nothing below may move in front of the first tile's loads
 
-        int b = first_b;
-        int npend = 0;                   // finished segments waiting in ring slots 0 .. npend-1
-        int pend0 = 0, pend1 = 0, pend2 = 0, pend3 = 0;          // their requests
-        while (true) {
+        // where this wave's states go: behind those of the waves before it (one per wave with a run, and one more for
+        // every request that begins inside a run); worked out while the first tile is on its way
+        int wbase = 0;
+        for (int ww = 0; ww < wave; ++ww) wbase += run_start(clen, ww + 1) > run_start(clen, ww) ? 1 : 0;
+        if (wave_plan) {                 // from the plan in registers: the boundaries in front of this wave's run ...
+            const int mine = run_start(clen, wave);
+            wbase += wave_count_ends(wp, cs, cs + mine);
+            for (int ww = 1; ww < wave; ++ww)                    // ... less those a run begins with
+                if (run_start(clen, ww) < mine) wbase -= wave_count_ends(wp, cs + run_start(clen, ww) - 1, cs + run_start(clen, ww) + 1);
+        } else {
+            int bb = cb;
+            while (true) {
+                const int e1 = __builtin_amdgcn_readfirstlane(E[bb + 1]) - cs;   // where the next request begins, in the chunk
+                if (e1 >= clen) break;
+                const int ww = wave_of_tile(clen, e1);
+                if (ww < wave && e1 != run_start(clen, ww)) ++wbase;
+                do { ++bb; } while (__builtin_amdgcn_readfirstlane(E[bb + 1]) == __builtin_amdgcn_readfirstlane(E[bb]));
+            }
+        }
+        int nstate = 0;                  // states this wave has left in shared memory for this chunk
+        while (cur.req >= 0) {           // one pass per request the wave's run touches
+            const int b = cur.req;
             const Segment seg = plan_segment(E, Lc, pl, b, range, start, end);
             // several query tokens: query i of the request's n sits at position L - n + i; a column with no query behind
             // it runs unmasked on zero queries and is dropped when the segment is combined
@@ -634,13 +695,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                 ++s; cur = nxt;
             }
 
-            // ---- end of the segment: the wave leaves its state in LDS and goes on; the workgroup meets to combine
-            // the waiting segments when the ring is full or the range ends
+            // ---- end of the wave's share of this request: it leaves its state in shared memory and goes on
             st.l += __shfl_xor(st.l, 16);                        // per-lane sums of the four lane groups; m is common
             st.l += __shfl_xor(st.l, 32);
-            float *slot = ring + (size_t)npend * slot_floats;
+            float *state = ring + (size_t)(wbase + nstate) * state_floats;
+            ++nstate;
             if (col < Gq) {
-                float *orow = slot + (wave * Gq + col) * (D + 4);
+                float *orow = state + col * (D + 4);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     float4 lo4 = make_float4(st.acc[0][i], st.acc[1][i], st.acc[2][i], st.acc[3][i]);
@@ -649,29 +710,39 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                     *reinterpret_cast<float4 *>(orow + 32 * j + 8 * i + 4) = hi4;
                 }
                 if (j == 0) {
-                    float *sm_m = slot + kWaves * Gq * (D + 4);
-                    sm_m[wave * kMaxGroup + col] = st.m; sm_m[kWaves * kMaxGroup + wave * kMaxGroup + col] = st.l;
+                    float *sm_m = state + Gq * (D + 4);
+                    sm_m[col] = st.m; sm_m[kMaxGroup + col] = st.l;
                 }
             }
-            if (npend == 0) pend0 = b; else if (npend == 1) pend1 = b; else if (npend == 2) pend2 = b; else pend3 = b;
-            ++npend;
-            const bool last = __builtin_amdgcn_readfirstlane(E[b]) + seg.hi >= end;
-            if (last || npend == RING) {
-                lds_barrier();
-#pragma unroll
-                for (int r = 0; r < kMaxRing; ++r) {
-                    if (r < npend) {
-                        const int rb = r == 0 ? pend0 : (r == 1 ? pend1 : (r == 2 ? pend2 : pend3));
-                        const Segment sg = plan_segment(E, Lc, pl, rb, range, start, end);
-                        mfma_combine_segment<D, MT>(ring + (size_t)r * slot_floats, p, sg, kvh, MT ? Nc[rb] : 1);   // nobody waits for its stores
-                    }
-                }
-                lds_barrier();
-                npend = 0;
-            }
-            if (last) break;
-            do { ++b; } while (b < p.plan.B - 1 && E[b + 1] == E[b]);    // skip requests that own no tile
         }
+
+        // ---- the chunk is done: the workgroup meets and combines, request by request, the states that belong to it
+        // (consecutive ones: the runs are in tile order).  Which states a request has depends on the plan alone, so the
+        // first request's are worked out before the meeting and each further one's while the stores of the one before
+        // are on their way.
+        {
+            int bb = cb, at = 0, e1, cnt;
+            Segment sg;
+            auto piece = [&]() {
+                const int e0 = __builtin_amdgcn_readfirstlane(E[bb]);
+                e1 = __builtin_amdgcn_readfirstlane(E[bb + 1]);
+                const int lo = max(e0, cs) - cs, hi = min(e1, ce) - cs;              // the request's tiles in the chunk
+                cnt = wave_of_tile(clen, hi - 1) - wave_of_tile(clen, lo) + 1;
+                sg = plan_segment(E, Lc, pl, bb, range, start, end);
+            };
+            piece();
+            lds_barrier();
+            while (true) {
+                mfma_combine_states<D, MT>(ring + (size_t)at * state_floats, cnt, state_floats, p, sg, kvh, MT ? Nc[bb] : 1);   // nobody waits for its stores
+                at += cnt;
+                if (e1 >= ce) break;
+                do { ++bb; } while (__builtin_amdgcn_readfirstlane(E[bb + 1]) == __builtin_amdgcn_readfirstlane(E[bb]));
+                piece();
+            }
+        }
+        lds_barrier();
+        cs = ce; cb = nb;
+      }
     }
 }
 

@@ -96,16 +96,15 @@ struct omni_handle_s {
         kernel = fp8 ? 2 : ((tune_kernel == 2 && mfma_ok) ? 2 : (tune_kernel == 1 ? 1 : (mfma_ok ? 2 : 1)));
         nw = tune_target_wgs / d.num_kv_heads;
         if (nw < 1) nw = 1;
-        // K goes through the staging area unless that leaves the ring with fewer than three slots where it would have
-        // three or four without (measured: four slots beat staging with two at 8 columns; staging with one slot beats
-        // two slots without at 14 and 16 columns)
         // query tokens one launch takes: as many as fit the 16 columns of a KV head's tiles; more go in several passes
         pass_tokens = tune_query_tokens;
         if (pass_tokens * G > kMaxGroup) pass_tokens = kMaxGroup / G;
         const int Gq = G * pass_tokens;          // columns of a KV head: (query token, head) pairs
         const bool mt = tune_query_tokens > 1;
+        // K goes through the staging area wherever the states' area beside it still holds five states (two requests
+        // per chunk) with two workgroups per compute unit
         const MfmaLds plain = mfma_lds_layout(d.batch, Gq, fp8, false, mt), staged = mfma_lds_layout(d.batch, Gq, fp8, true, mt);
-        k_staged = staged.two_per_cu && (staged.ring_depth >= 3 || plain.ring_depth <= 2);
+        k_staged = staged.two_per_cu && staged.ring_states >= kWaves + 1;
         lds = k_staged ? staged : plain;
         lds_attr_set = false;
         long long ranges = nw;
@@ -518,7 +517,7 @@ omni_status_t omni_debug_last_plan(omni_handle_t h, int32_t host_out[4], void *s
 omni_status_t omni_debug_lds_layout(omni_handle_t h, int32_t host_out[6]) {
     if (!h || !host_out) return OMNI_ERR_NULL;
     if (h->kernel != 2) return OMNI_ERR_UNSUPPORTED;
-    host_out[0] = h->lds.total; host_out[1] = h->lds.static_bytes; host_out[2] = h->lds.ring_depth;
+    host_out[0] = h->lds.total; host_out[1] = h->lds.static_bytes; host_out[2] = h->lds.ring_states;
     host_out[3] = h->k_staged ? 1 : 0; host_out[4] = h->lds.two_per_cu ? 1 : 0; host_out[5] = kMaxDynamicLds;
     return OMNI_OK;
 }

@@ -132,6 +132,7 @@ constexpr int kWavePlanMax = 256;
 
 struct WavePlan {
     int i0, i1, i2, i3;  // tiles up to and including request 4*lane + i (requests beyond the batch own no tile)
+    int owns;            // bit i: request 4*lane + i owns at least one tile
 };
 
 // `zero_row(b)` is called, by all lanes of the wave together, for each request of length <= 0 if `zero_rows`;
@@ -179,6 +180,7 @@ __device__ __forceinline__ Plan plan_build_wave(const int32_t *__restrict__ lens
         if (b < pp.B) { E[b] = incl[i] - c[i]; Lc[b] = L[i]; }
     }
     wp->i0 = incl[0]; wp->i1 = incl[1]; wp->i2 = incl[2]; wp->i3 = incl[3];
+    wp->owns = (c[0] > 0 ? 1 : 0) | (c[1] > 0 ? 2 : 0) | (c[2] > 0 ? 4 : 0) | (c[3] > 0 ? 8 : 0);
     Plan pl;
     pl.C = __builtin_amdgcn_readlane(scan, 63);
     if (lane == 0) E[pp.B] = pl.C;
@@ -195,6 +197,13 @@ __device__ __forceinline__ Plan plan_build_wave(const int32_t *__restrict__ lens
 __device__ __forceinline__ int wave_first_request(const WavePlan &wp, int start) {
     return __popcll(__ballot(wp.i0 <= start)) + __popcll(__ballot(wp.i1 <= start)) +
            __popcll(__ballot(wp.i2 <= start)) + __popcll(__ballot(wp.i3 <= start));
+}
+
+// Requests that own tiles and end strictly between tiles lo and hi of the line (their last tile is p - 1, lo < p < hi):
+// the request boundaries inside the stretch.
+__device__ __forceinline__ int wave_count_ends(const WavePlan &wp, int lo, int hi) {
+    return __popcll(__ballot((wp.owns & 1) && wp.i0 > lo && wp.i0 < hi)) + __popcll(__ballot((wp.owns & 2) && wp.i1 > lo && wp.i1 < hi)) +
+           __popcll(__ballot((wp.owns & 4) && wp.i2 > lo && wp.i2 < hi)) + __popcll(__ballot((wp.owns & 8) && wp.i3 > lo && wp.i3 < hi));
 }
 
 // Request that holds tile `start` (0 <= start < C).  All 256 threads call this; E[] must be complete.

@@ -171,6 +171,22 @@ def test_large_batches(B, G, Hkv, top):
         assert np.all(np.isfinite(got)) and err <= TOL[wl.dtype], f"B {B} kernel {kernel}: {err:.3e}"
 
 
+@pytest.mark.parametrize("B,G,Hkv,tw", [(200, 8, 2, 8), (256, 7, 4, 16), (600, 16, 1, 8), (90, 4, 2, 2)])
+def test_many_requests_per_range(B, G, Hkv, tw):
+    """Few workgroups and many short requests: one range holds far more requests than the kernel keeps states for at a
+    time, below and above the 256 requests up to which every wave plans for itself."""
+    rng = np.random.default_rng(B * 7 + tw)
+    lens = rng.integers(0, 100, size=B)
+    lens[rng.integers(0, B, size=3)] = 700                      # and a few that span several runs of tiles
+    wl = W.build("crowd", 5000 + B, lens, Hq=G * Hkv, Hkv=Hkv, D=128, ps=16, dtype=W.BF16, pool_factor=1.5)
+    ref = oracle_out(wl)
+    for kernel in kernels_for(wl):
+        got = DeviceBatch(wl, tuning={omni.OMNI_TUNE_KERNEL: kernel, omni.OMNI_TUNE_TARGET_WORKGROUPS: tw,
+                                      omni.OMNI_TUNE_MIN_PARTITION: 32}).attend()
+        err = np.max(np.abs(got - ref))
+        assert np.all(np.isfinite(got)) and err <= TOL[wl.dtype], f"B {B} kernel {kernel}: {err:.3e}"
+
+
 def test_large_scores_and_peaked_softmax():
     # keys 6x larger: |scores| reach ~60, the softmax is nearly one-hot; the running-max rescale must hold up
     wl = W.build("peaked", 77, [700, 33, 1500], Hq=14, Hkv=2, D=128, ps=16, dtype=W.BF16)
