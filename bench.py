@@ -30,8 +30,8 @@ HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 # 2.000, WRITE_SIZE by 1.000, the factors a plain 1 GiB copy gives); see profiles/decode_mfma_kernel_<workload>.txt.
 # Not measured by this script; valid only for the launch plan of the counter run, so the key holds that plan:
 # (workload, seed, range length in tokens, ranges, workgroups) -> bytes.  Anything else reports null.
-MEASURED_TRAFFIC_BYTES = {("thinker", 1, 1152, 126, 512): 300.2e6, ("talker", 2, 608, 254, 512): 162.8e6,
-                          ("long", 3, 1536, 126, 512): 397.0e6, ("mixed", 4, 3104, 64, 512): 813.0e6}
+MEASURED_TRAFFIC_BYTES = {("thinker", 1, 1152, 126, 512): 300.2e6, ("talker", 2, 608, 254, 512): 162.6e6,
+                          ("long", 3, 1536, 126, 512): 397.1e6, ("mixed", 4, 3104, 64, 512): 812.9e6}
 KERNEL_EVENT_LAUNCHES = 48      # launches of the attention kernel that carry an event pair (untimed loop)
 STEADY_STEPS = 300              # steps of the steady-state loop reported beside the --steps figure
 OTHER_STEPS = 200               # timed steps for each of the other workloads
