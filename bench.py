@@ -12,7 +12,8 @@ Prints ONE JSON line: metric/value (tokens/s = requests decoded per second, one 
 exactly --steps timed steps with nothing else in the stream; the roofline of the dominant kernel (algorithmic KV bytes
 per launch / its average duration over at least 32 launches, each with a HIP event pair in its own dispatch, in an
 untimed loop after the timed region) with the whole-step fraction beside it; the same figures for the other three
-stage-shaped batches (extra.other_workloads); and the fp64 CPU oracle timed on this machine's host cores.
+stage-shaped batches and for the thinker and talker shapes at four times the batch (extra.other_workloads); and the
+fp64 CPU oracle timed on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -35,6 +36,7 @@ MEASURED_TRAFFIC_BYTES = {("thinker", 1, 1152, 126, 512): 300.2e6, ("talker", 2,
 KERNEL_EVENT_LAUNCHES = 48      # launches of the attention kernel that carry an event pair (untimed loop)
 STEADY_STEPS = 300              # steps of the steady-state loop reported beside the --steps figure
 OTHER_STEPS = 200               # timed steps for each of the other workloads
+LARGER_BATCHES = (("thinker", 256), ("talker", 1024))   # also measured: the two stage shapes at four times the batch
 
 
 def parse():
@@ -176,10 +178,11 @@ def traffic_for(wl, plan):
     return MEASURED_TRAFFIC_BYTES.get((wl.name, wl.seed, plan["partition_len"], plan["request_parts"], plan["partition_grid"]))
 
 
-def measure_other(name, args, torch, np, omni, W, oracle):
+def measure_other(name, args, torch, np, omni, W, oracle, batch=None):
     """One of the other stage-shaped batches through the same step, default tuning: step time over OTHER_STEPS timed
-    steps, the attention kernel over KERNEL_EVENT_LAUNCHES event-carrying launches, the stream-read ceiling."""
-    wl = W.make(name, append=True)
+    steps, the attention kernel over KERNEL_EVENT_LAUNCHES event-carrying launches, the stream-read ceiling.
+    `batch`: the same shape and length distribution with that many requests."""
+    wl = W.make(name, append=True, batch=batch)
     d = DecodeSetup(wl, args, torch, np, omni, W, tuned=False)
     for i in range(10):
         d.step_fused(i)
@@ -496,6 +499,11 @@ def main():
                 log(f"other workload: {name}")
                 others[name] = measure_other(name, args, torch, np, omni, W, oracle)
                 torch.cuda.empty_cache()
+        # the same shapes with four times the requests (what a fuller engine would hand over per step)
+        for name, batch in LARGER_BATCHES:
+            log(f"larger batch: {name} x {batch}")
+            others[f"{name}_batch_{batch}"] = measure_other(name, args, torch, np, omni, W, oracle, batch=batch)
+            torch.cuda.empty_cache()
 
     # ---- CPU baseline: the oracle as it stands, all host threads, whole batch, one warm-up slice then timed passes
     cpu = None

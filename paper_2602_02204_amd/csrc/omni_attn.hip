@@ -53,7 +53,7 @@ struct omni_handle_s {
     int max_ctx = 0;
     int nw = 1;                  // workgroups per KV head
     int r_cap = 0;               // bound on partial-result slots (range index + request index)
-    size_t off_ml = 0, off_o = 0, ws_bytes = 0;
+    size_t off_ml = 0, off_o = 0, off_e = 0, ws_bytes = 0;
     MfmaLds lds{};               // shared-memory layout of the matrix-core kernel
     bool k_staged = true;        // K tiles through shared memory (matrix-core kernel)
     bool lds_attr_set = false;   // the kernel has been told how much dynamic shared memory it may get
@@ -119,7 +119,8 @@ struct omni_handle_s {
         const size_t rows = (size_t)r_cap * d.num_q_heads * pass_tokens;             // partial-result rows
         off_ml = 256;
         off_o = align256(off_ml + rows * sizeof(float2));
-        ws_bytes = align256(off_o + rows * d.head_dim * sizeof(float));
+        off_e = align256(off_o + rows * d.head_dim * sizeof(float));
+        ws_bytes = d.batch > kWavePlanMax ? align256(off_e + ((size_t)d.batch + 1) * sizeof(int32_t)) : off_e;   // tile offsets for the merge kernel
     }
 };
 
@@ -313,6 +314,7 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.ws.plan_words = reinterpret_cast<int32_t *>(ws);
     p.ws.part_ml = reinterpret_cast<float2 *>(ws + h->off_ml);
     p.ws.part_o = reinterpret_cast<float *>(ws + h->off_o);
+    p.ws.tile_off = reinterpret_cast<int32_t *>(ws + h->off_e);
     p.plan.B = d.batch;
     p.plan.nw = h->nw;
     p.plan.s_min = h->tune_min_partition / kTile;

@@ -62,6 +62,16 @@ struct Plan {
     int nranges;
 };
 
+// The cut of a line of C tiles into ranges.
+__device__ __forceinline__ Plan plan_cut(const PlanParams &pp, int C) {
+    Plan pl;
+    pl.C = C;
+    const int S = pp.s_force > 0 ? pp.s_force : max(pp.s_min, ceil_div(C, pp.nw));
+    pl.S = max(S, 1);
+    pl.nranges = ceil_div(C, pl.S);
+    return pl;
+}
+
 // Inclusive scan over the 256 threads of the workgroup (two shared-memory barriers).
 __device__ __forceinline__ int block_inclusive_scan(int v, PlanSmem *ps, int *total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -116,12 +126,7 @@ __device__ __forceinline__ Plan plan_build(const int32_t *__restrict__ lens, con
     for (int off = 32; off > 0; off >>= 1) tokens += __shfl_xor(tokens, off);
     if ((threadIdx.x & 63) == 0 && tokens) atomicAdd(&ps->total_tokens, tokens);
     lds_barrier();
-    Plan pl;
-    pl.C = __builtin_amdgcn_readfirstlane(carry);
-    int S = pp.s_force > 0 ? pp.s_force : max(pp.s_min, ceil_div(pl.C, pp.nw));
-    pl.S = max(S, 1);
-    pl.nranges = ceil_div(pl.C, pl.S);
-    return pl;
+    return plan_cut(pp, __builtin_amdgcn_readfirstlane(carry));
 }
 
 // ---- Plan without workgroup barriers, for batches of up to kWavePlanMax requests.
@@ -181,16 +186,12 @@ __device__ __forceinline__ Plan plan_build_wave(const int32_t *__restrict__ lens
     }
     wp->i0 = incl[0]; wp->i1 = incl[1]; wp->i2 = incl[2]; wp->i3 = incl[3];
     wp->owns = (c[0] > 0 ? 1 : 0) | (c[1] > 0 ? 2 : 0) | (c[2] > 0 ? 4 : 0) | (c[3] > 0 ? 8 : 0);
-    Plan pl;
-    pl.C = __builtin_amdgcn_readlane(scan, 63);
-    if (lane == 0) E[pp.B] = pl.C;
+    const int C = __builtin_amdgcn_readlane(scan, 63);
+    if (lane == 0) E[pp.B] = C;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) tokens += __shfl_xor(tokens, off);
     total_tokens = tokens;
-    int S = pp.s_force > 0 ? pp.s_force : max(pp.s_min, ceil_div(pl.C, pp.nw));
-    pl.S = max(S, 1);
-    pl.nranges = ceil_div(pl.C, pl.S);
-    return pl;
+    return plan_cut(pp, C);
 }
 
 // Request that holds tile `start` (0 <= start < C): the number of requests that end at or before it.
