@@ -46,10 +46,8 @@ __device__ __forceinline__ void merge_request(const AttnParams &p, int b, int kv
             }
         }
         const bool live = den > 0.f;
-        store_out(p, out0 + 0, live ? num.x / den : 0.f);
-        store_out(p, out0 + 1, live ? num.y / den : 0.f);
-        store_out(p, out0 + 2, live ? num.z / den : 0.f);
-        store_out(p, out0 + 3, live ? num.w / den : 0.f);
+        store_out4(p, out0, make_float4(live ? num.x / den : 0.f, live ? num.y / den : 0.f, live ? num.z / den : 0.f,
+                                        live ? num.w / den : 0.f));
     }
 }
 

@@ -114,6 +114,17 @@ __device__ __forceinline__ void store_out(const AttnParams &p, size_t index, flo
     if (p.out_bf16) reinterpret_cast<uint16_t *>(p.out)[index] = float_to_bf16_rne(v);
     else reinterpret_cast<float *>(p.out)[index] = v;
 }
+// Four consecutive output elements in one store (index a multiple of four).
+__device__ __forceinline__ void store_out4(const AttnParams &p, size_t index, const float4 &r) {
+    if (p.out_bf16) {
+        uint2 pk;
+        pk.x = (uint32_t)float_to_bf16_rne(r.x) | ((uint32_t)float_to_bf16_rne(r.y) << 16);
+        pk.y = (uint32_t)float_to_bf16_rne(r.z) | ((uint32_t)float_to_bf16_rne(r.w) << 16);
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(p.out) + index) = pk;
+    } else {
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.out) + index) = r;
+    }
+}
 
 // One element of a finished segment: the normalised output if the request lies inside one range, else the
 // unnormalised value (plus, once per head, the running max and sum) into the segment's partial-result slot.  The

@@ -380,16 +380,8 @@ __device__ __forceinline__ void mfma_combine_states(const float *first, int cnt,
         if (seg.nparts == 1) {
             const size_t o0 = (MT ? out_row(p, seg.b, kvh, g) : (size_t)seg.b * p.Hq + kvh * G + g) * D + d;
             const bool live = den > 0.f;
-            const float4 r = make_float4(live ? num.x / den : 0.f, live ? num.y / den : 0.f, live ? num.z / den : 0.f,
-                                         live ? num.w / den : 0.f);
-            if (p.out_bf16) {
-                uint2 pk;
-                pk.x = (uint32_t)float_to_bf16_rne(r.x) | ((uint32_t)float_to_bf16_rne(r.y) << 16);
-                pk.y = (uint32_t)float_to_bf16_rne(r.z) | ((uint32_t)float_to_bf16_rne(r.w) << 16);
-                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(p.out) + o0) = pk;
-            } else {
-                *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.out) + o0) = r;
-            }
+            store_out4(p, o0, make_float4(live ? num.x / den : 0.f, live ? num.y / den : 0.f, live ? num.z / den : 0.f,
+                                          live ? num.w / den : 0.f));
         } else {
             const size_t pi = MT ? partial_row(p, seg.slot, kvh, g) : (size_t)seg.slot * p.Hq + kvh * G + g;
             *reinterpret_cast<float4 *>(p.ws.part_o + pi * D + d) = num;
