@@ -39,6 +39,25 @@ def test_static_scratch_matches_the_workspace_call_twice_in_a_row(kernel):
         assert np.array_equal(got, want)                    # same kernels, same plan: the same bits
 
 
+def test_static_scratch_holds_a_large_batch():
+    """Above 256 requests the attention kernel leaves the tile offsets for the merge kernel in the workspace: here in
+    the static array, twice in a row with different lengths."""
+    for seed in (1, 2):
+        rng = np.random.default_rng(40 + seed)
+        lens = rng.integers(0, 200, size=300)
+        wl = W.build("crowd", 7000 + seed, lens, Hq=8, Hkv=2, D=128, ps=16, dtype=W.BF16, pool_factor=1.2)
+        dev = DeviceBatch(wl)
+        want = dev.attend()
+        ref = oracle.paged_decode_attn(wl.q, wl.k_cache, wl.v_cache, wl.block_table, wl.context_lens, wl.scale, wl.dtype)
+        bare = omni.Handle(batch=wl.B, num_q_heads=wl.Hq, num_kv_heads=wl.Hkv, head_dim=wl.D, page_size=wl.ps,
+                           num_pages=wl.P, max_blocks_per_seq=wl.MB, kv_dtype=omni.OMNI_BF16)
+        assert bare.omni_workspace_bytes() <= (8 << 20)
+        dev.h = bare
+        got = static_call(dev)
+        assert np.max(np.abs(got - ref)) <= TOL[wl.dtype]
+        assert np.array_equal(got, want)
+
+
 def test_static_scratch_rejects_what_does_not_fit():
     h = omni.Handle(batch=4096, num_q_heads=64, num_kv_heads=4, head_dim=128, page_size=16, num_pages=4096,
                     max_blocks_per_seq=4, kv_dtype=omni.OMNI_BF16)
