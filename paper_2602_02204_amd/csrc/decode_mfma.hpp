@@ -550,11 +550,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             si.pg0 = __builtin_amdgcn_readlane(meta.z, l); si.pg1 = __builtin_amdgcn_readlane(meta.w, l);
             return si;
         };
-        // Fused decode step: the tile that holds the request's last token gets the new K/V row written into its page
-        // (a bit copy, the first lanes the K row, the next ones the V row, 16 bytes each) before the tile is requested; the wave waits for
-        // the write to be acknowledged, so the loads that follow see it.
-        // With several query tokens per request the new rows are [B, T, Hkv, D] and each tile takes those of the
-        // request's last T positions that fall into it.
+        // Fused decode step, with several query tokens per request or K loaded straight into registers: the tile that
+        // holds the request's last token gets the new K/V row written into its page (a bit copy, the first lanes the K
+        // row, the next ones the V row, 16 bytes each) before the tile is requested; the wave waits for the write to be
+        // acknowledged, so the loads that follow see it.  With several query tokens per request the new rows are
+        // [B, T, Hkv, D] and each tile takes those of the request's last T positions that fall into it.
         auto append_row = [&](const SlotInfo &si) {
             constexpr int kRowPieces = D * ES / 16;              // 16-byte pieces of a row: 16 (16-bit cache) or 8
             const int L = Lc[si.req];
@@ -576,6 +576,29 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_s_waitcnt(0);           // all counters: the row is in memory before the tile is read
+        };
+        // One query token per request and K staged: no wait at all.  The new rows are asked for together with the
+        // tile's loads (every lane one 16-byte piece of each); when the tile has arrived the K row is written over its
+        // place in the staging area, the V row over the registers of the lanes that hold that token, and both go to
+        // their page with stores nobody waits for: within this launch only this wave reads that row of that KV head.
+        constexpr bool kPatchAppend = KST && !MT;
+        constexpr int kRowPieces = D * ES / 16;                  // 16-byte pieces of a row: 16 (16-bit cache) or 8
+        int patch_row = -1;                                      // the new token's place in the tile in flight, or none
+        size_t patch_dst = 0;                                    // byte offset of its row behind kbase / vbase
+        uint4 Kn = make_uint4(0, 0, 0, 0), Vn = make_uint4(0, 0, 0, 0);
+        auto request_new_row = [&](const SlotInfo &si) {
+            const int pos = __builtin_amdgcn_readfirstlane(Lc[si.req]) - 1;
+            patch_row = pos - si.tile * kTile;
+            const int pg = (PS == 16 && (pos & 16)) ? si.pg1 : si.pg0;
+            patch_dst = (size_t)pg * ld.page_stride + (size_t)(pos & (PS - 1)) * (D * ES);
+            const size_t src = ((size_t)si.req * p.Hkv + kvh) * (D * ES);
+            Kn = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(p.k_new) + src + (lane & (kRowPieces - 1)) * 16);
+            if constexpr (KV8) {                                 // a lane's V piece is 8 bytes there: dims 8 col ..
+                const uint2 v8 = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(p.v_new) + src + col * 8);
+                Vn.x = v8.x; Vn.y = v8.y;
+            } else {
+                Vn = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(p.v_new) + src + col * 16);
+            }
         };
 
         // Software pipeline of one wave (single K and V buffers): the K rows of the next tile are requested as soon
@@ -599,7 +622,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         int s = 0;                       // slot being computed; its loads are in flight
         SlotInfo cur = slot_info(0);
         if (cur.req >= 0) {
-            if (cur.append) append_row(cur);
+            if (cur.append) { if constexpr (kPatchAppend) request_new_row(cur); else append_row(cur); }
             issue_k(cur.pg0, cur.pg1);
             load_q(cur.req, Q);
             issue_v(cur.pg0, cur.pg1);
@@ -650,11 +673,33 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
                     // the compiler would turn any wait for an older load into one for all loads while a copy into
                     // shared memory is in flight.
                     __builtin_amdgcn_s_waitcnt(0x0f70);
+                    if constexpr (kPatchAppend) {
+                        if (patch_row >= 0) {                    // this tile holds its request's new token (uniform)
+                            const int blk = patch_row >> 4, row = patch_row & 15;
+                            if (lane < kRowPieces) {             // piece `lane` of the K row: staging area, and its page
+                                *reinterpret_cast<uint4 *>(kstage + blk * (kRowPieces * 256) + row * (D * ES) +
+                                                           (((lane ^ row) & (kRowPieces - 1)) << 4)) = Kn;
+                                *reinterpret_cast<uint4 *>(const_cast<char *>(ld.kbase) + patch_dst + lane * 16) = Kn;
+                            }
+                            if (lane < 16) {                     // piece `lane` of the V row to its page
+                                char *vdst = const_cast<char *>(ld.vbase) + patch_dst;
+                                if constexpr (KV8) *reinterpret_cast<uint2 *>(vdst + lane * 8) = make_uint2(Vn.x, Vn.y);
+                                else *reinterpret_cast<uint4 *>(vdst + lane * 16) = Vn;
+                            }
+#pragma unroll
+                            for (int r = 0; r < 8; ++r) {        // the lane group that holds the token takes the new V
+                                if (slot_token(j, r) == patch_row) {
+                                    if constexpr (KV8) Vr[r] = make_uint2(Vn.x, Vn.y); else V[r] = Vn;
+                                }
+                            }
+                            patch_row = -1;
+                        }
+                    }
                     ks_cur[0] = ks[0]; ks_cur[1] = ks[1];
                     if constexpr (KV8) ld8.read_k_staged(kstage, Kr); else ld.read_k_staged(kstage, K);
                     __builtin_amdgcn_s_waitcnt(0xc07f);          // operands are in registers (lgkmcnt = 0) ...
                     if (more) {                                  // ... so the next tile may take their place
-                        if (nxt.append) append_row(nxt);
+                        if (nxt.append) { if constexpr (kPatchAppend) request_new_row(nxt); else append_row(nxt); }
                         issue_k(nxt.pg0, nxt.pg1);
                     }
                     if constexpr (KV8) mfma_scores_fp8(Kr, Q, sv, p.scale_log2, ks_cur);
