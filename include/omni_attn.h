@@ -211,9 +211,10 @@ omni_status_t omni_kv_append(omni_handle_t h,
  * forward step over the whole batch per iteration; Section 2.2: the AR decoding loop adds one token per request):
  * exactly omni_kv_append with
  * positions[b] = context_lens[b] - 1 (requests of length 0 are skipped) followed by omni_paged_decode_attn, but with
- * the append fused into the attention kernel where the hardware path allows it (bf16, head_dim 128): the workgroup
- * that will read a request's last tile first writes the new K/V row into that page.  Same results, bit for bit, as
- * the two separate calls.
+ * the append fused into the attention kernel where the hardware path allows it (bf16, head_dim 128): the wave that
+ * reads a request's last tile takes the new K/V row from k_new / v_new in place of that row of the page and writes it
+ * into the page.  Same results, bit for bit, as the two separate calls; k_cache / v_cache hold the new rows when the
+ * call has completed in stream order.
  * Errors: NULL, WORKSPACE, HIP.
  */
 omni_status_t omni_decode_step(omni_handle_t h,
