@@ -102,6 +102,10 @@ class DecodeSetup:
         self.h.omni_kv_append(self.k_new, self.v_new, self.kc[r], self.vc[r], self.bt, self.pos, self.stream)
         self.h.omni_paged_decode_attn(self.q, self.kc[r], self.vc[r], self.bt, self.lens, self.scale, self.out, self.stream)
 
+    def attention_only(self, i):
+        r = i % self.R
+        self.h.omni_paged_decode_attn(self.q, self.kc[r], self.vc[r], self.bt, self.lens, self.scale, self.out, self.stream)
+
     def step_fused(self, i):
         r = i % self.R
         self.h.omni_decode_step(self.q, self.k_new, self.v_new, self.kc[r], self.vc[r], self.bt, self.lens, self.scale,
@@ -253,10 +257,12 @@ def main():
         return dec.timed(fn, steps or K, fixed_replica)
 
     # ---- for the record: a longer steady-state loop, the same K steps as two launches, and on a single replica
-    ms_steady = ms_other = ms_warm = ms_graph = host_us_graph = host_us_eager = None
+    ms_steady = ms_other = ms_warm = ms_graph = host_us_graph = host_us_eager = ms_attn = None
     if not args.timed_only:
         ms_steady = timed(step, steps=max(K, STEADY_STEPS))
         ms_other = timed(step_fused if args.unfused else step_two_launches)
+        # one omni_paged_decode_attn call (attention + merge; every token already in the pools): no append in it
+        ms_attn = timed(dec.attention_only, steps=max(K, STEADY_STEPS))
         ms_warm = timed(step, fixed_replica=True)
         # the same steps recorded once as a HIP graph (one step per pool replica) and replayed: what is left of the
         # step time when the host issues one call per R steps instead of one per kernel
@@ -573,6 +579,8 @@ def main():
                   "kernel_resources": resources,
                   "other_workloads": others,
                   ("ms_per_step_fused" if args.unfused else "ms_per_step_separate_append"): ms_other,
+                  "ms_per_call_attention_only": ms_attn,
+                  "frac_per_call_attention_only": kv_bytes / (ms_attn * 1e-3) / 1e9 / HBM_PEAK_GBS if ms_attn else None,
                   "ms_per_step_single_replica_cache_warm": ms_warm,
                   "ms_per_step_replayed_as_hip_graph": ms_graph,
                   "host_us_to_issue_a_step_eager": host_us_eager, "host_us_to_issue_a_step_in_graph": host_us_graph,
