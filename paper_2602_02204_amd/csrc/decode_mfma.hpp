@@ -555,8 +555,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         // row, the next ones the V row, 16 bytes each) before the tile is requested; the wave waits for the write to be
         // acknowledged, so the loads that follow see it.  With several query tokens per request the new rows are
         // [B, T, Hkv, D] and each tile takes those of the request's last T positions that fall into it.
+        constexpr int kRowPieces = D * ES / 16;                  // 16-byte pieces of a row: 16 (16-bit cache) or 8
         auto append_row = [&](const SlotInfo &si) {
-            constexpr int kRowPieces = D * ES / 16;              // 16-byte pieces of a row: 16 (16-bit cache) or 8
             const int L = Lc[si.req];
             const int n_new = MT ? Nc[si.req] : 1;               // rows 0 .. n_new - 1 of the request's new rows
 #pragma unroll 1
@@ -582,7 +582,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         // place in the staging area, the V row over the registers of the lanes that hold that token, and both go to
         // their page with stores nobody waits for: within this launch only this wave reads that row of that KV head.
         constexpr bool kPatchAppend = KST && !MT;
-        constexpr int kRowPieces = D * ES / 16;                  // 16-byte pieces of a row: 16 (16-bit cache) or 8
         int patch_row = -1;                                      // the new token's place in the tile in flight, or none
         size_t patch_dst = 0;                                    // byte offset of its row behind kbase / vbase
         uint4 Kn = make_uint4(0, 0, 0, 0), Vn = make_uint4(0, 0, 0, 0);
