@@ -255,6 +255,36 @@ def test_decode_step_equals_append_then_attention(name, kw, kernel, force_pl):
     assert np.max(np.abs(out_one - oracle_out(wl))) <= TOL[wl.dtype]
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_decode_step_random_shapes(seed):
+    """The fused step on random batches whose lengths sit on and around tile and page boundaries (the new token first
+    or last of a page, of a 32-token tile, alone in its request), any group size and page size, few and many
+    workgroups: the pools come out as the oracle's append leaves them, bit for bit, and the output is the attention
+    over them."""
+    rng = np.random.default_rng(800 + seed)
+    B = int(rng.integers(1, 48))
+    G = int(rng.choice([1, 2, 4, 7, 8, 16]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    ps = int(rng.choice([16, 32]))
+    base = rng.integers(0, 12, size=B) * 32
+    lens = np.maximum(base + rng.choice([0, 1, 2, 15, 16, 17, 31, 32, 33], size=B), 0)
+    lens[rng.integers(0, B)] = 0
+    wl = W.build("step", 6000 + seed, lens, Hq=G * Hkv, Hkv=Hkv, D=128, ps=ps, dtype=W.BF16, pool_factor=1.5, append=True)
+    tuning = {omni.OMNI_TUNE_TARGET_WORKGROUPS: int(rng.choice([16, 128, 512])), omni.OMNI_TUNE_MIN_PARTITION: 32}
+    one = DeviceBatch(wl, tuning=tuning)
+    one.out.fill_(float("nan"))
+    one.h.omni_decode_step(one.q, one.k_new, one.v_new, one.k_cache, one.v_cache, one.block_table, one.context_lens,
+                           float(wl.scale), one.out)
+    torch.cuda.synchronize()
+    got = one.out.float().cpu().numpy().astype(np.float64)
+    oracle.kv_append(wl.k_new, wl.v_new, wl.k_cache, wl.v_cache, wl.block_table, wl.positions, wl.dtype)
+    as_bytes = lambda a: a.view(np.uint8)
+    assert np.array_equal(as_bytes(bits_of(one.k_cache)), as_bytes(wl.k_cache))
+    assert np.array_equal(as_bytes(bits_of(one.v_cache)), as_bytes(wl.v_cache))
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got - oracle_out(wl))) <= TOL[wl.dtype], (seed, B, G, Hkv, ps)
+
+
 @pytest.mark.parametrize("kernel", [omni.KERNEL_MFMA, omni.KERNEL_VALU], ids=["mfma", "valu"])
 def test_bit_identical_rerun_and_page_permutation(kernel):
     wl = W.make("thinker", batch=6)
