@@ -20,7 +20,7 @@ struct Workspace {
     int32_t *plan_words;
     float2 *part_ml;
     float *part_o;
-    int32_t *tile_off;                  // batches above kWavePlanMax requests: E[0 .. B], left for the merge kernel
+    int32_t *tile_off;                  // E[0 .. B], left by the attention kernel for the merge kernel
 };
 
 // Shared memory of the matrix-core kernel behind the plan's arrays: room for `ring_states` online-softmax states, each
@@ -221,9 +221,9 @@ __device__ __forceinline__ Plan attn_prologue(const AttnParams &p, PlanSmem *ps,
         p.ws.plan_words[0] = pl.S * kTile; p.ws.plan_words[1] = pl.nranges;
         p.ws.plan_words[2] = (int)(T & 0xffffffffULL); p.ws.plan_words[3] = (int)(T >> 32);
     }
-    // a large batch: the merge kernel's workgroups (one per request and KV head) take the tile offsets from here
-    // instead of scanning all the lengths again, each of them
-    if (blockIdx.x == 0 && p.plan.B > kWavePlanMax)
+    // the merge kernel's workgroups (one per request and KV head) take the tile offsets from here instead of
+    // scanning all the lengths again, each of them
+    if (blockIdx.x == 0)
         for (int b = threadIdx.x; b <= p.plan.B; b += kThreads) p.ws.tile_off[b] = E[b];
     return pl;
 }

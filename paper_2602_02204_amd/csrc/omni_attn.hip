@@ -120,7 +120,7 @@ struct omni_handle_s {
         off_ml = 256;
         off_o = align256(off_ml + rows * sizeof(float2));
         off_e = align256(off_o + rows * d.head_dim * sizeof(float));
-        ws_bytes = d.batch > kWavePlanMax ? align256(off_e + ((size_t)d.batch + 1) * sizeof(int32_t)) : off_e;   // tile offsets for the merge kernel
+        ws_bytes = align256(off_e + ((size_t)d.batch + 1) * sizeof(int32_t));     // tile offsets for the merge kernel
     }
 };
 
@@ -377,8 +377,8 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
         // Whether any request was cut by a range boundary is known only on the device: the merge kernel always runs, and
         // its workgroups return at once for requests that the attention kernel finished.
         const dim3 mgrid((unsigned)(d.batch * d.num_kv_heads));
-        if (d.head_dim == 128) merge_kernel<128><<<mgrid, kThreads, dyn, s>>>(p);
-        else merge_kernel<64><<<mgrid, kThreads, dyn, s>>>(p);
+        if (d.head_dim == 128) merge_kernel<128><<<mgrid, kThreads, 0, s>>>(p);
+        else merge_kernel<64><<<mgrid, kThreads, 0, s>>>(p);
         if (hipGetLastError() != hipSuccess) return OMNI_ERR_HIP;
     }
 
@@ -534,7 +534,7 @@ omni_status_t omni_debug_kernel_resources(omni_handle_t h, int32_t which, int32_
         dyn = h->lds.total;
     } else if (which == 1) {
         fn = h->d.head_dim == 128 ? (const void *)&merge_kernel<128> : (const void *)&merge_kernel<64>;
-        dyn = (int)((2 * h->d.batch + 1) * sizeof(int));
+        dyn = 0;
     } else {
         return OMNI_ERR_SHAPE;
     }
