@@ -5,9 +5,9 @@
 namespace omni {
 
 // Merge kernel: one workgroup per (request, KV head), launched right after the attention kernel.  It takes the
-// request's tile offsets and the total from the array the attention kernel's first workgroup left in the workspace
-// (one trip; scanning the lengths again in every workgroup cost 0.5 us at 256 requests and 10 - 28 us at 1024 - 2048)
-// and cuts the line with the same function the attention kernel used; for a request that was cut
+// request's first slot and number of pieces from the records the attention kernel's first workgroup left in the
+// workspace (one 8-byte read; scanning the lengths again in every workgroup and dividing by the range length cost
+// 0.5 us more at 256 requests and 10 - 28 us at 1024 - 2048); for a request that was cut
 // by range boundaries combines its partial-result slots, in slot order:
 //     out = sum_j 2^(m_j - M) o_j / sum_j 2^(m_j - M) l_j,   M = max_j m_j,   pieces with l_j = 0 skipped.
 // Requests inside one range (finished by the attention kernel) and empty requests return at once.
@@ -54,17 +54,14 @@ __device__ __forceinline__ void merge_request(const AttnParams &p, int b, int kv
 template <int D>
 __global__ __launch_bounds__(kThreads) void merge_kernel(AttnParams p) {
     const int b = blockIdx.x / p.Hkv, kvh = blockIdx.x - b * p.Hkv;
-    // the attention kernel has left the tile offsets E[0 .. B] behind: this request's tiles and the total
-    const int e0 = p.ws.tile_off[b], e1 = p.ws.tile_off[b + 1];
-    const Plan pl = plan_cut(p.plan, p.ws.tile_off[p.plan.B]);
-    if (e1 == e0) return;                                    // empty request: its zero row is already written
-    const int first_range = e0 / pl.S, last_range = (e1 - 1) / pl.S;
-    const int n = last_range - first_range + 1;
-    if (n == 1) return;                                      // finished by the attention kernel
+    const int2 rec = p.ws.merge_rec[b];                      // first slot and number of pieces, from the attention kernel
+    const int n = __builtin_amdgcn_readfirstlane(rec.y);
+    if (n < 2) return;                                       // no tile (its zero row is written) or finished already
+    const int slot_first = __builtin_amdgcn_readfirstlane(rec.x);
     // 4, 8 or 16 pieces per round, so that a request cut into many pieces still costs few dependent trips to memory
-    if (n <= 4) merge_request<D, 4>(p, b, kvh, first_range + b, n);
-    else if (n <= 8) merge_request<D, 8>(p, b, kvh, first_range + b, n);
-    else merge_request<D, 16>(p, b, kvh, first_range + b, n);
+    if (n <= 4) merge_request<D, 4>(p, b, kvh, slot_first, n);
+    else if (n <= 8) merge_request<D, 8>(p, b, kvh, slot_first, n);
+    else merge_request<D, 16>(p, b, kvh, slot_first, n);
 }
 
 struct AppendParams {

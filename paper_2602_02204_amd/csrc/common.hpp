@@ -20,7 +20,8 @@ struct Workspace {
     int32_t *plan_words;
     float2 *part_ml;
     float *part_o;
-    int32_t *tile_off;                  // E[0 .. B], left by the attention kernel for the merge kernel
+    int2 *merge_rec;                    // [B]: (first partial-result slot, pieces) of every request, left by the
+                                        // attention kernel for the merge kernel
 };
 
 // Shared memory of the matrix-core kernel behind the plan's arrays: room for `ring_states` online-softmax states, each
@@ -221,11 +222,19 @@ __device__ __forceinline__ Plan attn_prologue(const AttnParams &p, PlanSmem *ps,
         p.ws.plan_words[0] = pl.S * kTile; p.ws.plan_words[1] = pl.nranges;
         p.ws.plan_words[2] = (int)(T & 0xffffffffULL); p.ws.plan_words[3] = (int)(T >> 32);
     }
-    // the merge kernel's workgroups (one per request and KV head) take the tile offsets from here instead of
-    // scanning all the lengths again, each of them
-    if (blockIdx.x == 0)
-        for (int b = threadIdx.x; b <= p.plan.B; b += kThreads) p.ws.tile_off[b] = E[b];
     return pl;
+}
+
+// What the merge kernel needs to know of every request: its first partial-result slot and the number of ranges that
+// touch it (0: no tile, 1: finished by the attention kernel).  Written by the grid's first workgroup when its own
+// work is done (all 256 threads call this; E[] is the plan's array in shared memory), so that the merge kernel's
+// workgroups, one per request and KV head, neither scan the lengths nor divide: one 8-byte read each.
+__device__ __forceinline__ void write_merge_records(const AttnParams &p, const Plan &pl, const int *E) {
+    for (int b = threadIdx.x; b < p.plan.B; b += kThreads) {
+        const int e0 = E[b], e1 = E[b + 1];
+        const int first_range = e0 / pl.S;
+        p.ws.merge_rec[b] = make_int2(first_range + b, e1 > e0 ? (e1 - 1) / pl.S - first_range + 1 : 0);
+    }
 }
 
 // Drive `process(seg)` over every segment of every range of workgroup w, finishing each with the combine above.
@@ -243,6 +252,7 @@ __device__ __forceinline__ void for_each_segment(const AttnParams &p, const Plan
             do { ++b; } while (b < p.plan.B - 1 && E[b + 1] == E[b]);       // skip requests that own no tile
         }
     }
+    if (blockIdx.x == 0) write_merge_records(p, pl, E);
 }
 
 }  // namespace omni

@@ -470,8 +470,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
             p.ws.plan_words[0] = pl.S * kTile; p.ws.plan_words[1] = pl.nranges;
             p.ws.plan_words[2] = (int)(T & 0xffffffffULL); p.ws.plan_words[3] = (int)(T >> 32);
         }
-        if (first)                                               // the tile offsets, for the merge kernel
-            for (int b = lane; b <= p.plan.B; b += 64) p.ws.tile_off[b] = E[b];
     } else {
         pl = attn_prologue<D>(p, &ps, E, w, kvh);
     }
@@ -782,6 +780,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(AttnParams p) 
         cs = ce; cb = nb;
       }
     }
+    if (blockIdx.x == 0) write_merge_records(p, pl, E);
 }
 
 }  // namespace omni

@@ -120,7 +120,7 @@ struct omni_handle_s {
         off_ml = 256;
         off_o = align256(off_ml + rows * sizeof(float2));
         off_e = align256(off_o + rows * d.head_dim * sizeof(float));
-        ws_bytes = align256(off_e + ((size_t)d.batch + 1) * sizeof(int32_t));     // tile offsets for the merge kernel
+        ws_bytes = align256(off_e + (size_t)d.batch * sizeof(int2));              // the merge kernel's records
     }
 };
 
@@ -314,7 +314,7 @@ static omni_status_t launch_attention(omni_handle_t h, const void *q, const void
     p.ws.plan_words = reinterpret_cast<int32_t *>(ws);
     p.ws.part_ml = reinterpret_cast<float2 *>(ws + h->off_ml);
     p.ws.part_o = reinterpret_cast<float *>(ws + h->off_o);
-    p.ws.tile_off = reinterpret_cast<int32_t *>(ws + h->off_e);
+    p.ws.merge_rec = reinterpret_cast<int2 *>(ws + h->off_e);
     p.plan.B = d.batch;
     p.plan.nw = h->nw;
     p.plan.s_min = h->tune_min_partition / kTile;
